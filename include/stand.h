@@ -1,0 +1,172 @@
+/*
+ * stand.h -- C ABI of libstand: the per-step speculation loop of STAND (STochastic Adaptive
+ * N-gram Drafting, arxiv 2506.04708) for AMD MI355X (gfx950), with the target model's logits
+ * supplied by the caller.
+ *
+ * One handle owns one n-gram table in device memory that is shared by `max_batch`
+ * trajectories, the trajectories' context tails and the pending draft tree of each.
+ *
+ * Conventions
+ *   - Pointers named d_* are DEVICE memory owned by the caller; every output buffer is fully
+ *     overwritten.  Pointers named host_* are HOST memory.  Nothing is retained after return
+ *     except by stand_create (which copies the tree).
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls are
+ *     asynchronous on it and ordered by it; the functions documented as synchronising wait
+ *     for the stream themselves.
+ *   - Every function returns STAND_OK (0) or a negative STAND_E* code.  On STAND_EINVAL
+ *     nothing has been launched and no output has been written.
+ *   - One host thread per handle at a time.
+ *   - Tree layout: node 0 is the root (= the last committed token, whose logits row predicts
+ *     the first new token); parent[u] < u; nodes are numbered breadth first with the children
+ *     of a node contiguous, in rank order (rank j = j-th draw of the sampling without
+ *     replacement).  N = tree_nodes counts the root; D = depth of the deepest node.
+ *   - Logits layout: [max_batch][tree_nodes][vocab], row major, vocab contiguous, bf16 bit
+ *     patterns (uint16) or float32.  Entries must be finite or -inf, each row's maximum finite.
+ *   - Token ids are int32 in [0, vocab); -1 marks "no token" (an invalid tree node, padding).
+ */
+#ifndef STAND_H
+#define STAND_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define STAND_OK 0
+#define STAND_EINVAL (-1) /* bad argument or configuration                        */
+#define STAND_ENOMEM (-2) /* host or device allocation failed                     */
+#define STAND_EHIP (-3)   /* a HIP call failed; stand_last_hip_error() has its code */
+#define STAND_ESTATE (-4) /* call order violated (e.g. import into a used table)   */
+
+#define STAND_BF16 0
+#define STAND_F32 1
+
+#define STAND_UPDATE_ACCEPTED_PATH 0 /* merge the rows that produced committed tokens (paper Sec. 4.1) */
+
+#define STAND_MAX_TOPK 32
+#define STAND_MAX_ORDER 8
+#define STAND_MAX_NODES 256
+#define STAND_MAX_DEPTH 31
+
+typedef struct stand_handle stand_handle;
+
+typedef struct {
+    int32_t vocab;              /* V, topk <= V < 2^22                                              */
+    int32_t max_batch;          /* B >= 1 trajectories sharing the table                            */
+    int32_t order_min;          /* shortest context length used as a key, >= 1                      */
+    int32_t order_max;          /* longest, <= STAND_MAX_ORDER (paper Sec. 4.1: unigram .. 4-gram)   */
+    int32_t topk;               /* K ids and probabilities stored per key (paper: 10), <= 32;       */
+                                /* must be >= the largest fan-out of the tree                       */
+    int32_t tree_nodes;         /* N, root included, <= STAND_MAX_NODES                             */
+    const int32_t *tree_parent; /* host, [N], layout above; copied                                  */
+    float temperature;          /* T > 0; rows are softmax(logits / T) (paper Sec. 5: 0.6)          */
+    uint64_t table_capacity;    /* slots, a power of two >= 16                                      */
+    int32_t max_probe;          /* linear-probe limit, >= 1; past it an update is dropped+counted   */
+    uint64_t seed;              /* key of the counter-based uniforms                                */
+    int32_t logits_dtype;       /* STAND_BF16 or STAND_F32                                          */
+    int32_t update_mode;        /* STAND_UPDATE_ACCEPTED_PATH                                       */
+    int32_t device;             /* HIP device ordinal                                               */
+} stand_config;
+
+typedef struct {
+    uint64_t hits[STAND_MAX_ORDER + 1]; /* draft lookups answered by order n                          */
+    uint64_t misses;                    /* draft lookups that found no order                          */
+    uint64_t inserts, merges, drops;    /* table updates: new key / existing key / no slot in reach   */
+    uint64_t near_threshold;            /* accept tests decided by the exact normaliser because the   */
+                                        /* fast one left them within its error bound                  */
+    uint64_t tokens_emitted;
+    uint64_t accept_tests;
+    uint64_t filter_mismatch;           /* path nodes whose outcome changed under exact arithmetic     */
+                                        /* (must stay 0; a self-check of the error bound)              */
+} stand_stats;
+
+/* Creates a handle: validates the configuration, copies the tree, allocates and clears the
+ * table (capacity * (16 + 8*topk) bytes) and the per-trajectory state on cfg->device.
+ * Synchronises the device. */
+int stand_create(const stand_config *cfg, stand_handle **out);
+int stand_destroy(stand_handle *h);
+
+/* Depth D of the tree given at creation; the width of the out_* arrays below is D + 1. */
+int stand_depth(const stand_handle *h);
+
+/* Prompt / prefix of trajectory b (host tokens, n >= 0): replaces its context.  Nothing is
+ * merged into the table (no distribution exists for prompt positions) and the pending draft
+ * of b is dropped.  Synchronises `stream`. */
+int stand_set_context(stand_handle *h, int32_t b, const int32_t *host_tokens, int32_t n, void *stream);
+
+/* Beam copy: trajectory b continues from the context of host_src_of[b] (B entries).  Pending
+ * drafts are dropped; call stand_draft before the next verify.  Synchronises `stream`. */
+int stand_reorder(stand_handle *h, const int32_t *host_src_of, void *stream);
+
+/* Table update (paper Sec. 4.1, "Efficient logit approximation").  For committed token j of
+ * trajectory b (j < d_commit_len[b] <= D+1), produced by the distribution of logits row
+ * d_commit_row[b][j], and every order n the context is long enough for: the row's top-K
+ * (ids, softmax probabilities) is merged into the entry keyed by the n tokens preceding
+ * token j -- running mean with weights k/(k+1) and 1/(k+1), absent ids = 0, truncated to the
+ * K largest by (probability desc, id asc).  Records apply in the order b, j, n ascending.
+ * Afterwards the tokens are appended to the contexts.  d_commit_tok/d_commit_row: [B][D+1]. */
+int stand_update(stand_handle *h, uint64_t step, const void *d_logits, const int32_t *d_commit_tok,
+                 const int32_t *d_commit_row, const int32_t *d_commit_len, void *stream);
+
+/* Draft (paper Sec. 4.2, "Stochastic tree drafting" and "Gumbel-Top-K sampling").  For every
+ * trajectory, walks the tree: a node with a valid token looks up its context (committed
+ * context + tokens on the path from the root) from order_max down to order_min, first hit
+ * wins; its c children get the c largest of  ln mu_i - ln(-ln U_i)  over the stored ids with
+ * mu_i > 0, in rank order.  Fewer candidates than children, or a miss: the remaining
+ * children are -1 and so are their subtrees.  Writes d_draft_tok [B][N] (node 0 = last
+ * committed token, or -1 for an empty context) and keeps the proposals for stand_verify. */
+int stand_draft(stand_handle *h, uint64_t step, int32_t *d_draft_tok, void *stream);
+
+/* Verify (paper Sec. 3.2 applied recursively to the children of a node).  d_logits holds the
+ * target model's logits for the tree drafted with the same `step`.  From the root: the
+ * children of the current node are tested in rank order, child x accepted iff
+ * U < r(x) / w(x) with r the residual target and w the proposal renormalised over the
+ * children not yet rejected; on rejection r <- norm(max(0, r - w)).  An accepted child
+ * becomes the current node.  When no child is accepted (or there is none) one token is drawn
+ * from the residual of the current node and the walk stops.
+ * Outputs: d_out_tok [B][D+1] emitted tokens, d_out_node [B][D+1] the tree node whose logits
+ * row produced each of them (root, then the accepted nodes), d_out_len [B] in 1..D+1; unused
+ * entries are -1.  Handle state (table, contexts) is not changed. */
+int stand_verify(stand_handle *h, uint64_t step, const void *d_logits, int32_t *d_out_tok,
+                 int32_t *d_out_node, int32_t *d_out_len, void *stream);
+
+/* One speculation step = stand_verify(step) -> stand_update with the emitted tokens and their
+ * rows -> stand_draft(step + 1) into d_next_draft_tok [B][N].
+ * If d_force_tok ([B][D+1], may be NULL) is given, the tokens committed to the contexts and
+ * used as table keys are d_force_tok[b][0 .. out_len[b]) instead of the emitted ones (replay
+ * of a recorded trajectory); the emitted tokens are still returned in d_out_tok. */
+int stand_step(stand_handle *h, uint64_t step, const void *d_logits, int32_t *d_out_tok,
+               int32_t *d_out_node, int32_t *d_out_len, int32_t *d_next_draft_tok,
+               const int32_t *d_force_tok, void *stream);
+
+/* Per-row results of the last stand_verify / stand_step, for inspection: for each of the B*N
+ * rows the maximum logit, the softmax normaliser (fast single-pass value, relative error
+ * below 1e-5), and the K largest entries (ids exact; probabilities from the fast normaliser).
+ * Any pointer may be NULL.  d_row_max, d_row_sum: [B*N] float; d_top_idx: [B*N][K] int32;
+ * d_top_p: [B*N][K] float. */
+int stand_row_results(stand_handle *h, float *d_row_max, float *d_row_sum, int32_t *d_top_idx,
+                      float *d_top_p, void *stream);
+
+/* Table export: entries sorted by key fingerprint, each
+ *   uint64 fingerprint, uint32 count, uint32 order, int32 ids[K], float mu[K]   (16 + 8K bytes).
+ * On entry *inout_bytes is the size of host_buf; on return the bytes needed/written.
+ * host_buf == NULL only queries the size.  Synchronises the device. */
+int stand_table_export(stand_handle *h, void *host_buf, uint64_t *inout_bytes);
+/* Loads entries in the export format into an EMPTY table (STAND_ESTATE otherwise). */
+int stand_table_import(stand_handle *h, const void *host_buf, uint64_t bytes);
+
+/* Copies the last `n` context tokens of trajectory b to host (n <= order_max kept on device)
+ * and returns the context length through *len_out.  Synchronises `stream`. */
+int stand_get_context(stand_handle *h, int32_t b, int32_t *host_tail, int32_t n, int64_t *len_out, void *stream);
+
+/* Counters since creation.  Synchronises the device. */
+int stand_get_stats(stand_handle *h, stand_stats *out);
+
+const char *stand_strerror(int code);
+int stand_last_hip_error(const stand_handle *h);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* STAND_H */

@@ -1,0 +1,481 @@
+"""Pins of the CPU oracle against what the paper and the mathematics fix (no GPU needed).
+
+Each test names the passage of the paper (arxiv 2506.04708) or the closed form it checks.
+"""
+import itertools
+import math
+import os
+
+import numpy as np
+import pytest
+from scipy import stats
+
+import oracle
+from paper_2506_04708_amd import synth
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+rng0 = np.random.default_rng(20250604)
+
+
+def _chi(counts, probs):
+    """p-value of observed counts against a categorical law (probs renormalised in float64)."""
+    counts = np.asarray(counts, dtype=np.float64)
+    p = np.asarray(probs, dtype=np.float64)
+    return stats.chisquare(counts, counts.sum() * p / p.sum()).pvalue
+
+
+# ---- elementary functions ------------------------------------------------------------------
+def test_exp2_against_float64():
+    ys = np.concatenate([np.linspace(-64, 0.5, 20001), -rng0.random(20000) * 40]).astype(np.float32)
+    got = np.array([oracle.exp2(y) for y in ys], dtype=np.float64)
+    ref = np.exp2(ys.astype(np.float64))
+    assert np.max(np.abs(got / ref - 1)) < 2e-7
+    assert oracle.exp2(0.0) == 1.0
+    assert oracle.exp2(-1.0) == 0.5
+    assert oracle.exp2(-64.5) == 0.0 and oracle.exp2(-1e30) == 0.0 and oracle.exp2(float("-inf")) == 0.0
+
+
+def test_log_against_float64():
+    xs = np.concatenate([np.exp(rng0.uniform(-60, 3, 40000)), [1.0, 0.5, 2.0, 1 - 2.0 ** -24, 2.0 ** -24]]).astype(np.float32)
+    got = np.array([oracle.log(x) for x in xs], dtype=np.float64)
+    ref = np.log(xs.astype(np.float64))
+    assert np.max(np.abs(got - ref) / np.maximum(1e-6, np.abs(ref))) < 3e-7
+    assert oracle.log(1.0) == 0.0
+
+
+# ---- Philox uniforms -------------------------------------------------------------------------
+def _philox_py(seed, ctr):
+    # independent integer implementation of Philox4x32-10 (Salmon et al., SC'11)
+    c = list(ctr)
+    k0, k1 = seed & 0xFFFFFFFF, seed >> 32
+    for _ in range(10):
+        p0 = 0xD2511F53 * c[0]
+        p1 = 0xCD9E8D57 * c[2]
+        c = [((p1 >> 32) ^ c[1] ^ k0) & 0xFFFFFFFF, p1 & 0xFFFFFFFF, ((p0 >> 32) ^ c[3] ^ k1) & 0xFFFFFFFF, p0 & 0xFFFFFFFF]
+        k0 = (k0 + 0x9E3779B9) & 0xFFFFFFFF
+        k1 = (k1 + 0xBB67AE85) & 0xFFFFFFFF
+    return c
+
+
+def test_philox_two_implementations_agree_and_is_injective():
+    seed = 0x0123456789ABCDEF
+    seen = set()
+    for i in range(20000):
+        ctr = (i, i * 7 + 1, i >> 3, 5)
+        got = oracle.philox(seed, *ctr)
+        assert list(got) == _philox_py(seed, ctr)
+        seen.add(tuple(got))
+    assert len(seen) == 20000  # a block cipher in counter mode never repeats a block
+
+
+def test_uniform_open_interval_and_moments():
+    n = 200000
+    u = np.array([oracle.uniform(99, 3, 5, 2, t, oracle.STREAM_BONUS) for t in range(n)])
+    assert u.min() > 0.0 and u.max() < 1.0
+    assert np.all(u * 2 ** 24 == np.round(u * 2 ** 24)) and np.all((u * 2 ** 24) % 2 == 1)
+    assert abs(u.mean() - 0.5) < 4 / math.sqrt(12 * n)
+    assert abs(u.var() - 1 / 12) < 0.002
+    assert stats.kstest(u, "uniform").pvalue > 1e-3
+    # streams, nodes, steps and trajectories give different numbers
+    base = oracle.uniform(99, 3, 5, 2, 10, 0)
+    others = [oracle.uniform(99, 3, 5, 2, 10, 1), oracle.uniform(99, 4, 5, 2, 10, 0), oracle.uniform(99, 3, 6, 2, 10, 0),
+              oracle.uniform(99, 3, 5, 3, 10, 0), oracle.uniform(98, 3, 5, 2, 10, 0), oracle.uniform(99, 3, 5 + 2 ** 32, 2, 10, 0)]
+    assert all(o != base for o in others)
+
+
+# ---- O1 row distribution: softmax(logits / T), Sec. 4.1 + Sec. 5 (T = 0.6) ------------------
+def _softmax64(l, T):
+    z = l.astype(np.float64) / T
+    z -= z.max()
+    e = np.exp(z)
+    return e / e.sum()
+
+
+@pytest.mark.parametrize("V,T,dtype", [(1000, 0.6, "f32"), (32000, 0.6, "f32"), (152064, 0.6, "bf16"), (5000, 1.0, "bf16"), (777, 0.8, "f32")])
+def test_softmax_against_float64(V, T, dtype):
+    x = (rng0.standard_normal(V) * math.sqrt(3)).astype(np.float32)
+    x[rng0.integers(V, size=3)] += 8
+    row = x if dtype == "f32" else synth.f32_to_bf16_bits(x)
+    lf = x if dtype == "f32" else synth.bf16_bits_to_f32(row)
+    p, m, s, S = oracle.row_softmax(row, T)
+    ref = _softmax64(lf, T)
+    big = ref > 1e-12
+    assert np.max(np.abs(p[big] / ref[big] - 1)) < 5e-6
+    assert abs(p.astype(np.float64).sum() - 1) < 2e-6
+    assert m == lf.max()
+
+
+def test_softmax_shift_invariance_and_logistic():
+    # values on a 2^-10 grid: adding an integer is exact, so the result must not change at all
+    x = (rng0.integers(-8192, 8192, 4000) / 1024.0).astype(np.float32)
+    p0, *_ = oracle.row_softmax(x, 0.6)
+    p1, *_ = oracle.row_softmax(x + np.float32(5.0), 0.6)
+    assert np.array_equal(p0, p1)
+    # V = 2, T = 1: p0 = 1 / (1 + exp(l1 - l0))
+    for l0, l1 in [(0.0, 0.0), (1.5, -0.25), (-3.0, 2.0), (10.0, 9.0)]:
+        p, *_ = oracle.row_softmax(np.array([l0, l1], np.float32), 1.0)
+        assert abs(p[0] - 1 / (1 + math.exp(l1 - l0))) < 3e-7
+    # temperature really divides the logits: T = 0.5 on l equals T = 1 on 2 l
+    pa, *_ = oracle.row_softmax(x, 0.5)
+    pb, *_ = oracle.row_softmax(x * np.float32(2.0), 1.0)
+    assert np.max(np.abs(pa - pb)) < 1e-6
+
+
+def test_softmax_masked_tokens_get_zero():
+    x = rng0.standard_normal(100).astype(np.float32)
+    x[7] = -np.inf
+    x[9] = -1e30
+    p, *_ = oracle.row_softmax(x, 0.6)
+    assert p[7] == 0.0 and p[9] == 0.0 and abs(p.sum() - 1) < 1e-6
+
+
+# ---- O2 observation = top-k of the row, Sec. 4.1 --------------------------------------------
+def test_topk_equals_stable_sort_and_ties():
+    v = np.round(rng0.standard_normal(5000) * 4).astype(np.float32) / 4  # many ties
+    idx, val = oracle.topk(v, 32)
+    order = np.lexsort((np.arange(v.size), -v))[:32]
+    assert np.array_equal(idx, order) and np.array_equal(val, v[order])
+    idx, _ = oracle.topk(np.zeros(100, np.float32), 10)
+    assert list(idx) == list(range(10))
+    z = np.zeros(6, np.float32)
+    z[2] = -0.0
+    z[4] = -1.0
+    idx, _ = oracle.topk(z, 5)
+    assert list(idx) == [0, 1, 2, 3, 5]  # -0 ties with +0, the id decides
+
+
+def test_row_obs_is_topk_of_softmax():
+    x = (rng0.standard_normal(3000) * 1.7).astype(np.float32)
+    row = synth.f32_to_bf16_bits(x)
+    idx, p, m, s = oracle.row_obs(row, 0.6, 10)
+    pd, *_ = oracle.row_softmax(row, 0.6)
+    order = np.lexsort((np.arange(3000), -synth.bf16_bits_to_f32(row)))[:10]
+    assert np.array_equal(idx, order)
+    assert np.array_equal(p, pd[order])
+    assert np.all(np.diff(p) <= 0)
+
+
+# ---- O3 merge, Sec. 4.1 "Efficient logit approximation" ---------------------------------------
+def test_merge_worked_example_from_paper_rule():
+    for line in open(os.path.join(GOLD, "merge_worked.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        f = [x.split() for x in line.split("|")]
+        count = int(f[0][0])
+        ids, mu = [int(x) for x in f[1]], [float(x) for x in f[2]]
+        oid, op = [int(x) for x in f[3]], [float(x) for x in f[4]]
+        wid, wmu = [int(x) for x in f[5]], [float(x) for x in f[6]]
+        gid, gmu = oracle.merge(count, ids, mu, oid, op)
+        assert list(gid) == wid
+        assert np.allclose(gmu, wmu, rtol=1e-6)
+
+
+def test_merge_weights_k_over_k_plus_1():
+    ids = np.arange(4)
+    mu = np.array([0.4, 0.3, 0.2, 0.1], np.float32)
+    obs = np.array([0.1, 0.2, 0.3, 0.4], np.float32)
+    for k in (1, 2, 7):
+        gid, gmu = oracle.merge(k, ids, mu, ids, obs)
+        want = mu * (k / (k + 1)) + obs * (1 / (k + 1))
+        got = dict(zip(gid, gmu))
+        for i in range(4):
+            assert abs(got[i] - want[i]) < 1e-7
+    # first sight stores the observation itself
+    gid, gmu = oracle.merge(0, np.zeros(4, np.int32), np.zeros(4, np.float32), ids[::-1].copy(), obs)
+    assert list(gid) == [3, 2, 1, 0] and np.array_equal(gmu, obs)
+    # merging a distribution into itself leaves it (almost) unchanged
+    gid, gmu = oracle.merge(5, ids, mu, ids, mu)
+    assert list(gid) == [0, 1, 2, 3] and np.allclose(gmu, mu, rtol=3e-7)
+
+
+def test_merge_absent_ids_count_as_zero_and_tie_by_id():
+    gid, gmu = oracle.merge(1, [5, 9], [0.5, 0.5], [7, 3], [0.5, 0.5])
+    # every id ends at 0.25; the two smallest ids survive
+    assert list(gid) == [3, 5] and np.allclose(gmu, [0.25, 0.25])
+
+
+def _mini_oracle(V=8, K=8, B=1, parent=(-1, 0, 0, 1), omin=1, omax=3, T=0.6, seed=7, cap=1 << 12, dtype=oracle.DT_F32):
+    return oracle.Oracle(V, B, omin, omax, K, np.array(parent, np.int32), T, cap, 64, seed, dtype)
+
+
+def test_table_equals_brute_force_recount():
+    """With K >= number of distinct ids the stored vector is the arithmetic mean of all
+    observations of a context and the count is its number of occurrences (Sec. 4.1)."""
+    V, K, T = 8, 8, 0.6
+    o = _mini_oracle(V=V, K=K, T=T)
+    W = o.W
+    r = np.random.default_rng(5)
+    ctx = [int(x) for x in r.integers(V, size=3)]
+    o.set_context(0, ctx)
+    recount = {}
+    for step in range(200):
+        lg = r.standard_normal((1, o.N, V)).astype(np.float32)
+        n = int(r.integers(1, W + 1))
+        toks = r.integers(V, size=n)
+        rows = r.integers(o.N, size=n)
+        ct = np.full((1, W), -1, np.int32)
+        cr = np.full((1, W), -1, np.int32)
+        ct[0, :n], cr[0, :n] = toks, rows
+        for j in range(n):
+            p = _softmax64(lg[0, rows[j]], T)
+            for order in (1, 2, 3):
+                if len(ctx) >= order:
+                    key = tuple(ctx[-order:])
+                    acc = recount.setdefault(key, [0, np.zeros(V)])
+                    acc[0] += 1
+                    acc[1] += p
+            ctx.append(int(toks[j]))
+        o.update(step, lg, ct, cr, np.array([n], np.int32))
+    tab = o.table_export()
+    assert len(tab) == len(recount)
+    byfp = {int(t["fp"]): t for t in tab}
+    for key, (cnt, psum) in recount.items():
+        t = byfp[oracle.fingerprint(key)]
+        assert t["count"] == cnt and t["order"] == len(key)
+        mean = psum / cnt
+        got = np.zeros(V)
+        got[t["ids"]] = t["mu"]
+        assert np.max(np.abs(got - mean)) < 2e-6
+        assert np.all(np.diff(t["mu"]) <= 0)
+    assert o.context_len(0) == len(ctx) and list(o.context_tail(0, 3)) == ctx[-3:]
+
+
+def test_fingerprint_separates_orders_and_permutations():
+    fps = {oracle.fingerprint(t) for t in [(1,), (1, 1), (1, 2), (2, 1), (0,), (0, 0), (0, 0, 0), (2 ** 31 - 1,)]}
+    assert len(fps) == 8 and 0 not in fps
+    keys = {oracle.fingerprint((a, b)) for a in range(300) for b in range(300)}
+    assert len(keys) == 90000
+
+
+# ---- O4 multi-level lookup, Sec. 4.2 "Stochastic tree drafting" -------------------------------
+def test_lookup_longest_order_first():
+    o = _mini_oracle(V=50, K=4, omax=4)
+    ids = np.arange(4)
+    mu = np.array([0.4, 0.3, 0.2, 0.1], np.float32)
+    o.table_put([9], 3, ids, mu)            # unigram exists
+    o.table_put([8, 9], 2, ids + 10, mu)    # bigram exists
+    n, gid, gmu, cnt = o.lookup([5, 6, 7, 8, 9])
+    assert n == 2 and list(gid) == [10, 11, 12, 13] and cnt == 2  # 4- and 3-gram miss, bigram wins over unigram
+    n, gid, _, _ = o.lookup([1, 9])
+    assert n == 1 and list(gid) == [0, 1, 2, 3]
+    n, *_ = o.lookup([1, 2])
+    assert n == 0
+    n, gid, _, _ = o.lookup([9])             # context shorter than the longer orders
+    assert n == 1
+    o.table_put([6, 7, 8, 9], 1, ids + 20, mu)
+    n, gid, _, _ = o.lookup([5, 6, 7, 8, 9])
+    assert n == 4 and gid[0] == 20
+
+
+# ---- O5 Gumbel-Top-K, Sec. 4.2 -----------------------------------------------------------------
+def _plackett_luce(q, tup):
+    pr, rest = 1.0, 1.0
+    for i in tup:
+        pr *= q[i] / rest
+        rest -= q[i]
+    return pr
+
+
+def test_gumbel_topk_matches_sampling_without_replacement():
+    ids = np.array([11, 3, 7, 20, 5], np.int32)
+    mu = np.array([0.35, 0.05, 0.2, 0.1, 0.02], np.float32)  # raw masses, not normalised
+    q = mu.astype(np.float64) / mu.astype(np.float64).sum()
+    K, c, trials = 5, 3, 1_000_000
+    counts = oracle.mc_gumbel_topk(ids, mu, c, trials, seed=42)
+    obs, exp = [], []
+    for tup in itertools.permutations(range(K), c):
+        code = 0
+        for i in tup:
+            code = code * K + i
+        obs.append(counts[code])
+        exp.append(trials * _plackett_luce(q, tup))
+    assert sum(obs) == trials
+    assert _chi(obs, exp) > 1e-3
+    # k = 1 is plain categorical sampling
+    c1 = oracle.mc_gumbel_topk(ids, mu, 1, 400_000, seed=43)
+    assert _chi(c1, q) > 1e-3
+
+
+def test_gumbel_topk_formula_and_order():
+    ids = np.array([4, 2, 9], np.int32)
+    mu = np.array([0.5, 0.25, 0.0], np.float32)
+    U = np.array([0.3, 0.9, 0.5], np.float32)
+    score = np.log(mu[:2].astype(np.float64)) - np.log(-np.log(U[:2].astype(np.float64)))  # phi - log(-log U)
+    want = [int(ids[i]) for i in np.argsort(-score)]
+    assert list(oracle.gumbel_topk(ids, mu, 2, U)) == want
+    assert list(oracle.gumbel_topk(ids, mu, 3, U)) == want  # zero-mass ids are never drawn
+
+
+# ---- O6 verification, Sec. 3.2 (single draft) and its recursive use for several children ----
+def _rand_dist(r, V, conc=0.5):
+    return r.dirichlet(np.full(V, conc)).astype(np.float32)
+
+
+@pytest.mark.parametrize("fanout", [1, 2, 3, 4])
+def test_verification_preserves_target_distribution(fanout):
+    """Chi-square over 10^6 trials at V = 8: the emitted token follows p whatever q is."""
+    r = np.random.default_rng(100 + fanout)
+    V, K = 8, 5
+    p = _rand_dist(r, V)
+    ids = r.permutation(V)[:K].astype(np.int32)   # support not aligned with the top of p
+    mu = (r.dirichlet(np.full(K, 0.7)) * 0.8).astype(np.float32)
+    counts, acc, near, err, mn = oracle.mc_node(p, ids, mu, fanout, 1_000_000, seed=1000 + fanout)
+    assert counts.sum() == 1_000_000
+    assert _chi(counts, p) > 1e-3
+    assert err < 5e-6 and mn >= 0.0  # residuals sum to 1 and are non-negative after every round
+
+
+def test_single_draft_acceptance_rate_closed_form():
+    r = np.random.default_rng(7)
+    V, K = 8, 8
+    p = _rand_dist(r, V)
+    ids = np.arange(V, dtype=np.int32)
+    mu = _rand_dist(r, V)
+    trials = 400_000
+    counts, acc, *_ = oracle.mc_node(p, ids, mu, 1, trials, seed=5)
+    q = mu.astype(np.float64) / mu.astype(np.float64).sum()
+    want = np.minimum(p, q).sum()   # P(accept) = sum_x min(p, q)
+    assert abs(acc / trials - want) < 4 * math.sqrt(want * (1 - want) / trials)
+    assert _chi(counts, p) > 1e-3
+
+
+def test_q_equal_p_always_accepts_and_one_hot_accepts_with_p():
+    V = 8
+    r = np.random.default_rng(8)
+    p = _rand_dist(r, V, 2.0)
+    ids = np.arange(V, dtype=np.int32)
+    counts, acc, *_ = oracle.mc_node(p, ids, p, 1, 100_000, seed=6)
+    assert acc == 100_000                      # "accepted if q <= p", Sec. 3.2
+    onehot = np.zeros(V, np.float32)
+    onehot[3] = 1.0
+    counts, acc, *_ = oracle.mc_node(p, ids, onehot, 1, 400_000, seed=7)
+    assert abs(acc / 400_000 - p[3]) < 4 * math.sqrt(p[3] * (1 - p[3]) / 400_000)   # Sec. 3.2, deterministic drafting
+    assert _chi(counts, p) > 1e-3
+
+
+def test_verify_node_rule_by_hand():
+    # p = (.5,.3,.2), q = (.2,.8,0): drafting token 1 (q=.8 > p=.3) is accepted iff omega < .375
+    p = np.array([0.5, 0.3, 0.2], np.float32)
+    ids, mu = np.array([0, 1, 2], np.int32), np.array([0.2, 0.8, 0.0], np.float32)
+    acc, _ = oracle.verify_node(p, ids, mu, [1], [0.37])
+    assert acc == 0
+    acc, st = oracle.verify_node(p, ids, mu, [1], [0.38])
+    assert acc == -1
+    res = oracle.residual_dense(p, ids, st)   # norm(max(0, p - q)) = (.3, 0, .2) / .5
+    assert np.allclose(res, [0.6, 0.0, 0.4], atol=1e-6)
+    # q <= p: always accepted
+    acc, _ = oracle.verify_node(p, ids, mu, [0], [0.999999])
+    assert acc == 0
+    # second round uses the residual target and the proposal without the rejected token
+    acc, st = oracle.verify_node(p, ids, mu, [1, 0], [0.9, 0.59])
+    assert acc == 1   # r(0) = .6, w(0) = 1 -> accept iff omega < .6
+    acc, st = oracle.verify_node(p, ids, mu, [1, 0], [0.9, 0.61])
+    assert acc == -1
+    assert np.allclose(oracle.residual_dense(p, ids, st), [0.0, 0.0, 1.0], atol=1e-6)
+
+
+def test_race_samples_the_distribution():
+    r = _rand_dist(np.random.default_rng(9), 8)
+    r[2] = 0.0
+    r /= r.sum()
+    counts = oracle.mc_race(r, 400_000, seed=11)
+    assert counts[2] == 0
+    keep = r > 0
+    assert _chi(counts[keep], r[keep]) > 1e-3
+
+
+def test_two_level_tree_joint_distribution():
+    """Root with 2 children, first child with 2 children: the first two emitted tokens follow
+    p(x1) p(x2 | x1) when the logits of a node depend only on its token."""
+    V, K, T, B = 6, 4, 0.6, 4096
+    parent = np.array([-1, 0, 0, 1, 1, 2], np.int32)
+    r = np.random.default_rng(21)
+    o = oracle.Oracle(V, B, 1, 2, K, parent, T, 1 << 12, 64, 77, oracle.DT_F32)
+    # target: distribution of the next token given the last token (order-1 model)
+    cond = np.stack([_rand_dist(r, V, 1.0) for _ in range(V)])
+    logit_of = (np.log(cond.astype(np.float64)) * T).astype(np.float32)
+    # a table with imperfect unigram entries for every token
+    for t in range(V):
+        ids = r.permutation(V)[:K].astype(np.int32)
+        o.table_put([t], 1, ids, (r.dirichlet(np.ones(K)) * 0.9).astype(np.float32))
+    root = 2
+    joint = np.zeros((V, V))
+    n1 = np.zeros(V)
+    steps = 60
+    for step in range(steps):
+        for b in range(B):
+            o.set_context(b, [root])
+        d = o.draft(step)
+        lg = np.zeros((B, o.N, V), np.float32)
+        tok = np.where(d >= 0, d, 0)
+        lg[:] = logit_of[tok]
+        out_tok, out_node, out_len = o.verify(step, lg)
+        for b in range(B):
+            n1[out_tok[b, 0]] += 1
+            if out_len[b] >= 2:
+                joint[out_tok[b, 0], out_tok[b, 1]] += 1
+    total = B * steps
+    assert _chi(n1, cond[root]) > 1e-3
+    # given that a second token was emitted after x1, it follows p(. | x1)
+    for x1 in range(V):
+        if joint[x1].sum() > 2000:
+            assert _chi(joint[x1], cond[x1]) > 1e-4
+
+
+# ---- draft: tree walk, validity, contexts ----------------------------------------------------
+def test_draft_contexts_and_invalid_subtrees():
+    V, K = 40, 3
+    parent = np.array([-1, 0, 0, 1, 1, 2, 3], np.int32)  # node1 has 2 children, node 2 has 1, node 3 has 1
+    o = oracle.Oracle(V, 1, 1, 2, K, parent, 0.6, 1 << 10, 64, 5, oracle.DT_F32)
+    o.set_context(0, [30, 31])
+    one = lambda t: (np.array([t, 0, 1], np.int32), np.array([1.0, 0.0, 0.0], np.float32))
+    o.table_put([31], 1, np.array([10, 11, 0], np.int32), np.array([0.5, 0.5, 0.0], np.float32))  # root: 2 candidates
+    o.table_put([31, 10], 1, *one(12))   # bigram for the path (root, 10): only one candidate
+    o.table_put([10], 1, *one(13))       # unigram that must lose to the bigram
+    o.table_put([12], 1, *one(14))
+    d = o.draft(0)[0]
+    assert d[0] == 31 and sorted(d[1:3]) == [10, 11]
+    n10 = 1 if d[1] == 10 else 2
+    first = {1: 3, 2: 5}[n10]
+    assert d[first] == 12                      # bigram (31,10) -> 12, not the unigram's 13
+    if n10 == 1:
+        assert d[4] == -1                      # one candidate for two children: the second is invalid
+        assert d[6] == 14                      # child of node 3 (token 12) via unigram (12)
+        assert d[5] == -1                      # node 2 holds token 11: nothing known -> miss
+    s = o.stats()
+    assert s.hits[2] == 1 and s.misses >= 1
+
+
+def test_tree_generator_matches_fixture():
+    lines = [l.split() for l in open(os.path.join(GOLD, "cfg1_tree.txt")) if not l.startswith("#")]
+    par = [int(x) for x in lines[0][1:]]
+    assert list(synth.make_tree(16, 4, [4, 2, 1, 1])) == par
+    for l in lines[2:]:
+        N, D, caps = int(l[1]), int(l[2]), [int(x) for x in l[3].split(",")]
+        widths = [int(x) for x in l[5:]]
+        depth, nchild, first, dmax = synth.tree_info(synth.make_tree(N, D, caps))
+        assert dmax == D and [int((depth == d).sum()) for d in range(D + 1)] == widths
+
+
+# ---- whole-method sanity (not parity): repetition helps, Sec. 5.1 ----------------------------
+def _run_accept_len(rho, B, steps=150, V=2048):
+    w = synth.Workload("cfg1", run_steps=steps, V=V, rho=rho, B=B)
+    o = oracle.Oracle(w.V, w.B, 1, 3, w.K, w.parent, w.T, 1 << 14, 64, 1, oracle.DT_F32)
+    for b in range(B):
+        o.set_context(b, w.prompt(b))
+    d = o.draft(0)
+    tot = 0
+    for step in range(steps):
+        lg = w.logits(step, d)
+        tok, node, ln = o.verify(step, lg)
+        o.update(step, lg, w.commit(ln), node, ln)
+        d = o.draft(step + 1)
+        if step >= steps // 2:
+            tot += ln.sum()
+    return tot / (B * (steps - steps // 2))
+
+
+def test_acceptance_length_rises_with_repetition():
+    lo = _run_accept_len(0.0, 1)
+    hi = _run_accept_len(0.9, 1)
+    assert hi > lo
