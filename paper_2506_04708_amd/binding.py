@@ -1,0 +1,203 @@
+"""Thin ctypes binding of libstand.so (see include/stand.h): argument marshalling only.
+
+Device buffers are torch tensors (PyTorch-ROCm is used for memory and streams, nothing else);
+every step of the path runs in the HIP kernels of the library.  There is no CPU fallback: if
+the library has not been built, importing this module raises.
+"""
+import ctypes as C
+import os
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libstand.so")
+
+STAND_BF16, STAND_F32 = 0, 1
+MAX_ORDER = 8
+
+EXPORTED = [
+    "stand_create", "stand_destroy", "stand_depth", "stand_set_context", "stand_reorder", "stand_update",
+    "stand_draft", "stand_verify", "stand_step", "stand_row_results", "stand_table_export", "stand_table_import",
+    "stand_get_context", "stand_get_stats", "stand_strerror", "stand_last_hip_error",
+]
+
+
+class Config(C.Structure):
+    _fields_ = [
+        ("vocab", C.c_int32), ("max_batch", C.c_int32), ("order_min", C.c_int32), ("order_max", C.c_int32),
+        ("topk", C.c_int32), ("tree_nodes", C.c_int32), ("tree_parent", C.POINTER(C.c_int32)),
+        ("temperature", C.c_float), ("table_capacity", C.c_uint64), ("max_probe", C.c_int32),
+        ("seed", C.c_uint64), ("logits_dtype", C.c_int32), ("update_mode", C.c_int32), ("device", C.c_int32),
+    ]
+
+
+class Stats(C.Structure):
+    _fields_ = [
+        ("hits", C.c_uint64 * (MAX_ORDER + 1)), ("misses", C.c_uint64),
+        ("inserts", C.c_uint64), ("merges", C.c_uint64), ("drops", C.c_uint64),
+        ("near_threshold", C.c_uint64), ("tokens_emitted", C.c_uint64), ("accept_tests", C.c_uint64),
+        ("filter_mismatch", C.c_uint64),
+    ]
+
+
+def load_library():
+    if not os.path.exists(LIB_PATH):
+        raise ImportError("libstand.so is not built: run `python -c 'import __graft_entry__ as g; g.build()'` "
+                          "(or python -m paper_2506_04708_amd.build) first; there is no fallback path")
+    lib = C.CDLL(LIB_PATH)
+    vp, i32p = C.c_void_p, C.c_void_p
+    lib.stand_create.argtypes = [C.POINTER(Config), C.POINTER(vp)]
+    lib.stand_destroy.argtypes = [vp]
+    lib.stand_depth.argtypes = [vp]
+    lib.stand_set_context.argtypes = [vp, C.c_int32, i32p, C.c_int32, vp]
+    lib.stand_reorder.argtypes = [vp, i32p, vp]
+    lib.stand_update.argtypes = [vp, C.c_uint64, vp, i32p, i32p, i32p, vp]
+    lib.stand_draft.argtypes = [vp, C.c_uint64, i32p, vp]
+    lib.stand_verify.argtypes = [vp, C.c_uint64, vp, i32p, i32p, i32p, vp]
+    lib.stand_step.argtypes = [vp, C.c_uint64, vp, i32p, i32p, i32p, i32p, i32p, vp]
+    lib.stand_row_results.argtypes = [vp, vp, vp, vp, vp, vp]
+    lib.stand_table_export.argtypes = [vp, vp, C.POINTER(C.c_uint64)]
+    lib.stand_table_import.argtypes = [vp, vp, C.c_uint64]
+    lib.stand_get_context.argtypes = [vp, C.c_int32, i32p, C.c_int32, C.POINTER(C.c_int64), vp]
+    lib.stand_get_stats.argtypes = [vp, C.POINTER(Stats)]
+    lib.stand_strerror.restype = C.c_char_p
+    lib.stand_strerror.argtypes = [C.c_int]
+    lib.stand_last_hip_error.argtypes = [vp]
+    return lib
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        _lib = load_library()
+    return _lib
+
+
+class StandError(RuntimeError):
+    pass
+
+
+def _check(rc, handle=None):
+    if rc != 0:
+        msg = lib().stand_strerror(rc).decode()
+        if handle is not None and rc == -3:
+            msg += " [hip error %d]" % lib().stand_last_hip_error(handle)
+        raise StandError("libstand: %s (%d)" % (msg, rc))
+
+
+def _dptr(t, dtype=None):
+    if t is None:
+        return None
+    assert t.is_cuda and t.is_contiguous()
+    if dtype is not None:
+        assert t.dtype == dtype, (t.dtype, dtype)
+    return C.c_void_p(t.data_ptr())
+
+
+def _stream_ptr():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+class Stand:
+    """One n-gram table shared by B trajectories on one GPU; methods carry the C ABI's names."""
+
+    def __init__(self, vocab, max_batch, order_min, order_max, topk, tree_parent, temperature, table_capacity,
+                 max_probe, seed, logits_dtype, device=0):
+        par = np.ascontiguousarray(tree_parent, dtype=np.int32)
+        cfg = Config(vocab, max_batch, order_min, order_max, topk, par.shape[0],
+                     par.ctypes.data_as(C.POINTER(C.c_int32)), temperature, table_capacity, max_probe, seed,
+                     logits_dtype, 0, device)
+        self.h = C.c_void_p()
+        _check(lib().stand_create(C.byref(cfg), C.byref(self.h)))
+        self.B, self.N, self.K, self.V = max_batch, par.shape[0], topk, vocab
+        self.D = lib().stand_depth(self.h)
+        self.W = self.D + 1
+        self.logits_dtype = logits_dtype
+        self.device = torch.device("cuda", device)
+
+    def close(self):
+        if getattr(self, "h", None):
+            lib().stand_destroy(self.h)
+            self.h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _logits_ptr(self, logits):
+        assert logits.is_cuda and logits.is_contiguous() and logits.numel() == self.B * self.N * self.V
+        if self.logits_dtype == STAND_BF16:
+            assert logits.dtype in (torch.bfloat16, torch.uint16, torch.int16)
+        else:
+            assert logits.dtype == torch.float32
+        return C.c_void_p(logits.data_ptr())
+
+    def new_outputs(self):
+        i32 = dict(dtype=torch.int32, device=self.device)
+        return (torch.empty((self.B, self.W), **i32), torch.empty((self.B, self.W), **i32),
+                torch.empty((self.B,), **i32), torch.empty((self.B, self.N), **i32))
+
+    def set_context(self, b, tokens):
+        t = np.ascontiguousarray(tokens, dtype=np.int32)
+        _check(lib().stand_set_context(self.h, b, t.ctypes.data_as(C.c_void_p), t.shape[0], _stream_ptr()), self.h)
+
+    def reorder(self, src_of):
+        s = np.ascontiguousarray(src_of, dtype=np.int32)
+        assert s.shape[0] == self.B
+        _check(lib().stand_reorder(self.h, s.ctypes.data_as(C.c_void_p), _stream_ptr()), self.h)
+
+    def update(self, step, logits, commit_tok, commit_row, commit_len):
+        assert commit_tok.shape == (self.B, self.W) and commit_row.shape == (self.B, self.W) and commit_len.shape == (self.B,)
+        _check(lib().stand_update(self.h, step, self._logits_ptr(logits), _dptr(commit_tok, torch.int32),
+                                  _dptr(commit_row, torch.int32), _dptr(commit_len, torch.int32), _stream_ptr()), self.h)
+
+    def draft(self, step, draft_tok):
+        assert draft_tok.shape == (self.B, self.N)
+        _check(lib().stand_draft(self.h, step, _dptr(draft_tok, torch.int32), _stream_ptr()), self.h)
+
+    def verify(self, step, logits, out_tok, out_node, out_len):
+        _check(lib().stand_verify(self.h, step, self._logits_ptr(logits), _dptr(out_tok, torch.int32),
+                                  _dptr(out_node, torch.int32), _dptr(out_len, torch.int32), _stream_ptr()), self.h)
+
+    def step(self, step, logits, out_tok, out_node, out_len, next_draft_tok, force_tok=None):
+        _check(lib().stand_step(self.h, step, self._logits_ptr(logits), _dptr(out_tok, torch.int32),
+                                _dptr(out_node, torch.int32), _dptr(out_len, torch.int32),
+                                _dptr(next_draft_tok, torch.int32), _dptr(force_tok, torch.int32), _stream_ptr()), self.h)
+
+    def row_results(self):
+        rows = self.B * self.N
+        m = torch.empty(rows, dtype=torch.float32, device=self.device)
+        s = torch.empty(rows, dtype=torch.float32, device=self.device)
+        idx = torch.empty((rows, self.K), dtype=torch.int32, device=self.device)
+        p = torch.empty((rows, self.K), dtype=torch.float32, device=self.device)
+        _check(lib().stand_row_results(self.h, _dptr(m), _dptr(s), _dptr(idx), _dptr(p), _stream_ptr()), self.h)
+        return m, s, idx, p
+
+    def table_export(self):
+        n = C.c_uint64(0)
+        _check(lib().stand_table_export(self.h, None, C.byref(n)), self.h)
+        buf = np.zeros(max(int(n.value), 1), np.uint8)
+        n2 = C.c_uint64(buf.shape[0])
+        _check(lib().stand_table_export(self.h, buf.ctypes.data_as(C.c_void_p), C.byref(n2)), self.h)
+        return buf[: int(n2.value)]
+
+    def table_import(self, buf):
+        b = np.ascontiguousarray(buf, dtype=np.uint8)
+        _check(lib().stand_table_import(self.h, b.ctypes.data_as(C.c_void_p), b.shape[0]), self.h)
+
+    def get_context(self, b, n):
+        out = np.zeros(max(n, 1), np.int32)
+        ln = C.c_int64(0)
+        _check(lib().stand_get_context(self.h, b, out.ctypes.data_as(C.c_void_p), n, C.byref(ln), _stream_ptr()), self.h)
+        return out[:n], int(ln.value)
+
+    def stats(self):
+        s = Stats()
+        _check(lib().stand_get_stats(self.h, C.byref(s)), self.h)
+        return s

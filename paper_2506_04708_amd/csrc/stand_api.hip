@@ -1,0 +1,473 @@
+// stand_api.hip -- host side of libstand: the C ABI declared in include/stand.h.
+// Validates arguments, owns the device state of a handle and launches the kernels of
+// kernels.hpp.  No CPU fallback exists: every step of the path runs in the HIP kernels.
+#include "../../include/stand.h"
+#include "kernels.hpp"
+
+#include <algorithm>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+using namespace stand;
+
+struct stand_handle {
+    stand_config cfg;
+    int N, D, K, B, V, W, NO, slot_bytes;
+    float c;
+    int last_hip;
+    std::vector<int32_t> parent, depth, nchild, first_child, level_start;
+    int32_t *d_tree;  // parent | depth | nchild | first_child | level_start
+    char *table;
+    int32_t *ctx_tail;
+    long long *ctx_len;
+    int32_t *draft_tok, *draft_has, *draft_qid;
+    float *draft_qmu;
+    float *row_m, *row_s, *top_l, *top_p;
+    int32_t *top_idx, *outcome;
+    int32_t *obs_idx;
+    float *obs_p;
+    long long *rec_slot;
+    unsigned long long *stats;
+    unsigned long long *counter;
+    bool table_used;
+};
+
+#define HIP_TRY(h, expr)                                   \
+    do {                                                   \
+        hipError_t e_ = (expr);                            \
+        if (e_ != hipSuccess) {                            \
+            if (h) (h)->last_hip = (int)e_;                \
+            return STAND_EHIP;                             \
+        }                                                  \
+    } while (0)
+
+static TreeDev tree_dev(const stand_handle *h)
+{
+    TreeDev t;
+    t.parent = h->d_tree;
+    t.depth = h->d_tree + h->N;
+    t.nchild = h->d_tree + 2 * h->N;
+    t.first_child = h->d_tree + 3 * h->N;
+    t.level_start = h->d_tree + 4 * h->N;
+    t.N = h->N;
+    t.D = h->D;
+    return t;
+}
+
+template <typename T>
+static hipError_t dmalloc(T **p, size_t n)
+{
+    return hipMalloc((void **)p, n * sizeof(T) ? n * sizeof(T) : sizeof(T));
+}
+
+static void free_all(stand_handle *h)
+{
+    if (!h) return;
+    void *ptrs[] = {h->d_tree, h->table, h->ctx_tail, h->ctx_len, h->draft_tok, h->draft_has, h->draft_qid, h->draft_qmu,
+                    h->row_m, h->row_s, h->top_l, h->top_p, h->top_idx, h->outcome, h->obs_idx, h->obs_p, h->rec_slot,
+                    h->stats, h->counter};
+    for (void *p : ptrs) (void)hipFree(p);
+    delete h;
+}
+
+extern "C" int stand_create(const stand_config *cfg, stand_handle **out)
+{
+    if (!cfg || !out || !cfg->tree_parent) return STAND_EINVAL;
+    *out = nullptr;
+    const int N = cfg->tree_nodes, K = cfg->topk;
+    if (K < 1 || K > STAND_MAX_TOPK) return STAND_EINVAL;
+    if (cfg->vocab < K || cfg->vocab < 2 || cfg->vocab >= (1 << 22)) return STAND_EINVAL;
+    if (cfg->max_batch < 1 || cfg->max_batch >= (1 << 20)) return STAND_EINVAL;
+    if (cfg->order_min < 1 || cfg->order_max < cfg->order_min || cfg->order_max > STAND_MAX_ORDER) return STAND_EINVAL;
+    if (N < 1 || N > STAND_MAX_NODES) return STAND_EINVAL;
+    if (!(cfg->temperature > 0.0f) || !(cfg->temperature < 1e6f)) return STAND_EINVAL;
+    if (cfg->table_capacity < 16 || (cfg->table_capacity & (cfg->table_capacity - 1))) return STAND_EINVAL;
+    if (cfg->max_probe < 1) return STAND_EINVAL;
+    if (cfg->logits_dtype != STAND_BF16 && cfg->logits_dtype != STAND_F32) return STAND_EINVAL;
+    if (cfg->update_mode != STAND_UPDATE_ACCEPTED_PATH) return STAND_EINVAL;
+    if ((int64_t)cfg->max_batch * N * (int64_t)cfg->vocab >= ((int64_t)1 << 40)) return STAND_EINVAL;
+    int ndev = 0;
+    if (hipGetDeviceCount(&ndev) != hipSuccess || cfg->device < 0 || cfg->device >= ndev) return STAND_EINVAL;
+
+    stand_handle *h = new (std::nothrow) stand_handle();
+    if (!h) return STAND_ENOMEM;
+    h->cfg = *cfg;
+    h->N = N; h->K = K; h->B = cfg->max_batch; h->V = cfg->vocab;
+    h->NO = cfg->order_max - cfg->order_min + 1;
+    h->slot_bytes = 16 + 8 * K;
+    h->c = (float)(1.4426950408889634 / (double)cfg->temperature);
+    h->last_hip = 0;
+    h->table_used = false;
+
+    // tree: breadth-first numbering with contiguous siblings <=> parents non-decreasing
+    h->parent.assign(cfg->tree_parent, cfg->tree_parent + N);
+    h->depth.assign(N, 0); h->nchild.assign(N, 0); h->first_child.assign(N, -1);
+    bool ok = h->parent[0] == -1;
+    for (int u = 1; ok && u < N; ++u) {
+        const int p = h->parent[u];
+        ok = p >= 0 && p < u && (u == 1 || p >= h->parent[u - 1]);
+        if (!ok) break;
+        h->depth[u] = h->depth[p] + 1;
+        if (h->nchild[p] == 0) h->first_child[p] = u;
+        h->nchild[p]++;
+    }
+    h->D = 0;
+    for (int u = 0; ok && u < N; ++u) {
+        h->D = std::max(h->D, h->depth[u]);
+        if (h->nchild[u] > K) ok = false;
+    }
+    if (!ok || h->D > STAND_MAX_DEPTH) { delete h; return STAND_EINVAL; }
+    h->cfg.tree_parent = nullptr;
+    h->W = h->D + 1;
+    h->level_start.assign(h->D + 2, N);
+    for (int u = N - 1; u >= 0; --u) h->level_start[h->depth[u]] = u;
+
+    if (hipSetDevice(cfg->device) != hipSuccess) { delete h; return STAND_EHIP; }
+    const size_t B = h->B, rows = B * N;
+    const size_t nrec = B * h->W * h->NO;
+    hipError_t e = hipSuccess;
+    auto acc = [&](hipError_t x) { if (e == hipSuccess) e = x; };
+    acc(dmalloc(&h->d_tree, 4 * (size_t)N + h->D + 2));
+    acc(hipMalloc((void **)&h->table, (size_t)cfg->table_capacity * h->slot_bytes));
+    acc(dmalloc(&h->ctx_tail, B * kMaxOrder));
+    acc(dmalloc(&h->ctx_len, B));
+    acc(dmalloc(&h->draft_tok, rows)); acc(dmalloc(&h->draft_has, rows));
+    acc(dmalloc(&h->draft_qid, rows * K)); acc(dmalloc(&h->draft_qmu, rows * K));
+    acc(dmalloc(&h->row_m, rows)); acc(dmalloc(&h->row_s, rows));
+    acc(dmalloc(&h->top_l, rows * K)); acc(dmalloc(&h->top_p, rows * K)); acc(dmalloc(&h->top_idx, rows * K));
+    acc(dmalloc(&h->outcome, rows));
+    acc(dmalloc(&h->obs_idx, B * h->W * K)); acc(dmalloc(&h->obs_p, B * h->W * K));
+    acc(dmalloc(&h->rec_slot, nrec));
+    acc(dmalloc(&h->stats, (size_t)kStatCount));
+    acc(dmalloc(&h->counter, 1));
+    if (e != hipSuccess) { free_all(h); return e == hipErrorOutOfMemory ? STAND_ENOMEM : STAND_EHIP; }
+
+    std::vector<int32_t> tree(4 * (size_t)N + h->D + 2);
+    std::copy(h->parent.begin(), h->parent.end(), tree.begin());
+    std::copy(h->depth.begin(), h->depth.end(), tree.begin() + N);
+    std::copy(h->nchild.begin(), h->nchild.end(), tree.begin() + 2 * N);
+    std::copy(h->first_child.begin(), h->first_child.end(), tree.begin() + 3 * N);
+    std::copy(h->level_start.begin(), h->level_start.end(), tree.begin() + 4 * N);
+    acc(hipMemcpy(h->d_tree, tree.data(), tree.size() * sizeof(int32_t), hipMemcpyHostToDevice));
+    acc(hipMemset(h->table, 0, (size_t)cfg->table_capacity * h->slot_bytes));
+    acc(hipMemset(h->ctx_tail, 0, B * kMaxOrder * sizeof(int32_t)));
+    acc(hipMemset(h->ctx_len, 0, B * sizeof(long long)));
+    acc(hipMemset(h->draft_tok, 0xFF, rows * sizeof(int32_t)));
+    acc(hipMemset(h->draft_has, 0, rows * sizeof(int32_t)));
+    acc(hipMemset(h->draft_qid, 0, rows * K * sizeof(int32_t)));
+    acc(hipMemset(h->draft_qmu, 0, rows * K * sizeof(float)));
+    acc(hipMemset(h->outcome, 0xFF, rows * sizeof(int32_t)));
+    acc(hipMemset(h->row_m, 0, rows * sizeof(float))); acc(hipMemset(h->row_s, 0, rows * sizeof(float)));
+    acc(hipMemset(h->top_l, 0, rows * K * sizeof(float))); acc(hipMemset(h->top_p, 0, rows * K * sizeof(float)));
+    acc(hipMemset(h->top_idx, 0, rows * K * sizeof(int32_t)));
+    acc(hipMemset(h->stats, 0, kStatCount * sizeof(unsigned long long)));
+    acc(hipDeviceSynchronize());
+    if (e != hipSuccess) { free_all(h); return STAND_EHIP; }
+    *out = h;
+    return STAND_OK;
+}
+
+extern "C" int stand_destroy(stand_handle *h)
+{
+    if (!h) return STAND_EINVAL;
+    (void)hipSetDevice(h->cfg.device);
+    (void)hipDeviceSynchronize();
+    free_all(h);
+    return STAND_OK;
+}
+
+extern "C" int stand_depth(const stand_handle *h) { return h ? h->D : STAND_EINVAL; }
+
+static int drop_drafts(stand_handle *h, int b0, int nb, hipStream_t s)
+{
+    const size_t n = (size_t)nb * h->N;
+    fill_i32_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s>>>(h->draft_tok + (size_t)b0 * h->N, -1, n);
+    fill_i32_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s>>>(h->draft_has + (size_t)b0 * h->N, 0, n);
+    HIP_TRY(h, hipGetLastError());
+    return STAND_OK;
+}
+
+extern "C" int stand_set_context(stand_handle *h, int32_t b, const int32_t *host_tokens, int32_t n, void *stream)
+{
+    if (!h || b < 0 || b >= h->B || n < 0 || (n > 0 && !host_tokens)) return STAND_EINVAL;
+    hipStream_t s = (hipStream_t)stream;
+    HIP_TRY(h, hipSetDevice(h->cfg.device));
+    int32_t tail[kMaxOrder] = {0};
+    for (int i = 0; i < kMaxOrder && i < n; ++i) tail[kMaxOrder - 1 - i] = host_tokens[n - 1 - i];
+    long long len = n;
+    HIP_TRY(h, hipMemcpyAsync(h->ctx_tail + (size_t)b * kMaxOrder, tail, sizeof(tail), hipMemcpyHostToDevice, s));
+    HIP_TRY(h, hipMemcpyAsync(h->ctx_len + b, &len, sizeof(len), hipMemcpyHostToDevice, s));
+    int rc = drop_drafts(h, b, 1, s);
+    if (rc) return rc;
+    HIP_TRY(h, hipStreamSynchronize(s));
+    return STAND_OK;
+}
+
+extern "C" int stand_reorder(stand_handle *h, const int32_t *host_src_of, void *stream)
+{
+    if (!h || !host_src_of) return STAND_EINVAL;
+    for (int b = 0; b < h->B; ++b) if (host_src_of[b] < 0 || host_src_of[b] >= h->B) return STAND_EINVAL;
+    hipStream_t s = (hipStream_t)stream;
+    HIP_TRY(h, hipSetDevice(h->cfg.device));
+    std::vector<int32_t> tail((size_t)h->B * kMaxOrder), tail2((size_t)h->B * kMaxOrder);
+    std::vector<long long> len(h->B), len2(h->B);
+    HIP_TRY(h, hipMemcpyAsync(tail.data(), h->ctx_tail, tail.size() * sizeof(int32_t), hipMemcpyDeviceToHost, s));
+    HIP_TRY(h, hipMemcpyAsync(len.data(), h->ctx_len, len.size() * sizeof(long long), hipMemcpyDeviceToHost, s));
+    HIP_TRY(h, hipStreamSynchronize(s));
+    for (int b = 0; b < h->B; ++b) {
+        std::copy(tail.begin() + (size_t)host_src_of[b] * kMaxOrder, tail.begin() + (size_t)(host_src_of[b] + 1) * kMaxOrder,
+                  tail2.begin() + (size_t)b * kMaxOrder);
+        len2[b] = len[host_src_of[b]];
+    }
+    HIP_TRY(h, hipMemcpyAsync(h->ctx_tail, tail2.data(), tail2.size() * sizeof(int32_t), hipMemcpyHostToDevice, s));
+    HIP_TRY(h, hipMemcpyAsync(h->ctx_len, len2.data(), len2.size() * sizeof(long long), hipMemcpyHostToDevice, s));
+    int rc = drop_drafts(h, 0, h->B, s);
+    if (rc) return rc;
+    HIP_TRY(h, hipStreamSynchronize(s));
+    return STAND_OK;
+}
+
+// ---- launches ----------------------------------------------------------------------------------
+static int launch_row_pass(stand_handle *h, uint64_t step, const void *d_logits, hipStream_t s)
+{
+    RowPassArgs a;
+    a.logits = d_logits; a.B = h->B; a.N = h->N; a.V = h->V; a.K = h->K; a.c = h->c;
+    a.seed = h->cfg.seed; a.step = step; a.tree = tree_dev(h);
+    a.draft_tok = h->draft_tok; a.draft_has = h->draft_has; a.draft_qid = h->draft_qid; a.draft_qmu = h->draft_qmu;
+    a.row_m = h->row_m; a.row_s = h->row_s; a.top_idx = h->top_idx; a.top_l = h->top_l; a.top_p = h->top_p;
+    a.outcome = h->outcome; a.stats = h->stats;
+    const dim3 grid((unsigned)(h->B * h->N)), block(kRowThreads);
+    if (h->cfg.logits_dtype == STAND_BF16) row_pass_kernel<kDtBf16><<<grid, block, 0, s>>>(a);
+    else row_pass_kernel<kDtF32><<<grid, block, 0, s>>>(a);
+    HIP_TRY(h, hipGetLastError());
+    return STAND_OK;
+}
+
+static int launch_path_pass(stand_handle *h, uint64_t step, const void *d_logits, int mode, const int32_t *commit_row,
+                            const int32_t *commit_len, int32_t *out_tok, int32_t *out_node, int32_t *out_len, hipStream_t s)
+{
+    PathPassArgs a;
+    a.logits = d_logits; a.B = h->B; a.N = h->N; a.V = h->V; a.K = h->K; a.W = h->W; a.mode = mode; a.c = h->c;
+    a.seed = h->cfg.seed; a.step = step; a.tree = tree_dev(h);
+    a.draft_tok = h->draft_tok; a.draft_has = h->draft_has; a.draft_qid = h->draft_qid; a.draft_qmu = h->draft_qmu;
+    a.row_m = h->row_m; a.top_idx = h->top_idx; a.top_l = h->top_l; a.outcome = h->outcome;
+    a.commit_row = commit_row; a.commit_len = commit_len;
+    a.out_tok = out_tok; a.out_node = out_node; a.out_len = out_len;
+    a.obs_idx = h->obs_idx; a.obs_p = h->obs_p; a.stats = h->stats;
+    const dim3 grid((unsigned)h->W, (unsigned)h->B), block(kPathThreads);
+    if (h->cfg.logits_dtype == STAND_BF16) path_pass_kernel<kDtBf16><<<grid, block, 0, s>>>(a);
+    else path_pass_kernel<kDtF32><<<grid, block, 0, s>>>(a);
+    HIP_TRY(h, hipGetLastError());
+    return STAND_OK;
+}
+
+static int launch_merge(stand_handle *h, const int32_t *commit_tok, const int32_t *commit_row, const int32_t *commit_len,
+                        hipStream_t s)
+{
+    MergeArgs a;
+    a.table = h->table; a.mask = h->cfg.table_capacity - 1; a.slot_bytes = h->slot_bytes; a.K = h->K;
+    a.max_probe = h->cfg.max_probe; a.B = h->B; a.W = h->W; a.omin = h->cfg.order_min; a.omax = h->cfg.order_max;
+    a.ctx_tail = h->ctx_tail; a.ctx_len = h->ctx_len; a.commit_tok = commit_tok; a.commit_row = commit_row;
+    a.commit_len = commit_len; a.N = h->N; a.rec_slot = h->rec_slot; a.obs_idx = h->obs_idx; a.obs_p = h->obs_p;
+    a.stats = h->stats;
+    const int nrec = h->B * h->W * h->NO;
+    merge_claim_kernel<<<dim3((unsigned)((nrec + 255) / 256)), dim3(256), 0, s>>>(a);
+    merge_apply_kernel<<<dim3((unsigned)nrec), dim3(64), 0, s>>>(a);
+    ctx_append_kernel<<<dim3((unsigned)((h->B + 63) / 64)), dim3(64), 0, s>>>(h->B, h->W, h->ctx_tail, h->ctx_len, commit_tok,
+                                                                            commit_len);
+    HIP_TRY(h, hipGetLastError());
+    h->table_used = true;
+    return STAND_OK;
+}
+
+static int launch_draft(stand_handle *h, uint64_t step, int32_t *d_draft_tok, hipStream_t s)
+{
+    DraftArgs a;
+    a.table = h->table; a.mask = h->cfg.table_capacity - 1; a.slot_bytes = h->slot_bytes; a.K = h->K;
+    a.max_probe = h->cfg.max_probe; a.B = h->B; a.omin = h->cfg.order_min; a.omax = h->cfg.order_max;
+    a.seed = h->cfg.seed; a.step = step; a.tree = tree_dev(h);
+    a.ctx_tail = h->ctx_tail; a.ctx_len = h->ctx_len;
+    a.draft_tok = h->draft_tok; a.draft_has = h->draft_has; a.draft_qid = h->draft_qid; a.draft_qmu = h->draft_qmu;
+    a.out_tok = d_draft_tok; a.stats = h->stats;
+    draft_kernel<<<dim3((unsigned)h->B), dim3(kDraftThreads), 0, s>>>(a);
+    HIP_TRY(h, hipGetLastError());
+    return STAND_OK;
+}
+
+extern "C" int stand_update(stand_handle *h, uint64_t step, const void *d_logits, const int32_t *d_commit_tok,
+                            const int32_t *d_commit_row, const int32_t *d_commit_len, void *stream)
+{
+    if (!h || !d_logits || !d_commit_tok || !d_commit_row || !d_commit_len) return STAND_EINVAL;
+    hipStream_t s = (hipStream_t)stream;
+    HIP_TRY(h, hipSetDevice(h->cfg.device));
+    int rc = launch_path_pass(h, step, d_logits, 1, d_commit_row, d_commit_len, nullptr, nullptr, nullptr, s);
+    if (rc) return rc;
+    return launch_merge(h, d_commit_tok, d_commit_row, d_commit_len, s);
+}
+
+extern "C" int stand_draft(stand_handle *h, uint64_t step, int32_t *d_draft_tok, void *stream)
+{
+    if (!h) return STAND_EINVAL;
+    HIP_TRY(h, hipSetDevice(h->cfg.device));
+    return launch_draft(h, step, d_draft_tok, (hipStream_t)stream);
+}
+
+extern "C" int stand_verify(stand_handle *h, uint64_t step, const void *d_logits, int32_t *d_out_tok, int32_t *d_out_node,
+                            int32_t *d_out_len, void *stream)
+{
+    if (!h || !d_logits || !d_out_tok || !d_out_node || !d_out_len) return STAND_EINVAL;
+    hipStream_t s = (hipStream_t)stream;
+    HIP_TRY(h, hipSetDevice(h->cfg.device));
+    int rc = launch_row_pass(h, step, d_logits, s);
+    if (rc) return rc;
+    return launch_path_pass(h, step, d_logits, 0, nullptr, nullptr, d_out_tok, d_out_node, d_out_len, s);
+}
+
+extern "C" int stand_step(stand_handle *h, uint64_t step, const void *d_logits, int32_t *d_out_tok, int32_t *d_out_node,
+                          int32_t *d_out_len, int32_t *d_next_draft_tok, const int32_t *d_force_tok, void *stream)
+{
+    if (!h || !d_logits || !d_out_tok || !d_out_node || !d_out_len) return STAND_EINVAL;
+    hipStream_t s = (hipStream_t)stream;
+    HIP_TRY(h, hipSetDevice(h->cfg.device));
+    int rc = launch_row_pass(h, step, d_logits, s);
+    if (rc) return rc;
+    rc = launch_path_pass(h, step, d_logits, 0, nullptr, nullptr, d_out_tok, d_out_node, d_out_len, s);
+    if (rc) return rc;
+    rc = launch_merge(h, d_force_tok ? d_force_tok : d_out_tok, nullptr, d_out_len, s);
+    if (rc) return rc;
+    return launch_draft(h, step + 1, d_next_draft_tok, s);
+}
+
+extern "C" int stand_row_results(stand_handle *h, float *d_row_max, float *d_row_sum, int32_t *d_top_idx, float *d_top_p,
+                                 void *stream)
+{
+    if (!h) return STAND_EINVAL;
+    HIP_TRY(h, hipSetDevice(h->cfg.device));
+    const size_t n = (size_t)h->B * h->N * h->K;
+    copy_row_results_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, (hipStream_t)stream>>>(
+        h->B * h->N, h->K, h->row_m, h->row_s, h->top_idx, h->top_p, d_row_max, d_row_sum, d_top_idx, d_top_p);
+    HIP_TRY(h, hipGetLastError());
+    return STAND_OK;
+}
+
+extern "C" int stand_table_export(stand_handle *h, void *host_buf, uint64_t *inout_bytes)
+{
+    if (!h || !inout_bytes) return STAND_EINVAL;
+    HIP_TRY(h, hipSetDevice(h->cfg.device));
+    HIP_TRY(h, hipDeviceSynchronize());
+    const uint64_t cap = h->cfg.table_capacity;
+    const unsigned blocks = (unsigned)((cap + 255) / 256);
+    unsigned long long n = 0;
+    HIP_TRY(h, hipMemset(h->counter, 0, sizeof(unsigned long long)));
+    table_compact_kernel<<<dim3(blocks), dim3(256)>>>(h->table, cap, h->slot_bytes, h->counter, nullptr, 0);
+    HIP_TRY(h, hipGetLastError());
+    HIP_TRY(h, hipMemcpy(&n, h->counter, sizeof(n), hipMemcpyDeviceToHost));
+    const uint64_t need = n * (uint64_t)h->slot_bytes;
+    const uint64_t have = *inout_bytes;
+    *inout_bytes = need;
+    if (!host_buf) return STAND_OK;
+    if (have < need) return STAND_EINVAL;
+    if (n == 0) return STAND_OK;
+    char *dbuf = nullptr;
+    HIP_TRY(h, hipMalloc((void **)&dbuf, need));
+    hipError_t e = hipMemset(h->counter, 0, sizeof(unsigned long long));
+    if (e == hipSuccess) {
+        table_compact_kernel<<<dim3(blocks), dim3(256)>>>(h->table, cap, h->slot_bytes, h->counter, dbuf, n);
+        e = hipGetLastError();
+    }
+    std::vector<char> tmp(need);
+    if (e == hipSuccess) e = hipMemcpy(tmp.data(), dbuf, need, hipMemcpyDeviceToHost);
+    (void)hipFree(dbuf);
+    HIP_TRY(h, e);
+    std::vector<uint64_t> order(n);
+    for (uint64_t i = 0; i < n; ++i) order[i] = i;
+    const int sb = h->slot_bytes;
+    std::sort(order.begin(), order.end(), [&](uint64_t x, uint64_t y) {
+        uint64_t fx, fy;
+        memcpy(&fx, tmp.data() + x * sb, 8);
+        memcpy(&fy, tmp.data() + y * sb, 8);
+        return fx < fy;
+    });
+    for (uint64_t i = 0; i < n; ++i) memcpy((char *)host_buf + i * sb, tmp.data() + order[i] * sb, sb);
+    return STAND_OK;
+}
+
+extern "C" int stand_table_import(stand_handle *h, const void *host_buf, uint64_t bytes)
+{
+    if (!h || (!host_buf && bytes) || bytes % (uint64_t)h->slot_bytes) return STAND_EINVAL;
+    if (h->table_used) return STAND_ESTATE;
+    HIP_TRY(h, hipSetDevice(h->cfg.device));
+    const uint64_t n = bytes / h->slot_bytes, cap = h->cfg.table_capacity, mask = cap - 1;
+    const int sb = h->slot_bytes, K = h->K;
+    if (n > cap) return STAND_EINVAL;
+    // place the entries on the host exactly as the device would (linear probing), then upload
+    std::vector<char> img;
+    try { img.assign((size_t)cap * sb, 0); } catch (...) { return STAND_ENOMEM; }
+    for (uint64_t i = 0; i < n; ++i) {
+        const char *src = (const char *)host_buf + i * sb;
+        uint64_t fp; uint32_t count, order;
+        memcpy(&fp, src, 8); memcpy(&count, src + 8, 4); memcpy(&order, src + 12, 4);
+        if (fp == 0 || count == 0 || order < 1 || order > STAND_MAX_ORDER) return STAND_EINVAL;
+        for (int q = 0; q < K; ++q) {
+            int32_t id; memcpy(&id, src + 16 + 4 * q, 4);
+            if (id < 0 || id >= h->V) return STAND_EINVAL;
+        }
+        bool placed = false;
+        for (int p = 0; p < h->cfg.max_probe && !placed; ++p) {
+            char *dst = img.data() + ((fp + (uint64_t)p) & mask) * sb;
+            uint64_t cur; memcpy(&cur, dst, 8);
+            if (cur == fp) return STAND_EINVAL;  // duplicate key
+            if (cur == 0) { memcpy(dst, src, sb); placed = true; }
+        }
+        if (!placed) return STAND_EINVAL;
+    }
+    HIP_TRY(h, hipMemcpy(h->table, img.data(), img.size(), hipMemcpyHostToDevice));
+    h->table_used = true;
+    return STAND_OK;
+}
+
+extern "C" int stand_get_context(stand_handle *h, int32_t b, int32_t *host_tail, int32_t n, int64_t *len_out, void *stream)
+{
+    if (!h || b < 0 || b >= h->B || n < 0 || n > kMaxOrder || (n > 0 && !host_tail)) return STAND_EINVAL;
+    hipStream_t s = (hipStream_t)stream;
+    HIP_TRY(h, hipSetDevice(h->cfg.device));
+    int32_t tail[kMaxOrder];
+    long long len = 0;
+    HIP_TRY(h, hipMemcpyAsync(tail, h->ctx_tail + (size_t)b * kMaxOrder, sizeof(tail), hipMemcpyDeviceToHost, s));
+    HIP_TRY(h, hipMemcpyAsync(&len, h->ctx_len + b, sizeof(len), hipMemcpyDeviceToHost, s));
+    HIP_TRY(h, hipStreamSynchronize(s));
+    for (int i = 0; i < n; ++i) host_tail[i] = tail[kMaxOrder - n + i];
+    if (len_out) *len_out = len;
+    return STAND_OK;
+}
+
+extern "C" int stand_get_stats(stand_handle *h, stand_stats *out)
+{
+    if (!h || !out) return STAND_EINVAL;
+    HIP_TRY(h, hipSetDevice(h->cfg.device));
+    HIP_TRY(h, hipDeviceSynchronize());
+    unsigned long long st[kStatCount];
+    HIP_TRY(h, hipMemcpy(st, h->stats, sizeof(st), hipMemcpyDeviceToHost));
+    memset(out, 0, sizeof(*out));
+    for (int n = 0; n <= STAND_MAX_ORDER; ++n) out->hits[n] = st[kStatHits + n];
+    out->misses = st[kStatMisses]; out->inserts = st[kStatInserts]; out->merges = st[kStatMerges];
+    out->drops = st[kStatDrops]; out->near_threshold = st[kStatNear]; out->tokens_emitted = st[kStatTokens];
+    out->accept_tests = st[kStatTests]; out->filter_mismatch = st[kStatMismatch];
+    return STAND_OK;
+}
+
+extern "C" const char *stand_strerror(int code)
+{
+    switch (code) {
+    case STAND_OK: return "ok";
+    case STAND_EINVAL: return "invalid argument or configuration";
+    case STAND_ENOMEM: return "out of memory";
+    case STAND_EHIP: return "HIP runtime error (see stand_last_hip_error)";
+    case STAND_ESTATE: return "call not allowed in this state";
+    default: return "unknown error";
+    }
+}
+
+extern "C" int stand_last_hip_error(const stand_handle *h) { return h ? h->last_hip : 0; }

@@ -255,6 +255,7 @@ class Workload:
         self.cfg = cfg
         self.B, self.V, self.N, self.D, self.K = cfg["B"], cfg["V"], cfg["N"], cfg["D"], cfg["K"]
         self.dtype, self.T, self.seed = cfg["dtype"], cfg["T"], cfg["seed"]
+        self.W = self.D + 1
         self.parent = make_tree(cfg["N"], cfg["D"], cfg["caps"])
         self.depth, self.nchild, self.first_child, dmax = tree_info(self.parent)
         assert dmax == self.D

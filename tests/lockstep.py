@@ -1,0 +1,138 @@
+"""Lock-step parity runner: drives libstand (GPU, through the C ABI binding) and the CPU oracle
+with the same seeded inputs and compares every output of every step.
+
+Bars (BASELINE the benchmark spec): token ids, tree nodes, lengths, table fingerprints, counts and ids
+bit-exact; stored probabilities bit-exact as well (both sides follow one numeric contract);
+the row pass's fast per-row probabilities within 1e-5 relative of the oracle's.
+"""
+import numpy as np
+import torch
+
+import oracle
+from paper_2506_04708_amd import binding, synth
+
+
+def _logits_to_device(lg, dtype):
+    t = torch.from_numpy(lg.view(np.int16) if dtype == "bf16" else lg)
+    t = t.cuda()
+    return t.view(torch.bfloat16) if dtype == "bf16" else t
+
+
+def make_pair(w, capacity, max_probe=64, seed=None, order_min=None, order_max=None):
+    cfg = w.cfg
+    seed = cfg["seed"] ^ 0xABCDEF if seed is None else seed
+    omin = cfg["order_min"] if order_min is None else order_min
+    omax = cfg["order_max"] if order_max is None else order_max
+    dt_o = oracle.DT_F32 if w.dtype == "f32" else oracle.DT_BF16
+    dt_g = binding.STAND_F32 if w.dtype == "f32" else binding.STAND_BF16
+    o = oracle.Oracle(w.V, w.B, omin, omax, w.K, w.parent, w.T, capacity, max_probe, seed, dt_o)
+    g = binding.Stand(w.V, w.B, omin, omax, w.K, w.parent, w.T, capacity, max_probe, seed, dt_g)
+    return o, g
+
+
+def compare_tables(o, g, K):
+    to = o.table_export()
+    tg = oracle.parse_table_export(g.table_export(), K)
+    assert len(to) == len(tg), "table sizes differ: oracle %d gpu %d" % (len(to), len(tg))
+    assert np.array_equal(to["fp"], tg["fp"]), "key fingerprints differ"
+    assert np.array_equal(to["count"], tg["count"]), "counts differ"
+    assert np.array_equal(to["order"], tg["order"]), "orders differ"
+    assert np.array_equal(to["ids"], tg["ids"]), "stored ids differ"
+    assert np.array_equal(to["mu"].view(np.uint32), tg["mu"].view(np.uint32)), "stored probabilities differ"
+    return len(to)
+
+
+def compare_rows(o_logits, w, g, rows=None, rtol=1e-5):
+    """Row-pass results of the GPU against the oracle for the given flat row indices (default: all)."""
+    m, s, idx, p = (t.cpu().numpy() for t in g.row_results())
+    flat = o_logits.reshape(w.B * w.N, w.V)
+    rows = range(w.B * w.N) if rows is None else rows
+    worst = 0.0
+    for r in rows:
+        oi, op, om, os_ = oracle.row_obs(flat[r], w.T, w.K)
+        assert np.array_equal(idx[r], oi), "row %d: top-k ids differ" % r
+        assert m[r] == om or (m[r] == 0 and om == 0), "row %d: max differs" % r
+        nz = op > 0
+        rel = np.abs(p[r][nz] / op[nz] - 1).max() if nz.any() else 0.0
+        rel = max(rel, abs(s[r] / os_ - 1))
+        worst = max(worst, rel)
+        assert rel < rtol, "row %d: probabilities differ by %g" % (r, rel)
+    return worst
+
+
+def run_lockstep(w, steps, mode="separate", capacity=1 << 12, check_rows=True, table_every=1, forced=True,
+                 max_probe=64, verbose=False):
+    """mode "separate": stand_verify / stand_update / stand_draft; mode "step": stand_step.
+    forced=True commits the workload's stream tokens (open-loop replay); False commits what was emitted."""
+    o, g = make_pair(w, capacity, max_probe)
+    for b in range(w.B):
+        o.set_context(b, w.prompt(b))
+        g.set_context(b, w.prompt(b))
+    out_tok, out_node, out_len, d_draft = g.new_outputs()
+    od = o.draft(0)
+    g.draft(0, d_draft)
+    torch.cuda.synchronize()
+    assert np.array_equal(d_draft.cpu().numpy(), od), "draft 0 differs"
+    info = dict(emitted=0, len_hist=np.zeros(w.W + 1, int), worst_rel=0.0, entries=0)
+    for step in range(steps):
+        lg = w.logits(step, od)
+        dl = _logits_to_device(lg, w.dtype)
+        otok, onode, olen = o.verify(step, lg)
+        W = w.W if hasattr(w, "W") else w.D + 1
+        if forced:
+            # the stream's next W tokens; the first out_len[b] of them are committed
+            force = np.full((w.B, W), -1, np.int32)
+            for b in range(w.B):
+                nxt = w.streams[b, w.pos[b] + 1: w.pos[b] + 1 + W]
+                force[b, : len(nxt)] = nxt
+            commit = w.commit(olen)
+        else:
+            force = None
+            commit = otok.copy()
+        o.update(step, lg, commit, onode, olen)
+        od = o.draft(step + 1)
+        if mode == "step":
+            d_force = torch.from_numpy(force).cuda() if forced else None
+            g.step(step, dl, out_tok, out_node, out_len, d_draft, d_force)
+        else:
+            g.verify(step, dl, out_tok, out_node, out_len)
+            torch.cuda.synchronize()
+            glen = out_len.cpu().numpy()
+            if forced:
+                # commit tokens come from the stream, paced by the GPU's own lengths
+                gc = np.full((w.B, W), -1, np.int32)
+                for b in range(w.B):
+                    gc[b, : glen[b]] = force[b, : glen[b]]
+                d_commit = torch.from_numpy(gc).cuda()
+            else:
+                d_commit = out_tok.clone()
+            g.update(step, dl, d_commit, out_node, out_len)
+            g.draft(step + 1, d_draft)
+        torch.cuda.synchronize()
+        gt, gn, gl = out_tok.cpu().numpy(), out_node.cpu().numpy(), out_len.cpu().numpy()
+        assert np.array_equal(gl, olen), "step %d: accepted lengths differ %s vs %s" % (step, gl, olen)
+        assert np.array_equal(gn, onode), "step %d: accepted nodes differ" % step
+        assert np.array_equal(gt, otok), "step %d: emitted tokens differ\n%s\n%s" % (step, gt, otok)
+        if check_rows:
+            info["worst_rel"] = max(info["worst_rel"], compare_rows(lg, w, g))
+        assert np.array_equal(d_draft.cpu().numpy(), od), "step %d: next draft differs" % step
+        if table_every and (step % table_every == 0 or step == steps - 1):
+            info["entries"] = compare_tables(o, g, w.K)
+        for b in range(w.B):
+            tail, ln = g.get_context(b, 1)
+            assert ln == o.context_len(b) and tail[0] == o.context_tail(b, 1)[0]
+        info["emitted"] += int(olen.sum())
+        for l in olen:
+            info["len_hist"][l] += 1
+        if verbose:
+            print("step", step, "len", olen.tolist(), flush=True)
+    so, sg = o.stats(), g.stats()
+    assert list(so.hits) == list(sg.hits) and so.misses == sg.misses, "lookup statistics differ"
+    assert (so.inserts, so.merges, so.drops) == (sg.inserts, sg.merges, sg.drops), "update statistics differ"
+    assert so.tokens_emitted == sg.tokens_emitted and so.accept_tests == sg.accept_tests
+    assert sg.filter_mismatch == 0, "an accept decision changed under exact arithmetic"
+    info["near_oracle"], info["near_gpu"] = so.near_threshold, sg.near_threshold
+    info["fp_collisions"] = so.fp_collisions
+    o.close()
+    g.close()
+    return info
