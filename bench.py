@@ -1,0 +1,211 @@
+#!/usr/bin/env python3
+"""Benchmark of the STAND speculation step on one MI355X.
+
+A step = one stand_step call (verify the pending tree, merge the accepted path into the
+n-gram table, draft the next tree) over one batch of synthetic verify-pass logits
+[B x tree_nodes x V].  Workload: B=32, V=152064, 64-node tree, bf16 logits, K=16, orders 1-4,
+T=0.6, 2^22 table slots ("cfg3"), open-loop replay of seeded token streams with repeated spans.
+
+Procedure (all inputs are generated on the GPU before the timed region):
+  1. table warm-up: `--table-warm` untimed steps with logits generated on the fly;
+  2. record: the next warmup+steps steps are run once while their logits stay resident in HBM;
+  3. timed: a second handle that starts from a copy of the state reached after (1) replays the
+     recorded steps back to back; the wall clock around the last `--steps` of them is the
+     result, and its outputs must equal the recorded ones.
+Also printed: the row pass's achieved HBM bandwidth from HIP events recorded inside the
+library around that kernel (same timed region), and the CPU oracle timed on the first steps
+of the same workload on the host.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+
+
+def gen_logits(torch, w, step, draft_tok_host, gen):
+    """[B, N, V] bf16 logits on the GPU: N(0, 3) noise plus +8 on each row's peaked tokens."""
+    import numpy as np
+    peaks = w.peaks(step, draft_tok_host)                      # [B, N, 4] int64, -1 = none
+    x = torch.randn((w.B, w.N, w.V), generator=gen, device="cuda", dtype=torch.float32)
+    x.mul_(3.0 ** 0.5)
+    pk = torch.from_numpy(peaks).cuda()
+    add = torch.where(pk >= 0, torch.full(pk.shape, 8.0, device="cuda"), torch.zeros(pk.shape, device="cuda"))
+    x.scatter_add_(2, pk.clamp(min=0), add)
+    return x.to(torch.bfloat16).contiguous()
+
+
+def force_tokens(np, w):
+    f = np.full((w.B, w.W), -1, np.int32)
+    for b in range(w.B):
+        nxt = w.streams[b, w.pos[b] + 1: w.pos[b] + 1 + w.W]
+        f[b, : len(nxt)] = nxt
+    return f
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=48)
+    ap.add_argument("--warmup", type=int, default=8)
+    ap.add_argument("--table-warm", type=int, default=200)
+    ap.add_argument("--workload", default="cfg3")
+    ap.add_argument("--cpu-steps", type=int, default=3)
+    ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--no-events", action="store_true", help="do not time the row pass with HIP events")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU; every GPU box here has one, so --gpus %d is not run" % args.gpus,
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2506_04708_amd import binding, synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    K_steps, W_steps, T_warm = args.steps, args.warmup, args.table_warm
+    total = T_warm + W_steps + K_steps
+    cfg = synth.CONFIGS[args.workload]
+    w = synth.Workload(args.workload, run_steps=total + 2)
+    dt = binding.STAND_BF16 if w.dtype == "bf16" else binding.STAND_F32
+    assert w.dtype == "bf16"
+    mk = lambda: binding.Stand(w.V, w.B, cfg["order_min"], cfg["order_max"], w.K, w.parent, w.T, cfg["capacity"], 64,
+                               cfg["seed"], dt)
+    gen = torch.Generator(device="cuda").manual_seed(cfg["seed"] & 0x7FFFFFFF)
+    h1 = mk()
+    for b in range(w.B):
+        h1.set_context(b, w.prompt(b))
+    out_tok, out_node, out_len, draft = h1.new_outputs()
+    h1.draft(0, draft)
+    cpu_inputs = []           # host copies of the first steps for the oracle leg
+    lens = []
+    t0 = time.time()
+    # ---- 1. warm the table (untimed, logits generated on the fly) --------------------------------
+    for step in range(T_warm):
+        d_host = draft.cpu().numpy()
+        lg = gen_logits(torch, w, step, d_host, gen)
+        force = force_tokens(np, w)
+        if step < args.cpu_steps and not args.no_cpu:
+            cpu_inputs.append((lg.view(torch.int16).cpu().numpy().view(np.uint16), force.copy(), d_host.copy()))
+        h1.step(step, lg, out_tok, out_node, out_len, draft, torch.from_numpy(force).cuda())
+        ln = out_len.cpu().numpy()
+        if step < args.cpu_steps and not args.no_cpu:
+            cpu_inputs[-1] = cpu_inputs[-1] + (out_tok.cpu().numpy().copy(), ln.copy())
+        w.commit(ln)
+        lens.append(ln.mean())
+        del lg
+    # ---- state copy for the replay handle ---------------------------------------------------------
+    h2 = mk()
+    snapshot = h1.table_export()
+    entries0 = snapshot.shape[0] // (16 + 8 * w.K)
+    h2.table_import(snapshot)
+    for b in range(w.B):
+        tail, ln_ctx = h1.get_context(b, binding.MAX_ORDER)
+        h2.set_context(b, tail)
+    # ---- 2. record ------------------------------------------------------------------------------------
+    rec = []
+    for step in range(T_warm, total):
+        d_host = draft.cpu().numpy()
+        lg = gen_logits(torch, w, step, d_host, gen)
+        force = torch.from_numpy(force_tokens(np, w)).cuda()
+        h1.step(step, lg, out_tok, out_node, out_len, draft, force)
+        ln = out_len.cpu().numpy()
+        w.commit(ln)
+        lens.append(ln.mean())
+        rec.append((lg, force, out_tok.clone(), out_len.clone(), draft.clone()))
+    torch.cuda.synchronize()
+    prep_s = time.time() - t0
+    # ---- 3. timed replay ----------------------------------------------------------------------------------
+    o_tok = [torch.empty_like(out_tok) for _ in rec]
+    o_node = [torch.empty_like(out_node) for _ in rec]
+    o_len = [torch.empty_like(out_len) for _ in rec]
+    o_draft = [torch.empty_like(draft) for _ in rec]
+    h2.draft(T_warm, draft)
+    for i in range(W_steps):
+        lg, force, *_ = rec[i]
+        h2.step(T_warm + i, lg, o_tok[i], o_node[i], o_len[i], o_draft[i], force)
+    if not args.no_events:
+        h2.profile_begin(K_steps)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    for i in range(W_steps, W_steps + K_steps):
+        lg, force, *_ = rec[i]
+        h2.step(T_warm + i, lg, o_tok[i], o_node[i], o_len[i], o_draft[i], force)
+    torch.cuda.synchronize()
+    t2 = time.perf_counter()
+    row_ms, row_n = (0.0, 0) if args.no_events else h2.profile_end()
+    for i, (lg, force, r_tok, r_len, r_draft) in enumerate(rec):
+        assert torch.equal(o_len[i], r_len) and torch.equal(o_tok[i], r_tok) and torch.equal(o_draft[i], r_draft), \
+            "replay diverged from the recorded run at step %d" % i
+    st = h2.stats()
+    ms_per_step = (t2 - t1) * 1e3 / K_steps
+    steps_per_s = K_steps / (t2 - t1)
+
+    rows = w.B * w.N
+    logits_bytes = rows * w.V * 2
+    acc_len = float(np.mean(lens[T_warm:]))
+    # algorithmic bytes of a step: logits once + one re-read of the stop row per trajectory
+    # + row outputs + table traffic of the merges and probes + draft / verify state
+    step_bytes = logits_bytes + w.B * w.V * 2 + rows * (8 + 12 * w.K) + 1_200_000 + 500_000
+    row_bytes = logits_bytes + rows * (8 + 12 * w.K)
+    roof = None
+    if row_n:
+        row_us = row_ms * 1e3 / row_n
+        achieved = row_bytes / (row_us * 1e-6) / 1e9
+        roof = {"bound": "hbm", "kernel": "row_pass_kernel", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
+                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
+                "avg_launch_us": round(row_us, 2), "bytes_per_launch": row_bytes}
+
+    cpu = None
+    if not args.no_cpu and cpu_inputs:
+        import oracle
+        o = oracle.Oracle(w.V, w.B, cfg["order_min"], cfg["order_max"], w.K, w.parent, w.T, cfg["capacity"], 64,
+                          cfg["seed"], oracle.DT_BF16)
+        w0 = synth.Workload(args.workload, run_steps=total + 2)
+        for b in range(w.B):
+            o.set_context(b, w0.prompt(b))
+        od = o.draft(0)
+        tc = 0.0
+        for step, (lg, force, d_host, g_tok, g_len) in enumerate(cpu_inputs):
+            assert np.array_equal(od, d_host), "oracle and GPU drafts differ at step %d" % step
+            c0 = time.perf_counter()
+            otok, onode, olen = o.verify(step, lg)
+            commit = np.full_like(force, -1)
+            for b in range(w.B):
+                commit[b, : olen[b]] = force[b, : olen[b]]
+            o.update(step, lg, commit, onode, olen)
+            od = o.draft(step + 1)
+            tc += time.perf_counter() - c0
+            assert np.array_equal(olen, g_len) and np.array_equal(otok, g_tok), "oracle and GPU outputs differ"
+        cpu = {"value": round(len(cpu_inputs) / tc, 4), "unit": "steps/s", "cores": 1, "kind": "oracle",
+               "sample": "first %d steps of the same workload (cold table); the oracle evaluates only the rows its "
+                         "walk visits, the GPU all %d rows; outputs checked equal" % (len(cpu_inputs), rows)}
+
+    out = {
+        "metric": "speculation steps/s (stand_step: verify + table merge + draft), B=32, V=152064, 64-node tree",
+        "value": round(steps_per_s, 2), "unit": "steps/s", "n_gpus": 1, "steps": K_steps, "warmup": W_steps,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32 arithmetic on bf16 logits", "data": "synthetic",
+        "config": {"workload": "cfg3: B=32 trajectories sharing one table, V=152064, bf16 logits, 64-node tree (depth 8), "
+                               "orders 1-4, K=16, T=0.6, 2^22 slots; open-loop replay of seeded streams, table warmed "
+                               "for %d steps" % T_warm,
+                   "acceptance_len": round(acc_len, 3), "table_entries": int(entries0 + st.inserts)},
+        "hbm_gbps_algorithmic": round(step_bytes * steps_per_s / 1e9, 1),
+        "hbm_frac_of_peak": round(step_bytes * steps_per_s / 1e9 / HBM_PEAK_GBPS, 4),
+        "bytes_per_step": step_bytes,
+        "roofline": roof, "cpu_baseline": cpu,
+        "near_threshold_fallbacks": int(st.near_threshold), "filter_mismatch": int(st.filter_mismatch),
+        "prep_seconds": round(prep_s, 1),
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -163,6 +163,14 @@ int stand_get_context(stand_handle *h, int32_t b, int32_t *host_tail, int32_t n,
 /* Counters since creation.  Synchronises the device. */
 int stand_get_stats(stand_handle *h, stand_stats *out);
 
+/* Timing of the row pass (the kernel that streams all logits; paper Sec. 4.1 softmax + top-k):
+ * after stand_profile_begin, each of the next max_launches row-pass launches made by
+ * stand_verify / stand_step is bracketed by a pair of HIP events on the caller's stream.
+ * stand_profile_end synchronises the device, returns the summed event time in milliseconds
+ * and the number of launches measured, and switches the timing off. */
+int stand_profile_begin(stand_handle *h, int32_t max_launches);
+int stand_profile_end(stand_handle *h, double *row_pass_ms_total, int32_t *launches);
+
 const char *stand_strerror(int code);
 int stand_last_hip_error(const stand_handle *h);
 

@@ -20,6 +20,7 @@ EXPORTED = [
     "stand_create", "stand_destroy", "stand_depth", "stand_set_context", "stand_reorder", "stand_update",
     "stand_draft", "stand_verify", "stand_step", "stand_row_results", "stand_table_export", "stand_table_import",
     "stand_get_context", "stand_get_stats", "stand_strerror", "stand_last_hip_error",
+    "stand_profile_begin", "stand_profile_end",
 ]
 
 
@@ -61,6 +62,8 @@ def load_library():
     lib.stand_table_import.argtypes = [vp, vp, C.c_uint64]
     lib.stand_get_context.argtypes = [vp, C.c_int32, i32p, C.c_int32, C.POINTER(C.c_int64), vp]
     lib.stand_get_stats.argtypes = [vp, C.POINTER(Stats)]
+    lib.stand_profile_begin.argtypes = [vp, C.c_int32]
+    lib.stand_profile_end.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_int32)]
     lib.stand_strerror.restype = C.c_char_p
     lib.stand_strerror.argtypes = [C.c_int]
     lib.stand_last_hip_error.argtypes = [vp]
@@ -196,6 +199,15 @@ class Stand:
         ln = C.c_int64(0)
         _check(lib().stand_get_context(self.h, b, out.ctypes.data_as(C.c_void_p), n, C.byref(ln), _stream_ptr()), self.h)
         return out[:n], int(ln.value)
+
+    def profile_begin(self, max_launches):
+        _check(lib().stand_profile_begin(self.h, max_launches), self.h)
+
+    def profile_end(self):
+        ms = C.c_double(0)
+        n = C.c_int32(0)
+        _check(lib().stand_profile_end(self.h, C.byref(ms), C.byref(n)), self.h)
+        return ms.value, n.value
 
     def stats(self):
         s = Stats()

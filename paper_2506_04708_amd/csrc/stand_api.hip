@@ -32,6 +32,10 @@ struct stand_handle {
     unsigned long long *stats;
     unsigned long long *counter;
     bool table_used;
+    // optional timing of the row pass: event pairs recorded on the caller's stream
+    bool profiling;
+    std::vector<hipEvent_t> ev_begin, ev_end;
+    size_t ev_used;
 };
 
 #define HIP_TRY(h, expr)                                   \
@@ -69,6 +73,8 @@ static void free_all(stand_handle *h)
                     h->row_m, h->row_s, h->top_l, h->top_p, h->top_idx, h->outcome, h->obs_idx, h->obs_p, h->rec_slot,
                     h->stats, h->counter};
     for (void *p : ptrs) (void)hipFree(p);
+    for (hipEvent_t e : h->ev_begin) (void)hipEventDestroy(e);
+    for (hipEvent_t e : h->ev_end) (void)hipEventDestroy(e);
     delete h;
 }
 
@@ -100,6 +106,8 @@ extern "C" int stand_create(const stand_config *cfg, stand_handle **out)
     h->c = (float)(1.4426950408889634 / (double)cfg->temperature);
     h->last_hip = 0;
     h->table_used = false;
+    h->profiling = false;
+    h->ev_used = 0;
 
     // tree: breadth-first numbering with contiguous siblings <=> parents non-decreasing
     h->parent.assign(cfg->tree_parent, cfg->tree_parent + N);
@@ -239,9 +247,12 @@ static int launch_row_pass(stand_handle *h, uint64_t step, const void *d_logits,
     a.row_m = h->row_m; a.row_s = h->row_s; a.top_idx = h->top_idx; a.top_l = h->top_l; a.top_p = h->top_p;
     a.outcome = h->outcome; a.stats = h->stats;
     const dim3 grid((unsigned)(h->B * h->N)), block(kRowThreads);
+    const bool timed = h->profiling && h->ev_used < h->ev_begin.size();
+    if (timed) HIP_TRY(h, hipEventRecord(h->ev_begin[h->ev_used], s));
     if (h->cfg.logits_dtype == STAND_BF16) row_pass_kernel<kDtBf16><<<grid, block, 0, s>>>(a);
     else row_pass_kernel<kDtF32><<<grid, block, 0, s>>>(a);
     HIP_TRY(h, hipGetLastError());
+    if (timed) HIP_TRY(h, hipEventRecord(h->ev_end[h->ev_used++], s));
     return STAND_OK;
 }
 
@@ -455,6 +466,40 @@ extern "C" int stand_get_stats(stand_handle *h, stand_stats *out)
     out->misses = st[kStatMisses]; out->inserts = st[kStatInserts]; out->merges = st[kStatMerges];
     out->drops = st[kStatDrops]; out->near_threshold = st[kStatNear]; out->tokens_emitted = st[kStatTokens];
     out->accept_tests = st[kStatTests]; out->filter_mismatch = st[kStatMismatch];
+    return STAND_OK;
+}
+
+extern "C" int stand_profile_begin(stand_handle *h, int32_t max_launches)
+{
+    if (!h || max_launches < 0 || max_launches > (1 << 20)) return STAND_EINVAL;
+    HIP_TRY(h, hipSetDevice(h->cfg.device));
+    while ((int32_t)h->ev_begin.size() < max_launches) {
+        hipEvent_t a, b;
+        HIP_TRY(h, hipEventCreate(&a));
+        h->ev_begin.push_back(a);
+        HIP_TRY(h, hipEventCreate(&b));
+        h->ev_end.push_back(b);
+    }
+    h->ev_used = 0;
+    h->profiling = max_launches > 0;
+    return STAND_OK;
+}
+
+extern "C" int stand_profile_end(stand_handle *h, double *row_pass_ms_total, int32_t *launches)
+{
+    if (!h || !row_pass_ms_total || !launches) return STAND_EINVAL;
+    HIP_TRY(h, hipSetDevice(h->cfg.device));
+    HIP_TRY(h, hipDeviceSynchronize());
+    double total = 0.0;
+    for (size_t i = 0; i < h->ev_used; ++i) {
+        float ms = 0.0f;
+        HIP_TRY(h, hipEventElapsedTime(&ms, h->ev_begin[i], h->ev_end[i]));
+        total += (double)ms;
+    }
+    *row_pass_ms_total = total;
+    *launches = (int32_t)h->ev_used;
+    h->profiling = false;
+    h->ev_used = 0;
     return STAND_OK;
 }
 
