@@ -332,7 +332,7 @@ __device__ unsigned long long wg_row_exact_sum(const void *rowp, int V, float m,
 // Returns the rank of the accepted child or -1.  With track_err the values r are taken to
 // carry a relative error of at most eps and `near` reports a test that the error could flip.
 // ---------------------------------------------------------------------------------------------
-__device__ __forceinline__ float wave_ordered_sum(float x, int lane, int K, volatile float *tmp)
+__device__ __forceinline__ float wave_ordered_sum(float x, int lane, int K, float *tmp)
 {
     // LDS operations of one wave execute in order, so the reads below see the writes
     if (lane < K) tmp[lane] = x;
@@ -345,9 +345,9 @@ __device__ __forceinline__ float wave_ordered_sum(float x, int lane, int K, vola
 
 struct NodeResult { int accepted; int rounds; bool near; float r; float rho; };
 
-__device__ NodeResult wave_node_outcome(int lane, int K, int32_t my_id, float my_mu, float my_p, int nchild,
+__device__ __forceinline__ NodeResult wave_node_outcome(int lane, int K, int32_t my_id, float my_mu, float my_p, int nchild,
                                         const int32_t *child_tok, uint64_t seed, uint32_t b, uint64_t step,
-                                        int first_child, volatile float *tmp, bool track_err, float eps)
+                                        int first_child, float *tmp, bool track_err, float eps)
 {
     NodeResult res;
     res.accepted = -1; res.rounds = 0; res.near = false;
@@ -396,8 +396,289 @@ __device__ NodeResult wave_node_outcome(int lane, int K, int32_t my_id, float my
 }
 
 // ---------------------------------------------------------------------------------------------
-// Row pass: one workgroup per logits row.
+// Row pass: one wave per logits row, no workgroup barriers.  The wave streams its row with
+// kRowPF batches of kRowU 16-byte vectors per lane in flight, keeps a wave-uniform running
+// maximum as the reference of the fast exponentials, and collects top-K candidates (elements
+// not below the current K-th best) in a small per-wave list that is pruned by rank counting.
 // ---------------------------------------------------------------------------------------------
+#ifndef STAND_ROW_U
+#define STAND_ROW_U 2
+#endif
+#ifndef STAND_ROW_PF
+#define STAND_ROW_PF 2
+#endif
+constexpr int kRowU = STAND_ROW_U;     // vectors per lane per batch
+constexpr int kRowPF = STAND_ROW_PF;   // batches in flight per wave
+constexpr int kWaveCap = 128;          // vector records per wave (pruned when above 64)
+#ifndef STAND_ROW_WPR
+#define STAND_ROW_WPR 4
+#endif
+constexpr int kRowWPR = STAND_ROW_WPR;                 // waves that share one row (1, 2 or 4)
+constexpr int kRowsPerBlock = kRowThreads / 64 / kRowWPR;
+
+constexpr int kElemCap = 8 * kMaxK + 64;  // element candidates at the end of a row (<= 8 per kept vector + edges)
+
+struct WaveScan {
+    unsigned long long buf[kWaveCap + 8];   // vector records: (maximum of the vector, vector index)
+    unsigned long long top[kMaxK];      // pruned / final keys, best first
+    unsigned long long ebuf[kElemCap + 8];  // element keys offered to the final selection
+    float tmp[kMaxK];
+};
+
+__device__ __forceinline__ int lane_prefix_count(unsigned long long mask)
+{
+    return (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+}
+
+__device__ __forceinline__ float wave_max_f32(float x)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) x = fmaxf(x, __shfl_xor(x, off));
+    return x;
+}
+
+// Rank counting over n distinct non-zero keys in list[0..n): the K best are written, best
+// first, to top[0..min(n,K)).  Returns the K-th best key (0 if n < K).  The list must have
+// room for 7 padding entries behind n (they are zeroed here so that the scan can run in
+// groups of 8 independent LDS reads).
+__device__ __forceinline__ unsigned long long wave_select(unsigned long long *list, unsigned long long *top, int lane, int K,
+                                                          int n)
+{
+    const int npad = (n + 7) & ~7;
+    if (lane < npad - n) list[n + lane] = 0ull;
+    __builtin_amdgcn_wave_barrier();
+    for (int base = 0; base < n; base += 64) {
+        const int i = base + lane;
+        const unsigned long long c = i < n ? list[i] : ~0ull;
+        int r = 0;
+        for (int j = 0; j < npad; j += 8) {
+            unsigned long long k8[8];
+#pragma unroll
+            for (int q = 0; q < 8; ++q) k8[q] = list[j + q];
+#pragma unroll
+            for (int q = 0; q < 8; ++q) r += k8[q] > c ? 1 : 0;
+        }
+        if (i < n && r < K) top[r] = c;
+    }
+    __builtin_amdgcn_wave_barrier();
+    return n >= K ? top[K - 1] : 0ull;
+}
+
+struct WaveScanState {
+    unsigned long long theta_key;  // only records above it can enter the list
+    float theta_val;               // value of theta_key (-inf if none): cheap pre-filter
+    int cnt;                       // records in ws->buf (wave-uniform)
+};
+
+__device__ __forceinline__ void set_theta(WaveScanState &st, unsigned long long key)
+{
+    st.theta_key = key;
+    st.theta_val = key ? rank_key_value(key) : -__builtin_inff();
+}
+
+// Prune the record list to its K best; they stay in ws->buf, the K-th best becomes the threshold.
+__device__ __forceinline__ void wave_prune(WaveScan *ws, WaveScanState &st, int lane, int K)
+{
+    const unsigned long long th = wave_select(ws->buf, ws->top, lane, K, st.cnt);
+    const int keep = st.cnt < K ? st.cnt : K;
+    if (lane < keep) ws->buf[lane] = ws->top[lane];
+    __builtin_amdgcn_wave_barrier();
+    st.cnt = keep;
+    if (th) set_theta(st, th);
+}
+
+// Lanes with `has` append the record (cm, vec) if it beats the threshold; prune above 64 records.
+__device__ __forceinline__ void wave_offer(WaveScan *ws, WaveScanState &st, int lane, int K, bool has, float cm,
+                                           uint32_t vec)
+{
+    const unsigned long long key = rank_key(cm, vec);
+    const bool pred = has && key > st.theta_key;
+    const unsigned long long bal = __ballot(pred);
+    if (!bal) return;
+    if (pred) ws->buf[st.cnt + lane_prefix_count(bal)] = key;
+    st.cnt += __popcll(bal);
+    __builtin_amdgcn_wave_barrier();
+    if (st.cnt > 64) wave_prune(ws, st, lane, K);
+}
+
+// Leaves the row's K best element keys (value desc, id asc) sorted in ws->top[0..K), returns
+// the row maximum and the fast normaliser sum_v 2^((l_v - m) c).
+//
+// While streaming, only one record per 16-byte vector is kept: its maximum.  The K vectors
+// with the largest maxima (ties: lower index) contain the K best elements, so the elements
+// are ranked only at the end, among those kept vectors.
+struct WavePartial {
+    float m_ref, s;   // reference maximum of this wave's part and its fast sum relative to it
+    int cnt;          // vector records left in ws->buf (the wave's K best, sorted, also in ws->top)
+};
+
+// Streaming part: wave `wsub` of `wpr` cooperating waves takes every wpr-th batch of the row.
+template <int DT>
+__device__ __forceinline__ WavePartial wave_row_stream(const void *rowp, int V, float c, int K, WaveScan *ws, int lane,
+                                                       int wsub, int wpr)
+{
+    constexpr int EPV = VecTraits<DT>::EPV;
+    constexpr int U = kRowU, PF = kRowPF;
+    const RowGeom g = row_geom<DT>(rowp, V);
+    const int per_batch = 64 * U;
+    const int nbatch_row = (g.nvec + per_batch - 1) / per_batch;
+    const int nbatch = (nbatch_row - wsub + wpr - 1) / wpr;  // batches of this wave: wsub, wsub + wpr, ...
+
+    WaveScanState st;
+    st.cnt = 0;
+    set_theta(st, 0ull);
+    float m_ref = -3.402823466e38f, nb = 0.0f, s_t = 0.0f;  // m_ref, nb wave-uniform
+
+    auto raise_reference = [&](float cm) {
+        // some lane saw a value above the reference: move the reference to the wave's maximum
+        const float nm = fmaxf(wave_max_f32(cm), m_ref);
+        s_t *= fast_exp2((m_ref - nm) * c);
+        m_ref = nm;
+        nb = -nm * c;
+    };
+    // Loads are issued unconditionally (indices clamped to the last vector) so that the number of
+    // loads in flight is the same on every path and only the oldest batch is waited for.
+    const int last_vec = g.nvec > 0 ? g.nvec - 1 : 0;
+    auto load_batch = [&](uint4 (&w)[U], int k) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int idx = ((k * wpr + wsub) * U + u) * 64 + lane;
+            w[u] = g.vp[idx < last_vec ? idx : last_vec];
+        }
+    };
+
+    uint4 ring[PF][U];
+    if (g.nvec > 0) {
+#pragma unroll
+        for (int s = 0; s < PF; ++s) load_batch(ring[s], s);
+    }
+
+    // scalar edge elements (row start / end not on a 16-byte boundary): at most one per lane,
+    // summed by the first wave of the row (they are ranked in wave_row_finish)
+    int edge_id = -1;
+    if (wsub == 0) {
+        if (lane < g.head) edge_id = lane;
+        else if (lane < g.head + g.ntail) edge_id = g.tail0 + (lane - g.head);
+    }
+    const float edge_val = edge_id >= 0 ? load_scalar<DT>(rowp, edge_id) : -__builtin_inff();
+    if (__ballot(edge_val > m_ref)) raise_reference(edge_val);
+    if (edge_id >= 0) s_t += fast_exp2(__builtin_fmaf(edge_val, c, nb));
+
+    auto one_vector = [&](const uint4 &w, int idx, bool valid) {
+        float x[EPV];
+        unpack<DT>(w, x);
+        float cm = x[0];
+#pragma unroll
+        for (int j = 1; j < EPV; ++j) cm = fmaxf(cm, x[j]);
+        if (!valid) cm = -__builtin_inff();
+        if (__ballot(cm > m_ref)) raise_reference(cm);
+        float e = 0.0f;
+#pragma unroll
+        for (int j = 0; j < EPV; ++j) e += fast_exp2(__builtin_fmaf(x[j], c, nb));
+        s_t += valid ? e : 0.0f;
+#ifndef STAND_TUNE_NOTOPK
+        if (__ballot(valid && cm >= st.theta_val)) wave_offer(ws, st, lane, K, valid && cm >= st.theta_val, cm, (uint32_t)idx);
+#endif
+    };
+    auto do_batch = [&](uint4 (&w)[U], int k) {
+        const int kb = k * wpr + wsub;        // batch of the row
+        if ((kb + 1) * per_batch <= g.nvec) {  // wave-uniform: every lane has all its vectors
+#pragma unroll
+            for (int u = 0; u < U; ++u) one_vector(w[u], (kb * U + u) * 64 + lane, true);
+        } else {
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int idx = (kb * U + u) * 64 + lane;
+                const bool valid = idx < g.nvec;
+                one_vector(valid ? w[u] : make_uint4(0, 0, 0, 0), idx, valid);
+            }
+        }
+    };
+
+    // batches beyond the row (when nbatch is not a multiple of PF) have no valid lane and add nothing
+    for (int k0 = 0; k0 < nbatch; k0 += PF) {
+#pragma unroll
+        for (int s = 0; s < PF; ++s) {
+            do_batch(ring[s], k0 + s);
+            load_batch(ring[s], k0 + s + PF);
+        }
+    }
+
+    // leave this wave's K best records sorted in ws->buf / ws->top
+    wave_prune(ws, st, lane, K);
+    float s = s_t;
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off);
+    WavePartial out;
+    out.m_ref = m_ref;
+    out.s = s;
+    out.cnt = st.cnt;
+    return out;
+}
+
+// Finishing part (one wave per row): `cnt` vector records are in ws->buf.  The K vectors with
+// the largest maxima contain the K best elements; their elements and the row's edge elements
+// are ranked exactly.  Leaves the K best element keys sorted in ws->top[0..K).
+template <int DT>
+__device__ __forceinline__ void wave_row_finish(const void *rowp, int V, int K, WaveScan *ws, int lane, int cnt)
+{
+    constexpr int EPV = VecTraits<DT>::EPV;
+    const RowGeom g = row_geom<DT>(rowp, V);
+    int edge_id = -1;
+    if (lane < g.head) edge_id = lane;
+    else if (lane < g.head + g.ntail) edge_id = g.tail0 + (lane - g.head);
+    const float edge_val = edge_id >= 0 ? load_scalar<DT>(rowp, edge_id) : -__builtin_inff();
+
+    const unsigned long long th_vec = wave_select(ws->buf, ws->top, lane, K, cnt);
+    const int kept = cnt < K ? cnt : K;
+    const float th_val = th_vec ? rank_key_value(th_vec) : -__builtin_inff();
+    int ne = 0;
+    {
+        const unsigned long long eb = __ballot(edge_id >= 0 && edge_val >= th_val);
+        if (edge_id >= 0 && edge_val >= th_val) ws->ebuf[lane_prefix_count(eb)] = rank_key(edge_val, (uint32_t)edge_id);
+        ne = __popcll(eb);
+        float x[EPV];
+        uint32_t vec = 0;
+        const bool own = lane < kept;
+        if (own) {
+            vec = rank_key_id(ws->top[lane]);
+            unpack<DT>(g.vp[vec], x);
+        }
+#pragma unroll
+        for (int j = 0; j < EPV; ++j) {
+            const bool pred = own && x[j] >= th_val;
+            const unsigned long long bal = __ballot(pred);
+            if (pred) ws->ebuf[ne + lane_prefix_count(bal)] = rank_key(x[j], (uint32_t)(g.head + (int)vec * EPV + j));
+            ne += __popcll(bal);
+        }
+    }
+    __builtin_amdgcn_wave_barrier();
+    wave_select(ws->ebuf, ws->top, lane, K, ne);
+}
+
+// Exact normaliser of a row by one wave (rare path).
+template <int DT>
+__device__ unsigned long long wave_row_exact_sum(const void *rowp, int V, float m, float c, int lane)
+{
+    constexpr int EPV = VecTraits<DT>::EPV;
+    const int F = fixed_bits(V);
+    const RowGeom g = row_geom<DT>(rowp, V);
+    unsigned long long S = 0ull;
+    int edge_id = -1;
+    if (lane < g.head) edge_id = lane;
+    else if (lane < g.head + g.ntail) edge_id = g.tail0 + (lane - g.head);
+    if (edge_id >= 0) S += fixed_contrib(exact_exp2(scaled_offset(load_scalar<DT>(rowp, edge_id), m, c)), F);
+    for (int idx = lane; idx < g.nvec; idx += 64) {
+        float x[EPV];
+        unpack<DT>(g.vp[idx], x);
+#pragma unroll
+        for (int j = 0; j < EPV; ++j) S += fixed_contrib(exact_exp2(scaled_offset(x[j], m, c)), F);
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) S += __shfl_xor(S, off);
+    return S;
+}
+
 struct RowPassArgs {
     const void *logits;
     int B, N, V, K;
@@ -419,22 +700,52 @@ template <int DT>
 __global__ __launch_bounds__(kRowThreads) void row_pass_kernel(RowPassArgs a)
 {
     constexpr int ES = VecTraits<DT>::ES;
-    __shared__ ScanShared sh;
-    const int row = blockIdx.x;
-    const int tid = threadIdx.x;
-    const int b = row / a.N, u = row % a.N;
-    const char *rowp = (const char *)a.logits + (size_t)row * (size_t)a.V * ES;
+    __shared__ WaveScan wsh[kRowThreads / 64];
+    __shared__ float part_m[kRowThreads / 64], part_s[kRowThreads / 64];
+    __shared__ int part_cnt[kRowThreads / 64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wsub = wave % kRowWPR;
+    const int row = blockIdx.x * kRowsPerBlock + wave / kRowWPR;
+    const bool live = row < a.B * a.N;
+    WaveScan *ws = &wsh[wave];
+    const int b = live ? row / a.N : 0, u = live ? row % a.N : 0;
+    const char *rowp = (const char *)a.logits + (size_t)(live ? row : 0) * (size_t)a.V * ES;
     float m, s;
-    wg_row_scan<DT, kRowThreads>(rowp, a.V, a.c, a.K, sh, m, s);
-
-    if (tid < a.K) {
-        const unsigned long long key = sh.top[tid];
-        const float l = rank_key_value(key);
-        a.top_idx[(size_t)row * a.K + tid] = (int32_t)rank_key_id(key);
-        a.top_l[(size_t)row * a.K + tid] = l;
-        a.top_p[(size_t)row * a.K + tid] = exact_exp2(scaled_offset(l, m, a.c)) / s;
+    if constexpr (kRowWPR == 1) {
+        if (!live) return;  // whole wave; no workgroup barrier in this configuration
+        const WavePartial wp = wave_row_stream<DT>(rowp, a.V, a.c, a.K, ws, lane, 0, 1);
+        wave_row_finish<DT>(rowp, a.V, a.K, ws, lane, wp.cnt);
+        m = rank_key_value(ws->top[0]);
+        s = wp.s * fast_exp2((wp.m_ref - m) * a.c);  // m_ref equals m: the factor is 1
+    } else {
+        if (live) {
+            const WavePartial wp = wave_row_stream<DT>(rowp, a.V, a.c, a.K, ws, lane, wsub, kRowWPR);
+            if (lane == 0) { part_m[wave] = wp.m_ref; part_s[wave] = wp.s; part_cnt[wave] = wp.cnt; }
+        }
+        __syncthreads();
+        if (!live || wsub != 0) return;
+        // gather the partner waves' records behind this wave's own (all lists hold at most K records)
+        int cnt = part_cnt[wave];
+        for (int q = 1; q < kRowWPR; ++q) {
+            const int cq = part_cnt[wave + q];
+            if (lane < cq) ws->buf[cnt + lane] = wsh[wave + q].buf[lane];
+            cnt += cq;
+        }
+        __builtin_amdgcn_wave_barrier();
+        wave_row_finish<DT>(rowp, a.V, a.K, ws, lane, cnt);
+        m = rank_key_value(ws->top[0]);
+        s = 0.0f;
+        for (int q = 0; q < kRowWPR; ++q) s += part_s[wave + q] * fast_exp2((part_m[wave + q] - m) * a.c);
     }
-    if (tid == 0) { a.row_m[row] = m; a.row_s[row] = s; }
+
+    if (lane < a.K) {
+        const unsigned long long key = ws->top[lane];
+        const float l = rank_key_value(key);
+        a.top_idx[(size_t)row * a.K + lane] = (int32_t)rank_key_id(key);
+        a.top_l[(size_t)row * a.K + lane] = l;
+        a.top_p[(size_t)row * a.K + lane] = exact_exp2(scaled_offset(l, m, a.c)) / s;
+    }
+    if (lane == 0) { a.row_m[row] = m; a.row_s[row] = s; }
 
     // ---- accept / reject outcome of this node's children (paper Sec. 3.2, applied recursively)
     const int nch_tree = a.tree.nchild[u];
@@ -442,38 +753,31 @@ __global__ __launch_bounds__(kRowThreads) void row_pass_kernel(RowPassArgs a)
     int nch = 0;
     if (a.draft_has[row] && a.draft_tok[row] >= 0)
         for (int j = 0; j < nch_tree; ++j) { if (a.draft_tok[(size_t)b * a.N + fc + j] < 0) break; ++nch; }
-    if (nch == 0) {  // uniform over the workgroup
-        if (tid == 0) a.outcome[row] = -1;
+    if (nch == 0) {  // uniform over the wave
+        if (lane == 0) a.outcome[row] = -1;
         return;
     }
-    const int lane = tid & 63;
     int32_t my_id = -1;
     float my_mu = 0.0f, my_l = 0.0f;
-    if (tid < a.K) {
-        my_id = a.draft_qid[(size_t)row * a.K + tid];
-        my_mu = a.draft_qmu[(size_t)row * a.K + tid];
+    if (lane < a.K) {
+        my_id = a.draft_qid[(size_t)row * a.K + lane];
+        my_mu = a.draft_qmu[(size_t)row * a.K + lane];
         if ((uint32_t)my_id >= (uint32_t)a.V) { my_id = -1; my_mu = 0.0f; }  // never index outside the row
         else my_l = load_scalar<DT>(rowp, my_id);
     }
     const int32_t *child_tok = a.draft_tok + (size_t)b * a.N + fc;
-    if (tid < 64) {
-        const float e = (tid < a.K) ? exact_exp2(scaled_offset(my_l, m, a.c)) : 0.0f;
-        NodeResult nr = wave_node_outcome(lane, a.K, my_id, my_mu, e / s, nch, child_tok, a.seed, (uint32_t)b, a.step,
-                                          fc, sh.tmp, true, kFastEps);
-        if (tid == 0) { sh.flag = nr.near ? 1 : 0; a.outcome[row] = nr.accepted; }
-    }
-    __syncthreads();
-    if (sh.flag) {
+    const float e = (lane < a.K && my_id >= 0) ? exact_exp2(scaled_offset(my_l, m, a.c)) : 0.0f;
+    NodeResult nr = wave_node_outcome(lane, a.K, my_id, my_mu, e / s, nch, child_tok, a.seed, (uint32_t)b, a.step, fc,
+                                      ws->tmp, true, kFastEps);
+    if (nr.near) {
         // a test fell inside the error bound of the fast normaliser: decide with the exact one
-        const unsigned long long S = wg_row_exact_sum<DT, kRowThreads>(rowp, a.V, m, a.c, &sh.acc64);
+        const unsigned long long S = wave_row_exact_sum<DT>(rowp, a.V, m, a.c, lane);
         const float sx = normaliser_from_fixed(S, fixed_bits(a.V));
-        if (tid < 64) {
-            const float e = (tid < a.K) ? exact_exp2(scaled_offset(my_l, m, a.c)) : 0.0f;
-            NodeResult nr = wave_node_outcome(lane, a.K, my_id, my_mu, e / sx, nch, child_tok, a.seed, (uint32_t)b,
-                                              a.step, fc, sh.tmp, false, 0.0f);
-            if (tid == 0) { a.outcome[row] = nr.accepted; atomicAdd(&a.stats[kStatNear], 1ull); }
-        }
+        nr = wave_node_outcome(lane, a.K, my_id, my_mu, e / sx, nch, child_tok, a.seed, (uint32_t)b, a.step, fc, ws->tmp,
+                               false, 0.0f);
+        if (lane == 0) atomicAdd(&a.stats[kStatNear], 1ull);
     }
+    if (lane == 0) a.outcome[row] = nr.accepted;
 }
 
 // ---------------------------------------------------------------------------------------------

@@ -246,7 +246,7 @@ static int launch_row_pass(stand_handle *h, uint64_t step, const void *d_logits,
     a.draft_tok = h->draft_tok; a.draft_has = h->draft_has; a.draft_qid = h->draft_qid; a.draft_qmu = h->draft_qmu;
     a.row_m = h->row_m; a.row_s = h->row_s; a.top_idx = h->top_idx; a.top_l = h->top_l; a.top_p = h->top_p;
     a.outcome = h->outcome; a.stats = h->stats;
-    const dim3 grid((unsigned)(h->B * h->N)), block(kRowThreads);
+    const dim3 grid((unsigned)((h->B * h->N + kRowsPerBlock - 1) / kRowsPerBlock)), block(kRowThreads);
     const bool timed = h->profiling && h->ev_used < h->ev_begin.size();
     if (timed) HIP_TRY(h, hipEventRecord(h->ev_begin[h->ev_used], s));
     if (h->cfg.logits_dtype == STAND_BF16) row_pass_kernel<kDtBf16><<<grid, block, 0, s>>>(a);
