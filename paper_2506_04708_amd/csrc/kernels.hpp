@@ -18,10 +18,10 @@
 namespace stand {
 
 constexpr int kDtBf16 = 0, kDtF32 = 1;
-constexpr int kCap = 2048;      // candidate buffer entries per workgroup (>= kRefresh + largest block)
-constexpr int kRefresh = 256;   // prune the buffer when it holds more than this
 constexpr int kRowThreads = 256;
-constexpr int kPathThreads = 1024;
+constexpr int kMaxNodes = 256;
+constexpr int kMaxDepth = 31;
+constexpr int kPathThreads = 256;
 constexpr float kFastEps = 5e-5f;  // bound on the relative error of the fast normaliser
 
 enum StatSlot {
@@ -49,54 +49,6 @@ __device__ __forceinline__ int32_t *slot_ids(char *table, uint64_t slot, int slo
 __device__ __forceinline__ float *slot_mu(char *table, uint64_t slot, int slot_bytes, int K)
 {
     return (float *)(table + slot * (uint64_t)slot_bytes + 16 + 4 * K);
-}
-
-// ---------------------------------------------------------------------------------------------
-// Workgroup-level streaming scan of one row: running max / sum (fast) and exact top-K.
-// ---------------------------------------------------------------------------------------------
-struct ScanShared {
-    unsigned long long buf[kCap];
-    unsigned long long top[kMaxK];
-    unsigned long long theta_key;
-    unsigned long long acc64;
-    uint32_t cnt;
-    int flag;
-    float red[32];
-    float tmp[kMaxK];
-};
-
-// Keeps the K best of the n candidates in sh.buf (sorted into sh.top and copied back) and sets
-// sh.theta_key to the K-th best (0 if n < K).  Precondition: a barrier has passed since the last
-// push, every thread holds the same n == sh.cnt, and nobody touches sh until the call returns.
-template <int BS>
-__device__ __noinline__ uint32_t wg_select_topk(ScanShared &sh, int K, uint32_t n_in)
-{
-    const int tid = threadIdx.x;
-    const int n = (int)n_in;
-    for (int i = tid; i < n; i += BS) {
-        unsigned long long a = sh.buf[i];
-        int r = 0;
-        for (int j = 0; j < n; ++j) r += (sh.buf[j] > a) ? 1 : 0;
-        if (r < K) sh.top[r] = a;
-    }
-    __syncthreads();
-    const int keep = n < K ? n : K;
-    if (tid < keep) sh.buf[tid] = sh.top[tid];
-    if (tid == 0) {
-        sh.cnt = (uint32_t)keep;
-        sh.theta_key = (n >= K) ? sh.top[K - 1] : 0ull;
-    }
-    __syncthreads();
-    return (uint32_t)keep;
-}
-
-__device__ __forceinline__ void push_candidate(ScanShared &sh, float val, uint32_t id, unsigned long long thr)
-{
-    unsigned long long key = rank_key(val, id);
-    if (key > thr) {
-        uint32_t pos = atomicAdd(&sh.cnt, 1u);
-        if (pos < (uint32_t)kCap) sh.buf[pos] = key;
-    }
 }
 
 template <int DT> struct VecTraits;
@@ -145,215 +97,40 @@ __device__ __forceinline__ RowGeom row_geom(const void *rowp, int V)
 
 __device__ __forceinline__ float fast_exp2(float y) { return __builtin_amdgcn_exp2f(y); }
 
-// Returns through m_out the exact row maximum, through s_out the fast normaliser
-// sum_v 2^((l_v - m) c); leaves the K best (value desc, id asc) keys sorted in sh.top[0..K).
-template <int DT, int BS>
-__device__ void wg_row_scan(const void *rowp, int V, float c, int K, ScanShared &sh, float &m_out, float &s_out)
-{
-    constexpr int EPV = VecTraits<DT>::EPV;
-    constexpr int U = 4;
-    const int tid = threadIdx.x;
-    const RowGeom g = row_geom<DT>(rowp, V);
-
-    if (tid == 0) { sh.cnt = 0; sh.theta_key = 0ull; }
-    __syncthreads();
-
-    float m_t = -3.402823466e38f, s_t = 0.0f, nb = 0.0f;  // nb = -m_t * c once a finite value was seen
-    auto absorb_max = [&](float cm) {
-        if (cm > m_t) {
-            s_t *= fast_exp2((m_t - cm) * c);
-            m_t = cm;
-            nb = -cm * c;
-        }
-    };
-
-    // the scalar edge element of this thread, if any (only threads < head + ntail have one)
-    float edge_val = 0.0f;
-    int edge_id = -1;
-    if (tid < g.head) edge_id = tid;
-    else if (tid < g.head + g.ntail) edge_id = g.tail0 + (tid - g.head);
-    if (edge_id >= 0) {
-        edge_val = load_scalar<DT>(rowp, edge_id);
-        absorb_max(edge_val);
-        s_t += fast_exp2(__builtin_fmaf(edge_val, c, nb));
-    }
-
-    // Shared state is only read between two barriers and only written (pushes aside) by
-    // wg_select_topk or thread 0 between two barriers; `cnt` mirrors sh.cnt at those points.
-    uint32_t cnt = 0;
-    bool first = true;
-    for (int base = 0; base < g.nvec || first; base += BS * U) {
-        uint4 w[U];
-        bool ok[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            int idx = base + u * BS + tid;
-            ok[u] = idx < g.nvec;
-            if (ok[u]) w[u] = g.vp[idx];
-        }
-        const uint32_t cnt0 = cnt;
-        const unsigned long long theta = sh.theta_key;
-        const float theta_val = theta ? rank_key_value(theta) : -__builtin_inff();
-
-        // ---- softmax statistics + candidate filter
-        unsigned long long best = 0ull;  // best key of this thread (seeding only)
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            if (!ok[u]) continue;
-            float x[EPV];
-            unpack<DT>(w[u], x);
-            float cm = x[0];
-#pragma unroll
-            for (int j = 1; j < EPV; ++j) cm = fmaxf(cm, x[j]);
-            absorb_max(cm);
-#pragma unroll
-            for (int j = 0; j < EPV; ++j) s_t += fast_exp2(__builtin_fmaf(x[j], c, nb));
-            const uint32_t id0 = (uint32_t)(g.head + (base + u * BS + tid) * EPV);
-            if (first) {
-#pragma unroll
-                for (int j = 0; j < EPV; ++j) {
-                    unsigned long long k = rank_key(x[j], id0 + j);
-                    best = k > best ? k : best;
-                }
-            } else if (cm >= theta_val) {
-#pragma unroll
-                for (int j = 0; j < EPV; ++j)
-                    if (x[j] >= theta_val) push_candidate(sh, x[j], id0 + j, theta);
-            }
-        }
-
-        unsigned long long thr = theta;  // strict threshold for a replay of this super-iteration
-        if (first) {
-            // seed: the K-th best of the per-thread maxima bounds the K-th best element from below
-            if (edge_id >= 0) {
-                unsigned long long k = rank_key(edge_val, (uint32_t)edge_id);
-                best = k > best ? k : best;
-            }
-            if (best) { uint32_t pos = atomicAdd(&sh.cnt, 1u); sh.buf[pos] = best; }
-            __syncthreads();
-            const uint32_t nseed = sh.cnt;
-            __syncthreads();
-            wg_select_topk<BS>(sh, K, nseed);
-            thr = sh.theta_key ? sh.theta_key - 1ull : 0ull;
-            __syncthreads();
-            if (tid == 0) sh.cnt = 0;
-            __syncthreads();
-            if (edge_id >= 0) push_candidate(sh, edge_val, (uint32_t)edge_id, thr);
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                if (!ok[u]) continue;
-                float x[EPV];
-                unpack<DT>(w[u], x);
-                const uint32_t id0 = (uint32_t)(g.head + (base + u * BS + tid) * EPV);
-#pragma unroll
-                for (int j = 0; j < EPV; ++j) push_candidate(sh, x[j], id0 + j, thr);
-            }
-        }
-        __syncthreads();
-        cnt = sh.cnt;
-        __syncthreads();
-        if (cnt > (uint32_t)kCap) {
-            // More candidates than the buffer holds (e.g. an ascending run): replay this
-            // super-iteration one element per thread at a time, pruning in between.
-            cnt = first ? 0u : cnt0;
-            if (tid == 0) sh.cnt = cnt;
-            __syncthreads();
-            if (first && edge_id >= 0) push_candidate(sh, edge_val, (uint32_t)edge_id, thr);
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-#pragma unroll
-                for (int j = 0; j < EPV; ++j) {
-                    if (ok[u]) {
-                        float x[EPV];
-                        unpack<DT>(w[u], x);
-                        push_candidate(sh, x[j], (uint32_t)(g.head + (base + u * BS + tid) * EPV + j), thr);
-                    }
-                    __syncthreads();
-                    cnt = sh.cnt;
-                    __syncthreads();
-                    if (cnt > (uint32_t)kRefresh) {
-                        cnt = wg_select_topk<BS>(sh, K, cnt);
-                        if (sh.theta_key) thr = sh.theta_key;  // the K-th best is in the buffer now: strict
-                        __syncthreads();
-                    }
-                }
-            }
-        }
-        if (first || cnt > (uint32_t)kRefresh) cnt = wg_select_topk<BS>(sh, K, cnt);
-        first = false;
-    }
-    wg_select_topk<BS>(sh, K, cnt);  // leaves sh.top[0..min(K, V)) sorted
-
-    const float m = rank_key_value(sh.top[0]);
-    float part = s_t * fast_exp2((m_t - m) * c);
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) part += __shfl_xor(part, off);
-    if ((tid & 63) == 0) sh.red[tid >> 6] = part;
-    __syncthreads();
-    float s = 0.0f;
-    for (int wv = 0; wv < BS / 64; ++wv) s += sh.red[wv];
-    __syncthreads();
-    m_out = m;
-    s_out = s;
-}
-
-// Exact normaliser of a row whose maximum is known: S = sum_v floor(E((l_v - m) c) * 2^F).
-template <int DT, int BS>
-__device__ unsigned long long wg_row_exact_sum(const void *rowp, int V, float m, float c, unsigned long long *acc /* LDS */)
-{
-    constexpr int EPV = VecTraits<DT>::EPV;
-    const int tid = threadIdx.x;
-    const int F = fixed_bits(V);
-    const RowGeom g = row_geom<DT>(rowp, V);
-    if (tid == 0) *acc = 0ull;
-    __syncthreads();
-    unsigned long long S = 0ull;
-    int edge_id = -1;
-    if (tid < g.head) edge_id = tid;
-    else if (tid < g.head + g.ntail) edge_id = g.tail0 + (tid - g.head);
-    if (edge_id >= 0) S += fixed_contrib(exact_exp2(scaled_offset(load_scalar<DT>(rowp, edge_id), m, c)), F);
-    for (int idx = tid; idx < g.nvec; idx += BS) {
-        float x[EPV];
-        unpack<DT>(g.vp[idx], x);
-#pragma unroll
-        for (int j = 0; j < EPV; ++j) S += fixed_contrib(exact_exp2(scaled_offset(x[j], m, c)), F);
-    }
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) S += __shfl_xor(S, off);
-    if ((tid & 63) == 0) atomicAdd(acc, S);
-    __syncthreads();
-    unsigned long long total = *acc;
-    __syncthreads();
-    return total;
-}
-
 // ---------------------------------------------------------------------------------------------
 // Accept/reject sequence at one tree node, executed by one wave (lane i = stored id i).
 // Returns the rank of the accepted child or -1.  With track_err the values r are taken to
 // carry a relative error of at most eps and `near` reports a test that the error could flip.
 // ---------------------------------------------------------------------------------------------
-__device__ __forceinline__ float wave_ordered_sum(float x, int lane, int K, float *tmp)
+// Sum of the values of lanes 0..K-1 in lane order (one rounding per addition), the same in
+// every lane.  Lanes K..31 must hold +0, which leaves the sum unchanged.
+__device__ __forceinline__ float wave_ordered_sum(float x)
 {
-    // LDS operations of one wave execute in order, so the reads below see the writes
-    if (lane < K) tmp[lane] = x;
-    __builtin_amdgcn_wave_barrier();
     float t = 0.0f;
-    for (int i = 0; i < K; ++i) t = t + tmp[i];
-    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int i = 0; i < kMaxK; ++i) t = t + u2f((uint32_t)__builtin_amdgcn_readlane((int)f2u(x), i));
     return t;
+}
+
+// 64-bit key of lane i (i uniform)
+__device__ __forceinline__ unsigned long long readlane_u64(unsigned long long v, int i)
+{
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)v, i);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(v >> 32), i);
+    return ((unsigned long long)hi << 32) | lo;
 }
 
 struct NodeResult { int accepted; int rounds; bool near; float r; float rho; };
 
 __device__ __forceinline__ NodeResult wave_node_outcome(int lane, int K, int32_t my_id, float my_mu, float my_p, int nchild,
                                         const int32_t *child_tok, uint64_t seed, uint32_t b, uint64_t step,
-                                        int first_child, float *tmp, bool track_err, float eps)
+                                        int first_child, bool track_err, float eps)
 {
     NodeResult res;
     res.accepted = -1; res.rounds = 0; res.near = false;
     const bool act = lane < K;
     float w = (act && my_mu > 0.0f) ? my_mu : 0.0f;
-    float zw = wave_ordered_sum(w, lane, K, tmp);
+    float zw = wave_ordered_sum(w);
     w = zw > 0.0f ? w / zw : 0.0f;
     float r = act ? my_p : 0.0f;
     float rho = 1.0f;
@@ -370,8 +147,8 @@ __device__ __forceinline__ NodeResult wave_node_outcome(int lane, int K, int32_t
         res.rounds++;
         if (track_err && fabsf(lhs - ri) <= ei + 4e-7f * ri) res.near = true;
         if (lhs < ri) { res.accepted = j; break; }
-        const float mn = r < w ? r : w;
-        const float M = wave_ordered_sum(mn, lane, K, tmp);
+        const float mn = act ? (r < w ? r : w) : 0.0f;
+        const float M = wave_ordered_sum(mn);
         float Z = 1.0f - M;
         if (!(Z > 1e-30f)) Z = 1e-30f;
         float d = r - w;
@@ -387,7 +164,7 @@ __device__ __forceinline__ NodeResult wave_node_outcome(int lane, int K, int32_t
         r = rn;
         rho = rho / Z;
         if (lane == i) w = 0.0f;
-        const float zw2 = wave_ordered_sum(w, lane, K, tmp);
+        const float zw2 = wave_ordered_sum(w);
         w = zw2 > 0.0f ? w / zw2 : 0.0f;
     }
     res.r = r;
@@ -422,7 +199,6 @@ struct WaveScan {
     unsigned long long buf[kWaveCap + 8];   // vector records: (maximum of the vector, vector index)
     unsigned long long top[kMaxK];      // pruned / final keys, best first
     unsigned long long ebuf[kElemCap + 8];  // element keys offered to the final selection
-    float tmp[kMaxK];
 };
 
 __device__ __forceinline__ int lane_prefix_count(unsigned long long mask)
@@ -656,24 +432,70 @@ __device__ __forceinline__ void wave_row_finish(const void *rowp, int V, int K, 
     wave_select(ws->ebuf, ws->top, lane, K, ne);
 }
 
+// floor(e * 2^40) for e in [0, 1] as hi * 2^20 + lo with hi = floor(e * 2^20) <= 2^20 and
+// lo = floor((e * 2^20 - hi) * 2^20) < 2^20; every step is exact in binary32.
+__device__ __forceinline__ void fixed_split(float e, uint32_t &hi, uint32_t &lo)
+{
+    const float t = e * 0x1p20f;
+    hi = (uint32_t)t;
+    const float r = t - (float)hi;
+    lo = (uint32_t)(r * 0x1p20f);
+}
+
+// Exact fixed-point sum over the vectors [v0, v1) of a row (plus the edge elements if with_edge),
+// strided over `nthreads` threads; returns this thread's partial sum_v floor(E((l_v - m) c) * 2^40).
+template <int DT>
+__device__ __forceinline__ unsigned long long thread_exact_partial(const void *rowp, const RowGeom &g, int v0, int v1,
+                                                                   bool with_edge, float m, float c, int t, int nthreads)
+{
+    constexpr int EPV = VecTraits<DT>::EPV;
+    unsigned long long S = 0ull;
+    uint32_t ahi = 0, alo = 0;
+    if (with_edge) {
+        int edge_id = -1;
+        if (t < g.head) edge_id = t;
+        else if (t < g.head + g.ntail) edge_id = g.tail0 + (t - g.head);
+        if (edge_id >= 0) {
+            uint32_t hi, lo;
+            fixed_split(exact_exp2(scaled_offset(load_scalar<DT>(rowp, edge_id), m, c)), hi, lo);
+            ahi += hi; alo += lo;
+        }
+    }
+    // four independent loads are issued before any of them is used (indices clamped, so the
+    // number of loads in flight does not depend on the position in the row)
+    const int vlast = v1 > v0 ? v1 - 1 : v0;
+    auto add_vec = [&](const uint4 &w, int idx) {
+        if (idx < v1) {
+            float x[EPV];
+            unpack<DT>(w, x);
+#pragma unroll
+            for (int j = 0; j < EPV; ++j) {
+                uint32_t hi, lo;
+                fixed_split(exact_exp2(scaled_offset(x[j], m, c)), hi, lo);
+                ahi += hi; alo += lo;
+            }
+        }
+    };
+    for (int base = v0 + t; base < v1; base += 4 * nthreads) {
+        const int i0 = base, i1 = base + nthreads, i2 = base + 2 * nthreads, i3 = base + 3 * nthreads;
+        const uint4 w0 = g.vp[i0 < vlast ? i0 : vlast];
+        const uint4 w1 = g.vp[i1 < vlast ? i1 : vlast];
+        const uint4 w2 = g.vp[i2 < vlast ? i2 : vlast];
+        const uint4 w3 = g.vp[i3 < vlast ? i3 : vlast];
+        add_vec(w0, i0); add_vec(w1, i1); add_vec(w2, i2); add_vec(w3, i3);
+        // at most 32 elements since the last flush: the 32-bit accumulators stay below 2^26
+        S += ((unsigned long long)ahi << 20) + alo;
+        ahi = 0; alo = 0;
+    }
+    return S + ((unsigned long long)ahi << 20) + alo;
+}
+
 // Exact normaliser of a row by one wave (rare path).
 template <int DT>
 __device__ unsigned long long wave_row_exact_sum(const void *rowp, int V, float m, float c, int lane)
 {
-    constexpr int EPV = VecTraits<DT>::EPV;
-    const int F = fixed_bits(V);
     const RowGeom g = row_geom<DT>(rowp, V);
-    unsigned long long S = 0ull;
-    int edge_id = -1;
-    if (lane < g.head) edge_id = lane;
-    else if (lane < g.head + g.ntail) edge_id = g.tail0 + (lane - g.head);
-    if (edge_id >= 0) S += fixed_contrib(exact_exp2(scaled_offset(load_scalar<DT>(rowp, edge_id), m, c)), F);
-    for (int idx = lane; idx < g.nvec; idx += 64) {
-        float x[EPV];
-        unpack<DT>(g.vp[idx], x);
-#pragma unroll
-        for (int j = 0; j < EPV; ++j) S += fixed_contrib(exact_exp2(scaled_offset(x[j], m, c)), F);
-    }
+    unsigned long long S = thread_exact_partial<DT>(rowp, g, 0, g.nvec, true, m, c, lane, 64);
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) S += __shfl_xor(S, off);
     return S;
@@ -694,11 +516,19 @@ struct RowPassArgs {
     float *top_l, *top_p;       // [B*N][K]
     int32_t *outcome;           // [B*N] accepted child rank or -1
     unsigned long long *stats;
+    // accumulators of the path pass, cleared here for the kernels that follow
+    int W;
+    unsigned long long *rowS, *race;
+    unsigned int *done;
 };
 
 template <int DT>
 __global__ __launch_bounds__(kRowThreads) void row_pass_kernel(RowPassArgs a)
 {
+    if (blockIdx.x == 0) {
+        for (int i = threadIdx.x; i < a.B * a.W; i += kRowThreads) { a.rowS[i] = 0ull; a.done[i] = 0u; }
+        for (int i = threadIdx.x; i < a.B; i += kRowThreads) a.done[a.B * a.W + i] = 0u;
+    }
     constexpr int ES = VecTraits<DT>::ES;
     __shared__ WaveScan wsh[kRowThreads / 64];
     __shared__ float part_m[kRowThreads / 64], part_s[kRowThreads / 64];
@@ -748,11 +578,8 @@ __global__ __launch_bounds__(kRowThreads) void row_pass_kernel(RowPassArgs a)
     if (lane == 0) { a.row_m[row] = m; a.row_s[row] = s; }
 
     // ---- accept / reject outcome of this node's children (paper Sec. 3.2, applied recursively)
-    const int nch_tree = a.tree.nchild[u];
     const int fc = a.tree.first_child[u];
-    int nch = 0;
-    if (a.draft_has[row] && a.draft_tok[row] >= 0)
-        for (int j = 0; j < nch_tree; ++j) { if (a.draft_tok[(size_t)b * a.N + fc + j] < 0) break; ++nch; }
+    const int nch = a.draft_has[row];  // children drafted from this node's table entry (0: none)
     if (nch == 0) {  // uniform over the wave
         if (lane == 0) a.outcome[row] = -1;
         return;
@@ -768,186 +595,345 @@ __global__ __launch_bounds__(kRowThreads) void row_pass_kernel(RowPassArgs a)
     const int32_t *child_tok = a.draft_tok + (size_t)b * a.N + fc;
     const float e = (lane < a.K && my_id >= 0) ? exact_exp2(scaled_offset(my_l, m, a.c)) : 0.0f;
     NodeResult nr = wave_node_outcome(lane, a.K, my_id, my_mu, e / s, nch, child_tok, a.seed, (uint32_t)b, a.step, fc,
-                                      ws->tmp, true, kFastEps);
+                                      true, kFastEps);
     if (nr.near) {
         // a test fell inside the error bound of the fast normaliser: decide with the exact one
         const unsigned long long S = wave_row_exact_sum<DT>(rowp, a.V, m, a.c, lane);
-        const float sx = normaliser_from_fixed(S, fixed_bits(a.V));
-        nr = wave_node_outcome(lane, a.K, my_id, my_mu, e / sx, nch, child_tok, a.seed, (uint32_t)b, a.step, fc, ws->tmp,
-                               false, 0.0f);
+        const float sx = normaliser_from_fixed(S);
+        nr = wave_node_outcome(lane, a.K, my_id, my_mu, e / sx, nch, child_tok, a.seed, (uint32_t)b, a.step, fc, false,
+                               0.0f);
         if (lane == 0) atomicAdd(&a.stats[kStatNear], 1ull);
     }
     if (lane == 0) a.outcome[row] = nr.accepted;
 }
 
 // ---------------------------------------------------------------------------------------------
-// Path pass: workgroup (j, b) handles the j-th row of trajectory b's accepted path.
-// mode 0 (verify): the path follows `outcome`; writes out_tok / out_node / out_len and, for
-//                  every path row, the exact observation (top-K ids, probabilities).
-// mode 1 (update): rows are given (commit_row); statistics are computed here.
+// Path pass.  The accepted path of trajectory b follows `outcome` from the root (verify), or is
+// given as commit rows (update).  For each path row the exact normaliser is needed (its
+// observation is stored in the table), for the last one also the resampled token.  The work is
+// cut into segments so that it spreads over all compute units:
+//   path_exact_kernel  block (seg, j, b): exact partial sum of a segment of path row j; the last
+//                      block of a trajectory to finish writes the observations of its path rows
+//                      and the residual state of its stop node
+//   race_kernel        block (seg, b): exponential race over a segment of the stop row; the last
+//                      block of a trajectory writes the winner
 // ---------------------------------------------------------------------------------------------
-struct PathPassArgs {
+struct PathArgs {
     const void *logits;
-    int B, N, V, K, W, mode;
+    int B, N, V, K, W, mode;   // mode 0: verify (path from outcome), 1: update (rows given)
     float c;
     uint64_t seed, step;
     TreeDev tree;
     const int32_t *draft_tok, *draft_has, *draft_qid;
     const float *draft_qmu;
-    const float *row_m;
-    const int32_t *top_idx;
-    const float *top_l;
+    const float *src_m;        // mode 0: [B*N] by row; mode 1: [B*W] by (b, j)
+    const int32_t *src_top_idx;
+    const float *src_top_l;
     const int32_t *outcome;
     const int32_t *commit_row, *commit_len;  // mode 1
     int32_t *out_tok, *out_node, *out_len;   // mode 0
-    int32_t *obs_idx;                         // [B][W][K]
-    float *obs_p;                             // [B][W][K]
+    unsigned long long *rowS;  // [B][W] exact fixed-point sums, zero on entry of path_exact_kernel
+    unsigned long long *race;  // [B][kRaceSlots] best (time, token) of each race block
+    unsigned int *done;        // [B*W] finished blocks per path row, then [B] finished race blocks; zero on entry
+    int32_t *obs_idx;          // [B][W][K]
+    float *obs_p;              // [B][W][K]
+    // residual state of the stop node: written by path_exact_kernel, read by race_kernel
+    int32_t *res_id;           // [B][K] stored ids of the stop node's proposal
+    float *res_r;              // [B][K] residual target on them
+    float *res_f;              // [B][4] rho, s, m of the stop row
+    int32_t *res_i;            // [B][4] number of stored ids (0: no proposal), stop node, path length
     unsigned long long *stats;
 };
 
-struct PathShared {
-    ScanShared scan;
-    int path[32];
-    int len;
-    int32_t sup_id[kMaxK];
-    float sup_r[kMaxK];
-    float rho;
-    int nsup;
-    unsigned long long best;
-};
+// Walks the accepted path of trajectory b and leaves it in path[0..len) (shared memory).  The
+// outcomes of the trajectory's nodes are staged in shared memory first, so the walk itself
+// does not wait on global memory.  Must be called by the whole workgroup; returns len.
+__device__ __forceinline__ int resolve_path(const PathArgs &a, int b, int *path, int *oc /* [kMaxNodes] shared */,
+                                            int *len_sh)
+{
+    for (int u = threadIdx.x; u < a.N; u += blockDim.x) oc[u] = a.outcome[(size_t)b * a.N + u];
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int cur = 0, len = 0;
+        for (;;) {
+            path[len++] = cur;
+            const int acc = oc[cur];
+            if (acc < 0 || len > a.tree.D) break;
+            cur = a.tree.first_child[cur] + acc;
+        }
+        *len_sh = len;
+    }
+    __syncthreads();
+    return *len_sh;
+}
+
+__device__ __forceinline__ int path_row_of(const PathArgs &a, int b, int j, const int *path, int len)
+{
+    // returns the tree node of path position j, or -1 if there is none
+    if (a.mode == 0) return j < len ? path[j] : -1;
+    int cl = a.commit_len[b];
+    cl = cl < 0 ? 0 : (cl > a.W ? a.W : cl);
+    if (j >= cl) return -1;
+    const int node = a.commit_row[(size_t)b * a.W + j];
+    return (node < 0 || node >= a.N) ? -1 : node;
+}
 
 template <int DT>
-__global__ __launch_bounds__(kPathThreads) void path_pass_kernel(PathPassArgs a)
+__global__ __launch_bounds__(kPathThreads) void path_exact_kernel(PathArgs a)
 {
-    constexpr int ES = VecTraits<DT>::ES, EPV = VecTraits<DT>::EPV, BS = kPathThreads;
-    __shared__ PathShared ps;
-    const int j = blockIdx.x, b = blockIdx.y, tid = threadIdx.x, lane = tid & 63;
-    int node;
-    bool is_stop = false;
-    if (a.mode == 0) {
-        if (tid == 0) {
-            int cur = 0, len = 0;
-            for (;;) {
-                ps.path[len++] = cur;
-                const int acc = a.outcome[(size_t)b * a.N + cur];
-                if (acc < 0 || len > a.tree.D) break;
-                cur = a.tree.first_child[cur] + acc;
-            }
-            ps.len = len;
+    constexpr int ES = VecTraits<DT>::ES;
+    __shared__ int path[32];
+    __shared__ int oc[kMaxNodes];
+    __shared__ int s_len, s_last;
+    __shared__ unsigned long long s_part[kPathThreads / 64];
+    const int seg = blockIdx.x, nseg = gridDim.x, j = blockIdx.y, b = blockIdx.z, tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int len = a.mode == 0 ? resolve_path(a, b, path, oc, &s_len) : 0;
+    if (a.mode == 0 && seg == 0 && j == 0) {
+        // accepted tokens are the tokens of the path nodes after the root; the last emitted
+        // token (position len - 1) is written by race_kernel
+        if (tid < a.W) {
+            a.out_node[(size_t)b * a.W + tid] = tid < len ? path[tid] : -1;
+            if (tid + 1 < len) a.out_tok[(size_t)b * a.W + tid] = a.draft_tok[(size_t)b * a.N + path[tid + 1]];
+            else if (tid >= len) a.out_tok[(size_t)b * a.W + tid] = -1;
         }
-        __syncthreads();
-        const int len = ps.len;
-        if (j == 0) {
-            // accepted tokens are the tokens of the path nodes after the root
-            if (tid < a.W) {
-                a.out_node[(size_t)b * a.W + tid] = tid < len ? ps.path[tid] : -1;
-                if (tid + 1 < len) a.out_tok[(size_t)b * a.W + tid] = a.draft_tok[(size_t)b * a.N + ps.path[tid + 1]];
-                else if (tid >= len) a.out_tok[(size_t)b * a.W + tid] = -1;
-            }
-            if (tid == 0) { a.out_len[b] = len; atomicAdd(&a.stats[kStatTokens], (unsigned long long)len); }
-        }
-        if (j >= len) return;
-        node = ps.path[j];
-        is_stop = (j == len - 1);
-    } else {
-        int len = a.commit_len[b];
-        len = len < 0 ? 0 : (len > a.W ? a.W : len);
-        if (j >= len) return;
-        node = a.commit_row[(size_t)b * a.W + j];
-        if (node < 0 || node >= a.N) return;  // ignored record (the merge skips it too)
+        if (tid == 0) { a.out_len[b] = len; atomicAdd(&a.stats[kStatTokens], (unsigned long long)len); }
     }
+    {
+        const int node = path_row_of(a, b, j, path, len);
+        if (node >= 0) {
+            const int row = b * a.N + node;
+            const char *rowp = (const char *)a.logits + (size_t)row * (size_t)a.V * ES;
+            const float m = a.src_m[a.mode == 0 ? row : b * a.W + j];
+            const RowGeom g = row_geom<DT>(rowp, a.V);
+            const int per = (g.nvec + nseg - 1) / nseg;
+            const int v0 = seg * per, v1 = (v0 + per < g.nvec) ? v0 + per : g.nvec;
+            unsigned long long S = thread_exact_partial<DT>(rowp, g, v0, v1, seg == 0, m, a.c, tid, kPathThreads);
+#pragma unroll
+            for (int off = 32; off > 0; off >>= 1) S += __shfl_xor(S, off);
+            if (lane == 0) s_part[wave] = S;
+        }
+    }
+    // ---- the last block of this row to get here finishes the row.  Everything that crosses
+    // blocks (row sum, ticket) goes through device-scope atomics, one per block and address, so
+    // no cache flush is needed and few atomics queue up on one address.
+    __syncthreads();
+    const int my_node = path_row_of(a, b, j, path, len);
+    if (my_node < 0) return;  // block-uniform: no such path row
+    if (tid == 0) {
+        unsigned long long S = 0ull;
+        for (int q = 0; q < kPathThreads / 64; ++q) S += s_part[q];
+        // the returned value makes the thread wait until the addition has been performed
+        const unsigned long long old = atomicAdd(&a.rowS[(size_t)b * a.W + j], S);
+        asm volatile("" : : "v"((uint32_t)old));
+        const unsigned int ticket = atomicAdd(&a.done[(size_t)b * a.W + j], 1u);
+        s_last = ticket == (unsigned int)nseg - 1u;
+    }
+    __syncthreads();
+    if (!s_last || wave != 0) return;
+
+    // observation of this row (paper Sec. 4.1: top-k ids and probabilities)
+    {
+        const int src = a.mode == 0 ? b * a.N + my_node : b * a.W + j;
+        const float m = a.src_m[src];
+        const float s = normaliser_from_fixed(atomicAdd(&a.rowS[(size_t)b * a.W + j], 0ull));
+        if (lane < a.K) {
+            a.obs_idx[((size_t)b * a.W + j) * a.K + lane] = a.src_top_idx[(size_t)src * a.K + lane];
+            a.obs_p[((size_t)b * a.W + j) * a.K + lane] =
+                exact_exp2(scaled_offset(a.src_top_l[(size_t)src * a.K + lane], m, a.c)) / s;
+        }
+    }
+    if (a.mode != 0 || j != len - 1) return;
+
+    // residual state at the stop node: replay its accept sequence with exact probabilities
+    const int node = path[len - 1];
     const int row = b * a.N + node;
     const char *rowp = (const char *)a.logits + (size_t)row * (size_t)a.V * ES;
-
-    // ---- row maximum and top-K: from the row pass, or computed here
-    float m;
-    int32_t my_top = -1;
-    float my_topl = 0.0f;
-    if (a.mode == 0) {
-        m = a.row_m[row];
-        if (tid < a.K) { my_top = a.top_idx[(size_t)row * a.K + tid]; my_topl = a.top_l[(size_t)row * a.K + tid]; }
-    } else {
-        float s_unused;
-        wg_row_scan<DT, BS>(rowp, a.V, a.c, a.K, ps.scan, m, s_unused);
-        if (tid < a.K) { my_top = (int32_t)rank_key_id(ps.scan.top[tid]); my_topl = rank_key_value(ps.scan.top[tid]); }
-    }
-
-    // ---- exact normaliser and the observation (paper Sec. 4.1: top-k ids and probabilities)
-    const unsigned long long S = wg_row_exact_sum<DT, BS>(rowp, a.V, m, a.c, &ps.scan.acc64);
-    const float s = normaliser_from_fixed(S, fixed_bits(a.V));
-    if (tid < a.K) {
-        a.obs_idx[((size_t)b * a.W + j) * a.K + tid] = my_top;
-        a.obs_p[((size_t)b * a.W + j) * a.K + tid] = exact_exp2(scaled_offset(my_topl, m, a.c)) / s;
-    }
-    if (a.mode != 0) return;
-
-    // ---- replay the node's accept sequence with exact probabilities
-    const int nch_tree = a.tree.nchild[node];
+    const float m = a.src_m[row];
+    const float s = normaliser_from_fixed(atomicAdd(&a.rowS[(size_t)b * a.W + (len - 1)], 0ull));
     const int fc = a.tree.first_child[node];
-    int nch = 0;
-    if (a.draft_has[row] && a.draft_tok[row] >= 0)
-        for (int q = 0; q < nch_tree; ++q) { if (a.draft_tok[(size_t)b * a.N + fc + q] < 0) break; ++nch; }
-    if (tid == 0) { ps.nsup = 0; ps.rho = 1.0f; ps.best = ~0ull; }
-    __syncthreads();
-    if (nch > 0 && tid < 64) {
+    const int nch = a.draft_has[row];
+    float rho = 1.0f;
+    if (nch > 0) {
         int32_t my_id = -1;
         float my_mu = 0.0f, my_p = 0.0f;
-        if (tid < a.K) {
-            my_id = a.draft_qid[(size_t)row * a.K + tid];
-            my_mu = a.draft_qmu[(size_t)row * a.K + tid];
+        if (lane < a.K) {
+            my_id = a.draft_qid[(size_t)row * a.K + lane];
+            my_mu = a.draft_qmu[(size_t)row * a.K + lane];
             if ((uint32_t)my_id >= (uint32_t)a.V) { my_id = -1; my_mu = 0.0f; }
             else my_p = exact_exp2(scaled_offset(load_scalar<DT>(rowp, my_id), m, a.c)) / s;
         }
         NodeResult nr = wave_node_outcome(lane, a.K, my_id, my_mu, my_p, nch, a.draft_tok + (size_t)b * a.N + fc, a.seed,
-                                          (uint32_t)b, a.step, fc, ps.scan.tmp, false, 0.0f);
-        if (tid < a.K) { ps.sup_id[tid] = my_id; ps.sup_r[tid] = nr.r; }
-        if (tid == 0) {
-            ps.nsup = a.K;
-            ps.rho = nr.rho;
-            atomicAdd(&a.stats[kStatTests], (unsigned long long)nr.rounds);
-            if (nr.accepted != a.outcome[row]) atomicAdd(&a.stats[kStatMismatch], 1ull);
-        }
+                                          (uint32_t)b, a.step, fc, false, 0.0f);
+        if (lane < a.K) { a.res_id[(size_t)b * a.K + lane] = my_id; a.res_r[(size_t)b * a.K + lane] = nr.r; }
+        rho = nr.rho;
+        if (lane == 0 && nr.accepted != -1) atomicAdd(&a.stats[kStatMismatch], 1ull);  // the stop node rejects all
+    }
+    if (lane == 0) {
+        a.res_f[(size_t)b * 4 + 0] = rho; a.res_f[(size_t)b * 4 + 1] = s; a.res_f[(size_t)b * 4 + 2] = m;
+        a.res_i[(size_t)b * 4 + 0] = nch > 0 ? a.K : 0; a.res_i[(size_t)b * 4 + 1] = node; a.res_i[(size_t)b * 4 + 2] = len;
+        // accept tests along the path: rank + 1 at every accepted node, all children at the stop node
+        unsigned long long tests = (unsigned long long)nch;
+        for (int q = 0; q + 1 < len; ++q) tests += (unsigned long long)(oc[path[q]] + 1);
+        atomicAdd(&a.stats[kStatTests], tests);
+    }
+}
+
+// Fast approximations used only to rank tokens and to skip those that provably cannot win the
+// race; every token that may win is evaluated with the exact functions.
+__device__ __forceinline__ float fast_exp_time(float U)
+{
+    // -ln U: series in d = 1 - U (exact) close to 1, hardware log2 elsewhere
+    const float d = 1.0f - U;
+    const float ser = d * __builtin_fmaf(d, __builtin_fmaf(d, 0.33333334f, 0.5f), 1.0f);
+    const float lg = -0.6931472f * __builtin_amdgcn_logf(U);
+    return d < 0.0078125f ? ser : lg;
+}
+constexpr int kRaceSlots = 64;         // most race blocks per trajectory
+constexpr int kRaceVecs = 2;           // vectors per thread and round
+constexpr float kRaceMargin = 1.001f;  // the fast time is within 1e-4 relative of the exact one
+
+struct RaceShared {
+    int32_t sup_id[kMaxK];
+    float sup_r[kMaxK];
+    unsigned long long best;      // best exact key of the block
+    unsigned long long sup_mask;  // bit (vector index & 63) set if the vector may hold a stored id
+    int last;
+};
+
+// Exact finishing time of token v as a key (time bits, token); all ones if the token has no
+// residual mass.  Kept out of line: it runs for one or two tokens per thread only.
+__device__ __noinline__ unsigned long long race_exact_key(float l, uint32_t v, uint32_t uword, float m, float c, float s,
+                                                           float rho, const int32_t *sup_id, const float *sup_r, int nsup)
+{
+    float r = (exact_exp2(scaled_offset(l, m, c)) / s) * rho;
+    for (int q = 0; q < nsup; ++q) if (sup_id[q] == (int32_t)v) r = sup_r[q];
+    if (!(r > 0.0f)) return ~0ull;
+    const float xv = -exact_log(word_to_uniform(uword));
+    const float t = xv / r;
+    return ((unsigned long long)f2u(t) << 32) | (unsigned long long)v;
+}
+
+template <int DT>
+__global__ __launch_bounds__(kPathThreads) void race_kernel(PathArgs a)
+{
+    // Resample at the stop node (paper Sec. 3.2, "resampled from an adjusted distribution"):
+    // token v finishes at -ln(U_v) / r(v), r = residual target; the earliest wins, ties to the
+    // lowest id.
+    //
+    // Per round every thread estimates the finishing times of its tokens with the hardware
+    // exp2 / log2 / rcp, evaluates its own front-runner exactly, and the block's best exact time
+    // then bounds the winner: only tokens whose estimate is within the margin of that bound are
+    // evaluated exactly as well.  Tokens stored in the node's proposal (their residual differs
+    // from p * rho) are always evaluated exactly.
+    constexpr int ES = VecTraits<DT>::ES, EPV = VecTraits<DT>::EPV, BS = kPathThreads, NV = kRaceVecs;
+    __shared__ RaceShared rs;
+    const int seg = blockIdx.x, nseg = gridDim.x, b = blockIdx.y, tid = threadIdx.x, lane = tid & 63;
+    const int nsup = a.res_i[(size_t)b * 4 + 0], node = a.res_i[(size_t)b * 4 + 1], len = a.res_i[(size_t)b * 4 + 2];
+    const float rho = a.res_f[(size_t)b * 4 + 0], s = a.res_f[(size_t)b * 4 + 1], m = a.res_f[(size_t)b * 4 + 2];
+    const int row = b * a.N + node;
+    const char *rowp = (const char *)a.logits + (size_t)row * (size_t)a.V * ES;
+    const RowGeom g = row_geom<DT>(rowp, a.V);
+    if (tid == 0) { rs.best = (0x7F800000ull << 32) | 0xFFFFFFFFull; rs.sup_mask = 0ull; }  // time = +inf
+    __syncthreads();
+    if (tid < nsup) {
+        const int32_t id = a.res_id[(size_t)b * a.K + tid];
+        rs.sup_id[tid] = id;
+        rs.sup_r[tid] = a.res_r[(size_t)b * a.K + tid];
+        if (id >= g.head) atomicOr(&rs.sup_mask, 1ull << (((id - g.head) / EPV) & 63));
     }
     __syncthreads();
-    if (!is_stop) return;
-
-    // ---- resample at the stop node: exponential race over the vocabulary (paper Sec. 3.2,
-    //      "resampled from an adjusted distribution")
-    const int nsup = ps.nsup;
-    const float rho = ps.rho;
-    const RowGeom g = row_geom<DT>(rowp, a.V);
+    const unsigned long long sup_mask = rs.sup_mask;
+    const float scale_fast = rho / s;
     unsigned long long best = ~0ull;
-    auto consider = [&](float l, uint32_t v, const Philox4 &ph, bool near_support) {
-        float r = (exact_exp2(scaled_offset(l, m, a.c)) / s) * rho;
-        if (near_support)
-            for (int q = 0; q < nsup; ++q) if (ps.sup_id[q] == (int32_t)v) r = ps.sup_r[q];
-        if (r > 0.0f) {
-            const float xv = -exact_log(word_to_uniform(philox_word(ph, v & 3u)));
-            const float t = xv / r;
-            const unsigned long long key = ((unsigned long long)f2u(t) << 32) | (unsigned long long)v;
-            best = key < best ? key : best;
-        }
+
+    auto exact_token = [&](float l, uint32_t v, uint32_t uword, bool near_support) {
+        const unsigned long long key = race_exact_key(l, v, uword, m, a.c, s, rho, rs.sup_id, rs.sup_r, near_support ? nsup : 0);
+        if (key < best) best = key;
     };
-    int edge_id = -1;
-    if (tid < g.head) edge_id = tid;
-    else if (tid < g.head + g.ntail) edge_id = g.tail0 + (tid - g.head);
-    if (edge_id >= 0) {
-        Philox4 ph = philox_group(a.seed, (uint32_t)b, a.step, (uint32_t)node, (uint32_t)edge_id >> 2, kStreamBonus);
-        consider(load_scalar<DT>(rowp, edge_id), (uint32_t)edge_id, ph, true);
+    // the scalar edge elements and the stored ids: exact, by the first block
+    if (seg == 0) {
+        int edge_id = -1;
+        if (tid < g.head) edge_id = tid;
+        else if (tid < g.head + g.ntail) edge_id = g.tail0 + (tid - g.head);
+        if (edge_id >= 0) {
+            const Philox4 ph = philox_group(a.seed, (uint32_t)b, a.step, (uint32_t)node, (uint32_t)edge_id >> 2, kStreamBonus);
+            exact_token(load_scalar<DT>(rowp, edge_id), (uint32_t)edge_id, philox_word(ph, (uint32_t)edge_id & 3u), true);
+        }
+        if (tid >= 64 && tid < 64 + nsup) {
+            const uint32_t v = (uint32_t)rs.sup_id[tid - 64];
+            if (v < (uint32_t)a.V) {
+                const Philox4 ph = philox_group(a.seed, (uint32_t)b, a.step, (uint32_t)node, v >> 2, kStreamBonus);
+                exact_token(load_scalar<DT>(rowp, (int)v), v, philox_word(ph, v & 3u), true);
+            }
+        }
     }
-    for (int idx = tid; idx < g.nvec; idx += BS) {
-        float x[EPV];
-        unpack<DT>(g.vp[idx], x);
-        const uint32_t id0 = (uint32_t)(g.head + idx * EPV);
-        bool near_support = false;  // does a stored id fall into this vector?
-        for (int q = 0; q < nsup; ++q) near_support |= ((uint32_t)ps.sup_id[q] - id0) < (uint32_t)EPV;
-        uint32_t grp = 0xFFFFFFFFu;
-        Philox4 ph;
+
+    const int per = (g.nvec + nseg - 1) / nseg;
+    const int v0 = seg * per, v1 = (v0 + per < g.nvec) ? v0 + per : g.nvec;
+    const int vlast = v1 > v0 ? v1 - 1 : v0;
+    const int nrounds = (v1 - v0 + NV * BS - 1) / (NV * BS);  // block-uniform
+    for (int round = 0; round < nrounds; ++round) {
+        // ---- estimates of all tokens of this thread's vectors (kept in registers)
+        float tf[NV][EPV];
+        uint4 w[NV];
+        int vidx[NV];
+        unsigned long long front = ~0ull;  // (estimate, token) of the thread's front-runner
 #pragma unroll
-        for (int q = 0; q < EPV; ++q) {
-            const uint32_t v = id0 + q;
-            if ((v >> 2) != grp) { grp = v >> 2; ph = philox_group(a.seed, (uint32_t)b, a.step, (uint32_t)node, grp, kStreamBonus); }
-            consider(x[q], v, ph, near_support);
+        for (int u = 0; u < NV; ++u) {
+            vidx[u] = v0 + (round * NV + u) * BS + tid;
+            w[u] = g.vp[vidx[u] < vlast ? vidx[u] : vlast];
+        }
+#pragma unroll
+        for (int u = 0; u < NV; ++u) {
+            const bool valid = vidx[u] < v1;
+            float x[EPV];
+            unpack<DT>(w[u], x);
+            const uint32_t id0 = (uint32_t)(g.head + vidx[u] * EPV);
+            Philox4 ph = philox_group(a.seed, (uint32_t)b, a.step, (uint32_t)node, id0 >> 2, kStreamBonus);
+#pragma unroll
+            for (int q = 0; q < EPV; ++q) {
+                const uint32_t v = id0 + q;
+                if (q > 0 && (v & 3u) == 0u) ph = philox_group(a.seed, (uint32_t)b, a.step, (uint32_t)node, v >> 2, kStreamBonus);
+                const float rf = fast_exp2(scaled_offset(x[q], m, a.c)) * scale_fast;
+                const float t = fast_exp_time(word_to_uniform(philox_word(ph, v & 3u))) * __builtin_amdgcn_rcpf(rf);
+                tf[u][q] = valid ? t : __builtin_inff();
+                const unsigned long long k = ((unsigned long long)f2u(tf[u][q]) << 32) | v;
+                front = k < front ? k : front;
+            }
+        }
+        // ---- the front-runner, exactly (stored ids were handled above and are skipped here)
+        const uint32_t fv = (uint32_t)front;
+        if ((uint32_t)(front >> 32) < 0x7F800000u) {
+            const int fvec = ((int)fv - g.head) / EPV;
+            const bool in_sup = (sup_mask >> (fvec & 63)) & 1ull;
+            bool is_sup = false;
+            if (in_sup) for (int q = 0; q < nsup; ++q) is_sup |= rs.sup_id[q] == (int32_t)fv;
+            if (!is_sup) {
+                const Philox4 ph = philox_group(a.seed, (uint32_t)b, a.step, (uint32_t)node, fv >> 2, kStreamBonus);
+                exact_token(load_scalar<DT>(rowp, (int)fv), fv, philox_word(ph, fv & 3u), false);
+            }
+        }
+        atomicMin(&rs.best, best);
+        __syncthreads();
+        // ---- every other token whose estimate is not clearly behind the best exact time
+        const float bound = u2f((uint32_t)(rs.best >> 32)) * kRaceMargin;
+#pragma unroll
+        for (int u = 0; u < NV; ++u) {
+            const uint32_t id0 = (uint32_t)(g.head + vidx[u] * EPV);
+            const bool in_sup = (sup_mask >> (vidx[u] & 63)) & 1ull;
+#pragma unroll
+            for (int q = 0; q < EPV; ++q) {
+                const uint32_t v = id0 + q;
+                if (vidx[u] < v1 && !(tf[u][q] > bound) && v != fv) {
+                    bool is_sup = false;
+                    if (in_sup) for (int z = 0; z < nsup; ++z) is_sup |= rs.sup_id[z] == (int32_t)v;
+                    if (!is_sup) {
+                        const Philox4 ph = philox_group(a.seed, (uint32_t)b, a.step, (uint32_t)node, v >> 2, kStreamBonus);
+                        exact_token(load_scalar<DT>(rowp, (int)v), v, philox_word(ph, v & 3u), false);
+                    }
+                }
+            }
         }
     }
 #pragma unroll
@@ -955,9 +941,83 @@ __global__ __launch_bounds__(kPathThreads) void path_pass_kernel(PathPassArgs a)
         unsigned long long o = __shfl_xor(best, off);
         best = o < best ? o : best;
     }
-    if (lane == 0) atomicMin(&ps.best, best);
+    if (lane == 0) atomicMin(&rs.best, best);
     __syncthreads();
-    if (tid == 0) a.out_tok[(size_t)b * a.W + j] = (int32_t)(uint32_t)ps.best;
+    // Each block publishes its best key in a slot of its own (no two blocks queue on one address);
+    // the last block of the trajectory to arrive reduces the slots.  All of it goes through
+    // device-scope atomics, so no cache flush is needed.
+    if (tid == 0) {
+        const unsigned long long old = atomicExch(&a.race[(size_t)b * kRaceSlots + seg], rs.best);  // returned: performed
+        asm volatile("" : : "v"((uint32_t)old));
+        const unsigned int ticket = atomicAdd(&a.done[(size_t)a.B * a.W + b], 1u);
+        rs.last = ticket == (unsigned int)nseg - 1u;
+    }
+    __syncthreads();
+    if (!rs.last || tid >= 64) return;
+    unsigned long long win = ~0ull;
+    for (int q = lane; q < nseg; q += 64) {
+        const unsigned long long o = atomicAdd(&a.race[(size_t)b * kRaceSlots + q], 0ull);
+        win = o < win ? o : win;
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        unsigned long long o = __shfl_xor(win, off);
+        win = o < win ? o : win;
+    }
+    if (lane == 0) a.out_tok[(size_t)b * a.W + (len - 1)] = (int32_t)(uint32_t)win;
+}
+
+// Update mode: maximum and top-K of the given commit rows (one workgroup of 4 waves per row).
+struct CommitScanArgs {
+    const void *logits;
+    int B, N, V, K, W;
+    float c;
+    const int32_t *commit_row, *commit_len;
+    float *pr_m;          // [B*W]
+    int32_t *pr_top_idx;  // [B*W][K]
+    float *pr_top_l;      // [B*W][K]
+};
+
+template <int DT>
+__global__ __launch_bounds__(256) void commit_scan_kernel(CommitScanArgs a)
+{
+    constexpr int ES = VecTraits<DT>::ES;
+    __shared__ WaveScan wsh[4];
+    __shared__ int part_cnt[4];
+    const int j = blockIdx.x, b = blockIdx.y, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int cl = a.commit_len[b];
+    cl = cl < 0 ? 0 : (cl > a.W ? a.W : cl);
+    if (j >= cl) return;
+    const int node = a.commit_row[(size_t)b * a.W + j];
+    if (node < 0 || node >= a.N) return;
+    const char *rowp = (const char *)a.logits + ((size_t)b * a.N + node) * (size_t)a.V * ES;
+    WaveScan *ws = &wsh[wave];
+    const WavePartial wp = wave_row_stream<DT>(rowp, a.V, a.c, a.K, ws, lane, wave, 4);
+    if (lane == 0) part_cnt[wave] = wp.cnt;
+    __syncthreads();
+    if (wave != 0) return;
+    int cnt = part_cnt[0];
+    for (int q = 1; q < 4; ++q) {
+        const int cq = part_cnt[q];
+        if (lane < cq) ws->buf[cnt + lane] = wsh[q].buf[lane];
+        cnt += cq;
+    }
+    __builtin_amdgcn_wave_barrier();
+    wave_row_finish<DT>(rowp, a.V, a.K, ws, lane, cnt);
+    const size_t src = (size_t)b * a.W + j;
+    if (lane < a.K) {
+        a.pr_top_idx[src * a.K + lane] = (int32_t)rank_key_id(ws->top[lane]);
+        a.pr_top_l[src * a.K + lane] = rank_key_value(ws->top[lane]);
+    }
+    if (lane == 0) a.pr_m[src] = rank_key_value(ws->top[0]);
+}
+
+// clears the accumulators of the path pass
+__global__ void path_reset_kernel(int B, int W, unsigned long long *rowS, unsigned long long *race, unsigned int *done)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < B * W) { rowS[i] = 0ull; done[i] = 0u; }
+    if (i < B) done[B * W + i] = 0u;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -1077,22 +1137,21 @@ __global__ __launch_bounds__(64) void merge_apply_kernel(MergeArgs a)
                 bool act = lane < 32 ? (lane < K) : (lane < 32 + K);
                 float other = 0.0f;  // for stored lanes: the observation's value for the same id
                 bool dup = false;    // for observation lanes: id already stored
-                for (int q = 0; q < K; ++q) {
-                    const int32_t sid = __shfl(e_id, q);
-                    const int32_t oid = __shfl(o_id, 32 + q);
-                    const float op = __shfl(o_p, 32 + q);
-                    if (lane < 32 && act && oid == id) other = op;
-                    if (lane >= 32 && act && sid == id) dup = true;
+#pragma unroll
+                for (int q = 0; q < kMaxK; ++q) {
+                    const int32_t sid = __builtin_amdgcn_readlane(e_id, q);
+                    const int32_t oid = __builtin_amdgcn_readlane(o_id, 32 + q);
+                    const float op = u2f((uint32_t)__builtin_amdgcn_readlane((int)f2u(o_p), 32 + q));
+                    if (q < K && lane < 32 && act && oid == id) other = op;
+                    if (q < K && lane >= 32 && act && sid == id) dup = true;
                 }
                 float val;
                 if (lane < 32) { float t = cf * e_mu; t = t + other; val = t / denom; }
                 else { float t = cf * 0.0f; t = t + o_p; val = t / denom; act = act && !dup; }
                 const unsigned long long key = act ? rank_key(val, (uint32_t)id) : 0ull;
                 int rank = 0;
-                for (int q = 0; q < 64; ++q) {
-                    const unsigned long long ok = __shfl(key, q);
-                    rank += (ok > key) ? 1 : 0;
-                }
+#pragma unroll
+                for (int q = 0; q < 64; ++q) rank += readlane_u64(key, q) > key ? 1 : 0;
                 if (act && rank < K) { l_id[rank] = id; l_val[rank] = val; }
                 __syncthreads();
                 if (lane < K) { e_id = l_id[lane]; e_mu = l_val[lane]; }
@@ -1129,11 +1188,13 @@ struct DraftArgs {
     char *table;
     uint64_t mask;
     int slot_bytes, K, max_probe;
-    int B, omin, omax;
+    int B, W, omin, omax;
     uint64_t seed, step;
     TreeDev tree;
-    const int32_t *ctx_tail;
-    const long long *ctx_len;
+    int32_t *ctx_tail;
+    long long *ctx_len;
+    const int32_t *append_tok;   // [B][W] tokens to append to the contexts first, or NULL
+    const int32_t *append_len;   // [B]
     int32_t *draft_tok, *draft_has, *draft_qid;
     float *draft_qmu;
     int32_t *out_tok;  // caller's copy, may be NULL
@@ -1141,43 +1202,86 @@ struct DraftArgs {
 };
 
 constexpr int kDraftThreads = 256;
-constexpr int kMaxNodes = 256;
-constexpr int kMaxDepth = 31;
 
 __global__ __launch_bounds__(kDraftThreads) void draft_kernel(DraftArgs a)
 {
     __shared__ int32_t tok[kMaxNodes];
+    __shared__ int32_t tail[kMaxOrder];
+    __shared__ long long s_clen;
     const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int N = a.tree.N, K = a.K;
-    const long long clen = a.ctx_len[b];
+    if (tid == 0) {
+        // context tail of this trajectory, after appending the tokens committed by this step
+        int32_t t[kMaxOrder];
+        for (int i = 0; i < kMaxOrder; ++i) t[i] = a.ctx_tail[(size_t)b * kMaxOrder + i];
+        long long len = a.ctx_len[b];
+        if (a.append_tok) {
+            const int n = clamp_len(a.append_len[b], a.W);
+            for (int j = 0; j < n; ++j) {
+                for (int i = 0; i + 1 < kMaxOrder; ++i) t[i] = t[i + 1];
+                t[kMaxOrder - 1] = a.append_tok[(size_t)b * a.W + j];
+            }
+            len += n;
+            for (int i = 0; i < kMaxOrder; ++i) a.ctx_tail[(size_t)b * kMaxOrder + i] = t[i];
+            a.ctx_len[b] = len;
+        }
+        for (int i = 0; i < kMaxOrder; ++i) tail[i] = t[i];
+        s_clen = len;
+    }
     for (int u = tid; u < N; u += kDraftThreads) {
         tok[u] = -1;
         a.draft_has[(size_t)b * N + u] = 0;
     }
     __syncthreads();
-    if (tid == 0 && clen > 0) tok[0] = a.ctx_tail[(size_t)b * kMaxOrder + kMaxOrder - 1];
+    const long long clen = s_clen;
+    if (tid == 0 && clen > 0) tok[0] = tail[kMaxOrder - 1];
     __syncthreads();
+    const int NO = a.omax - a.omin + 1;
     for (int d = 0; d < a.tree.D; ++d) {
         const int lo = a.tree.level_start[d], hi = a.tree.level_start[d + 1];
         for (int u = lo + wave; u < hi; u += kDraftThreads / 64) {
             const int nch = a.tree.nchild[u];
             if (nch == 0 || tok[u] < 0) continue;  // uniform per wave
-            // lane q < NO looks up order n = omax - q
-            const int NO = a.omax - a.omin + 1;
-            long long hit_slot = -1;
+            // ---- multi-level lookup (paper Sec. 4.2): lane q < NO takes order n = omax - q.
+            // The home slot of every order is read together with its payload in one round
+            // trip; only a key that was displaced by linear probing needs further probes.
+            unsigned long long fp = 0ull;
             if (lane < NO) {
                 const int n = a.omax - lane;
                 if (clen + d >= n) {
                     int32_t key[kMaxOrder];
-                    // newest token first while walking up: position n-1 is the node's own token
                     int x = u;
                     for (int i = n - 1; i >= 0; --i) {
                         const int back = n - 1 - i;  // tokens back from the node itself
                         if (back < d) { key[i] = tok[x]; x = a.tree.parent[x]; }
-                        else key[i] = a.ctx_tail[(size_t)b * kMaxOrder + (kMaxOrder - 1 - (back - d))];
+                        else key[i] = tail[kMaxOrder - 1 - (back - d)];
                     }
-                    const unsigned long long fp = fingerprint(n, key);
-                    for (int i = 0; i < a.max_probe; ++i) {
+                    fp = fingerprint(n, key);
+                }
+            }
+            unsigned long long home_fp = 0ull;
+            uint32_t home_cnt = 0;
+            if (fp) {
+                const SlotHeader *h = slot_header(a.table, fp & a.mask, a.slot_bytes);
+                home_fp = h->fp;
+                home_cnt = h->count;
+            }
+            int32_t pid[kMaxOrder];
+            float pmu[kMaxOrder];
+#pragma unroll
+            for (int q = 0; q < kMaxOrder; ++q) {
+                pid[q] = -1; pmu[q] = 0.0f;
+                const unsigned long long fq = readlane_u64(fp, q);  // uniform
+                if (q < NO && fq && lane < K) {
+                    pid[q] = slot_ids(a.table, fq & a.mask, a.slot_bytes)[lane];
+                    pmu[q] = slot_mu(a.table, fq & a.mask, a.slot_bytes, K)[lane];
+                }
+            }
+            long long hit_slot = -1;
+            if (fp) {
+                if (home_fp == fp) { if (home_cnt > 0) hit_slot = (long long)(fp & a.mask); }
+                else if (home_fp != 0ull) {
+                    for (int i = 1; i < a.max_probe; ++i) {  // displaced key: keep probing
                         const uint64_t slot = (fp + (uint64_t)i) & a.mask;
                         const SlotHeader *h = slot_header(a.table, slot, a.slot_bytes);
                         const unsigned long long cur = h->fp;
@@ -1193,17 +1297,23 @@ __global__ __launch_bounds__(kDraftThreads) void draft_kernel(DraftArgs a)
             }
             const int win = __ffsll((long long)hits) - 1;  // lowest lane = longest order
             const long long slot = __shfl(hit_slot, win);
+            const unsigned long long win_fp = readlane_u64(fp, win);
             if (lane == 0) atomicAdd(&a.stats[kStatHits + (a.omax - win)], 1ull);
             int32_t id = -1;
             float mu = 0.0f;
-            if (lane < K) {
+            if ((unsigned long long)slot == (win_fp & a.mask)) {
+                // the payload fetched with the home slot is the entry's
+#pragma unroll
+                for (int q = 0; q < kMaxOrder; ++q) if (q == win) { id = pid[q]; mu = pmu[q]; }
+            } else if (lane < K) {
                 id = slot_ids(a.table, (uint64_t)slot, a.slot_bytes)[lane];
                 mu = slot_mu(a.table, (uint64_t)slot, a.slot_bytes, K)[lane];
+            }
+            if (lane < K) {
                 a.draft_qid[((size_t)b * N + u) * K + lane] = id;
                 a.draft_qmu[((size_t)b * N + u) * K + lane] = mu;
             }
-            if (lane == 0) a.draft_has[(size_t)b * N + u] = 1;
-            // Gumbel-Top-K: score = ln mu - ln(-ln U); children get the largest scores in order
+            // ---- Gumbel-Top-K: score = ln mu - ln(-ln U); children get the largest scores in order
             const bool cand = lane < K && mu > 0.0f;
             unsigned long long key = 0ull;
             if (cand) {
@@ -1212,11 +1322,11 @@ __global__ __launch_bounds__(kDraftThreads) void draft_kernel(DraftArgs a)
                 key = rank_key(exact_log(mu) - g, (uint32_t)id);
             }
             int rank = 0;
-            for (int q = 0; q < K; ++q) {
-                const unsigned long long ok = __shfl(key, q);
-                rank += (ok > key) ? 1 : 0;
-            }
+#pragma unroll
+            for (int q = 0; q < kMaxK; ++q) rank += readlane_u64(key, q) > key ? 1 : 0;
             if (cand && rank < nch) tok[a.tree.first_child[u] + rank] = id;
+            const int ncand = __popcll(__ballot(cand));
+            if (lane == 0) a.draft_has[(size_t)b * N + u] = ncand < nch ? ncand : nch;
         }
         __syncthreads();
     }

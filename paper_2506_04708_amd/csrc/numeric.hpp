@@ -99,33 +99,13 @@ __device__ __forceinline__ float scaled_offset(float l, float m, float c)
     return d * c;
 }
 
-// fixed-point contribution of one element to the row normaliser: floor(e * 2^F), e in [0, 1]
-__device__ __forceinline__ uint64_t fixed_contrib(float e, int F)
-{
-    // e = mant * 2^(ex - 150) with a 24-bit integer mantissa; shift it into place
-    uint32_t bits = f2u(e);
-    int ex = (int)(bits >> 23);
-    if (ex == 0) return 0;  // zero (exact_exp2 never returns subnormals)
-    uint64_t mant = (uint64_t)((bits & 0x007FFFFFu) | 0x00800000u);
-    int sh = ex - 150 + F;
-    if (sh >= 0) return mant << sh;
-    if (sh <= -24) return 0;
-    return mant >> (-sh);
-}
-
-__device__ __forceinline__ float normaliser_from_fixed(uint64_t S, int F)
+// The row normaliser is the integer S = sum_v floor(E(y_v) * 2^40) (V < 2^22, so S < 2^63);
+// s = (float)((double)S * 2^-40).
+__device__ __forceinline__ float normaliser_from_fixed(uint64_t S)
 {
     double d = (double)S;
-    d = __builtin_ldexp(d, -F);
+    d = __builtin_ldexp(d, -40);
     return (float)d;
-}
-
-__host__ __device__ inline int fixed_bits(int V)
-{
-    int lg = 0;
-    while (((int64_t)1 << lg) < (int64_t)V) ++lg;
-    int f = 62 - lg;
-    return f > 40 ? 40 : f;
 }
 
 // ---- ordering keys --------------------------------------------------------------------------
