@@ -91,8 +91,11 @@ def lib():
         L.so_verify_node.restype = C.c_int
         L.so_verify_node.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.POINTER(NodeState)]
         L.so_residual_dense.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.POINTER(NodeState), C.c_void_p]
-        L.so_race.restype = C.c_int32
-        L.so_race.argtypes = [C.c_void_p, C.c_int, C.c_uint64, C.c_uint32, C.c_uint64, C.c_uint32]
+        L.so_uniform_u64.restype = C.c_uint64
+        L.so_uniform_u64.argtypes = [C.c_uint64, C.c_uint32, C.c_uint64, C.c_uint32, C.c_uint32]
+        L.so_row_masses.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_float, C.c_void_p]
+        L.so_residual_draw.restype = C.c_int32
+        L.so_residual_draw.argtypes = [C.c_void_p, C.c_int, C.c_uint64, C.c_int, C.c_void_p, C.POINTER(NodeState), C.c_uint64]
         L.so_create.restype = C.c_void_p
         L.so_create.argtypes = [C.POINTER(_Config)]
         L.so_destroy.argtypes = [C.c_void_p]
@@ -119,7 +122,8 @@ def lib():
         L.so_mc_gumbel_topk.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_uint64, C.c_uint64, C.c_void_p]
         L.so_mc_node.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_int, C.c_uint64, C.c_uint64,
                                  C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
-        L.so_mc_race.argtypes = [C.c_void_p, C.c_int, C.c_uint64, C.c_uint64, C.c_void_p]
+        L.so_mc_draw.argtypes = [C.c_void_p, C.c_int, C.c_uint64, C.c_int, C.c_void_p, C.c_void_p, C.c_float,
+                                 C.c_uint64, C.c_uint64, C.c_void_p]
         _lib = L
     return _lib
 
@@ -230,9 +234,23 @@ def residual_dense(p, ids, st):
     return r
 
 
-def race(r, seed, b, step, node):
-    r = _f32(r)
-    return int(lib().so_race(_p(r), r.shape[0], seed, b, step, node))
+def uniform_u64(seed, b, step, node, stream):
+    return int(lib().so_uniform_u64(seed, b, step, node, stream))
+
+
+def row_masses(row, temperature):
+    row = np.ascontiguousarray(row)
+    F = np.empty(row.shape[0], np.uint64)
+    lib().so_row_masses(_p(row), _dtype_code(row), row.shape[0], temperature, _p(F))
+    return F
+
+
+def residual_draw(F, S, ids, st, u):
+    """st: NodeState or None (no proposal); ids may be empty when st is None."""
+    F = np.ascontiguousarray(F, np.uint64)
+    ids = _i32(ids)
+    return int(lib().so_residual_draw(_p(F), F.shape[0], int(S), ids.shape[0], _p(ids),
+                                      C.byref(st) if st is not None else None, int(u)))
 
 
 def mc_gumbel_topk(ids, mu, c, trials, seed):
@@ -255,10 +273,11 @@ def mc_node(p, ids, mu, c, trials, seed):
     return counts, acc.value, near.value, err.value, mn.value
 
 
-def mc_race(r, trials, seed):
-    r = _f32(r)
-    counts = np.zeros(r.shape[0], np.uint64)
-    lib().so_mc_race(_p(r), r.shape[0], trials, seed, _p(counts))
+def mc_draw(F, S, ids, r, rho, trials, seed):
+    F = np.ascontiguousarray(F, np.uint64)
+    ids, r = _i32(ids), _f32(r)
+    counts = np.zeros(F.shape[0], np.uint64)
+    lib().so_mc_draw(_p(F), F.shape[0], int(S), ids.shape[0], _p(ids), _p(r), float(rho), trials, seed, _p(counts))
     return counts
 
 

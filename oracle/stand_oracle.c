@@ -85,6 +85,18 @@ float so_uniform(uint64_t seed, uint32_t b, uint64_t step, uint32_t node, uint32
     return (float)(2u * (x >> 9) + 1u) * 0x1p-24f;
 }
 
+/* 64 uniform bits of (b, step, node, stream): words 0 and 1 of the block of token group 0. */
+uint64_t so_uniform_u64(uint64_t seed, uint32_t b, uint64_t step, uint32_t node, uint32_t stream)
+{
+    uint32_t ctr[4], out[4];
+    ctr[0] = 0u;
+    ctr[1] = node | (stream << 24);
+    ctr[2] = (uint32_t)step;
+    ctr[3] = b | ((uint32_t)(step >> 32) << 20);
+    philox4x32_10(ctr, seed, out);
+    return ((uint64_t)out[0] << 32) | (uint64_t)out[1];
+}
+
 /* ------------------------------------------------------------------------------------------
  * so_exp2(y) ~ 2^y for y <= small positive.  y < -64 gives exactly 0.
  * k = round-half-even(y), f = y - k in [-1/2, 1/2], 2^f = 1 + f*Q(f), Q of degree 5
@@ -189,6 +201,23 @@ void so_row_softmax(const void *row, int dtype, int V, float temperature,
     if (m_out) *m_out = m;
     if (s_out) *s_out = s;
     if (S_out) *S_out = S;
+}
+
+/* The integer terms of S: F_out[v] = floor(e_v * 2^F). */
+void so_row_masses(const void *row, int dtype, int V, float temperature, uint64_t *F_out)
+{
+    float c = so_scale(temperature);
+    float m = widen(row, dtype, 0);
+    for (int v = 1; v < V; ++v) {
+        float l = widen(row, dtype, v);
+        if (l > m) m = l;
+    }
+    int F = fx_bits(V);
+    for (int v = 0; v < V; ++v) {
+        float d = widen(row, dtype, v) - m;
+        float y = d * c;
+        F_out[v] = (uint64_t)floor(ldexp((double)so_exp2(y), F));
+    }
 }
 
 /* ------------------------------------------------------------------------------------------
@@ -401,20 +430,56 @@ void so_residual_dense(const float *p, int V, int K, const int32_t *ids, const s
     if (st) for (int i = 0; i < K; ++i) r_out[ids[i]] = st->r[i];
 }
 
-/* One token from a dense distribution r by an exponential race: token v finishes at
- * X_v / r(v), X_v = -ln U_v; the first to finish wins (the same law as argmax of
- * ln r + Gumbel noise).  Ties go to the lowest id. */
-int32_t so_race(const float *r, int V, uint64_t seed, uint32_t b, uint64_t step, uint32_t node)
+/* One token from the residual of a node (Sec. 3.2: on rejection, resample from the normalised
+ * positive part of target minus proposal), by inverting its cumulative mass in integers.
+ * Unit of mass: 2^-F / s * rho.  In it a token outside the support weighs F(v), the integer term
+ * it contributes to S (its residual is p(v) rho = e_v / s * rho); support token i weighs
+ * G_i = floor(r_i * (S / rho)), evaluated in binary64 (S and rho converted first, one division,
+ * one multiplication).  The entries are laid out as: the support tokens in stored order, then all
+ * tokens by id with the support left out.  With T the total mass and u uniform on [0, 2^64), the
+ * draw is the entry that covers position floor(u T / 2^64).  st == NULL (no proposal at the node)
+ * or T == 0 (the residual vanished): the draw is from the target, i.e. all tokens by id with F.
+ * Nothing depends on summation order. */
+int32_t so_residual_draw(const uint64_t *F, int V, uint64_t S, int K, const int32_t *ids,
+                         const so_node_state *st, uint64_t u)
 {
-    int32_t best = -1;
-    float best_t = 0.0f;
-    for (int v = 0; v < V; ++v) {
-        if (!(r[v] > 0.0f)) continue;
-        float x = -so_log(so_uniform(seed, b, step, node, (uint32_t)v, SO_STREAM_BONUS));
-        float t = x / r[v];
-        if (best < 0 || t < best_t) { best = v; best_t = t; }
+    uint64_t G[SO_MAX_K];
+    uint64_t total = 0;
+    int use_support = st != NULL;
+    if (use_support) {
+        double ratio = (double)S / (double)st->rho;
+        for (int i = 0; i < K; ++i) {
+            int valid = ids[i] >= 0 && ids[i] < V;
+            G[i] = valid ? (uint64_t)floor((double)st->r[i] * ratio) : 0;
+            total += G[i];
+        }
+        for (int v = 0; v < V; ++v) {
+            int in_support = 0;
+            for (int i = 0; i < K; ++i) if (ids[i] == v) in_support = 1;
+            if (!in_support) total += F[v];
+        }
+        if (total == 0) use_support = 0;
     }
-    return best;
+    if (!use_support) {
+        total = 0;
+        for (int v = 0; v < V; ++v) total += F[v];
+    }
+    uint64_t t = (uint64_t)(((unsigned __int128)u * (unsigned __int128)total) >> 64);
+    if (use_support)
+        for (int i = 0; i < K; ++i) {
+            if (t < G[i]) return ids[i];
+            t -= G[i];
+        }
+    for (int v = 0; v < V; ++v) {
+        if (use_support) {
+            int in_support = 0;
+            for (int i = 0; i < K; ++i) if (ids[i] == v) in_support = 1;
+            if (in_support) continue;
+        }
+        if (t < F[v]) return v;
+        t -= F[v];
+    }
+    return -1; /* not reached: t < total */
 }
 
 /* ==========================================================================================
@@ -751,13 +816,14 @@ void so_verify(so_handle *h, uint64_t step, const void *logits,
 {
     int N = h->N, K = h->K, V = h->V, W = h->D + 1;
     float *p = (float *)malloc(sizeof(float) * (size_t)V);
-    float *r = (float *)malloc(sizeof(float) * (size_t)V);
+    uint64_t *F = (uint64_t *)malloc(sizeof(uint64_t) * (size_t)V);
     for (int b = 0; b < h->B; ++b) {
         const int32_t *tok = h->draft_tok + (int64_t)b * N;
         const int32_t *has = h->draft_has + (int64_t)b * N;
         int cur = 0, len = 0;
         for (;;) {
-            so_row_softmax(row_ptr(h, logits, b, cur), h->cfg.logits_dtype, V, h->cfg.temperature, p, NULL, NULL, NULL);
+            uint64_t S;
+            so_row_softmax(row_ptr(h, logits, b, cur), h->cfg.logits_dtype, V, h->cfg.temperature, p, NULL, NULL, &S);
             int nc = 0;
             if (has[cur])
                 for (int j = 0; j < h->nchild[cur]; ++j) { if (tok[h->first_child[cur] + j] < 0) break; nc++; }
@@ -781,8 +847,10 @@ void so_verify(so_handle *h, uint64_t step, const void *logits,
                 cur = ch;
                 continue;
             }
-            so_residual_dense(p, V, K, qid, nc > 0 ? &st : NULL, r);
-            out_tok[(int64_t)b * W + len] = so_race(r, V, h->cfg.seed, (uint32_t)b, step, (uint32_t)cur);
+            so_row_masses(row_ptr(h, logits, b, cur), h->cfg.logits_dtype, V, h->cfg.temperature, F);
+            out_tok[(int64_t)b * W + len] = so_residual_draw(
+                F, V, S, K, qid, nc > 0 ? &st : NULL,
+                so_uniform_u64(h->cfg.seed, (uint32_t)b, step, (uint32_t)cur, SO_STREAM_BONUS));
             len++;
             break;
         }
@@ -791,7 +859,7 @@ void so_verify(so_handle *h, uint64_t step, const void *logits,
         h->st.tokens_emitted += (uint64_t)len;
     }
     free(p);
-    free(r);
+    free(F);
 }
 
 /* ------------------------------------------------------------------------------------------
@@ -902,6 +970,10 @@ void so_mc_node(const float *p, int V, int K, const int32_t *ids, const float *m
     float U[SO_MAX_K], om[SO_MAX_K];
     int32_t drawn[SO_MAX_K];
     float *r = (float *)malloc(sizeof(float) * (size_t)V);
+    /* masses of the given dense p on the grid the row masses live on: F(v) = floor(p(v) 2^40) */
+    uint64_t *F = (uint64_t *)malloc(sizeof(uint64_t) * (size_t)V);
+    uint64_t S = 0;
+    for (int v = 0; v < V; ++v) { F[v] = (uint64_t)floor(ldexp((double)p[v], 40)); S += F[v]; }
     *accepted = 0; *near = 0; *resid_err = 0.0; *resid_min = 0.0;
     for (uint64_t t = 0; t < trials; ++t) {
         for (int i = 0; i < K; ++i) U[i] = so_uniform(seed, 0, t, 0, (uint32_t)ids[i], SO_STREAM_DRAFT);
@@ -915,13 +987,20 @@ void so_mc_node(const float *p, int V, int K, const int32_t *ids, const float *m
         double sum = 0.0;
         for (int v = 0; v < V; ++v) { sum += (double)r[v]; if ((double)r[v] < *resid_min) *resid_min = (double)r[v]; }
         if (fabs(sum - 1.0) > *resid_err) *resid_err = fabs(sum - 1.0);
-        counts[so_race(r, V, seed, 0, t, 0)]++;
+        counts[so_residual_draw(F, V, S, K, ids, nd > 0 ? &st : NULL, so_uniform_u64(seed, 0, t, 0, SO_STREAM_BONUS))]++;
     }
     free(r);
+    free(F);
 }
 
-/* Frequencies of so_race on a fixed dense distribution. */
-void so_mc_race(const float *r, int V, uint64_t trials, uint64_t seed, uint64_t *counts)
+/* Frequencies of so_residual_draw: masses F, optional support (ids, r, rho) when K > 0. */
+void so_mc_draw(const uint64_t *F, int V, uint64_t S, int K, const int32_t *ids, const float *r, float rho,
+                uint64_t trials, uint64_t seed, uint64_t *counts)
 {
-    for (uint64_t t = 0; t < trials; ++t) counts[so_race(r, V, seed, 0, t, 0)]++;
+    so_node_state st;
+    memset(&st, 0, sizeof st);
+    for (int i = 0; i < K; ++i) st.r[i] = r[i];
+    st.rho = rho;
+    for (uint64_t t = 0; t < trials; ++t)
+        counts[so_residual_draw(F, V, S, K, ids, K > 0 ? &st : NULL, so_uniform_u64(seed, 0, t, 0, SO_STREAM_BONUS))]++;
 }

@@ -374,14 +374,86 @@ def test_verify_node_rule_by_hand():
     assert np.allclose(oracle.residual_dense(p, ids, st), [0.0, 0.0, 1.0], atol=1e-6)
 
 
-def test_race_samples_the_distribution():
-    r = _rand_dist(np.random.default_rng(9), 8)
-    r[2] = 0.0
-    r /= r.sum()
-    counts = oracle.mc_race(r, 400_000, seed=11)
-    assert counts[2] == 0
-    keep = r > 0
-    assert _chi(counts[keep], r[keep]) > 1e-3
+def _node_state(r, rho):
+    st = oracle.NodeState()
+    for i, x in enumerate(r):
+        st.r[i] = x
+    st.rho = rho
+    return st
+
+
+def test_residual_draw_inverts_the_cumulative_mass():
+    """Brute force on a tiny case: every position of [0, T) maps to the entry that covers it, in the
+    order support (stored order) then ids with the support left out; u -> floor(u T / 2^64)."""
+    F = np.array([5, 0, 7, 3, 2, 9], np.uint64)
+    S = int(F.sum())
+    ids = np.array([4, 1, 3], np.int32)
+    r = np.array([0.25, 0.0, 0.125], np.float32)
+    rho = np.float32(2.0)
+    st = _node_state(r, rho)
+    G = [int(math.floor(float(x) * (S / float(rho)))) for x in r]       # 3, 0, 1
+    assert G == [3, 0, 1]
+    layout = [4] * G[0] + [1] * G[1] + [3] * G[2]
+    for v in range(6):
+        if v not in (4, 1, 3):
+            layout += [v] * int(F[v])
+    T = len(layout)
+    assert T == 3 + 1 + 5 + 7 + 9
+    for pos in range(T):
+        # smallest and largest u that land on pos
+        lo = -(-(pos << 64) // T)
+        hi = (((pos + 1) << 64) - 1) // T
+        for u in (lo, hi):
+            assert (u * T) >> 64 == pos
+            assert oracle.residual_draw(F, S, ids, st, u) == layout[pos]
+    # no proposal: all tokens by id with their own mass
+    layout0 = [v for v in range(6) for _ in range(int(F[v]))]
+    for pos in range(S):
+        u = -(-(pos << 64) // S)
+        assert oracle.residual_draw(F, S, np.zeros(0, np.int32), None, u) == layout0[pos]
+    # vanished residual (support covers everything that has mass, r = 0): falls back to the target
+    F2 = np.array([0, 4, 0, 6], np.uint64)
+    st0 = _node_state([0.0, 0.0], np.float32(1.0))
+    got = {oracle.residual_draw(F2, 10, np.array([1, 3], np.int32), st0, u << 56) for u in range(256)}
+    assert got == {1, 3}
+    # ids outside the vocabulary carry no mass and mask nothing
+    stx = _node_state([0.5, 0.5], np.float32(1.0))
+    assert oracle.residual_draw(F2, 10, np.array([-1, 1], np.int32), stx, 0) == 1
+
+
+def test_residual_draw_samples_the_residual():
+    """Frequencies over the Philox stream against the distribution the masses define, and against
+    the dense residual of the accept/reject recursion (Sec. 3.2)."""
+    rng = np.random.default_rng(9)
+    V, K = 8, 4
+    p = _rand_dist(rng, V)
+    ids = np.array([6, 0, 3, 5], np.int32)
+    mu = np.array([0.5, 0.2, 0.2, 0.1], np.float32)
+    acc, st = oracle.verify_node(p, ids, mu, [6, 0], [0.999, 0.999])
+    assert acc == -1
+    dense = oracle.residual_dense(p, ids, st).astype(np.float64)
+    assert abs(dense.sum() - 1.0) < 1e-5
+    F = np.floor(p.astype(np.float64) * 2.0 ** 40).astype(np.uint64)
+    S = int(F.sum())
+    counts = oracle.mc_draw(F, S, ids, np.array([st.r[i] for i in range(K)], np.float32), st.rho, 400_000, seed=11)
+    keep = dense > 0
+    assert counts[~keep].sum() == 0
+    assert _chi(counts[keep], dense[keep]) > 1e-3
+    # without a proposal it samples p itself
+    counts = oracle.mc_draw(F, S, np.zeros(0, np.int32), np.zeros(0, np.float32), 1.0, 400_000, seed=12)
+    assert _chi(counts, p.astype(np.float64)) > 1e-3
+
+
+def test_row_masses_sum_to_the_normaliser():
+    rng = np.random.default_rng(4)
+    row = (rng.standard_normal(3001) * 3).astype(np.float32)
+    F = oracle.row_masses(row, 0.7)
+    p, m, s, S = oracle.row_softmax(row, 0.7)
+    assert int(F.sum()) == S and int(F.max()) == 1 << 40
+    assert np.allclose(F.astype(np.float64) / S, p, rtol=0, atol=2e-7)
+    u = oracle.uniform_u64(5, 1, 2, 3, oracle.STREAM_BONUS)
+    w = oracle.philox(5, 0, 3 | (oracle.STREAM_BONUS << 24), 2, 1)
+    assert u == (int(w[0]) << 32) | int(w[1])
 
 
 def test_two_level_tree_joint_distribution():
