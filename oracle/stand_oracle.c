@@ -437,8 +437,9 @@ void so_residual_dense(const float *p, int V, int K, const int32_t *ids, const s
  * G_i = floor(r_i * (S / rho)), evaluated in binary64 (S and rho converted first, one division,
  * one multiplication).  The entries are laid out as: the support tokens in stored order, then all
  * tokens by id with the support left out.  With T the total mass and u uniform on [0, 2^64), the
- * draw is the entry that covers position floor(u T / 2^64).  st == NULL (no proposal at the node)
- * or T == 0 (the residual vanished): the draw is from the target, i.e. all tokens by id with F.
+ * draw is the entry that covers position floor(u T / 2^64).  st == NULL (no proposal at the node),
+ * T == 0 (the residual vanished) or a state with sum_i r_i > 2 or rho not finite: the draw is from
+ * the target, i.e. all tokens by id with F.
  * Nothing depends on summation order. */
 int32_t so_residual_draw(const uint64_t *F, int V, uint64_t S, int K, const int32_t *ids,
                          const so_node_state *st, uint64_t u)
@@ -446,6 +447,9 @@ int32_t so_residual_draw(const uint64_t *F, int V, uint64_t S, int K, const int3
     uint64_t G[SO_MAX_K];
     uint64_t total = 0;
     int use_support = st != NULL;
+    /* a state that is no distribution any more (the normalising mass underflowed to the clamp)
+     * is not used; otherwise sum_i r_i <= 2 keeps every product below 2^63 */
+    if (use_support && (!(support_sum(st->r, K) <= 2.0f) || !(st->rho < INFINITY))) use_support = 0;
     if (use_support) {
         double ratio = (double)S / (double)st->rho;
         for (int i = 0; i < K; ++i) {

@@ -103,13 +103,22 @@ __device__ __forceinline__ float fast_exp2(float y) { return __builtin_amdgcn_ex
 // carry a relative error of at most eps and `near` reports a test that the error could flip.
 // ---------------------------------------------------------------------------------------------
 // Sum of the values of lanes 0..K-1 in lane order (one rounding per addition), the same in
-// every lane.  Lanes K..31 must hold +0, which leaves the sum unchanged.
-__device__ __forceinline__ float wave_ordered_sum(float x)
+// every lane.
+__device__ __forceinline__ float wave_ordered_sum(float x, int K)
 {
     float t = 0.0f;
-#pragma unroll
-    for (int i = 0; i < kMaxK; ++i) t = t + u2f((uint32_t)__builtin_amdgcn_readlane((int)f2u(x), i));
+    for (int i = 0; i < K; ++i) t = t + u2f((uint32_t)__builtin_amdgcn_readlane((int)f2u(x), i));
     return t;
+}
+// two such sums at once (independent chains)
+__device__ __forceinline__ void wave_ordered_sum2(float x, float y, int K, float &sx, float &sy)
+{
+    float t = 0.0f, v = 0.0f;
+    for (int i = 0; i < K; ++i) {
+        t = t + u2f((uint32_t)__builtin_amdgcn_readlane((int)f2u(x), i));
+        v = v + u2f((uint32_t)__builtin_amdgcn_readlane((int)f2u(y), i));
+    }
+    sx = t; sy = v;
 }
 
 // 64-bit key of lane i (i uniform)
@@ -122,33 +131,41 @@ __device__ __forceinline__ unsigned long long readlane_u64(unsigned long long v,
 
 struct NodeResult { int accepted; int rounds; bool near; float r; float rho; };
 
+// ch: the token of drafted child `lane` (lanes 0..nchild-1), so that the rounds wait on no memory.
 __device__ __forceinline__ NodeResult wave_node_outcome(int lane, int K, int32_t my_id, float my_mu, float my_p, int nchild,
-                                        const int32_t *child_tok, uint64_t seed, uint32_t b, uint64_t step,
-                                        int first_child, bool track_err, float eps)
+                                        int32_t ch, uint64_t seed, uint32_t b, uint64_t step, int first_child,
+                                        bool track_err, float eps)
 {
     NodeResult res;
     res.accepted = -1; res.rounds = 0; res.near = false;
     const bool act = lane < K;
+    nchild = nchild < kMaxK ? nchild : kMaxK;
+    if (lane >= nchild) ch = -1;
+    const float om_l = lane < nchild ? uniform(seed, b, step, (uint32_t)(first_child + lane), 0u, kStreamAccept) : 0.0f;
     float w = (act && my_mu > 0.0f) ? my_mu : 0.0f;
-    float zw = wave_ordered_sum(w);
+    float zw = wave_ordered_sum(w, K);
     w = zw > 0.0f ? w / zw : 0.0f;
     float r = act ? my_p : 0.0f;
     float rho = 1.0f;
     float err = track_err ? eps * r : 0.0f;
     for (int j = 0; j < nchild; ++j) {
-        const int32_t x = child_tok[j];
+        const int32_t x = __builtin_amdgcn_readlane(ch, j);
         if (x < 0) break;
         const unsigned long long mask = __ballot(act && my_id == x);
         if (!mask) break;
         const int i = __ffsll((long long)mask) - 1;
-        const float wi = __shfl(w, i), ri = __shfl(r, i), ei = __shfl(err, i);
-        const float om = uniform(seed, b, step, (uint32_t)(first_child + j), 0u, kStreamAccept);
+        const float wi = u2f((uint32_t)__builtin_amdgcn_readlane((int)f2u(w), i));
+        const float ri = u2f((uint32_t)__builtin_amdgcn_readlane((int)f2u(r), i));
+        const float ei = u2f((uint32_t)__builtin_amdgcn_readlane((int)f2u(err), i));
+        const float om = u2f((uint32_t)__builtin_amdgcn_readlane((int)f2u(om_l), j));
         const float lhs = om * wi;
         res.rounds++;
         if (track_err && fabsf(lhs - ri) <= ei + 4e-7f * ri) res.near = true;
         if (lhs < ri) { res.accepted = j; break; }
         const float mn = act ? (r < w ? r : w) : 0.0f;
-        const float M = wave_ordered_sum(mn);
+        const float w_next = lane == i ? 0.0f : w;  // the rejected token leaves the proposal
+        float M, zw2;
+        wave_ordered_sum2(mn, w_next, K, M, zw2);
         float Z = 1.0f - M;
         if (!(Z > 1e-30f)) Z = 1e-30f;
         float d = r - w;
@@ -163,9 +180,7 @@ __device__ __forceinline__ NodeResult wave_node_outcome(int lane, int K, int32_t
         }
         r = rn;
         rho = rho / Z;
-        if (lane == i) w = 0.0f;
-        const float zw2 = wave_ordered_sum(w);
-        w = zw2 > 0.0f ? w / zw2 : 0.0f;
+        w = zw2 > 0.0f ? w_next / zw2 : 0.0f;
     }
     res.r = r;
     res.rho = rho;
@@ -516,19 +531,11 @@ struct RowPassArgs {
     float *top_l, *top_p;       // [B*N][K]
     int32_t *outcome;           // [B*N] accepted child rank or -1
     unsigned long long *stats;
-    // accumulators of the path pass, cleared here for the kernels that follow
-    int W;
-    unsigned long long *rowS, *race;
-    unsigned int *done;
 };
 
 template <int DT>
 __global__ __launch_bounds__(kRowThreads) void row_pass_kernel(RowPassArgs a)
 {
-    if (blockIdx.x == 0) {
-        for (int i = threadIdx.x; i < a.B * a.W; i += kRowThreads) { a.rowS[i] = 0ull; a.done[i] = 0u; }
-        for (int i = threadIdx.x; i < a.B; i += kRowThreads) a.done[a.B * a.W + i] = 0u;
-    }
     constexpr int ES = VecTraits<DT>::ES;
     __shared__ WaveScan wsh[kRowThreads / 64];
     __shared__ float part_m[kRowThreads / 64], part_s[kRowThreads / 64];
@@ -592,15 +599,15 @@ __global__ __launch_bounds__(kRowThreads) void row_pass_kernel(RowPassArgs a)
         if ((uint32_t)my_id >= (uint32_t)a.V) { my_id = -1; my_mu = 0.0f; }  // never index outside the row
         else my_l = load_scalar<DT>(rowp, my_id);
     }
-    const int32_t *child_tok = a.draft_tok + (size_t)b * a.N + fc;
+    const int32_t ch = (lane < nch && lane < kMaxK && fc >= 0 && fc + lane < a.N) ? a.draft_tok[(size_t)b * a.N + fc + lane] : -1;
     const float e = (lane < a.K && my_id >= 0) ? exact_exp2(scaled_offset(my_l, m, a.c)) : 0.0f;
-    NodeResult nr = wave_node_outcome(lane, a.K, my_id, my_mu, e / s, nch, child_tok, a.seed, (uint32_t)b, a.step, fc,
+    NodeResult nr = wave_node_outcome(lane, a.K, my_id, my_mu, e / s, nch, ch, a.seed, (uint32_t)b, a.step, fc,
                                       true, kFastEps);
     if (nr.near) {
         // a test fell inside the error bound of the fast normaliser: decide with the exact one
         const unsigned long long S = wave_row_exact_sum<DT>(rowp, a.V, m, a.c, lane);
         const float sx = normaliser_from_fixed(S);
-        nr = wave_node_outcome(lane, a.K, my_id, my_mu, e / sx, nch, child_tok, a.seed, (uint32_t)b, a.step, fc, false,
+        nr = wave_node_outcome(lane, a.K, my_id, my_mu, e / sx, nch, ch, a.seed, (uint32_t)b, a.step, fc, false,
                                0.0f);
         if (lane == 0) atomicAdd(&a.stats[kStatNear], 1ull);
     }
@@ -610,17 +617,22 @@ __global__ __launch_bounds__(kRowThreads) void row_pass_kernel(RowPassArgs a)
 // ---------------------------------------------------------------------------------------------
 // Path pass.  The accepted path of trajectory b follows `outcome` from the root (verify), or is
 // given as commit rows (update).  For each path row the exact normaliser is needed (its
-// observation is stored in the table), for the last one also the resampled token.  The work is
-// cut into segments so that it spreads over all compute units:
-//   path_exact_kernel  block (seg, j, b): exact partial sum of a segment of path row j; the last
-//                      block of a trajectory to finish writes the observations of its path rows
-//                      and the residual state of its stop node
-//   race_kernel        block (seg, b): exponential race over a segment of the stop row; the last
-//                      block of a trajectory writes the winner
+// observation is stored in the table), for the last one also the resampled token.
+//   path_exact_kernel   block (seg, j, b): exact partial sum of a segment of path row j, stored in
+//                       seg_part; the segments spread a handful of rows over all compute units
+//   path_finish_kernel  block (j, b): adds the partial sums, writes the observation of the row;
+//                       at the stop row it replays the node with exact probabilities and draws the
+//                       resampled token by inverting the residual's cumulative integer mass.
+//                       Further blocks of the same launch claim the table slots of the merge,
+//                       which depends on the tokens of the path only.
+// Kernel boundaries are the only synchronisation between blocks.
 // ---------------------------------------------------------------------------------------------
+constexpr int kSegMax = 32;  // most segments per path row
+
 struct PathArgs {
     const void *logits;
     int B, N, V, K, W, mode;   // mode 0: verify (path from outcome), 1: update (rows given)
+    int nseg;                  // segments per path row (grid.x of path_exact_kernel)
     float c;
     uint64_t seed, step;
     TreeDev tree;
@@ -632,16 +644,17 @@ struct PathArgs {
     const int32_t *outcome;
     const int32_t *commit_row, *commit_len;  // mode 1
     int32_t *out_tok, *out_node, *out_len;   // mode 0
-    unsigned long long *rowS;  // [B][W] exact fixed-point sums, zero on entry of path_exact_kernel
-    unsigned long long *race;  // [B][kRaceSlots] best (time, token) of each race block
-    unsigned int *done;        // [B*W] finished blocks per path row, then [B] finished race blocks; zero on entry
+    unsigned long long *seg_part;  // [B][W][kSegMax] exact fixed-point partial sums
+    // record of the stop node of each trajectory, gathered by path_exact_kernel so that
+    // path_finish_kernel starts its replay after one round trip to memory
+    int32_t *stop_i;           // [B][4] node, path length, drafted children, first child
+    float *stop_m;             // [B] maximum of the stop row
+    int32_t *stop_qid;         // [B][kMaxK] stored ids of the stop node's proposal (-1: none)
+    float *stop_qmu;           // [B][kMaxK] their means
+    float *stop_ql;            // [B][kMaxK] the stop row's logits at these ids
+    int32_t *stop_child;       // [B][kMaxK] tokens of the drafted children (-1: none)
     int32_t *obs_idx;          // [B][W][K]
     float *obs_p;              // [B][W][K]
-    // residual state of the stop node: written by path_exact_kernel, read by race_kernel
-    int32_t *res_id;           // [B][K] stored ids of the stop node's proposal
-    float *res_r;              // [B][K] residual target on them
-    float *res_f;              // [B][4] rho, s, m of the stop row
-    int32_t *res_i;            // [B][4] number of stored ids (0: no proposal), stop node, path length
     unsigned long long *stats;
 };
 
@@ -667,15 +680,44 @@ __device__ __forceinline__ int resolve_path(const PathArgs &a, int b, int *path,
     return *len_sh;
 }
 
-__device__ __forceinline__ int path_row_of(const PathArgs &a, int b, int j, const int *path, int len)
+// tree node of path position j in update mode, or -1 if there is none
+__device__ __forceinline__ int commit_row_of(const PathArgs &a, int b, int j)
 {
-    // returns the tree node of path position j, or -1 if there is none
-    if (a.mode == 0) return j < len ? path[j] : -1;
     int cl = a.commit_len[b];
     cl = cl < 0 ? 0 : (cl > a.W ? a.W : cl);
     if (j >= cl) return -1;
     const int node = a.commit_row[(size_t)b * a.W + j];
     return (node < 0 || node >= a.N) ? -1 : node;
+}
+
+// Inclusive prefix sum over the 64 lanes of a wave, by data-parallel-primitive moves inside
+// rows of 16 lanes and two row broadcasts (no LDS traffic).  A lane without a source adds 0.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ unsigned long long dpp_fetch_u64(unsigned long long x)
+{
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)(uint32_t)x, CTRL, ROW_MASK, 0xF, false);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)(uint32_t)(x >> 32), CTRL, ROW_MASK, 0xF, false);
+    return ((unsigned long long)hi << 32) | lo;
+}
+__device__ __forceinline__ unsigned long long wave_inclusive_scan_u64(unsigned long long x)
+{
+    x += dpp_fetch_u64<0x111, 0xF>(x);  // row_shr:1
+    x += dpp_fetch_u64<0x112, 0xF>(x);  // row_shr:2
+    x += dpp_fetch_u64<0x114, 0xF>(x);  // row_shr:4
+    x += dpp_fetch_u64<0x118, 0xF>(x);  // row_shr:8
+    x += dpp_fetch_u64<0x142, 0xA>(x);  // row_bcast:15 into rows 1 and 3
+    x += dpp_fetch_u64<0x143, 0xC>(x);  // row_bcast:31 into rows 2 and 3
+    return x;
+}
+__device__ __forceinline__ unsigned long long wave_sum_u64(unsigned long long x)
+{
+    return readlane_u64(wave_inclusive_scan_u64(x), 63);
+}
+__device__ __forceinline__ unsigned long long fixed_mass(float e)
+{
+    uint32_t hi, lo;
+    fixed_split(e, hi, lo);
+    return ((unsigned long long)hi << 20) + lo;
 }
 
 template <int DT>
@@ -684,289 +726,102 @@ __global__ __launch_bounds__(kPathThreads) void path_exact_kernel(PathArgs a)
     constexpr int ES = VecTraits<DT>::ES;
     __shared__ int path[32];
     __shared__ int oc[kMaxNodes];
-    __shared__ int s_len, s_last;
+    __shared__ int s_len;
     __shared__ unsigned long long s_part[kPathThreads / 64];
-    const int seg = blockIdx.x, nseg = gridDim.x, j = blockIdx.y, b = blockIdx.z, tid = threadIdx.x;
+    const int seg = blockIdx.x, nseg = a.nseg, j = blockIdx.y, b = blockIdx.z, tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
-    const int len = a.mode == 0 ? resolve_path(a, b, path, oc, &s_len) : 0;
-    if (a.mode == 0 && seg == 0 && j == 0) {
+    if (seg == nseg) {
+        // ---- the extra block of a trajectory (verify only): outputs and the stop record
+        if (a.mode != 0 || j != 0) return;
+        const int len = resolve_path(a, b, path, oc, &s_len);
         // accepted tokens are the tokens of the path nodes after the root; the last emitted
-        // token (position len - 1) is written by race_kernel
+        // token (position len - 1) is written by path_finish_kernel
         if (tid < a.W) {
             a.out_node[(size_t)b * a.W + tid] = tid < len ? path[tid] : -1;
             if (tid + 1 < len) a.out_tok[(size_t)b * a.W + tid] = a.draft_tok[(size_t)b * a.N + path[tid + 1]];
             else if (tid >= len) a.out_tok[(size_t)b * a.W + tid] = -1;
         }
-        if (tid == 0) { a.out_len[b] = len; atomicAdd(&a.stats[kStatTokens], (unsigned long long)len); }
-    }
-    {
-        const int node = path_row_of(a, b, j, path, len);
-        if (node >= 0) {
-            const int row = b * a.N + node;
-            const char *rowp = (const char *)a.logits + (size_t)row * (size_t)a.V * ES;
-            const float m = a.src_m[a.mode == 0 ? row : b * a.W + j];
-            const RowGeom g = row_geom<DT>(rowp, a.V);
-            const int per = (g.nvec + nseg - 1) / nseg;
-            const int v0 = seg * per, v1 = (v0 + per < g.nvec) ? v0 + per : g.nvec;
-            unsigned long long S = thread_exact_partial<DT>(rowp, g, v0, v1, seg == 0, m, a.c, tid, kPathThreads);
-#pragma unroll
-            for (int off = 32; off > 0; off >>= 1) S += __shfl_xor(S, off);
-            if (lane == 0) s_part[wave] = S;
+        if (wave != 1) return;
+        const int node = path[len - 1];
+        const int row = b * a.N + node;
+        const char *rowp = (const char *)a.logits + (size_t)row * (size_t)a.V * ES;
+        const int fc = a.tree.first_child[node];
+        const int nch = a.draft_has[row];
+        const float m = a.src_m[row];
+        int32_t qid = -1, ch = -1;
+        float qmu = 0.0f, ql = 0.0f;
+        if (lane < a.K) { qid = a.draft_qid[(size_t)row * a.K + lane]; qmu = a.draft_qmu[(size_t)row * a.K + lane]; }
+        if (lane < nch && lane < kMaxK && fc >= 0 && fc + lane < a.N) ch = a.draft_tok[(size_t)b * a.N + fc + lane];
+        if ((uint32_t)qid >= (uint32_t)a.V) { qid = -1; qmu = 0.0f; }  // never index outside the row
+        else ql = load_scalar<DT>(rowp, qid);
+        if (lane < kMaxK) {
+            a.stop_qid[(size_t)b * kMaxK + lane] = qid; a.stop_qmu[(size_t)b * kMaxK + lane] = qmu;
+            a.stop_ql[(size_t)b * kMaxK + lane] = ql; a.stop_child[(size_t)b * kMaxK + lane] = ch;
         }
-    }
-    // ---- the last block of this row to get here finishes the row.  Everything that crosses
-    // blocks (row sum, ticket) goes through device-scope atomics, one per block and address, so
-    // no cache flush is needed and few atomics queue up on one address.
-    __syncthreads();
-    const int my_node = path_row_of(a, b, j, path, len);
-    if (my_node < 0) return;  // block-uniform: no such path row
-    if (tid == 0) {
-        unsigned long long S = 0ull;
-        for (int q = 0; q < kPathThreads / 64; ++q) S += s_part[q];
-        // the returned value makes the thread wait until the addition has been performed
-        const unsigned long long old = atomicAdd(&a.rowS[(size_t)b * a.W + j], S);
-        asm volatile("" : : "v"((uint32_t)old));
-        const unsigned int ticket = atomicAdd(&a.done[(size_t)b * a.W + j], 1u);
-        s_last = ticket == (unsigned int)nseg - 1u;
-    }
-    __syncthreads();
-    if (!s_last || wave != 0) return;
-
-    // observation of this row (paper Sec. 4.1: top-k ids and probabilities)
-    {
-        const int src = a.mode == 0 ? b * a.N + my_node : b * a.W + j;
-        const float m = a.src_m[src];
-        const float s = normaliser_from_fixed(atomicAdd(&a.rowS[(size_t)b * a.W + j], 0ull));
-        if (lane < a.K) {
-            a.obs_idx[((size_t)b * a.W + j) * a.K + lane] = a.src_top_idx[(size_t)src * a.K + lane];
-            a.obs_p[((size_t)b * a.W + j) * a.K + lane] =
-                exact_exp2(scaled_offset(a.src_top_l[(size_t)src * a.K + lane], m, a.c)) / s;
+        if (lane == 0) {
+            a.stop_i[(size_t)b * 4 + 0] = node; a.stop_i[(size_t)b * 4 + 1] = len;
+            a.stop_i[(size_t)b * 4 + 2] = nch; a.stop_i[(size_t)b * 4 + 3] = fc;
+            a.stop_m[b] = m;
+            a.out_len[b] = len;
+            // accept tests along the path: rank + 1 at every accepted node, all children at the stop node
+            unsigned long long tests = (unsigned long long)nch;
+            for (int q = 0; q + 1 < len; ++q) tests += (unsigned long long)(oc[path[q]] + 1);
+            atomicAdd(&a.stats[kStatTokens], (unsigned long long)len);
+            atomicAdd(&a.stats[kStatTests], tests);
         }
+        return;
     }
-    if (a.mode != 0 || j != len - 1) return;
-
-    // residual state at the stop node: replay its accept sequence with exact probabilities
-    const int node = path[len - 1];
+    // ---- partial sum of segment seg of path row j; the root row needs no walk
+    int node;
+    if (a.mode != 0) node = commit_row_of(a, b, j);
+    else if (j == 0) node = 0;
+    else {
+        const int len = resolve_path(a, b, path, oc, &s_len);
+        node = j < len ? path[j] : -1;
+    }
+    if (node < 0) return;  // block-uniform: no such path row
     const int row = b * a.N + node;
     const char *rowp = (const char *)a.logits + (size_t)row * (size_t)a.V * ES;
-    const float m = a.src_m[row];
-    const float s = normaliser_from_fixed(atomicAdd(&a.rowS[(size_t)b * a.W + (len - 1)], 0ull));
-    const int fc = a.tree.first_child[node];
-    const int nch = a.draft_has[row];
-    float rho = 1.0f;
-    if (nch > 0) {
-        int32_t my_id = -1;
-        float my_mu = 0.0f, my_p = 0.0f;
-        if (lane < a.K) {
-            my_id = a.draft_qid[(size_t)row * a.K + lane];
-            my_mu = a.draft_qmu[(size_t)row * a.K + lane];
-            if ((uint32_t)my_id >= (uint32_t)a.V) { my_id = -1; my_mu = 0.0f; }
-            else my_p = exact_exp2(scaled_offset(load_scalar<DT>(rowp, my_id), m, a.c)) / s;
-        }
-        NodeResult nr = wave_node_outcome(lane, a.K, my_id, my_mu, my_p, nch, a.draft_tok + (size_t)b * a.N + fc, a.seed,
-                                          (uint32_t)b, a.step, fc, false, 0.0f);
-        if (lane < a.K) { a.res_id[(size_t)b * a.K + lane] = my_id; a.res_r[(size_t)b * a.K + lane] = nr.r; }
-        rho = nr.rho;
-        if (lane == 0 && nr.accepted != -1) atomicAdd(&a.stats[kStatMismatch], 1ull);  // the stop node rejects all
-    }
-    if (lane == 0) {
-        a.res_f[(size_t)b * 4 + 0] = rho; a.res_f[(size_t)b * 4 + 1] = s; a.res_f[(size_t)b * 4 + 2] = m;
-        a.res_i[(size_t)b * 4 + 0] = nch > 0 ? a.K : 0; a.res_i[(size_t)b * 4 + 1] = node; a.res_i[(size_t)b * 4 + 2] = len;
-        // accept tests along the path: rank + 1 at every accepted node, all children at the stop node
-        unsigned long long tests = (unsigned long long)nch;
-        for (int q = 0; q + 1 < len; ++q) tests += (unsigned long long)(oc[path[q]] + 1);
-        atomicAdd(&a.stats[kStatTests], tests);
+    const float m = a.src_m[a.mode == 0 ? row : b * a.W + j];
+    const RowGeom g = row_geom<DT>(rowp, a.V);
+    const int per = (g.nvec + nseg - 1) / nseg;
+    const int v0 = seg * per < g.nvec ? seg * per : g.nvec;
+    const int v1 = (v0 + per < g.nvec) ? v0 + per : g.nvec;
+    unsigned long long S = thread_exact_partial<DT>(rowp, g, v0, v1, seg == 0, m, a.c, tid, kPathThreads);
+    S = wave_sum_u64(S);
+    if (lane == 0) s_part[wave] = S;
+    __syncthreads();
+    if (tid == 0) {
+        unsigned long long t = 0ull;
+        for (int q = 0; q < kPathThreads / 64; ++q) t += s_part[q];
+        a.seg_part[((size_t)b * a.W + j) * kSegMax + seg] = t;
     }
 }
 
-// Fast approximations used only to rank tokens and to skip those that provably cannot win the
-// race; every token that may win is evaluated with the exact functions.
-__device__ __forceinline__ float fast_exp_time(float U)
-{
-    // -ln U: series in d = 1 - U (exact) close to 1, hardware log2 elsewhere
-    const float d = 1.0f - U;
-    const float ser = d * __builtin_fmaf(d, __builtin_fmaf(d, 0.33333334f, 0.5f), 1.0f);
-    const float lg = -0.6931472f * __builtin_amdgcn_logf(U);
-    return d < 0.0078125f ? ser : lg;
-}
-constexpr int kRaceSlots = 64;         // most race blocks per trajectory
-constexpr int kRaceVecs = 2;           // vectors per thread and round
-constexpr float kRaceMargin = 1.001f;  // the fast time is within 1e-4 relative of the exact one
-
-struct RaceShared {
-    int32_t sup_id[kMaxK];
-    float sup_r[kMaxK];
-    unsigned long long best;      // best exact key of the block
-    unsigned long long sup_mask;  // bit (vector index & 63) set if the vector may hold a stored id
-    int last;
+struct FinishShared {
+    unsigned long long P[kSegMax + 2];  // masked mass of: head elements, vector segments, tail elements
+    unsigned long long wave_tot[kPathThreads / 64];
+    unsigned long long rem;             // position inside the chosen segment
+    int32_t sup_id[kMaxK];              // stored ids that lie inside the chosen segment
+    int nsup, seg, found;
 };
 
-// Exact finishing time of token v as a key (time bits, token); all ones if the token has no
-// residual mass.  Kept out of line: it runs for one or two tokens per thread only.
-__device__ __noinline__ unsigned long long race_exact_key(float l, uint32_t v, uint32_t uword, float m, float c, float s,
-                                                           float rho, const int32_t *sup_id, const float *sup_r, int nsup)
-{
-    float r = (exact_exp2(scaled_offset(l, m, c)) / s) * rho;
-    for (int q = 0; q < nsup; ++q) if (sup_id[q] == (int32_t)v) r = sup_r[q];
-    if (!(r > 0.0f)) return ~0ull;
-    const float xv = -exact_log(word_to_uniform(uword));
-    const float t = xv / r;
-    return ((unsigned long long)f2u(t) << 32) | (unsigned long long)v;
-}
-
+// masked integer masses of the EPV elements of vector idx (elements e0 .. e0 + EPV - 1 of the row)
 template <int DT>
-__global__ __launch_bounds__(kPathThreads) void race_kernel(PathArgs a)
+__device__ __forceinline__ void vector_masses(const uint4 &w, int e0, float m, float c, const FinishShared &sh,
+                                              unsigned long long *f)
 {
-    // Resample at the stop node (paper Sec. 3.2, "resampled from an adjusted distribution"):
-    // token v finishes at -ln(U_v) / r(v), r = residual target; the earliest wins, ties to the
-    // lowest id.
-    //
-    // Per round every thread estimates the finishing times of its tokens with the hardware
-    // exp2 / log2 / rcp, evaluates its own front-runner exactly, and the block's best exact time
-    // then bounds the winner: only tokens whose estimate is within the margin of that bound are
-    // evaluated exactly as well.  Tokens stored in the node's proposal (their residual differs
-    // from p * rho) are always evaluated exactly.
-    constexpr int ES = VecTraits<DT>::ES, EPV = VecTraits<DT>::EPV, BS = kPathThreads, NV = kRaceVecs;
-    __shared__ RaceShared rs;
-    const int seg = blockIdx.x, nseg = gridDim.x, b = blockIdx.y, tid = threadIdx.x, lane = tid & 63;
-    const int nsup = a.res_i[(size_t)b * 4 + 0], node = a.res_i[(size_t)b * 4 + 1], len = a.res_i[(size_t)b * 4 + 2];
-    const float rho = a.res_f[(size_t)b * 4 + 0], s = a.res_f[(size_t)b * 4 + 1], m = a.res_f[(size_t)b * 4 + 2];
-    const int row = b * a.N + node;
-    const char *rowp = (const char *)a.logits + (size_t)row * (size_t)a.V * ES;
-    const RowGeom g = row_geom<DT>(rowp, a.V);
-    if (tid == 0) { rs.best = (0x7F800000ull << 32) | 0xFFFFFFFFull; rs.sup_mask = 0ull; }  // time = +inf
-    __syncthreads();
-    if (tid < nsup) {
-        const int32_t id = a.res_id[(size_t)b * a.K + tid];
-        rs.sup_id[tid] = id;
-        rs.sup_r[tid] = a.res_r[(size_t)b * a.K + tid];
-        if (id >= g.head) atomicOr(&rs.sup_mask, 1ull << (((id - g.head) / EPV) & 63));
-    }
-    __syncthreads();
-    const unsigned long long sup_mask = rs.sup_mask;
-    const float scale_fast = rho / s;
-    unsigned long long best = ~0ull;
-
-    auto exact_token = [&](float l, uint32_t v, uint32_t uword, bool near_support) {
-        const unsigned long long key = race_exact_key(l, v, uword, m, a.c, s, rho, rs.sup_id, rs.sup_r, near_support ? nsup : 0);
-        if (key < best) best = key;
-    };
-    // the scalar edge elements and the stored ids: exact, by the first block
-    if (seg == 0) {
-        int edge_id = -1;
-        if (tid < g.head) edge_id = tid;
-        else if (tid < g.head + g.ntail) edge_id = g.tail0 + (tid - g.head);
-        if (edge_id >= 0) {
-            const Philox4 ph = philox_group(a.seed, (uint32_t)b, a.step, (uint32_t)node, (uint32_t)edge_id >> 2, kStreamBonus);
-            exact_token(load_scalar<DT>(rowp, edge_id), (uint32_t)edge_id, philox_word(ph, (uint32_t)edge_id & 3u), true);
-        }
-        if (tid >= 64 && tid < 64 + nsup) {
-            const uint32_t v = (uint32_t)rs.sup_id[tid - 64];
-            if (v < (uint32_t)a.V) {
-                const Philox4 ph = philox_group(a.seed, (uint32_t)b, a.step, (uint32_t)node, v >> 2, kStreamBonus);
-                exact_token(load_scalar<DT>(rowp, (int)v), v, philox_word(ph, v & 3u), true);
-            }
-        }
-    }
-
-    const int per = (g.nvec + nseg - 1) / nseg;
-    const int v0 = seg * per, v1 = (v0 + per < g.nvec) ? v0 + per : g.nvec;
-    const int vlast = v1 > v0 ? v1 - 1 : v0;
-    const int nrounds = (v1 - v0 + NV * BS - 1) / (NV * BS);  // block-uniform
-    for (int round = 0; round < nrounds; ++round) {
-        // ---- estimates of all tokens of this thread's vectors (kept in registers)
-        float tf[NV][EPV];
-        uint4 w[NV];
-        int vidx[NV];
-        unsigned long long front = ~0ull;  // (estimate, token) of the thread's front-runner
-#pragma unroll
-        for (int u = 0; u < NV; ++u) {
-            vidx[u] = v0 + (round * NV + u) * BS + tid;
-            w[u] = g.vp[vidx[u] < vlast ? vidx[u] : vlast];
-        }
-#pragma unroll
-        for (int u = 0; u < NV; ++u) {
-            const bool valid = vidx[u] < v1;
-            float x[EPV];
-            unpack<DT>(w[u], x);
-            const uint32_t id0 = (uint32_t)(g.head + vidx[u] * EPV);
-            Philox4 ph = philox_group(a.seed, (uint32_t)b, a.step, (uint32_t)node, id0 >> 2, kStreamBonus);
-#pragma unroll
-            for (int q = 0; q < EPV; ++q) {
-                const uint32_t v = id0 + q;
-                if (q > 0 && (v & 3u) == 0u) ph = philox_group(a.seed, (uint32_t)b, a.step, (uint32_t)node, v >> 2, kStreamBonus);
-                const float rf = fast_exp2(scaled_offset(x[q], m, a.c)) * scale_fast;
-                const float t = fast_exp_time(word_to_uniform(philox_word(ph, v & 3u))) * __builtin_amdgcn_rcpf(rf);
-                tf[u][q] = valid ? t : __builtin_inff();
-                const unsigned long long k = ((unsigned long long)f2u(tf[u][q]) << 32) | v;
-                front = k < front ? k : front;
-            }
-        }
-        // ---- the front-runner, exactly (stored ids were handled above and are skipped here)
-        const uint32_t fv = (uint32_t)front;
-        if ((uint32_t)(front >> 32) < 0x7F800000u) {
-            const int fvec = ((int)fv - g.head) / EPV;
-            const bool in_sup = (sup_mask >> (fvec & 63)) & 1ull;
-            bool is_sup = false;
-            if (in_sup) for (int q = 0; q < nsup; ++q) is_sup |= rs.sup_id[q] == (int32_t)fv;
-            if (!is_sup) {
-                const Philox4 ph = philox_group(a.seed, (uint32_t)b, a.step, (uint32_t)node, fv >> 2, kStreamBonus);
-                exact_token(load_scalar<DT>(rowp, (int)fv), fv, philox_word(ph, fv & 3u), false);
-            }
-        }
-        atomicMin(&rs.best, best);
-        __syncthreads();
-        // ---- every other token whose estimate is not clearly behind the best exact time
-        const float bound = u2f((uint32_t)(rs.best >> 32)) * kRaceMargin;
-#pragma unroll
-        for (int u = 0; u < NV; ++u) {
-            const uint32_t id0 = (uint32_t)(g.head + vidx[u] * EPV);
-            const bool in_sup = (sup_mask >> (vidx[u] & 63)) & 1ull;
-#pragma unroll
-            for (int q = 0; q < EPV; ++q) {
-                const uint32_t v = id0 + q;
-                if (vidx[u] < v1 && !(tf[u][q] > bound) && v != fv) {
-                    bool is_sup = false;
-                    if (in_sup) for (int z = 0; z < nsup; ++z) is_sup |= rs.sup_id[z] == (int32_t)v;
-                    if (!is_sup) {
-                        const Philox4 ph = philox_group(a.seed, (uint32_t)b, a.step, (uint32_t)node, v >> 2, kStreamBonus);
-                        exact_token(load_scalar<DT>(rowp, (int)v), v, philox_word(ph, v & 3u), false);
-                    }
-                }
-            }
-        }
+    constexpr int EPV = VecTraits<DT>::EPV;
+    float x[EPV];
+    unpack<DT>(w, x);
+    uint32_t bits = 0u;
+    for (int q = 0; q < sh.nsup; ++q) {
+        const uint32_t d = (uint32_t)(sh.sup_id[q] - e0);
+        if (d < (uint32_t)EPV) bits |= 1u << d;
     }
 #pragma unroll
-    for (int off = 32; off > 0; off >>= 1) {
-        unsigned long long o = __shfl_xor(best, off);
-        best = o < best ? o : best;
-    }
-    if (lane == 0) atomicMin(&rs.best, best);
-    __syncthreads();
-    // Each block publishes its best key in a slot of its own (no two blocks queue on one address);
-    // the last block of the trajectory to arrive reduces the slots.  All of it goes through
-    // device-scope atomics, so no cache flush is needed.
-    if (tid == 0) {
-        const unsigned long long old = atomicExch(&a.race[(size_t)b * kRaceSlots + seg], rs.best);  // returned: performed
-        asm volatile("" : : "v"((uint32_t)old));
-        const unsigned int ticket = atomicAdd(&a.done[(size_t)a.B * a.W + b], 1u);
-        rs.last = ticket == (unsigned int)nseg - 1u;
-    }
-    __syncthreads();
-    if (!rs.last || tid >= 64) return;
-    unsigned long long win = ~0ull;
-    for (int q = lane; q < nseg; q += 64) {
-        const unsigned long long o = atomicAdd(&a.race[(size_t)b * kRaceSlots + q], 0ull);
-        win = o < win ? o : win;
-    }
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) {
-        unsigned long long o = __shfl_xor(win, off);
-        win = o < win ? o : win;
-    }
-    if (lane == 0) a.out_tok[(size_t)b * a.W + (len - 1)] = (int32_t)(uint32_t)win;
+    for (int q = 0; q < EPV; ++q) f[q] = ((bits >> q) & 1u) ? 0ull : fixed_mass(exact_exp2(scaled_offset(x[q], m, c)));
 }
-
 // Update mode: maximum and top-K of the given commit rows (one workgroup of 4 waves per row).
 struct CommitScanArgs {
     const void *logits;
@@ -1012,14 +867,6 @@ __global__ __launch_bounds__(256) void commit_scan_kernel(CommitScanArgs a)
     if (lane == 0) a.pr_m[src] = rank_key_value(ws->top[0]);
 }
 
-// clears the accumulators of the path pass
-__global__ void path_reset_kernel(int B, int W, unsigned long long *rowS, unsigned long long *race, unsigned int *done)
-{
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < B * W) { rowS[i] = 0ull; done[i] = 0u; }
-    if (i < B) done[B * W + i] = 0u;
-}
-
 // ---------------------------------------------------------------------------------------------
 // Table merge (paper Sec. 4.1): claim a slot per record, then apply the records of each slot in
 // record order (b, then position, then order ascending).
@@ -1043,10 +890,10 @@ struct MergeArgs {
 
 __device__ __forceinline__ int clamp_len(int len, int W) { return len < 0 ? 0 : (len > W ? W : len); }
 
-__global__ void merge_claim_kernel(MergeArgs a)
+// claims the table slot of merge record rec = (b, position j, order n); run by one thread
+__device__ __forceinline__ void merge_claim_record(const MergeArgs &a, int rec)
 {
     const int NO = a.omax - a.omin + 1;
-    const int rec = blockIdx.x * blockDim.x + threadIdx.x;
     if (rec >= a.B * a.W * NO) return;
     const int n = a.omin + rec % NO;
     const int j = (rec / NO) % a.W;
@@ -1086,6 +933,243 @@ __global__ void merge_claim_kernel(MergeArgs a)
         if (!placed) atomicAdd(&a.stats[kStatDrops], 1ull);
     }
     a.rec_slot[rec] = slot_out;
+}
+
+__global__ void merge_claim_kernel(MergeArgs a) { merge_claim_record(a, blockIdx.x * blockDim.x + threadIdx.x); }
+
+// See the comment above PathArgs.  Blocks [0, finish_blocks) finish path row (b, j) =
+// (block / W, block % W); the blocks after them claim merge records, kPathThreads per block.
+template <int DT>
+__global__ __launch_bounds__(kPathThreads) void path_finish_kernel(PathArgs a, MergeArgs mg, int finish_blocks)
+{
+    constexpr int ES = VecTraits<DT>::ES, EPV = VecTraits<DT>::EPV;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    if ((int)blockIdx.x >= finish_blocks) {
+        merge_claim_record(mg, ((int)blockIdx.x - finish_blocks) * kPathThreads + tid);
+        return;
+    }
+    __shared__ FinishShared sh;
+    const int j = (int)blockIdx.x % a.W, b = (int)blockIdx.x / a.W;
+    // Everything whose address depends on (b, j) only is requested at once: the partial sums and,
+    // in verify mode, the stop record of the trajectory (used if this turns out to be its stop row).
+    const int nseg = a.nseg;
+    const unsigned long long part = (wave == 0 && lane < nseg) ? a.seg_part[((size_t)b * a.W + j) * kSegMax + lane] : 0ull;
+    int len = 0, node, nch = 0, fc = -1;
+    int32_t my_id = -1, ch = -1;
+    float my_mu = 0.0f, my_l = 0.0f, m;
+    if (a.mode == 0) {
+        const int stop_node = a.stop_i[(size_t)b * 4 + 0];
+        len = a.stop_i[(size_t)b * 4 + 1];
+        nch = a.stop_i[(size_t)b * 4 + 2];
+        fc = a.stop_i[(size_t)b * 4 + 3];
+        m = a.stop_m[b];
+        if (wave == 0 && lane < kMaxK) {
+            my_id = a.stop_qid[(size_t)b * kMaxK + lane]; my_mu = a.stop_qmu[(size_t)b * kMaxK + lane];
+            my_l = a.stop_ql[(size_t)b * kMaxK + lane]; ch = a.stop_child[(size_t)b * kMaxK + lane];
+        }
+        node = j < len ? (j == len - 1 ? stop_node : a.out_node[(size_t)b * a.W + j]) : -1;
+    } else {
+        node = commit_row_of(a, b, j);
+        m = 0.0f;
+    }
+    if (node < 0) return;  // block-uniform
+    const bool stop = a.mode == 0 && j == len - 1;
+    if (!stop && wave != 0) return;
+    const int row = b * a.N + node;
+    const int src = a.mode == 0 ? row : b * a.W + j;
+    const char *rowp = (const char *)a.logits + (size_t)row * (size_t)a.V * ES;
+    if (!stop) m = a.src_m[src];
+    const RowGeom g = row_geom<DT>(rowp, a.V);
+    const int per = (g.nvec + nseg - 1) / nseg;
+
+    if (wave == 0) {
+        int32_t o_idx = 0;
+        float o_l = 0.0f;
+        if (lane < a.K) { o_idx = a.src_top_idx[(size_t)src * a.K + lane]; o_l = a.src_top_l[(size_t)src * a.K + lane]; }
+        if (!stop || nch <= 0 || lane >= a.K) { my_id = -1; my_mu = 0.0f; }
+        const float my_e = my_id >= 0 ? exact_exp2(scaled_offset(my_l, m, a.c)) : 0.0f;
+        int edge_id = -1;
+        if (stop) {
+            if (lane < g.head) edge_id = lane;
+            else if (lane < g.head + g.ntail) edge_id = g.tail0 + (lane - g.head);
+        }
+        const unsigned long long edge_f =
+            edge_id >= 0 ? fixed_mass(exact_exp2(scaled_offset(load_scalar<DT>(rowp, edge_id), m, a.c))) : 0ull;
+
+        const unsigned long long S = wave_sum_u64(part);
+        const float s = normaliser_from_fixed(S);
+        if (!stop) {
+            // observation of this row (paper Sec. 4.1: top-k ids and probabilities)
+            if (lane < a.K) {
+                a.obs_idx[((size_t)b * a.W + j) * a.K + lane] = o_idx;
+                a.obs_p[((size_t)b * a.W + j) * a.K + lane] = exact_exp2(scaled_offset(o_l, m, a.c)) / s;
+            }
+            return;
+        }
+
+        // ---- residual at the stop node: replay its accept sequence with exact probabilities
+        bool support = nch > 0;
+        float my_r = 0.0f, rho = 1.0f;
+        if (support) {
+            const NodeResult nr = wave_node_outcome(lane, a.K, my_id, my_mu, my_e / s, nch, ch, a.seed, (uint32_t)b, a.step,
+                                                    fc, false, 0.0f);
+            my_r = (lane < a.K && my_id >= 0) ? nr.r : 0.0f;
+            rho = nr.rho;
+            if (lane == 0 && nr.accepted != -1) atomicAdd(&a.stats[kStatMismatch], 1ull);  // the stop node rejects all
+            // a residual that is not a distribution any more (the normalising mass underflowed)
+            // is not used
+            const float rs = wave_ordered_sum(my_r, a.K);
+            if (!(rs <= 2.0f) || !(rho < __builtin_inff())) support = false;
+        }
+        // the stop row's observation (its loads have had the replay to arrive)
+        if (lane < a.K) {
+            a.obs_idx[((size_t)b * a.W + j) * a.K + lane] = o_idx;
+            a.obs_p[((size_t)b * a.W + j) * a.K + lane] = exact_exp2(scaled_offset(o_l, m, a.c)) / s;
+        }
+        // ---- integer masses (unit 2^-40 / s * rho): support token i weighs floor(r_i * (S / rho)),
+        // a token outside the support the term it contributes to S
+        const bool has_edge = g.head + g.ntail > 0;  // rows that start on a 16-byte boundary have none
+        const unsigned long long edge_all = has_edge ? wave_sum_u64(edge_f) : 0ull;
+        unsigned long long my_g = 0ull, g_inc = 0ull, gsum = 0ull, T = 0ull, edge_m = 0ull;
+        for (int attempt = 0; attempt < 2; ++attempt) {
+            unsigned long long my_f = 0ull;
+            int my_ps = -1;  // 0: head elements, 1 + q: vector segment q, nseg + 1: tail elements
+            my_g = 0ull;
+            if (support && lane < a.K && my_id >= 0) {
+                const double ratio = (double)S / (double)rho;
+                my_g = (unsigned long long)((double)my_r * ratio);
+                my_f = fixed_mass(my_e);
+                my_ps = my_id < g.head ? 0 : (my_id >= g.tail0 ? nseg + 1 : 1 + ((my_id - g.head) / EPV) / per);
+            }
+            unsigned long long head_m = 0ull, tail_m = 0ull;
+            if (has_edge) {
+                bool edge_in_support = false;
+                if (support)
+                    for (int q = 0; q < a.K; ++q) edge_in_support |= __builtin_amdgcn_readlane(my_id, q) == edge_id;
+                edge_m = (edge_id >= 0 && !edge_in_support) ? edge_f : 0ull;
+                head_m = wave_sum_u64(lane < g.head ? edge_m : 0ull);
+                tail_m = wave_sum_u64(lane >= g.head ? edge_m : 0ull);
+            }
+            if (lane < nseg) sh.P[1 + lane] = part - (lane == 0 ? edge_all : 0ull);
+            if (lane == 0) { sh.P[0] = head_m; sh.P[nseg + 1] = tail_m; }
+            __builtin_amdgcn_wave_barrier();
+            if (my_ps >= 1 && my_ps <= nseg) atomicAdd(&sh.P[my_ps], 0ull - my_f);
+            __builtin_amdgcn_wave_barrier();
+            // every support token lies in exactly one part, so the masked parts add up to S - sum my_f
+            g_inc = wave_inclusive_scan_u64(my_g);
+            gsum = readlane_u64(g_inc, 63);
+            T = S + gsum - wave_sum_u64(my_f);
+            if (!support || T != 0ull) break;
+            support = false;  // the residual vanished: draw from the target itself
+        }
+        const Philox4 ph = philox_group(a.seed, (uint32_t)b, a.step, (uint32_t)node, 0u, kStreamBonus);
+        const unsigned long long u = ((unsigned long long)ph.x << 32) | ph.y;
+        unsigned long long t = __umul64hi(u, T);
+        int32_t token = -1;
+        int seg = -1;
+        if (t < gsum) {
+            const int win = __ffsll((long long)__ballot(t < g_inc)) - 1;
+            token = __builtin_amdgcn_readlane(my_id, win);
+        } else {
+            t -= gsum;
+            const unsigned long long pv = lane < nseg + 2 ? sh.P[lane] : 0ull;
+            const unsigned long long inc = wave_inclusive_scan_u64(pv);
+            int win = __ffsll((long long)__ballot(lane < nseg + 2 && t < inc)) - 1;
+            if (win < 0) win = 1;  // not reachable: t is below the total mass
+            const unsigned long long rem = t - (readlane_u64(inc, win) - readlane_u64(pv, win));
+            if (win == 0 || win == nseg + 1) {
+                // inside the head or the tail elements: lanes hold them in id order
+                const unsigned long long em = ((win == 0) == (lane < g.head)) ? edge_m : 0ull;
+                const unsigned long long einc = wave_inclusive_scan_u64(em);
+                const int ew = __ffsll((long long)__ballot(rem < einc)) - 1;
+                token = ew >= 0 ? __builtin_amdgcn_readlane(edge_id, ew) : __builtin_amdgcn_readlane(o_idx, 0);
+            } else {
+                seg = win - 1;
+                // stored ids inside the chosen segment
+                const int e_lo = g.head + seg * per * EPV, e_hi = e_lo + per * EPV;
+                const bool in_seg = support && lane < a.K && my_id >= e_lo && my_id < e_hi && my_id < g.tail0;
+                const unsigned long long mk = __ballot(in_seg);
+                if (in_seg) sh.sup_id[lane_prefix_count(mk)] = my_id;
+                if (lane == 0) { sh.nsup = __popcll(mk); sh.rem = rem; }
+            }
+        }
+        if (lane == 0) {
+            sh.seg = seg;
+            sh.found = 0;
+            if (seg < 0) a.out_tok[(size_t)b * a.W + (len - 1)] = token;
+        }
+    }
+    __syncthreads();
+    const int seg = sh.seg;
+    if (seg < 0) return;
+
+    // ---- locate the token inside vector segment seg: every thread owns a contiguous run of
+    // vectors, so thread order is id order
+    const int vs = seg * per, ve = (vs + per < g.nvec) ? vs + per : g.nvec;
+    const int cpt = (ve - vs + kPathThreads - 1) / kPathThreads;
+    const int r0 = vs + tid * cpt < ve ? vs + tid * cpt : ve;
+    const int r1 = r0 + cpt < ve ? r0 + cpt : ve;
+    // four independent loads per round (indices clamped, unused vectors skipped)
+    const int rlast = r1 > r0 ? r1 - 1 : r0;
+    unsigned long long mine = 0ull;
+    auto vec_sum = [&](const uint4 &w, int idx) {
+        if (idx < r1) {
+            unsigned long long f[EPV];
+            vector_masses<DT>(w, g.head + idx * EPV, m, a.c, sh, f);
+#pragma unroll
+            for (int q = 0; q < EPV; ++q) mine += f[q];
+        }
+    };
+    uint4 w0 = make_uint4(0, 0, 0, 0), w1 = w0, w2 = w0, w3 = w0;  // the last round's vectors are kept
+    if (r0 < r1)
+        for (int base = r0; base < r1; base += 4) {
+            w0 = g.vp[base < rlast ? base : rlast];
+            w1 = g.vp[base + 1 < rlast ? base + 1 : rlast];
+            w2 = g.vp[base + 2 < rlast ? base + 2 : rlast];
+            w3 = g.vp[base + 3 < rlast ? base + 3 : rlast];
+            vec_sum(w0, base); vec_sum(w1, base + 1); vec_sum(w2, base + 2); vec_sum(w3, base + 3);
+        }
+    const unsigned long long inc = wave_inclusive_scan_u64(mine);
+    if (lane == 63) sh.wave_tot[wave] = inc;
+    __syncthreads();
+    unsigned long long before = inc - mine;
+    for (int q = 0; q < wave; ++q) before += sh.wave_tot[q];
+    const unsigned long long rem = sh.rem;
+    if (rem >= before && rem - before < mine) {
+        unsigned long long left = rem - before;
+        int32_t token = -1;
+        auto vec_find = [&](const uint4 &w, int idx) {
+            if (idx < r1 && token < 0) {
+                unsigned long long f[EPV];
+                vector_masses<DT>(w, g.head + idx * EPV, m, a.c, sh, f);
+#pragma unroll
+                for (int q = 0; q < EPV; ++q) {
+                    if (token < 0) {
+                        if (left < f[q]) token = g.head + idx * EPV + q;
+                        else left -= f[q];
+                    }
+                }
+            }
+        };
+        const bool single_round = r1 - r0 <= 4;  // then w0..w3 still hold this thread's whole run
+        for (int base = r0; base < r1 && token < 0; base += 4) {
+            if (!single_round) {
+                w0 = g.vp[base < rlast ? base : rlast];
+                w1 = g.vp[base + 1 < rlast ? base + 1 : rlast];
+                w2 = g.vp[base + 2 < rlast ? base + 2 : rlast];
+                w3 = g.vp[base + 3 < rlast ? base + 3 : rlast];
+            }
+            vec_find(w0, base); vec_find(w1, base + 1); vec_find(w2, base + 2); vec_find(w3, base + 3);
+        }
+        a.out_tok[(size_t)b * a.W + (len - 1)] = token;
+        sh.found = 1;
+    }
+    __syncthreads();
+    if (tid == 0 && !sh.found) {
+        // not reachable while the partial sums describe this row; keep the output a valid token
+        a.out_tok[(size_t)b * a.W + (len - 1)] = a.src_top_idx[(size_t)src * a.K];
+        atomicAdd(&a.stats[kStatMismatch], 1ull);
+    }
 }
 
 // one wave per record; the first record of a slot applies all records of that slot in order

@@ -29,12 +29,11 @@ struct stand_handle {
     int32_t *obs_idx;
     float *obs_p;
     long long *rec_slot;
-    unsigned long long *rowS, *race;
-    unsigned int *done;
+    unsigned long long *seg_part;
+    int32_t *stop_i, *stop_qid, *stop_child;
+    float *stop_m, *stop_qmu, *stop_ql;
     float *pr_m, *pr_top_l;
     int32_t *pr_top_idx;
-    int32_t *res_id, *res_i;
-    float *res_r, *res_f;
     unsigned long long *stats;
     unsigned long long *counter;
     bool table_used;
@@ -77,8 +76,7 @@ static void free_all(stand_handle *h)
     if (!h) return;
     void *ptrs[] = {h->d_tree, h->table, h->ctx_tail, h->ctx_len, h->draft_tok, h->draft_has, h->draft_qid, h->draft_qmu,
                     h->row_m, h->row_s, h->top_l, h->top_p, h->top_idx, h->outcome, h->obs_idx, h->obs_p, h->rec_slot,
-                    h->rowS, h->race, h->done, h->pr_m, h->pr_top_l, h->pr_top_idx, h->res_id, h->res_i, h->res_r,
-                    h->res_f, h->stats, h->counter};
+                    h->seg_part, h->stop_i, h->stop_qid, h->stop_child, h->stop_m, h->stop_qmu, h->stop_ql, h->pr_m, h->pr_top_l, h->pr_top_idx, h->stats, h->counter};
     for (void *p : ptrs) (void)hipFree(p);
     for (hipEvent_t e : h->ev_begin) (void)hipEventDestroy(e);
     for (hipEvent_t e : h->ev_end) (void)hipEventDestroy(e);
@@ -155,8 +153,9 @@ extern "C" int stand_create(const stand_config *cfg, stand_handle **out)
     acc(dmalloc(&h->outcome, rows));
     acc(dmalloc(&h->obs_idx, B * h->W * K)); acc(dmalloc(&h->obs_p, B * h->W * K));
     acc(dmalloc(&h->rec_slot, nrec));
-    acc(dmalloc(&h->rowS, B * h->W)); acc(dmalloc(&h->race, B * kRaceSlots)); acc(dmalloc(&h->done, B * h->W + B));
-    acc(dmalloc(&h->res_id, B * K)); acc(dmalloc(&h->res_r, B * K)); acc(dmalloc(&h->res_f, B * 4)); acc(dmalloc(&h->res_i, B * 4));
+    acc(dmalloc(&h->seg_part, B * h->W * kSegMax));
+    acc(dmalloc(&h->stop_i, B * 4)); acc(dmalloc(&h->stop_m, B)); acc(dmalloc(&h->stop_qid, B * kMaxK));
+    acc(dmalloc(&h->stop_qmu, B * kMaxK)); acc(dmalloc(&h->stop_ql, B * kMaxK)); acc(dmalloc(&h->stop_child, B * kMaxK));
     acc(dmalloc(&h->pr_m, B * h->W)); acc(dmalloc(&h->pr_top_l, B * h->W * K)); acc(dmalloc(&h->pr_top_idx, B * h->W * K));
     acc(dmalloc(&h->stats, (size_t)kStatCount));
     acc(dmalloc(&h->counter, 1));
@@ -256,7 +255,6 @@ static int launch_row_pass(stand_handle *h, uint64_t step, const void *d_logits,
     a.draft_tok = h->draft_tok; a.draft_has = h->draft_has; a.draft_qid = h->draft_qid; a.draft_qmu = h->draft_qmu;
     a.row_m = h->row_m; a.row_s = h->row_s; a.top_idx = h->top_idx; a.top_l = h->top_l; a.top_p = h->top_p;
     a.outcome = h->outcome; a.stats = h->stats;
-    a.W = h->W; a.rowS = h->rowS; a.race = h->race; a.done = h->done;
     const dim3 grid((unsigned)((h->B * h->N + kRowsPerBlock - 1) / kRowsPerBlock)), block(kRowThreads);
     const bool timed = h->profiling && h->ev_used < h->ev_begin.size();
     if (timed) HIP_TRY(h, hipEventRecord(h->ev_begin[h->ev_used], s));
@@ -269,14 +267,25 @@ static int launch_row_pass(stand_handle *h, uint64_t step, const void *d_logits,
 
 static int clampi(int x, int lo, int hi) { return x < lo ? lo : (x > hi ? hi : x); }
 
-// mode 0 (verify): path from the row pass's outcomes; mode 1 (update): rows given by the caller
+static MergeArgs merge_args(stand_handle *h, const int32_t *commit_tok, const int32_t *commit_row, const int32_t *commit_len)
+{
+    MergeArgs a;
+    a.table = h->table; a.mask = h->cfg.table_capacity - 1; a.slot_bytes = h->slot_bytes; a.K = h->K;
+    a.max_probe = h->cfg.max_probe; a.B = h->B; a.W = h->W; a.omin = h->cfg.order_min; a.omax = h->cfg.order_max;
+    a.ctx_tail = h->ctx_tail; a.ctx_len = h->ctx_len; a.commit_tok = commit_tok; a.commit_row = commit_row;
+    a.commit_len = commit_len; a.N = h->N; a.rec_slot = h->rec_slot; a.obs_idx = h->obs_idx; a.obs_p = h->obs_p;
+    a.stats = h->stats;
+    return a;
+}
+
+// mode 0 (verify): path from the row pass's outcomes; mode 1 (update): rows given by the caller.
+// With `claim` the launch that finishes the path rows also claims the table slots of that merge.
 static int launch_path_pass(stand_handle *h, uint64_t step, const void *d_logits, int mode, const int32_t *commit_row,
-                            const int32_t *commit_len, int32_t *out_tok, int32_t *out_node, int32_t *out_len, hipStream_t s)
+                            const int32_t *commit_len, int32_t *out_tok, int32_t *out_node, int32_t *out_len,
+                            const MergeArgs *claim, hipStream_t s)
 {
     const bool bf16 = h->cfg.logits_dtype == STAND_BF16;
     if (mode == 1) {
-        const int n = h->B * h->W;
-        path_reset_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s>>>(h->B, h->W, h->rowS, h->race, h->done);
         CommitScanArgs c;
         c.logits = d_logits; c.B = h->B; c.N = h->N; c.V = h->V; c.K = h->K; c.W = h->W; c.c = h->c;
         c.commit_row = commit_row; c.commit_len = commit_len;
@@ -294,39 +303,42 @@ static int launch_path_pass(stand_handle *h, uint64_t step, const void *d_logits
     a.src_top_l = mode == 0 ? h->top_l : h->pr_top_l;
     a.outcome = h->outcome; a.commit_row = commit_row; a.commit_len = commit_len;
     a.out_tok = out_tok; a.out_node = out_node; a.out_len = out_len;
-    a.rowS = h->rowS; a.race = h->race; a.done = h->done;
+    a.seg_part = h->seg_part;
+    a.stop_i = h->stop_i; a.stop_m = h->stop_m; a.stop_qid = h->stop_qid; a.stop_qmu = h->stop_qmu; a.stop_ql = h->stop_ql;
+    a.stop_child = h->stop_child;
     a.obs_idx = h->obs_idx; a.obs_p = h->obs_p; a.stats = h->stats;
-    a.res_id = h->res_id; a.res_r = h->res_r; a.res_f = h->res_f; a.res_i = h->res_i;
-    // segments: enough blocks to cover the chip even for one trajectory
-    const int nseg = clampi(4096 / (h->B * h->W), 1, 32);
-    const int nseg2 = clampi(1024 / h->B, 1, kRaceSlots);
-    const dim3 g1((unsigned)nseg, (unsigned)h->W, (unsigned)h->B), g2((unsigned)nseg2, (unsigned)h->B), block(kPathThreads);
+    // segments: one round of loads per thread (4 vectors of 16 bytes) where kSegMax allows it;
+    // one more block per (row, trajectory) slot for the outputs and the stop record
+    const int row_vectors = (int)(((size_t)h->V * (bf16 ? 2 : 4) + 15) / 16);
+    a.nseg = clampi((row_vectors + 4 * kPathThreads - 1) / (4 * kPathThreads), 1, kSegMax);
+    const dim3 g1((unsigned)a.nseg + 1, (unsigned)h->W, (unsigned)h->B), block(kPathThreads);
+    const int finish_blocks = h->B * h->W;
+#ifdef STAND_TUNE_SPLIT_CLAIM
+    if (claim) merge_claim_kernel<<<dim3((unsigned)((h->B * h->W * h->NO + 255) / 256)), dim3(256), 0, s>>>(*claim);
+    claim = nullptr;
+#endif
+    const int claim_blocks = claim ? (h->B * h->W * h->NO + kPathThreads - 1) / kPathThreads : 0;
+    const MergeArgs mg = claim ? *claim : merge_args(h, nullptr, nullptr, nullptr);
+    const dim3 g2((unsigned)(finish_blocks + claim_blocks));
     if (bf16) {
         path_exact_kernel<kDtBf16><<<g1, block, 0, s>>>(a);
-        if (mode == 0) race_kernel<kDtBf16><<<g2, block, 0, s>>>(a);
+        path_finish_kernel<kDtBf16><<<g2, block, 0, s>>>(a, mg, finish_blocks);
     } else {
         path_exact_kernel<kDtF32><<<g1, block, 0, s>>>(a);
-        if (mode == 0) race_kernel<kDtF32><<<g2, block, 0, s>>>(a);
+        path_finish_kernel<kDtF32><<<g2, block, 0, s>>>(a, mg, finish_blocks);
     }
     HIP_TRY(h, hipGetLastError());
     return STAND_OK;
 }
 
-static int launch_merge(stand_handle *h, const int32_t *commit_tok, const int32_t *commit_row, const int32_t *commit_len,
-                        bool append_ctx, hipStream_t s)
+// applies the records whose slots the path pass claimed
+static int launch_merge_apply(stand_handle *h, const MergeArgs &a, bool append_ctx, hipStream_t s)
 {
-    MergeArgs a;
-    a.table = h->table; a.mask = h->cfg.table_capacity - 1; a.slot_bytes = h->slot_bytes; a.K = h->K;
-    a.max_probe = h->cfg.max_probe; a.B = h->B; a.W = h->W; a.omin = h->cfg.order_min; a.omax = h->cfg.order_max;
-    a.ctx_tail = h->ctx_tail; a.ctx_len = h->ctx_len; a.commit_tok = commit_tok; a.commit_row = commit_row;
-    a.commit_len = commit_len; a.N = h->N; a.rec_slot = h->rec_slot; a.obs_idx = h->obs_idx; a.obs_p = h->obs_p;
-    a.stats = h->stats;
     const int nrec = h->B * h->W * h->NO;
-    merge_claim_kernel<<<dim3((unsigned)((nrec + 255) / 256)), dim3(256), 0, s>>>(a);
     merge_apply_kernel<<<dim3((unsigned)nrec), dim3(64), 0, s>>>(a);
     if (append_ctx)
         ctx_append_kernel<<<dim3((unsigned)((h->B + 63) / 64)), dim3(64), 0, s>>>(h->B, h->W, h->ctx_tail, h->ctx_len,
-                                                                                commit_tok, commit_len);
+                                                                                a.commit_tok, a.commit_len);
     HIP_TRY(h, hipGetLastError());
     h->table_used = true;
     return STAND_OK;
@@ -353,9 +365,10 @@ extern "C" int stand_update(stand_handle *h, uint64_t step, const void *d_logits
     if (!h || !d_logits || !d_commit_tok || !d_commit_row || !d_commit_len) return STAND_EINVAL;
     hipStream_t s = (hipStream_t)stream;
     HIP_TRY(h, hipSetDevice(h->cfg.device));
-    int rc = launch_path_pass(h, step, d_logits, 1, d_commit_row, d_commit_len, nullptr, nullptr, nullptr, s);
+    const MergeArgs mg = merge_args(h, d_commit_tok, d_commit_row, d_commit_len);
+    int rc = launch_path_pass(h, step, d_logits, 1, d_commit_row, d_commit_len, nullptr, nullptr, nullptr, &mg, s);
     if (rc) return rc;
-    return launch_merge(h, d_commit_tok, d_commit_row, d_commit_len, true, s);
+    return launch_merge_apply(h, mg, true, s);
 }
 
 extern "C" int stand_draft(stand_handle *h, uint64_t step, int32_t *d_draft_tok, void *stream)
@@ -373,7 +386,7 @@ extern "C" int stand_verify(stand_handle *h, uint64_t step, const void *d_logits
     HIP_TRY(h, hipSetDevice(h->cfg.device));
     int rc = launch_row_pass(h, step, d_logits, s);
     if (rc) return rc;
-    return launch_path_pass(h, step, d_logits, 0, nullptr, nullptr, d_out_tok, d_out_node, d_out_len, s);
+    return launch_path_pass(h, step, d_logits, 0, nullptr, nullptr, d_out_tok, d_out_node, d_out_len, nullptr, s);
 }
 
 extern "C" int stand_step(stand_handle *h, uint64_t step, const void *d_logits, int32_t *d_out_tok, int32_t *d_out_node,
@@ -384,10 +397,11 @@ extern "C" int stand_step(stand_handle *h, uint64_t step, const void *d_logits, 
     HIP_TRY(h, hipSetDevice(h->cfg.device));
     int rc = launch_row_pass(h, step, d_logits, s);
     if (rc) return rc;
-    rc = launch_path_pass(h, step, d_logits, 0, nullptr, nullptr, d_out_tok, d_out_node, d_out_len, s);
-    if (rc) return rc;
     const int32_t *commit = d_force_tok ? d_force_tok : d_out_tok;
-    rc = launch_merge(h, commit, nullptr, d_out_len, false, s);
+    const MergeArgs mg = merge_args(h, commit, nullptr, d_out_len);
+    rc = launch_path_pass(h, step, d_logits, 0, nullptr, nullptr, d_out_tok, d_out_node, d_out_len, &mg, s);
+    if (rc) return rc;
+    rc = launch_merge_apply(h, mg, false, s);
     if (rc) return rc;
     // the draft kernel appends the committed tokens to the contexts before it looks anything up
     return launch_draft(h, step + 1, d_next_draft_tok, commit, d_out_len, s);

@@ -140,8 +140,9 @@ def test_full_shape_rows_sampled(gpu):
     # no drafts pending: each trajectory emits one token resampled from its root row
     for b in (0, 1, 12, 16):
         row = flat[b * w.N]
-        pd, *_ = oracle.row_softmax(row, w.T)
-        assert out_tok.cpu().numpy()[b, 0] == oracle.race(pd, 11, b, 0, 0)
+        F = oracle.row_masses(row, w.T)
+        u = oracle.uniform_u64(11, b, 0, 0, oracle.STREAM_BONUS)
+        assert out_tok.cpu().numpy()[b, 0] == oracle.residual_draw(F, int(F.sum()), np.zeros(0, np.int32), None, u)
     assert np.all(out_len.cpu().numpy() == 1)
     g.close()
 
