@@ -628,6 +628,7 @@ __global__ __launch_bounds__(kRowThreads) void row_pass_kernel(RowPassArgs a)
 // Kernel boundaries are the only synchronisation between blocks.
 // ---------------------------------------------------------------------------------------------
 constexpr int kSegMax = 32;  // most segments per path row
+constexpr int kFinishThreads = 1024;  // path_finish_kernel: many waves, so that locating a token is one short round
 
 struct PathArgs {
     const void *logits;
@@ -800,7 +801,7 @@ __global__ __launch_bounds__(kPathThreads) void path_exact_kernel(PathArgs a)
 
 struct FinishShared {
     unsigned long long P[kSegMax + 2];  // masked mass of: head elements, vector segments, tail elements
-    unsigned long long wave_tot[kPathThreads / 64];
+    unsigned long long wave_tot[kFinishThreads / 64];
     unsigned long long rem;             // position inside the chosen segment
     int32_t sup_id[kMaxK];              // stored ids that lie inside the chosen segment
     int nsup, seg, found;
@@ -888,6 +889,9 @@ struct MergeArgs {
     unsigned long long *stats;
 };
 
+// transient use of the slot header between claiming and applying the records of one merge
+constexpr uint32_t kTagShift = 8, kTagMax = 0x7FFFFFu, kMultiBit = 0x80000000u;
+
 __device__ __forceinline__ int clamp_len(int len, int W) { return len < 0 ? 0 : (len > W ? W : len); }
 
 // claims the table slot of merge record rec = (b, position j, order n); run by one thread
@@ -920,13 +924,14 @@ __device__ __forceinline__ void merge_claim_record(const MergeArgs &a, int rec)
             const uint64_t slot = (fp + (uint64_t)i) & a.mask;
             SlotHeader *h = slot_header(a.table, slot, a.slot_bytes);
             const unsigned long long old = atomicCAS(&h->fp, 0ull, fp);
-            if (old == 0ull) {
-                h->order = (uint32_t)n;
-                atomicAdd(&a.stats[kStatInserts], 1ull);
-                slot_out = (long long)slot; placed = true; break;
-            }
-            if (old == fp) {
-                atomicAdd(&a.stats[kStatMerges], 1ull);
+            if (old == 0ull || old == fp) {
+                atomicAdd(&a.stats[old == 0ull ? kStatInserts : kStatMerges], 1ull);
+                // Until the records are applied the order word also carries the smallest record
+                // number that claimed the slot (stored inverted, so that atomicMax keeps it), and
+                // the top bit of the count word says that more than one record did.
+                const uint32_t tag = ((kTagMax - (uint32_t)rec) << kTagShift) | (uint32_t)n;
+                const uint32_t before = atomicMax(&h->order, tag);
+                if (before >> kTagShift) atomicOr(&h->count, kMultiBit);
                 slot_out = (long long)slot; placed = true; break;
             }
         }
@@ -938,14 +943,14 @@ __device__ __forceinline__ void merge_claim_record(const MergeArgs &a, int rec)
 __global__ void merge_claim_kernel(MergeArgs a) { merge_claim_record(a, blockIdx.x * blockDim.x + threadIdx.x); }
 
 // See the comment above PathArgs.  Blocks [0, finish_blocks) finish path row (b, j) =
-// (block / W, block % W); the blocks after them claim merge records, kPathThreads per block.
+// (block / W, block % W); the blocks after them claim merge records, kFinishThreads per block.
 template <int DT>
-__global__ __launch_bounds__(kPathThreads) void path_finish_kernel(PathArgs a, MergeArgs mg, int finish_blocks)
+__global__ __launch_bounds__(kFinishThreads) void path_finish_kernel(PathArgs a, MergeArgs mg, int finish_blocks)
 {
     constexpr int ES = VecTraits<DT>::ES, EPV = VecTraits<DT>::EPV;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     if ((int)blockIdx.x >= finish_blocks) {
-        merge_claim_record(mg, ((int)blockIdx.x - finish_blocks) * kPathThreads + tid);
+        merge_claim_record(mg, ((int)blockIdx.x - finish_blocks) * kFinishThreads + tid);
         return;
     }
     __shared__ FinishShared sh;
@@ -1036,7 +1041,7 @@ __global__ __launch_bounds__(kPathThreads) void path_finish_kernel(PathArgs a, M
             int my_ps = -1;  // 0: head elements, 1 + q: vector segment q, nseg + 1: tail elements
             my_g = 0ull;
             if (support && lane < a.K && my_id >= 0) {
-                const double ratio = (double)S / (double)rho;
+                const double ratio = (double)S / (double)rho;  // skipped by the whole wave without a support
                 my_g = (unsigned long long)((double)my_r * ratio);
                 my_f = fixed_mass(my_e);
                 my_ps = my_id < g.head ? 0 : (my_id >= g.tail0 ? nseg + 1 : 1 + ((my_id - g.head) / EPV) / per);
@@ -1106,7 +1111,7 @@ __global__ __launch_bounds__(kPathThreads) void path_finish_kernel(PathArgs a, M
     // ---- locate the token inside vector segment seg: every thread owns a contiguous run of
     // vectors, so thread order is id order
     const int vs = seg * per, ve = (vs + per < g.nvec) ? vs + per : g.nvec;
-    const int cpt = (ve - vs + kPathThreads - 1) / kPathThreads;
+    const int cpt = (ve - vs + kFinishThreads - 1) / kFinishThreads;
     const int r0 = vs + tid * cpt < ve ? vs + tid * cpt : ve;
     const int r1 = r0 + cpt < ve ? r0 + cpt : ve;
     // four independent loads per round (indices clamped, unused vectors skipped)
@@ -1172,7 +1177,9 @@ __global__ __launch_bounds__(kPathThreads) void path_finish_kernel(PathArgs a, M
     }
 }
 
-// one wave per record; the first record of a slot applies all records of that slot in order
+// One wave per record.  The lowest record that claimed a slot (its leader, named in the slot
+// header by the claim) applies all records of that slot in record order; the other records'
+// waves leave at once.  A slot claimed by one record only needs no search for followers.
 __global__ __launch_bounds__(64) void merge_apply_kernel(MergeArgs a)
 {
     __shared__ int32_t l_id[2 * kMaxK];
@@ -1184,68 +1191,81 @@ __global__ __launch_bounds__(64) void merge_apply_kernel(MergeArgs a)
     const int K = a.K;
     const long long slot = a.rec_slot[rec];
     if (slot < 0) return;
-    // leader test: no earlier record on this slot
-    for (int base = 0; base < rec; base += 64) {
-        const int r = base + lane;
-        const bool hit = r < rec && a.rec_slot[r] == slot;
-        if (__ballot(hit)) return;
-    }
     SlotHeader *h = slot_header(a.table, (uint64_t)slot, a.slot_bytes);
     int32_t *ids = slot_ids(a.table, (uint64_t)slot, a.slot_bytes);
     float *mus = slot_mu(a.table, (uint64_t)slot, a.slot_bytes, K);
+    // header, stored entry and this record's observation are requested together
+    const uint32_t order_word = h->order;
     uint32_t count = h->count;
-    // lanes 0..K-1: stored entry; lanes 32..32+K-1: observation
     int32_t e_id = -1;
     float e_mu = 0.0f;
-    if (lane < K && count > 0) { e_id = ids[lane]; e_mu = mus[lane]; }
-    for (int base = rec; base < nrec; base += 64) {
-        const int r = base + lane;
-        unsigned long long hits = __ballot(r < nrec && a.rec_slot[r] == slot);
-        while (hits) {
-            const int bit = __ffsll((long long)hits) - 1;
-            hits &= hits - 1;
-            const int rr = base + bit;
-            const int jb = rr / NO;  // = b * W + j
-            int32_t o_id = -1;
-            float o_p = 0.0f;
-            if (lane >= 32 && lane < 32 + K) { o_id = a.obs_idx[(size_t)jb * K + (lane - 32)]; o_p = a.obs_p[(size_t)jb * K + (lane - 32)]; }
-            if (count == 0) {
-                // first sight: the entry is the observation
-                const int32_t id2 = __shfl(o_id, 32 + (lane & 31));
-                const float p2 = __shfl(o_p, 32 + (lane & 31));
-                if (lane < K) { e_id = id2; e_mu = p2; }
-            } else {
-                const float cf = (float)count;
-                const float denom = cf + 1.0f;
-                int32_t id = lane < 32 ? e_id : o_id;
-                bool act = lane < 32 ? (lane < K) : (lane < 32 + K);
-                float other = 0.0f;  // for stored lanes: the observation's value for the same id
-                bool dup = false;    // for observation lanes: id already stored
-#pragma unroll
-                for (int q = 0; q < kMaxK; ++q) {
-                    const int32_t sid = __builtin_amdgcn_readlane(e_id, q);
-                    const int32_t oid = __builtin_amdgcn_readlane(o_id, 32 + q);
-                    const float op = u2f((uint32_t)__builtin_amdgcn_readlane((int)f2u(o_p), 32 + q));
-                    if (q < K && lane < 32 && act && oid == id) other = op;
-                    if (q < K && lane >= 32 && act && sid == id) dup = true;
-                }
-                float val;
-                if (lane < 32) { float t = cf * e_mu; t = t + other; val = t / denom; }
-                else { float t = cf * 0.0f; t = t + o_p; val = t / denom; act = act && !dup; }
-                const unsigned long long key = act ? rank_key(val, (uint32_t)id) : 0ull;
-                int rank = 0;
-#pragma unroll
-                for (int q = 0; q < 64; ++q) rank += readlane_u64(key, q) > key ? 1 : 0;
-                if (act && rank < K) { l_id[rank] = id; l_val[rank] = val; }
-                __syncthreads();
-                if (lane < K) { e_id = l_id[lane]; e_mu = l_val[lane]; }
-                __syncthreads();
+    if (lane < K) { e_id = ids[lane]; e_mu = mus[lane]; }
+    // lanes 0..K-1: stored entry; lanes 32..32+K-1: observation
+    int32_t o_id = -1;
+    float o_p = 0.0f;
+    if (lane >= 32 && lane < 32 + K) {
+        o_id = a.obs_idx[(size_t)(rec / NO) * K + (lane - 32)];
+        o_p = a.obs_p[(size_t)(rec / NO) * K + (lane - 32)];
+    }
+    if (kTagMax - (order_word >> kTagShift) != (uint32_t)rec) return;  // another record leads this slot
+    const bool multi = (count & kMultiBit) != 0u;
+    count &= ~kMultiBit;
+    if (count == 0) { e_id = -1; e_mu = 0.0f; }
+
+    auto apply = [&](int32_t o_id, float o_p) {
+        if (count == 0) {
+            // first sight: the entry is the observation
+            const int32_t id2 = __shfl(o_id, 32 + (lane & 31));
+            const float p2 = __shfl(o_p, 32 + (lane & 31));
+            if (lane < K) { e_id = id2; e_mu = p2; }
+        } else {
+            const float cf = (float)count;
+            const float denom = cf + 1.0f;
+            int32_t id = lane < 32 ? e_id : o_id;
+            bool act = lane < 32 ? (lane < K) : (lane < 32 + K);
+            float other = 0.0f;  // for stored lanes: the observation's value for the same id
+            bool dup = false;    // for observation lanes: id already stored
+            for (int q = 0; q < K; ++q) {
+                const int32_t sid = __builtin_amdgcn_readlane(e_id, q);
+                const int32_t oid = __builtin_amdgcn_readlane(o_id, 32 + q);
+                const float op = u2f((uint32_t)__builtin_amdgcn_readlane((int)f2u(o_p), 32 + q));
+                if (lane < 32 && act && oid == id) other = op;
+                if (lane >= 32 && act && sid == id) dup = true;
             }
-            count++;
+            float val;
+            if (lane < 32) { float t = cf * e_mu; t = t + other; val = t / denom; }
+            else { float t = cf * 0.0f; t = t + o_p; val = t / denom; act = act && !dup; }
+            const unsigned long long key = act ? rank_key(val, (uint32_t)id) : 0ull;
+            int rank = 0;
+#pragma unroll
+            for (int q = 0; q < 64; ++q) rank += readlane_u64(key, q) > key ? 1 : 0;
+            if (act && rank < K) { l_id[rank] = id; l_val[rank] = val; }
+            __syncthreads();
+            if (lane < K) { e_id = l_id[lane]; e_mu = l_val[lane]; }
+            __syncthreads();
+        }
+        count++;
+    };
+
+    apply(o_id, o_p);
+    if (multi) {
+        // the later records of this slot, in record order
+        for (int base = rec + 1; base < nrec; base += 64) {
+            const int r = base + lane;
+            unsigned long long hits = __ballot(r < nrec && a.rec_slot[r] == slot);
+            while (hits) {
+                const int bit = __ffsll((long long)hits) - 1;
+                hits &= hits - 1;
+                const int jb = (base + bit) / NO;  // = b * W + j
+                int32_t f_id = -1;
+                float f_p = 0.0f;
+                if (lane >= 32 && lane < 32 + K) { f_id = a.obs_idx[(size_t)jb * K + (lane - 32)]; f_p = a.obs_p[(size_t)jb * K + (lane - 32)]; }
+                apply(f_id, f_p);
+            }
         }
     }
     if (lane < K) { ids[lane] = e_id; mus[lane] = e_mu; }
-    if (lane == 0) h->count = count;
+    if (lane == 0) { h->count = count; h->order = order_word & ((1u << kTagShift) - 1u); }
 }
 
 // append the committed tokens to the context tails
@@ -1285,7 +1305,7 @@ struct DraftArgs {
     unsigned long long *stats;
 };
 
-constexpr int kDraftThreads = 256;
+constexpr int kDraftThreads = 1024;  // 16 waves: the nodes of a tree level are looked up side by side
 
 __global__ __launch_bounds__(kDraftThreads) void draft_kernel(DraftArgs a)
 {
@@ -1323,6 +1343,10 @@ __global__ __launch_bounds__(kDraftThreads) void draft_kernel(DraftArgs a)
     const int NO = a.omax - a.omin + 1;
     for (int d = 0; d < a.tree.D; ++d) {
         const int lo = a.tree.level_start[d], hi = a.tree.level_start[d + 1];
+        // a level without a drafted node ends the tree (tok is stable here: barrier below)
+        bool any = false;
+        for (int u = lo + lane; u < hi; u += 64) any |= tok[u] >= 0;
+        if (!__ballot(any)) break;  // the same in every wave
         for (int u = lo + wave; u < hi; u += kDraftThreads / 64) {
             const int nch = a.tree.nchild[u];
             if (nch == 0 || tok[u] < 0) continue;  // uniform per wave
@@ -1406,8 +1430,7 @@ __global__ __launch_bounds__(kDraftThreads) void draft_kernel(DraftArgs a)
                 key = rank_key(exact_log(mu) - g, (uint32_t)id);
             }
             int rank = 0;
-#pragma unroll
-            for (int q = 0; q < kMaxK; ++q) rank += readlane_u64(key, q) > key ? 1 : 0;
+            for (int q = 0; q < K; ++q) rank += readlane_u64(key, q) > key ? 1 : 0;
             if (cand && rank < nch) tok[a.tree.first_child[u] + rank] = id;
             const int ncand = __popcll(__ballot(cand));
             if (lane == 0) a.draft_has[(size_t)b * N + u] = ncand < nch ? ncand : nch;

@@ -99,6 +99,8 @@ extern "C" int stand_create(const stand_config *cfg, stand_handle **out)
     if (cfg->logits_dtype != STAND_BF16 && cfg->logits_dtype != STAND_F32) return STAND_EINVAL;
     if (cfg->update_mode != STAND_UPDATE_ACCEPTED_PATH) return STAND_EINVAL;
     if ((int64_t)cfg->max_batch * N * (int64_t)cfg->vocab >= ((int64_t)1 << 40)) return STAND_EINVAL;
+    // merge records are numbered in 23 bits (kTagMax); max_batch * tree depth * orders stays far below
+    if ((int64_t)cfg->max_batch * (kMaxDepth + 1) * STAND_MAX_ORDER > (int64_t)kTagMax) return STAND_EINVAL;
     int ndev = 0;
     if (hipGetDeviceCount(&ndev) != hipSuccess || cfg->device < 0 || cfg->device >= ndev) return STAND_EINVAL;
 
@@ -317,15 +319,15 @@ static int launch_path_pass(stand_handle *h, uint64_t step, const void *d_logits
     if (claim) merge_claim_kernel<<<dim3((unsigned)((h->B * h->W * h->NO + 255) / 256)), dim3(256), 0, s>>>(*claim);
     claim = nullptr;
 #endif
-    const int claim_blocks = claim ? (h->B * h->W * h->NO + kPathThreads - 1) / kPathThreads : 0;
+    const int claim_blocks = claim ? (h->B * h->W * h->NO + kFinishThreads - 1) / kFinishThreads : 0;
     const MergeArgs mg = claim ? *claim : merge_args(h, nullptr, nullptr, nullptr);
     const dim3 g2((unsigned)(finish_blocks + claim_blocks));
     if (bf16) {
         path_exact_kernel<kDtBf16><<<g1, block, 0, s>>>(a);
-        path_finish_kernel<kDtBf16><<<g2, block, 0, s>>>(a, mg, finish_blocks);
+        path_finish_kernel<kDtBf16><<<g2, dim3(kFinishThreads), 0, s>>>(a, mg, finish_blocks);
     } else {
         path_exact_kernel<kDtF32><<<g1, block, 0, s>>>(a);
-        path_finish_kernel<kDtF32><<<g2, block, 0, s>>>(a, mg, finish_blocks);
+        path_finish_kernel<kDtF32><<<g2, dim3(kFinishThreads), 0, s>>>(a, mg, finish_blocks);
     }
     HIP_TRY(h, hipGetLastError());
     return STAND_OK;
