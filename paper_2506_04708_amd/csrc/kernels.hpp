@@ -1310,11 +1310,22 @@ constexpr int kDraftThreads = 1024;  // 16 waves: the nodes of a tree level are 
 __global__ __launch_bounds__(kDraftThreads) void draft_kernel(DraftArgs a)
 {
     __shared__ int32_t tok[kMaxNodes];
-    __shared__ int32_t tail[kMaxOrder];
+    // recent[u][i]: the token i positions before the end of the sequence that ends at node u
+    // (recent[u][0] is the node's own token), so a key is read without walking up the tree
+    __shared__ int32_t recent[kMaxNodes][kMaxOrder];
+    __shared__ int32_t t_first[kMaxNodes], t_nchild[kMaxNodes];
+    __shared__ int32_t t_level[kMaxDepth + 3];
     __shared__ long long s_clen;
     const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int N = a.tree.N, K = a.K;
-    if (tid == 0) {
+    for (int u = tid; u < N; u += kDraftThreads) {
+        t_first[u] = a.tree.first_child[u];
+        t_nchild[u] = a.tree.nchild[u];
+        if (u > 0) tok[u] = -1;  // the root's token is set with the context below
+        a.draft_has[(size_t)b * N + u] = 0;
+    }
+    if (tid < a.tree.D + 2) t_level[tid] = a.tree.level_start[tid];
+    if (wave == 1 && lane == 0) {
         // context tail of this trajectory, after appending the tokens committed by this step
         int32_t t[kMaxOrder];
         for (int i = 0; i < kMaxOrder; ++i) t[i] = a.ctx_tail[(size_t)b * kMaxOrder + i];
@@ -1329,26 +1340,21 @@ __global__ __launch_bounds__(kDraftThreads) void draft_kernel(DraftArgs a)
             for (int i = 0; i < kMaxOrder; ++i) a.ctx_tail[(size_t)b * kMaxOrder + i] = t[i];
             a.ctx_len[b] = len;
         }
-        for (int i = 0; i < kMaxOrder; ++i) tail[i] = t[i];
+        for (int i = 0; i < kMaxOrder; ++i) recent[0][i] = t[kMaxOrder - 1 - i];
+        tok[0] = len > 0 ? t[kMaxOrder - 1] : -1;
         s_clen = len;
-    }
-    for (int u = tid; u < N; u += kDraftThreads) {
-        tok[u] = -1;
-        a.draft_has[(size_t)b * N + u] = 0;
     }
     __syncthreads();
     const long long clen = s_clen;
-    if (tid == 0 && clen > 0) tok[0] = tail[kMaxOrder - 1];
-    __syncthreads();
     const int NO = a.omax - a.omin + 1;
     for (int d = 0; d < a.tree.D; ++d) {
-        const int lo = a.tree.level_start[d], hi = a.tree.level_start[d + 1];
+        const int lo = t_level[d], hi = t_level[d + 1];
         // a level without a drafted node ends the tree (tok is stable here: barrier below)
         bool any = false;
         for (int u = lo + lane; u < hi; u += 64) any |= tok[u] >= 0;
         if (!__ballot(any)) break;  // the same in every wave
         for (int u = lo + wave; u < hi; u += kDraftThreads / 64) {
-            const int nch = a.tree.nchild[u];
+            const int nch = t_nchild[u];
             if (nch == 0 || tok[u] < 0) continue;  // uniform per wave
             // ---- multi-level lookup (paper Sec. 4.2): lane q < NO takes order n = omax - q.
             // The home slot of every order is read together with its payload in one round
@@ -1358,12 +1364,7 @@ __global__ __launch_bounds__(kDraftThreads) void draft_kernel(DraftArgs a)
                 const int n = a.omax - lane;
                 if (clen + d >= n) {
                     int32_t key[kMaxOrder];
-                    int x = u;
-                    for (int i = n - 1; i >= 0; --i) {
-                        const int back = n - 1 - i;  // tokens back from the node itself
-                        if (back < d) { key[i] = tok[x]; x = a.tree.parent[x]; }
-                        else key[i] = tail[kMaxOrder - 1 - (back - d)];
-                    }
+                    for (int i = 0; i < n; ++i) key[i] = recent[u][n - 1 - i];
                     fp = fingerprint(n, key);
                 }
             }
@@ -1431,7 +1432,13 @@ __global__ __launch_bounds__(kDraftThreads) void draft_kernel(DraftArgs a)
             }
             int rank = 0;
             for (int q = 0; q < K; ++q) rank += readlane_u64(key, q) > key ? 1 : 0;
-            if (cand && rank < nch) tok[a.tree.first_child[u] + rank] = id;
+            if (cand && rank < nch) {
+                const int child = t_first[u] + rank;
+                tok[child] = id;
+                recent[child][0] = id;
+#pragma unroll
+                for (int i = 1; i < kMaxOrder; ++i) recent[child][i] = recent[u][i - 1];
+            }
             const int ncand = __popcll(__ballot(cand));
             if (lane == 0) a.draft_has[(size_t)b * N + u] = ncand < nch ? ncand : nch;
         }
