@@ -59,6 +59,8 @@ def main():
     ap.add_argument("--cpu-steps", type=int, default=3)
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-events", action="store_true", help="do not time the row pass with HIP events")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also run a plain copy of one logits tensor (known HBM traffic) for counter calibration")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU; every GPU box here has one, so --gpus %d is not run" % args.gpus,
@@ -127,6 +129,13 @@ def main():
     o_node = [torch.empty_like(out_node) for _ in rec]
     o_len = [torch.empty_like(out_len) for _ in rec]
     o_draft = [torch.empty_like(draft) for _ in rec]
+    if args.calib_copy:
+        src = rec[0][0]
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            binding.copy_bytes(dst, src, src.numel() * src.element_size())
+        torch.cuda.synchronize()
+        del dst
     h2.draft(T_warm, draft)
     for i in range(W_steps):
         lg, force, *_ = rec[i]
@@ -155,12 +164,19 @@ def main():
     # + row outputs + table traffic of the merges and probes + draft / verify state
     step_bytes = logits_bytes + w.B * w.V * 2 + rows * (8 + 12 * w.K) + 1_200_000 + 500_000
     row_bytes = logits_bytes + rows * (8 + 12 * w.K)
+    # HBM bytes per row-pass launch from profiler counters, if the committed summary holds them
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "row_pass_kernel_cfg3_hbm_traffic.txt")
+    if args.workload == "cfg3" and os.path.exists(tpath):
+        for line in open(tpath):
+            if line.startswith("traffic_bytes_per_launch:"):
+                traffic = int(float(line.split(":")[1]))
     roof = None
     if row_n:
         row_us = row_ms * 1e3 / row_n
         achieved = row_bytes / (row_us * 1e-6) / 1e9
         roof = {"bound": "hbm", "kernel": "row_pass_kernel", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
-                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
+                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
                 "avg_launch_us": round(row_us, 2), "bytes_per_launch": row_bytes}
 
     cpu = None

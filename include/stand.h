@@ -171,6 +171,13 @@ int stand_get_stats(stand_handle *h, stand_stats *out);
 int stand_profile_begin(stand_handle *h, int32_t max_launches);
 int stand_profile_end(stand_handle *h, double *row_pass_ms_total, int32_t *launches);
 
+/* Measurement aid, not part of the method: copies `bytes` (a multiple of 16, both pointers
+ * 16-byte aligned, device memory, non-overlapping) with a plain grid-stride kernel on `stream`.
+ * Its HBM traffic is known (bytes read + bytes written), so profiler byte counters read for
+ * the kernels above can be scaled by what they read for this one.  STAND_EINVAL on a bad
+ * size or alignment. */
+int stand_copy_bytes(void *d_dst, const void *d_src, uint64_t bytes, void *stream);
+
 const char *stand_strerror(int code);
 int stand_last_hip_error(const stand_handle *h);
 

@@ -20,7 +20,7 @@ EXPORTED = [
     "stand_create", "stand_destroy", "stand_depth", "stand_set_context", "stand_reorder", "stand_update",
     "stand_draft", "stand_verify", "stand_step", "stand_row_results", "stand_table_export", "stand_table_import",
     "stand_get_context", "stand_get_stats", "stand_strerror", "stand_last_hip_error",
-    "stand_profile_begin", "stand_profile_end",
+    "stand_profile_begin", "stand_profile_end", "stand_copy_bytes",
 ]
 
 
@@ -64,6 +64,7 @@ def load_library():
     lib.stand_get_stats.argtypes = [vp, C.POINTER(Stats)]
     lib.stand_profile_begin.argtypes = [vp, C.c_int32]
     lib.stand_profile_end.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_int32)]
+    lib.stand_copy_bytes.argtypes = [vp, vp, C.c_uint64, vp]
     lib.stand_strerror.restype = C.c_char_p
     lib.stand_strerror.argtypes = [C.c_int]
     lib.stand_last_hip_error.argtypes = [vp]
@@ -71,6 +72,13 @@ def load_library():
 
 
 _lib = None
+
+
+def copy_bytes(dst, src, nbytes, stream=None):
+    """Plain device copy (measurement aid): dst, src are torch tensors on the GPU."""
+    rc = lib().stand_copy_bytes(dst.data_ptr(), src.data_ptr(), nbytes, stream)
+    if rc:
+        raise RuntimeError("stand_copy_bytes: %s" % lib().stand_strerror(rc).decode())
 
 
 def lib():

@@ -18,7 +18,11 @@
 namespace stand {
 
 constexpr int kDtBf16 = 0, kDtF32 = 1;
-constexpr int kRowThreads = 256;
+#ifndef STAND_ROW_WPR
+#define STAND_ROW_WPR 4
+#endif
+constexpr int kRowWPR = STAND_ROW_WPR;      // waves that share one logits row (1, 2 or 4)
+constexpr int kRowThreads = 64 * kRowWPR;   // row pass: one row per workgroup
 constexpr int kMaxNodes = 256;
 constexpr int kMaxDepth = 31;
 constexpr int kPathThreads = 256;
@@ -201,12 +205,9 @@ __device__ __forceinline__ NodeResult wave_node_outcome(int lane, int K, int32_t
 #endif
 constexpr int kRowU = STAND_ROW_U;     // vectors per lane per batch
 constexpr int kRowPF = STAND_ROW_PF;   // batches in flight per wave
-constexpr int kWaveCap = 128;          // vector records per wave (pruned when above 64)
-#ifndef STAND_ROW_WPR
-#define STAND_ROW_WPR 4
-#endif
-constexpr int kRowWPR = STAND_ROW_WPR;                 // waves that share one row (1, 2 or 4)
-constexpr int kRowsPerBlock = kRowThreads / 64 / kRowWPR;
+constexpr int kWaveCap = 192;          // vector records per wave (pruned when above kWavePrune)
+constexpr int kWavePrune = 128;
+constexpr int kRowsPerBlock = 1;
 
 constexpr int kElemCap = 8 * kMaxK + 64;  // element candidates at the end of a row (<= 8 per kept vector + edges)
 
@@ -278,7 +279,43 @@ __device__ __forceinline__ void wave_prune(WaveScan *ws, WaveScanState &st, int 
     if (th) set_theta(st, th);
 }
 
-// Lanes with `has` append the record (cm, vec) if it beats the threshold; prune above 64 records.
+// Cheap prune: finds, by bisection on the upper key word (the vector maximum) with ballots, a
+// threshold that at least K records reach, and keeps those records (unsorted; records whose
+// maximum equals the threshold all stay).  Used while streaming, where only the threshold and
+// a short list matter.  Falls back to the exact prune when ties leave too many records.
+constexpr int kPruneSlack = 16;
+__device__ __forceinline__ void wave_prune_fast(WaveScan *ws, WaveScanState &st, int lane, int K)
+{
+    const int n = st.cnt;  // <= kWaveCap = 3 * 64
+    if (n <= K) return;
+    const unsigned long long e0 = lane < n ? ws->buf[lane] : 0ull;
+    const unsigned long long e1 = 64 + lane < n ? ws->buf[64 + lane] : 0ull;
+    const unsigned long long e2 = 128 + lane < n ? ws->buf[128 + lane] : 0ull;
+    const uint32_t h0 = (uint32_t)(e0 >> 32), h1 = (uint32_t)(e1 >> 32), h2 = (uint32_t)(e2 >> 32);
+    uint32_t t = 0u;
+    for (int bit = 31; bit >= 0; --bit) {
+        const uint32_t cand = t | (1u << bit);
+        const int c = __popcll(__ballot(h0 >= cand)) + __popcll(__ballot(h1 >= cand)) + __popcll(__ballot(h2 >= cand));
+        if (c >= K) {
+            t = cand;
+            if (c == K) break;
+        }
+    }
+    // at least K records have an upper word >= t (t > 0: keys of existing records are not zero)
+    __builtin_amdgcn_wave_barrier();
+    const unsigned long long b0 = __ballot(h0 >= t), b1 = __ballot(h1 >= t), b2 = __ballot(h2 >= t);
+    const int c0 = __popcll(b0), c1 = __popcll(b1);
+    if (h0 >= t) ws->buf[lane_prefix_count(b0)] = e0;
+    if (h1 >= t) ws->buf[c0 + lane_prefix_count(b1)] = e1;
+    if (h2 >= t) ws->buf[c0 + c1 + lane_prefix_count(b2)] = e2;
+    __builtin_amdgcn_wave_barrier();
+    st.cnt = c0 + c1 + __popcll(b2);
+    const unsigned long long key = (unsigned long long)t << 32;
+    if (key > st.theta_key) { st.theta_key = key; st.theta_val = order_key_inv(t); }
+    if (st.cnt > K + kPruneSlack) wave_prune(ws, st, lane, K);
+}
+
+// Lanes with `has` append the record (cm, vec) if it beats the threshold; prune above kWavePrune records.
 __device__ __forceinline__ void wave_offer(WaveScan *ws, WaveScanState &st, int lane, int K, bool has, float cm,
                                            uint32_t vec)
 {
@@ -289,7 +326,7 @@ __device__ __forceinline__ void wave_offer(WaveScan *ws, WaveScanState &st, int 
     if (pred) ws->buf[st.cnt + lane_prefix_count(bal)] = key;
     st.cnt += __popcll(bal);
     __builtin_amdgcn_wave_barrier();
-    if (st.cnt > 64) wave_prune(ws, st, lane, K);
+    if (st.cnt > kWavePrune) wave_prune_fast(ws, st, lane, K);
 }
 
 // Leaves the row's K best element keys (value desc, id asc) sorted in ws->top[0..K), returns
@@ -300,7 +337,7 @@ __device__ __forceinline__ void wave_offer(WaveScan *ws, WaveScanState &st, int 
 // are ranked only at the end, among those kept vectors.
 struct WavePartial {
     float m_ref, s;   // reference maximum of this wave's part and its fast sum relative to it
-    int cnt;          // vector records left in ws->buf (the wave's K best, sorted, also in ws->top)
+    int cnt;          // vector records left in ws->buf: the wave's K best and at most kPruneSlack more, unsorted
 };
 
 // Streaming part: wave `wsub` of `wpr` cooperating waves takes every wpr-th batch of the row.
@@ -367,9 +404,7 @@ __device__ __forceinline__ WavePartial wave_row_stream(const void *rowp, int V, 
 #pragma unroll
         for (int j = 0; j < EPV; ++j) e += fast_exp2(__builtin_fmaf(x[j], c, nb));
         s_t += valid ? e : 0.0f;
-#ifndef STAND_TUNE_NOTOPK
         if (__ballot(valid && cm >= st.theta_val)) wave_offer(ws, st, lane, K, valid && cm >= st.theta_val, cm, (uint32_t)idx);
-#endif
     };
     auto do_batch = [&](uint4 (&w)[U], int k) {
         const int kb = k * wpr + wsub;        // batch of the row
@@ -395,8 +430,8 @@ __device__ __forceinline__ WavePartial wave_row_stream(const void *rowp, int V, 
         }
     }
 
-    // leave this wave's K best records sorted in ws->buf / ws->top
-    wave_prune(ws, st, lane, K);
+    // leave at most K + kPruneSlack records, the wave's K best among them, in ws->buf
+    wave_prune_fast(ws, st, lane, K);
     float s = s_t;
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off);
@@ -420,6 +455,14 @@ __device__ __forceinline__ void wave_row_finish(const void *rowp, int V, int K, 
     else if (lane < g.head + g.ntail) edge_id = g.tail0 + (lane - g.head);
     const float edge_val = edge_id >= 0 ? load_scalar<DT>(rowp, edge_id) : -__builtin_inff();
 
+    {
+        // cut the merged list down cheaply before the exact ranking
+        WaveScanState st;
+        st.cnt = cnt;
+        set_theta(st, 0ull);
+        wave_prune_fast(ws, st, lane, K);
+        cnt = st.cnt;
+    }
     const unsigned long long th_vec = wave_select(ws->buf, ws->top, lane, K, cnt);
     const int kept = cnt < K ? cnt : K;
     const float th_val = th_vec ? rank_key_value(th_vec) : -__builtin_inff();
@@ -533,10 +576,20 @@ struct RowPassArgs {
     unsigned long long *stats;
 };
 
+#ifndef STAND_TUNE_WAVES
+#define STAND_TUNE_WAVES_ATTR
+#else
+#define STAND_TUNE_WAVES_ATTR __attribute__((amdgpu_waves_per_eu(STAND_TUNE_WAVES, STAND_TUNE_WAVES)))
+#endif
 template <int DT>
-__global__ __launch_bounds__(kRowThreads) void row_pass_kernel(RowPassArgs a)
+__global__ __launch_bounds__(kRowThreads) STAND_TUNE_WAVES_ATTR void row_pass_kernel(RowPassArgs a)
 {
     constexpr int ES = VecTraits<DT>::ES;
+#ifdef STAND_TUNE_LDS_PAD
+    __shared__ int lds_pad[STAND_TUNE_LDS_PAD / 4];
+    if (a.V < 0) lds_pad[threadIdx.x] = a.K;  // never true: keeps the padding allocated
+    if (a.V < -1) a.outcome[0] = lds_pad[threadIdx.x ^ 1];
+#endif
     __shared__ WaveScan wsh[kRowThreads / 64];
     __shared__ float part_m[kRowThreads / 64], part_s[kRowThreads / 64];
     __shared__ int part_cnt[kRowThreads / 64];
@@ -548,9 +601,31 @@ __global__ __launch_bounds__(kRowThreads) void row_pass_kernel(RowPassArgs a)
     const int b = live ? row / a.N : 0, u = live ? row % a.N : 0;
     const char *rowp = (const char *)a.logits + (size_t)(live ? row : 0) * (size_t)a.V * ES;
     float m, s;
+    // The proposal of this node (needed for the accept tests at the end) is requested by the
+    // finishing wave as soon as it has streamed its part, so that its two dependent round trips
+    // to memory pass while the row is being ranked.
+    int nch = 0, fc = -1;
+    int32_t my_id = -1, ch = -1;
+    float my_mu = 0.0f, my_l = 0.0f;
+    auto request_proposal = [&]() {
+        fc = a.tree.first_child[u];
+        nch = a.draft_has[row];  // children drafted from this node's table entry (0: none)
+        if (lane < a.K) {
+            my_id = a.draft_qid[(size_t)row * a.K + lane];
+            my_mu = a.draft_qmu[(size_t)row * a.K + lane];
+        }
+    };
+    auto request_proposal_logits = [&]() {
+        if (nch == 0) return;  // uniform over the wave
+        if ((uint32_t)my_id >= (uint32_t)a.V) { my_id = -1; my_mu = 0.0f; }  // never index outside the row
+        else my_l = load_scalar<DT>(rowp, my_id);
+        if (lane < nch && lane < kMaxK && fc >= 0 && fc + lane < a.N) ch = a.draft_tok[(size_t)b * a.N + fc + lane];
+    };
     if constexpr (kRowWPR == 1) {
         if (!live) return;  // whole wave; no workgroup barrier in this configuration
         const WavePartial wp = wave_row_stream<DT>(rowp, a.V, a.c, a.K, ws, lane, 0, 1);
+        request_proposal();
+        request_proposal_logits();
         wave_row_finish<DT>(rowp, a.V, a.K, ws, lane, wp.cnt);
         m = rank_key_value(ws->top[0]);
         s = wp.s * fast_exp2((wp.m_ref - m) * a.c);  // m_ref equals m: the factor is 1
@@ -558,10 +633,12 @@ __global__ __launch_bounds__(kRowThreads) void row_pass_kernel(RowPassArgs a)
         if (live) {
             const WavePartial wp = wave_row_stream<DT>(rowp, a.V, a.c, a.K, ws, lane, wsub, kRowWPR);
             if (lane == 0) { part_m[wave] = wp.m_ref; part_s[wave] = wp.s; part_cnt[wave] = wp.cnt; }
+            if (wsub == 0) request_proposal();
         }
         __syncthreads();
         if (!live || wsub != 0) return;
-        // gather the partner waves' records behind this wave's own (all lists hold at most K records)
+        request_proposal_logits();
+        // gather the partner waves' records behind this wave's own (each list holds at most K + kPruneSlack)
         int cnt = part_cnt[wave];
         for (int q = 1; q < kRowWPR; ++q) {
             const int cq = part_cnt[wave + q];
@@ -585,21 +662,10 @@ __global__ __launch_bounds__(kRowThreads) void row_pass_kernel(RowPassArgs a)
     if (lane == 0) { a.row_m[row] = m; a.row_s[row] = s; }
 
     // ---- accept / reject outcome of this node's children (paper Sec. 3.2, applied recursively)
-    const int fc = a.tree.first_child[u];
-    const int nch = a.draft_has[row];  // children drafted from this node's table entry (0: none)
     if (nch == 0) {  // uniform over the wave
         if (lane == 0) a.outcome[row] = -1;
         return;
     }
-    int32_t my_id = -1;
-    float my_mu = 0.0f, my_l = 0.0f;
-    if (lane < a.K) {
-        my_id = a.draft_qid[(size_t)row * a.K + lane];
-        my_mu = a.draft_qmu[(size_t)row * a.K + lane];
-        if ((uint32_t)my_id >= (uint32_t)a.V) { my_id = -1; my_mu = 0.0f; }  // never index outside the row
-        else my_l = load_scalar<DT>(rowp, my_id);
-    }
-    const int32_t ch = (lane < nch && lane < kMaxK && fc >= 0 && fc + lane < a.N) ? a.draft_tok[(size_t)b * a.N + fc + lane] : -1;
     const float e = (lane < a.K && my_id >= 0) ? exact_exp2(scaled_offset(my_l, m, a.c)) : 0.0f;
     NodeResult nr = wave_node_outcome(lane, a.K, my_id, my_mu, e / s, nch, ch, a.seed, (uint32_t)b, a.step, fc,
                                       true, kFastEps);
@@ -1470,6 +1536,13 @@ __global__ void copy_row_results_kernel(int rows, int K, const float *row_m, con
         if (o_idx) o_idx[i] = top_idx[i];
         if (o_p) o_p[i] = top_p[i];
     }
+}
+
+// plain copy of 16-byte words: the known-size kernel against which HBM traffic counters are scaled
+__global__ __launch_bounds__(256) void copy_words_kernel(const uint4 *src, uint4 *dst, size_t nwords)
+{
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < nwords; i += stride) dst[i] = src[i];
 }
 
 // export support: count and compact the occupied slots

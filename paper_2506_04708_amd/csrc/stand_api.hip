@@ -259,11 +259,21 @@ static int launch_row_pass(stand_handle *h, uint64_t step, const void *d_logits,
     a.outcome = h->outcome; a.stats = h->stats;
     const dim3 grid((unsigned)((h->B * h->N + kRowsPerBlock - 1) / kRowsPerBlock)), block(kRowThreads);
     const bool timed = h->profiling && h->ev_used < h->ev_begin.size();
-    if (timed) HIP_TRY(h, hipEventRecord(h->ev_begin[h->ev_used], s));
-    if (h->cfg.logits_dtype == STAND_BF16) row_pass_kernel<kDtBf16><<<grid, block, 0, s>>>(a);
-    else row_pass_kernel<kDtF32><<<grid, block, 0, s>>>(a);
+    if (timed) {
+        // the events are attached to the dispatch itself: their difference is the kernel's own
+        // start-to-end time, without the marker packets a hipEventRecord pair would add
+        hipEvent_t e0 = h->ev_begin[h->ev_used], e1 = h->ev_end[h->ev_used];
+        h->ev_used++;
+        void *args[] = {&a};
+        const void *fn = h->cfg.logits_dtype == STAND_BF16 ? (const void *)row_pass_kernel<kDtBf16>
+                                                           : (const void *)row_pass_kernel<kDtF32>;
+        HIP_TRY(h, hipExtLaunchKernel(fn, grid, block, args, 0, s, e0, e1, 0));
+    } else if (h->cfg.logits_dtype == STAND_BF16) {
+        row_pass_kernel<kDtBf16><<<grid, block, 0, s>>>(a);
+    } else {
+        row_pass_kernel<kDtF32><<<grid, block, 0, s>>>(a);
+    }
     HIP_TRY(h, hipGetLastError());
-    if (timed) HIP_TRY(h, hipEventRecord(h->ev_end[h->ev_used++], s));
     return STAND_OK;
 }
 
@@ -559,6 +569,17 @@ extern "C" int stand_profile_end(stand_handle *h, double *row_pass_ms_total, int
     h->profiling = false;
     h->ev_used = 0;
     return STAND_OK;
+}
+
+extern "C" int stand_copy_bytes(void *d_dst, const void *d_src, uint64_t bytes, void *stream)
+{
+    if (!d_dst || !d_src || (bytes & 15u) || (((uintptr_t)d_dst | (uintptr_t)d_src) & 15u)) return STAND_EINVAL;
+    const size_t nwords = bytes / 16;
+    if (nwords == 0) return STAND_OK;
+    const size_t want = (nwords + 255) / 256;
+    const unsigned blocks = (unsigned)(want < 16384 ? want : 16384);
+    copy_words_kernel<<<dim3(blocks), dim3(256), 0, (hipStream_t)stream>>>((const uint4 *)d_src, (uint4 *)d_dst, nwords);
+    return hipGetLastError() == hipSuccess ? STAND_OK : STAND_EHIP;
 }
 
 extern "C" const char *stand_strerror(int code)
