@@ -1,17 +1,23 @@
 // kernels.hpp -- HIP kernels of the STAND speculation step for gfx950 (wave64).
 //
-//   row_pass_kernel   softmax statistics + top-K of every logits row in one streaming pass, and
-//                     the accept/reject outcome of the row's tree node        (paper Sec. 4.1, 3.2)
-//   path_pass_kernel  exact normaliser + observation of the rows on the accepted path, and the
-//                     resampled token at the stop node                        (paper Sec. 3.2, 4.1)
-//   merge_*           running-mean merge into the open-addressing table       (paper Sec. 4.1)
-//   draft_kernel      multi-level lookup + Gumbel-Top-K along the static tree (paper Sec. 4.2)
+//   row_pass_kernel     softmax statistics + top-K of every logits row in one streaming pass, and
+//                       the accept/reject outcome of the row's tree node      (paper Sec. 4.1, 3.2)
+//   path_exact_kernel   exact integer partial sums of the rows on the accepted path; walks the
+//                       path and gathers the stop node's proposal             (paper Sec. 3.2)
+//   path_finish_kernel  observation of each path row with the exact normaliser, replay of the
+//                       stop node, resampled token by inverting the residual's cumulative
+//                       integer mass; claims the table slots of the merge     (paper Sec. 3.2, 4.1)
+//   merge_apply_kernel  running-mean merge into the open-addressing table     (paper Sec. 4.1)
+//   draft_kernel        multi-level lookup + Gumbel-Top-K along the static tree (paper Sec. 4.2)
+//   commit_scan_kernel  top-K of caller-given rows (update without verify)
 //
 // The row pass is the only kernel that touches all of the logits; it is bound by HBM bandwidth.
-// Its softmax normaliser uses the hardware exp2 and float accumulation (relative error far
-// below the 5e-5 bound used here); every accept test whose margin is inside that bound, and
+// Its softmax normaliser uses the hardware exp2 and float accumulation (relative error below
+// the 5e-5 bound assumed here); every accept test whose margin is inside that bound, and
 // every probability that is stored in the table or used for resampling, is recomputed with
 // the exact integer normaliser of numeric.hpp, so all decisions are those of exact arithmetic.
+// The kernels after the row pass are chains of dependent memory round trips over little data;
+// workgroups exchange data only across kernel boundaries (no device-scope atomics or fences).
 #pragma once
 #include "numeric.hpp"
 
@@ -576,20 +582,10 @@ struct RowPassArgs {
     unsigned long long *stats;
 };
 
-#ifndef STAND_TUNE_WAVES
-#define STAND_TUNE_WAVES_ATTR
-#else
-#define STAND_TUNE_WAVES_ATTR __attribute__((amdgpu_waves_per_eu(STAND_TUNE_WAVES, STAND_TUNE_WAVES)))
-#endif
 template <int DT>
-__global__ __launch_bounds__(kRowThreads) STAND_TUNE_WAVES_ATTR void row_pass_kernel(RowPassArgs a)
+__global__ __launch_bounds__(kRowThreads) void row_pass_kernel(RowPassArgs a)
 {
     constexpr int ES = VecTraits<DT>::ES;
-#ifdef STAND_TUNE_LDS_PAD
-    __shared__ int lds_pad[STAND_TUNE_LDS_PAD / 4];
-    if (a.V < 0) lds_pad[threadIdx.x] = a.K;  // never true: keeps the padding allocated
-    if (a.V < -1) a.outcome[0] = lds_pad[threadIdx.x ^ 1];
-#endif
     __shared__ WaveScan wsh[kRowThreads / 64];
     __shared__ float part_m[kRowThreads / 64], part_s[kRowThreads / 64];
     __shared__ int part_cnt[kRowThreads / 64];
@@ -1005,8 +1001,6 @@ __device__ __forceinline__ void merge_claim_record(const MergeArgs &a, int rec)
     }
     a.rec_slot[rec] = slot_out;
 }
-
-__global__ void merge_claim_kernel(MergeArgs a) { merge_claim_record(a, blockIdx.x * blockDim.x + threadIdx.x); }
 
 // See the comment above PathArgs.  Blocks [0, finish_blocks) finish path row (b, j) =
 // (block / W, block % W); the blocks after them claim merge records, kFinishThreads per block.

@@ -325,10 +325,6 @@ static int launch_path_pass(stand_handle *h, uint64_t step, const void *d_logits
     a.nseg = clampi((row_vectors + 4 * kPathThreads - 1) / (4 * kPathThreads), 1, kSegMax);
     const dim3 g1((unsigned)a.nseg + 1, (unsigned)h->W, (unsigned)h->B), block(kPathThreads);
     const int finish_blocks = h->B * h->W;
-#ifdef STAND_TUNE_SPLIT_CLAIM
-    if (claim) merge_claim_kernel<<<dim3((unsigned)((h->B * h->W * h->NO + 255) / 256)), dim3(256), 0, s>>>(*claim);
-    claim = nullptr;
-#endif
     const int claim_blocks = claim ? (h->B * h->W * h->NO + kFinishThreads - 1) / kFinishThreads : 0;
     const MergeArgs mg = claim ? *claim : merge_args(h, nullptr, nullptr, nullptr);
     const dim3 g2((unsigned)(finish_blocks + claim_blocks));

@@ -147,6 +147,41 @@ def test_full_shape_rows_sampled(gpu):
     g.close()
 
 
+def test_full_shape_step(gpu):
+    """The configuration bench.py times (B=32, N=64, V=152064, bf16, K=16, orders 1-4), three whole
+    stand_step calls in lock step with the oracle: tokens, nodes, lengths, next drafts, table."""
+    binding, lockstep = gpu
+    w = synth.Workload("cfg3", run_steps=3)
+    _say("full shape stand_step, 3 steps")
+    info = lockstep.run_lockstep(w, 3, mode="step", capacity=1 << 16, forced=True, check_rows=False)
+    _say("  -> %s" % info)
+    assert info["emitted"] >= 3 * w.B and info["entries"] > 0
+
+
+def test_row_pass_timing_and_copy(gpu):
+    """stand_profile_begin / stand_profile_end bracket the row pass launches; stand_copy_bytes copies."""
+    binding, lockstep = gpu
+    w = synth.Workload("cfg1", run_steps=4, V=4096, B=2)
+    g = binding.Stand(w.V, w.B, 1, 3, w.K, w.parent, w.T, 1 << 12, 64, 5, binding.STAND_F32)
+    out_tok, out_node, out_len, d = g.new_outputs()
+    lg = torch.randn((w.B, w.N, w.V), device="cuda", dtype=torch.float32)
+    g.profile_begin(3)
+    for step in range(5):                      # more launches than events: the extra ones are not timed
+        g.verify(step, lg, out_tok, out_node, out_len)
+    ms, n = g.profile_end()
+    assert n == 3 and 0.0 < ms < 50.0
+    ms2, n2 = g.profile_end()                  # switched off: nothing measured
+    assert n2 == 0 and ms2 == 0.0
+    g.close()
+    src = torch.arange(1 << 16, device="cuda", dtype=torch.int32)
+    dst = torch.zeros_like(src)
+    binding.copy_bytes(dst, src, src.numel() * 4)
+    torch.cuda.synchronize()
+    assert torch.equal(dst, src)
+    with pytest.raises(RuntimeError):
+        binding.copy_bytes(dst, src, 24)       # not a multiple of 16
+
+
 # ---- state handling ------------------------------------------------------------------------------
 def test_determinism_and_import_export(gpu):
     binding, lockstep = gpu
