@@ -74,8 +74,15 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     K_steps, W_steps, T_warm = args.steps, args.warmup, args.table_warm
     total = T_warm + W_steps + K_steps
-    cfg = synth.CONFIGS[args.workload]
-    w = synth.Workload(args.workload, run_steps=total + 2)
+    if args.workload == "opt625":
+        # the tree-optimisation run of the paper (Sec. 4.3): speculation on the 625-node initial tree
+        big = binding.tree_initial(20)
+        cfg = dict(B=4, V=152064, dtype="bf16", N=len(big), D=20, caps=[8], parent=big, order_min=1, order_max=4, K=16,
+                   T=0.6, capacity=1 << 20, rho=0.5, seed=synth.BASE_SEED + 9)
+        w = synth.Workload(None, run_steps=total + 2, **cfg)
+    else:
+        cfg = synth.CONFIGS[args.workload]
+        w = synth.Workload(args.workload, run_steps=total + 2)
     dt = binding.STAND_BF16 if w.dtype == "bf16" else binding.STAND_F32
     assert w.dtype == "bf16"
     mk = lambda: binding.Stand(w.V, w.B, cfg["order_min"], cfg["order_max"], w.K, w.parent, w.T, cfg["capacity"], 64,
@@ -209,13 +216,14 @@ def main():
                          % (cpu_n, cpu_s, rows)}
 
     out = {
-        "metric": "speculation steps/s (stand_step: verify + table merge + draft), B=32, V=152064, 64-node tree",
+        "metric": "speculation steps/s (stand_step: verify + table merge + draft), B=%d, V=%d, %d-node tree" % (w.B, w.V, w.N),
         "value": round(steps_per_s, 2), "unit": "steps/s", "n_gpus": 1, "steps": K_steps, "warmup": W_steps,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": "cfg3: B=32 trajectories sharing one table, V=152064, bf16 logits, 64-node tree (depth 8), "
-                               "orders 1-4, K=16, T=0.6, 2^22 slots; open-loop replay of seeded streams, table warmed "
-                               "for %d steps" % T_warm,
+        "config": {"workload": "%s: B=%d trajectories sharing one table, V=%d, bf16 logits, %d-node tree (depth %d), "
+                               "orders %d-%d, K=%d, T=%.1f, %d slots; open-loop replay of seeded streams, table warmed "
+                               "for %d steps" % (args.workload, w.B, w.V, w.N, w.D, cfg["order_min"], cfg["order_max"], w.K,
+                                                 w.T, cfg["capacity"], T_warm),
                    "acceptance_len": round(acc_len, 3), "table_entries": int(entries0 + st.inserts)},
         "hbm_gbps_algorithmic": round(step_bytes * steps_per_s / 1e9, 1),
         "hbm_frac_of_peak": round(step_bytes * steps_per_s / 1e9 / HBM_PEAK_GBPS, 4),

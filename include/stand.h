@@ -46,7 +46,7 @@ extern "C" {
 
 #define STAND_MAX_TOPK 32
 #define STAND_MAX_ORDER 8
-#define STAND_MAX_NODES 256
+#define STAND_MAX_NODES 1024
 #define STAND_MAX_DEPTH 31
 
 typedef struct stand_handle stand_handle;
@@ -170,6 +170,35 @@ int stand_get_stats(stand_handle *h, stand_stats *out);
  * and the number of launches measured, and switches the timing off. */
 int stand_profile_begin(stand_handle *h, int32_t max_launches);
 int stand_profile_end(stand_handle *h, double *row_pass_ms_total, int32_t *launches);
+
+/* ---- data-driven draft tree (paper Sec. 4.3 and appendix "Initial tree for optimization") ----
+ *
+ * The paper starts from a large heuristic tree, runs speculative decoding on sample data while
+ * counting which nodes lie on accepted paths, keeps the most often accepted nodes and re-packs
+ * them into the static tree used afterwards.  The three host-side steps of that procedure:
+ *
+ * stand_tree_initial: the initial tree of the appendix (Alg. 1) with `levels` levels below the
+ *   root (the paper: 20, giving 625 nodes).  Fan-out by depth and by rank r among the siblings:
+ *   root 8; depth 1: max(8 - 2r, 1); deeper: ceil((siblings - 1) / (0.7 r + 1)), at least 2 at
+ *   depths 2 and 3; the first node of each level at least 3.  Writes the node count to *n_out
+ *   and, if capacity > 0, parent[] (layout of stand_config.tree_parent) to host_parent_out;
+ *   STAND_EINVAL if capacity is positive but too small.  Host memory only, no device needed.
+ *
+ * stand_get_node_counts / stand_reset_node_counts: every stand_verify / stand_step adds 1 to
+ *   counts[u] for each node u on each trajectory's accepted path (the root is on every path).
+ *   host_counts: [tree_nodes].  Both synchronise the device.
+ *
+ * stand_tree_select: keeps n_keep of the n nodes of `host_parent` -- ranked by (usable count
+ *   descending, depth ascending, id ascending), where a node's usable count is the smallest
+ *   count on its way to the root, so the kept set is closed under parents -- and re-packs them
+ *   breadth first with siblings in their old rank order.  Writes parent[] of the new tree to
+ *   host_parent_out[n_keep] and, if not NULL, the old id of every new node to
+ *   host_old_id_out[n_keep].  STAND_EINVAL if the input is not in the tree layout above. */
+int stand_tree_initial(int32_t levels, int32_t *host_parent_out, int32_t capacity, int32_t *n_out);
+int stand_get_node_counts(stand_handle *h, uint64_t *host_counts);
+int stand_reset_node_counts(stand_handle *h);
+int stand_tree_select(const int32_t *host_parent, const uint64_t *host_counts, int32_t n, int32_t n_keep,
+                      int32_t *host_parent_out, int32_t *host_old_id_out);
 
 /* Measurement aid, not part of the method: copies `bytes` (a multiple of 16, both pointers
  * 16-byte aligned, device memory, non-overlapping) with a plain grid-stride kernel on `stream`.

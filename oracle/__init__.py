@@ -119,6 +119,8 @@ def lib():
         L.so_table_export.restype = C.c_int64
         L.so_table_export.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64]
         L.so_get_stats.argtypes = [C.c_void_p, C.POINTER(Stats)]
+        L.so_get_node_counts.argtypes = [C.c_void_p, C.c_void_p]
+        L.so_reset_node_counts.argtypes = [C.c_void_p]
         L.so_mc_gumbel_topk.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_uint64, C.c_uint64, C.c_void_p]
         L.so_mc_node.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_int, C.c_uint64, C.c_uint64,
                                  C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
@@ -379,6 +381,14 @@ class Oracle:
         lib().so_get_stats(self.h, C.byref(s))
         return s
 
+    def node_counts(self):
+        out = np.zeros(self.N, np.uint64)
+        lib().so_get_node_counts(self.h, _p(out))
+        return out
+
+    def reset_node_counts(self):
+        lib().so_reset_node_counts(self.h)
+
 
 def parse_table_export(buf, K):
     """Split an exported table (entries sorted by fingerprint) into arrays."""
@@ -387,3 +397,67 @@ def parse_table_export(buf, K):
     rec = np.frombuffer(buf.tobytes(), dtype=np.dtype([
         ("fp", "<u8"), ("count", "<u4"), ("order", "<u4"), ("ids", "<i4", (K,)), ("mu", "<f4", (K,))]), count=n)
     return rec
+
+
+# ---- data-driven draft tree (Sec. 4.3, App. "Initial tree for optimization") -----------------------
+def tree_initial(levels=20):
+    """The large initial tree of the tree optimisation (Alg. 1 of the appendix), as parent[].
+
+    Built level by level from the root.  A node's fan-out depends on its depth and on its rank
+    among its siblings: the root gets 8 children; a depth-1 node of rank r gets max(8 - 2r, 1);
+    a deeper node gets ceil((s - 1) / (0.7 r + 1)) where s is the number of its siblings
+    (itself included), but at least 2 at depths 2 and 3; the first node of every level gets at
+    least 3.  Nodes are numbered in creation order, which is breadth first with the children of
+    a node contiguous in rank order.  levels = 20 gives the paper's 625 nodes of depth 20.
+    """
+    parent, depth, rank, fanout = [-1], [0], [0], [0]
+    level = [0]
+    for _ in range(levels):
+        nxt = []
+        for pos, u in enumerate(level):
+            if depth[u] == 0:
+                n = 8
+            elif depth[u] == 1:
+                n = max(8 - 2 * rank[u], 1)
+            else:
+                siblings = fanout[parent[u]]
+                n = int(np.ceil((siblings - 1) / (rank[u] * 0.7 + 1)))
+                n = max(n, 2 if depth[u] <= 3 else 0)
+            if pos == 0:
+                n = max(n, 3)
+            fanout[u] = n
+            for r in range(n):
+                parent.append(u)
+                depth.append(depth[u] + 1)
+                rank.append(r)
+                fanout.append(0)
+                nxt.append(len(parent) - 1)
+        level = nxt
+    return np.asarray(parent, np.int32)
+
+
+def tree_select(parent, counts, n_keep):
+    """Keeps the n_keep most often accepted nodes of a tree and re-packs them (Sec. 4.3: "select
+    the top-80 most effective nodes and reorganize them into a compact tree structure").
+
+    A node can only be used if all its ancestors are, so a node counts as often as the least
+    counted node on its way to the root; nodes are ranked by (that count descending, depth
+    ascending, id ascending) and the first n_keep are kept.  They are renumbered by (depth, old
+    id), which is again breadth first with siblings contiguous in their old rank order.
+    Returns (new parent[], old id of every new node).
+    """
+    parent = np.asarray(parent, np.int64)
+    counts = np.asarray(counts, np.uint64)
+    n = parent.shape[0]
+    assert 1 <= n_keep <= n
+    depth = np.zeros(n, np.int64)
+    eff = [int(c) for c in counts]
+    eff[0] = max(eff)                       # the root is on every path
+    for u in range(1, n):
+        depth[u] = depth[parent[u]] + 1
+        eff[u] = min(eff[u], eff[parent[u]])
+    order = sorted(range(n), key=lambda u: (-eff[u], depth[u], u))
+    kept = sorted(order[:n_keep], key=lambda u: (depth[u], u))
+    new_id = {u: i for i, u in enumerate(kept)}
+    new_parent = np.array([-1 if u == 0 else new_id[int(parent[u])] for u in kept], np.int32)
+    return new_parent, np.asarray(kept, np.int32)

@@ -542,6 +542,7 @@ typedef struct so_handle {
     int32_t *draft_has;   /* [B][N] node has an entry */
     int32_t *draft_qid;   /* [B][N][K] */
     float *draft_qmu;     /* [B][N][K] */
+    uint64_t *node_count; /* [N] how often each tree node lay on an accepted path (Sec. 4.3) */
     so_stats st;
 } so_handle;
 
@@ -581,6 +582,7 @@ so_handle *so_create(const so_config *cfg)
     h->draft_qid = (int32_t *)calloc((size_t)B * N * h->K, sizeof(int32_t));
     h->draft_qmu = (float *)calloc((size_t)B * N * h->K, sizeof(float));
     for (int64_t i = 0; i < (int64_t)B * N; ++i) h->draft_tok[i] = -1;
+    h->node_count = (uint64_t *)calloc((size_t)N, sizeof(uint64_t));
     return h;
 }
 
@@ -592,6 +594,7 @@ void so_destroy(so_handle *h)
     free(h->parent); free(h->depth); free(h->nchild); free(h->first_child);
     free(h->ent); free(h->bucket); free(h->slot_fp);
     free(h->draft_tok); free(h->draft_has); free(h->draft_qid); free(h->draft_qmu);
+    free(h->node_count);
     free(h);
 }
 
@@ -844,6 +847,7 @@ void so_verify(so_handle *h, uint64_t step, const void *logits,
                 h->st.near_threshold += (uint64_t)st.near_threshold;
             }
             out_node[(int64_t)b * W + len] = cur;
+            h->node_count[cur]++; /* this node is on the accepted path of this verification */
             if (acc >= 0) {
                 int ch = h->first_child[cur] + acc;
                 out_tok[(int64_t)b * W + len] = tok[ch];
@@ -940,6 +944,12 @@ int64_t so_table_export(const so_handle *h, void *buf, uint64_t cap_bytes)
 }
 
 void so_get_stats(const so_handle *h, so_stats *out) { *out = h->st; }
+
+/* Per-node acceptance counters for the data-driven tree (Sec. 4.3: "track which nodes are
+ * frequently part of successful speculation paths"): counts[u] = number of verifications in
+ * which node u lay on the accepted path (the root lies on every path). */
+void so_get_node_counts(const so_handle *h, uint64_t *out) { memcpy(out, h->node_count, sizeof(uint64_t) * (size_t)h->N); }
+void so_reset_node_counts(so_handle *h) { memset(h->node_count, 0, sizeof(uint64_t) * (size_t)h->N); }
 
 /* ==========================================================================================
  * Monte-Carlo drivers used by the statistical pins (they run the functions above in a loop).

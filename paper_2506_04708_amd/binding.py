@@ -21,6 +21,7 @@ EXPORTED = [
     "stand_draft", "stand_verify", "stand_step", "stand_row_results", "stand_table_export", "stand_table_import",
     "stand_get_context", "stand_get_stats", "stand_strerror", "stand_last_hip_error",
     "stand_profile_begin", "stand_profile_end", "stand_copy_bytes",
+    "stand_tree_initial", "stand_tree_select", "stand_get_node_counts", "stand_reset_node_counts",
 ]
 
 
@@ -65,6 +66,10 @@ def load_library():
     lib.stand_profile_begin.argtypes = [vp, C.c_int32]
     lib.stand_profile_end.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_int32)]
     lib.stand_copy_bytes.argtypes = [vp, vp, C.c_uint64, vp]
+    lib.stand_tree_initial.argtypes = [C.c_int32, i32p, C.c_int32, C.POINTER(C.c_int32)]
+    lib.stand_tree_select.argtypes = [i32p, vp, C.c_int32, C.c_int32, i32p, i32p]
+    lib.stand_get_node_counts.argtypes = [vp, vp]
+    lib.stand_reset_node_counts.argtypes = [vp]
     lib.stand_strerror.restype = C.c_char_p
     lib.stand_strerror.argtypes = [C.c_int]
     lib.stand_last_hip_error.argtypes = [vp]
@@ -79,6 +84,32 @@ def copy_bytes(dst, src, nbytes, stream=None):
     rc = lib().stand_copy_bytes(dst.data_ptr(), src.data_ptr(), nbytes, stream)
     if rc:
         raise RuntimeError("stand_copy_bytes: %s" % lib().stand_strerror(rc).decode())
+
+
+def tree_initial(levels=20):
+    """parent[] of the initial tree of the tree optimisation (host only)."""
+    n = C.c_int32(0)
+    rc = lib().stand_tree_initial(levels, None, 0, C.byref(n))
+    if rc:
+        raise RuntimeError("stand_tree_initial: %s" % lib().stand_strerror(rc).decode())
+    out = np.zeros(n.value, np.int32)
+    rc = lib().stand_tree_initial(levels, out.ctypes.data, n.value, C.byref(n))
+    if rc:
+        raise RuntimeError("stand_tree_initial: %s" % lib().stand_strerror(rc).decode())
+    return out
+
+
+def tree_select(parent, counts, n_keep):
+    """(new parent[], old ids) of the n_keep most often accepted nodes, re-packed (host only)."""
+    parent = np.ascontiguousarray(parent, np.int32)
+    counts = np.ascontiguousarray(counts, np.uint64)
+    out = np.zeros(n_keep, np.int32)
+    old = np.zeros(n_keep, np.int32)
+    rc = lib().stand_tree_select(parent.ctypes.data, counts.ctypes.data, parent.shape[0], n_keep, out.ctypes.data,
+                                 old.ctypes.data)
+    if rc:
+        raise RuntimeError("stand_tree_select: %s" % lib().stand_strerror(rc).decode())
+    return out, old
 
 
 def lib():
@@ -221,3 +252,11 @@ class Stand:
         s = Stats()
         _check(lib().stand_get_stats(self.h, C.byref(s)), self.h)
         return s
+
+    def node_counts(self):
+        out = np.zeros(self.N, np.uint64)
+        _check(lib().stand_get_node_counts(self.h, out.ctypes.data), self.h)
+        return out
+
+    def reset_node_counts(self):
+        _check(lib().stand_reset_node_counts(self.h), self.h)

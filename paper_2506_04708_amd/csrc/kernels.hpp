@@ -29,7 +29,7 @@ constexpr int kDtBf16 = 0, kDtF32 = 1;
 #endif
 constexpr int kRowWPR = STAND_ROW_WPR;      // waves that share one logits row (1, 2 or 4)
 constexpr int kRowThreads = 64 * kRowWPR;   // row pass: one row per workgroup
-constexpr int kMaxNodes = 256;
+constexpr int kMaxNodes = 1024;
 constexpr int kMaxDepth = 31;
 constexpr int kPathThreads = 256;
 constexpr float kFastEps = 5e-5f;  // bound on the relative error of the fast normaliser
@@ -719,6 +719,7 @@ struct PathArgs {
     int32_t *obs_idx;          // [B][W][K]
     float *obs_p;              // [B][W][K]
     unsigned long long *stats;
+    unsigned long long *node_count;  // [N] verifications in which a node lay on the accepted path (mode 0)
 };
 
 // Walks the accepted path of trajectory b and leaves it in path[0..len) (shared memory).  The
@@ -804,6 +805,7 @@ __global__ __launch_bounds__(kPathThreads) void path_exact_kernel(PathArgs a)
             if (tid + 1 < len) a.out_tok[(size_t)b * a.W + tid] = a.draft_tok[(size_t)b * a.N + path[tid + 1]];
             else if (tid >= len) a.out_tok[(size_t)b * a.W + tid] = -1;
         }
+        if (tid < len) atomicAdd(&a.node_count[path[tid]], 1ull);  // paper Sec. 4.3: acceptance statistics per node
         if (wave != 1) return;
         const int node = path[len - 1];
         const int row = b * a.N + node;

@@ -5,6 +5,7 @@
 #include "kernels.hpp"
 
 #include <algorithm>
+#include <cmath>
 #include <cstdio>
 #include <cstring>
 #include <new>
@@ -29,7 +30,7 @@ struct stand_handle {
     int32_t *obs_idx;
     float *obs_p;
     long long *rec_slot;
-    unsigned long long *seg_part;
+    unsigned long long *seg_part, *node_count;
     int32_t *stop_i, *stop_qid, *stop_child;
     float *stop_m, *stop_qmu, *stop_ql;
     float *pr_m, *pr_top_l;
@@ -76,7 +77,7 @@ static void free_all(stand_handle *h)
     if (!h) return;
     void *ptrs[] = {h->d_tree, h->table, h->ctx_tail, h->ctx_len, h->draft_tok, h->draft_has, h->draft_qid, h->draft_qmu,
                     h->row_m, h->row_s, h->top_l, h->top_p, h->top_idx, h->outcome, h->obs_idx, h->obs_p, h->rec_slot,
-                    h->seg_part, h->stop_i, h->stop_qid, h->stop_child, h->stop_m, h->stop_qmu, h->stop_ql, h->pr_m, h->pr_top_l, h->pr_top_idx, h->stats, h->counter};
+                    h->seg_part, h->node_count, h->stop_i, h->stop_qid, h->stop_child, h->stop_m, h->stop_qmu, h->stop_ql, h->pr_m, h->pr_top_l, h->pr_top_idx, h->stats, h->counter};
     for (void *p : ptrs) (void)hipFree(p);
     for (hipEvent_t e : h->ev_begin) (void)hipEventDestroy(e);
     for (hipEvent_t e : h->ev_end) (void)hipEventDestroy(e);
@@ -156,6 +157,7 @@ extern "C" int stand_create(const stand_config *cfg, stand_handle **out)
     acc(dmalloc(&h->obs_idx, B * h->W * K)); acc(dmalloc(&h->obs_p, B * h->W * K));
     acc(dmalloc(&h->rec_slot, nrec));
     acc(dmalloc(&h->seg_part, B * h->W * kSegMax));
+    acc(dmalloc(&h->node_count, (size_t)N));
     acc(dmalloc(&h->stop_i, B * 4)); acc(dmalloc(&h->stop_m, B)); acc(dmalloc(&h->stop_qid, B * kMaxK));
     acc(dmalloc(&h->stop_qmu, B * kMaxK)); acc(dmalloc(&h->stop_ql, B * kMaxK)); acc(dmalloc(&h->stop_child, B * kMaxK));
     acc(dmalloc(&h->pr_m, B * h->W)); acc(dmalloc(&h->pr_top_l, B * h->W * K)); acc(dmalloc(&h->pr_top_idx, B * h->W * K));
@@ -178,6 +180,7 @@ extern "C" int stand_create(const stand_config *cfg, stand_handle **out)
     acc(hipMemset(h->draft_qid, 0, rows * K * sizeof(int32_t)));
     acc(hipMemset(h->draft_qmu, 0, rows * K * sizeof(float)));
     acc(hipMemset(h->outcome, 0xFF, rows * sizeof(int32_t)));
+    acc(hipMemset(h->node_count, 0, (size_t)N * sizeof(unsigned long long)));
     acc(hipMemset(h->row_m, 0, rows * sizeof(float))); acc(hipMemset(h->row_s, 0, rows * sizeof(float)));
     acc(hipMemset(h->top_l, 0, rows * K * sizeof(float))); acc(hipMemset(h->top_p, 0, rows * K * sizeof(float)));
     acc(hipMemset(h->top_idx, 0, rows * K * sizeof(int32_t)));
@@ -315,7 +318,7 @@ static int launch_path_pass(stand_handle *h, uint64_t step, const void *d_logits
     a.src_top_l = mode == 0 ? h->top_l : h->pr_top_l;
     a.outcome = h->outcome; a.commit_row = commit_row; a.commit_len = commit_len;
     a.out_tok = out_tok; a.out_node = out_node; a.out_len = out_len;
-    a.seg_part = h->seg_part;
+    a.seg_part = h->seg_part; a.node_count = h->node_count;
     a.stop_i = h->stop_i; a.stop_m = h->stop_m; a.stop_qid = h->stop_qid; a.stop_qmu = h->stop_qmu; a.stop_ql = h->stop_ql;
     a.stop_child = h->stop_child;
     a.obs_idx = h->obs_idx; a.obs_p = h->obs_p; a.stats = h->stats;
@@ -565,6 +568,122 @@ extern "C" int stand_profile_end(stand_handle *h, double *row_pass_ms_total, int
     h->profiling = false;
     h->ev_used = 0;
     return STAND_OK;
+}
+
+extern "C" int stand_get_node_counts(stand_handle *h, uint64_t *host_counts)
+{
+    if (!h || !host_counts) return STAND_EINVAL;
+    HIP_TRY(h, hipSetDevice(h->cfg.device));
+    HIP_TRY(h, hipDeviceSynchronize());
+    HIP_TRY(h, hipMemcpy(host_counts, h->node_count, sizeof(uint64_t) * (size_t)h->N, hipMemcpyDeviceToHost));
+    return STAND_OK;
+}
+
+extern "C" int stand_reset_node_counts(stand_handle *h)
+{
+    if (!h) return STAND_EINVAL;
+    HIP_TRY(h, hipSetDevice(h->cfg.device));
+    HIP_TRY(h, hipDeviceSynchronize());
+    HIP_TRY(h, hipMemset(h->node_count, 0, sizeof(uint64_t) * (size_t)h->N));
+    return STAND_OK;
+}
+
+// ---- draft-tree shapes (host only) -----------------------------------------------------------------
+extern "C" int stand_tree_initial(int32_t levels, int32_t *host_parent_out, int32_t capacity, int32_t *n_out)
+{
+    if (levels < 1 || levels > STAND_MAX_DEPTH || !n_out || capacity < 0 || (capacity > 0 && !host_parent_out))
+        return STAND_EINVAL;
+    // Nodes of the current level are expanded left to right; `first`/`count` describe a level as
+    // a range of ids because ids are handed out in creation order.
+    struct Node { int32_t parent, depth, rank, fanout; };
+    std::vector<Node> nodes;
+    nodes.push_back(Node{-1, 0, 0, 0});
+    size_t first = 0, count = 1;
+    for (int32_t lv = 0; lv < levels; ++lv) {
+        const size_t next_first = nodes.size();
+        for (size_t pos = 0; pos < count; ++pos) {
+            const size_t u = first + pos;
+            const Node nd = nodes[u];
+            int32_t n;
+            if (nd.depth == 0) n = 8;
+            else if (nd.depth == 1) n = std::max(8 - 2 * nd.rank, 1);
+            else {
+                const double q = (double)(nodes[(size_t)nd.parent].fanout - 1) / ((double)nd.rank * 0.7 + 1.0);
+                n = std::max((int32_t)std::ceil(q), nd.depth <= 3 ? 2 : 0);
+            }
+            if (pos == 0) n = std::max(n, 3);
+            nodes[u].fanout = n;
+            for (int32_t r = 0; r < n; ++r) nodes.push_back(Node{(int32_t)u, nd.depth + 1, r, 0});
+        }
+        first = next_first;
+        count = nodes.size() - next_first;
+        if (count == 0) break;
+    }
+    *n_out = (int32_t)nodes.size();
+    if (capacity > 0) {
+        if ((size_t)capacity < nodes.size()) return STAND_EINVAL;
+        for (size_t u = 0; u < nodes.size(); ++u) host_parent_out[u] = nodes[u].parent;
+    }
+    return STAND_OK;
+}
+
+extern "C" int stand_tree_select(const int32_t *host_parent, const uint64_t *host_counts, int32_t n, int32_t n_keep,
+                                 int32_t *host_parent_out, int32_t *host_old_id_out)
+{
+    if (!host_parent || !host_counts || !host_parent_out || n < 1 || n_keep < 1 || n_keep > n) return STAND_EINVAL;
+    if (host_parent[0] != -1) return STAND_EINVAL;
+    for (int32_t u = 1; u < n; ++u)
+        if (host_parent[u] < 0 || host_parent[u] >= u) return STAND_EINVAL;
+    std::vector<int32_t> depth((size_t)n, 0), first_child((size_t)n, -1), nchild((size_t)n, 0);
+    for (int32_t u = 1; u < n; ++u) {
+        depth[u] = depth[host_parent[u]] + 1;
+        if (nchild[host_parent[u]]++ == 0) first_child[host_parent[u]] = u;
+        if (u > 1 && (host_parent[u] < host_parent[u - 1])) return STAND_EINVAL;  // children must be contiguous, breadth first
+    }
+    // Grow the kept set from the root: the candidates are the children of kept nodes, the best
+    // candidate is the one with the largest usable count (a node is used at most as often as
+    // its parent), then the shallowest, then the lowest id.
+    struct Cand { uint64_t count; int32_t depth, id; };
+    auto worse = [](const Cand &x, const Cand &y) {
+        if (x.count != y.count) return x.count < y.count;
+        if (x.depth != y.depth) return x.depth > y.depth;
+        return x.id > y.id;
+    };
+    std::vector<Cand> heap;
+    std::vector<char> kept((size_t)n, 0);
+    uint64_t top = 0;
+    for (int32_t u = 0; u < n; ++u) top = std::max(top, host_counts[u]);
+    heap.push_back(Cand{top, 0, 0});
+    int32_t taken = 0;
+    while (taken < n_keep && !heap.empty()) {
+        std::pop_heap(heap.begin(), heap.end(), worse);
+        const Cand c = heap.back();
+        heap.pop_back();
+        kept[(size_t)c.id] = 1;
+        ++taken;
+        for (int32_t j = 0; j < nchild[c.id]; ++j) {
+            const int32_t v = first_child[c.id] + j;
+            heap.push_back(Cand{std::min(host_counts[v], c.count), depth[v], v});
+            std::push_heap(heap.begin(), heap.end(), worse);
+        }
+    }
+    // breadth-first renumbering of the kept nodes, children in their old rank order
+    std::vector<int32_t> queue, new_of((size_t)n, -1);
+    queue.push_back(0);
+    new_of[0] = 0;
+    host_parent_out[0] = -1;
+    for (size_t head = 0; head < queue.size(); ++head) {
+        const int32_t u = queue[head];
+        if (host_old_id_out) host_old_id_out[head] = u;
+        for (int32_t j = 0; j < nchild[u]; ++j) {
+            const int32_t v = first_child[u] + j;
+            if (!kept[(size_t)v]) continue;
+            new_of[(size_t)v] = (int32_t)queue.size();
+            host_parent_out[queue.size()] = (int32_t)head;
+            queue.push_back(v);
+        }
+    }
+    return (int32_t)queue.size() == n_keep ? STAND_OK : STAND_EINVAL;
 }
 
 extern "C" int stand_copy_bytes(void *d_dst, const void *d_src, uint64_t bytes, void *stream)

@@ -256,7 +256,9 @@ class Workload:
         self.B, self.V, self.N, self.D, self.K = cfg["B"], cfg["V"], cfg["N"], cfg["D"], cfg["K"]
         self.dtype, self.T, self.seed = cfg["dtype"], cfg["T"], cfg["seed"]
         self.W = self.D + 1
-        self.parent = make_tree(cfg["N"], cfg["D"], cfg["caps"])
+        # a given parent[] (e.g. a tree produced by the tree optimisation) overrides the shape recipe
+        self.parent = (np.asarray(cfg["parent"], np.int32) if cfg.get("parent") is not None
+                       else make_tree(cfg["N"], cfg["D"], cfg["caps"]))
         self.depth, self.nchild, self.first_child, dmax = tree_info(self.parent)
         assert dmax == self.D
         self.prompt_len = cfg.get("prompt_len", 16)

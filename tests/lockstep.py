@@ -131,6 +131,8 @@ def run_lockstep(w, steps, mode="separate", capacity=1 << 12, check_rows=True, t
     assert (so.inserts, so.merges, so.drops) == (sg.inserts, sg.merges, sg.drops), "update statistics differ"
     assert so.tokens_emitted == sg.tokens_emitted and so.accept_tests == sg.accept_tests
     assert sg.filter_mismatch == 0, "an accept decision changed under exact arithmetic"
+    assert np.array_equal(o.node_counts(), g.node_counts()), "per-node acceptance counters differ"
+    info["node_counts"] = o.node_counts()
     info["near_oracle"], info["near_gpu"] = so.near_threshold, sg.near_threshold
     info["fp_collisions"] = so.fp_collisions
     o.close()

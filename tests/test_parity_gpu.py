@@ -158,6 +158,27 @@ def test_full_shape_step(gpu):
     assert info["emitted"] >= 3 * w.B and info["entries"] > 0
 
 
+def test_tree_optimisation_on_the_initial_tree(gpu):
+    """Paper Sec. 4.3 end to end at a small vocabulary: speculate on the 625-node initial tree
+    (depth 20), count accepted nodes on both sides, keep the best 80 and speculate on that tree."""
+    binding, lockstep = gpu
+    big = binding.tree_initial(20)
+    w = synth.Workload(None, B=2, V=3000, dtype="bf16", N=len(big), D=20, caps=[8], parent=big, order_min=1, order_max=4,
+                       K=10, T=0.6, rho=0.8, seed=99, run_steps=14)
+    _say("initial tree: %d nodes" % len(big))
+    info = lockstep.run_lockstep(w, 14, mode="step", capacity=1 << 14, forced=True, check_rows=False)
+    counts = info["node_counts"]
+    assert counts[0] == 14 * w.B and counts.sum() == info["emitted"]
+    small, old = binding.tree_select(big, counts, 80)
+    o_small, o_old = oracle.tree_select(big, counts, 80)
+    assert np.array_equal(small, o_small) and np.array_equal(old, o_old)
+    depth = synth.tree_info(small)[3]
+    w2 = synth.Workload(None, B=2, V=3000, dtype="bf16", N=80, D=int(depth), caps=[8], parent=small, order_min=1, order_max=4,
+                        K=10, T=0.6, rho=0.8, seed=99, run_steps=10)
+    info2 = lockstep.run_lockstep(w2, 10, mode="step", capacity=1 << 14, forced=True, check_rows=False)
+    _say("  selected tree depth %d -> %s" % (depth, {k: v for k, v in info2.items() if k != "node_counts"}))
+
+
 def test_row_pass_timing_and_copy(gpu):
     """stand_profile_begin / stand_profile_end bracket the row pass launches; stand_copy_bytes copies."""
     binding, lockstep = gpu
