@@ -20,6 +20,7 @@ MAX_ORDER = 8
 DT_BF16 = 0
 DT_F32 = 1
 STREAM_DRAFT, STREAM_ACCEPT, STREAM_BONUS = 0, 1, 2
+DRAFT_GUMBEL_TOPK, DRAFT_MULTINOMIAL, DRAFT_DETERMINISTIC = 0, 1, 2
 
 
 def build(force=False):
@@ -43,6 +44,7 @@ class _Config(C.Structure):
         ("seed", C.c_uint64),
         ("logits_dtype", C.c_int32),
         ("update_mode", C.c_int32),
+        ("draft_mode", C.c_int32),
     ]
 
 
@@ -89,7 +91,11 @@ def lib():
         L.so_gumbel_topk.restype = C.c_int
         L.so_gumbel_topk.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p]
         L.so_verify_node.restype = C.c_int
-        L.so_verify_node.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.POINTER(NodeState)]
+        L.so_verify_node.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.POINTER(NodeState), C.c_int]
+        L.so_multinomial_wor.restype = C.c_int
+        L.so_multinomial_wor.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p]
+        L.so_top_c.restype = C.c_int
+        L.so_top_c.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_void_p]
         L.so_residual_dense.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.POINTER(NodeState), C.c_void_p]
         L.so_uniform_u64.restype = C.c_uint64
         L.so_uniform_u64.argtypes = [C.c_uint64, C.c_uint32, C.c_uint64, C.c_uint32, C.c_uint32]
@@ -121,8 +127,8 @@ def lib():
         L.so_get_stats.argtypes = [C.c_void_p, C.POINTER(Stats)]
         L.so_get_node_counts.argtypes = [C.c_void_p, C.c_void_p]
         L.so_reset_node_counts.argtypes = [C.c_void_p]
-        L.so_mc_gumbel_topk.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_uint64, C.c_uint64, C.c_void_p]
-        L.so_mc_node.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_int, C.c_uint64, C.c_uint64,
+        L.so_mc_draft.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_uint64, C.c_uint64, C.c_int, C.c_void_p]
+        L.so_mc_node.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_int, C.c_uint64, C.c_uint64, C.c_int,
                                  C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         L.so_mc_draw.argtypes = [C.c_void_p, C.c_int, C.c_uint64, C.c_int, C.c_void_p, C.c_void_p, C.c_float,
                                  C.c_uint64, C.c_uint64, C.c_void_p]
@@ -221,11 +227,25 @@ def gumbel_topk(ids, mu, c, U):
     return out[:n]
 
 
-def verify_node(p, ids, mu, child_tok, omega):
+def multinomial_wor(ids, mu, c, U):
+    ids, mu, U = _i32(ids), _f32(mu), _f32(U)
+    out = np.full(c, -1, np.int32)
+    n = lib().so_multinomial_wor(_p(ids), _p(mu), ids.shape[0], c, _p(U), _p(out))
+    return out[:n]
+
+
+def top_c(ids, mu, c):
+    ids, mu = _i32(ids), _f32(mu)
+    out = np.full(c, -1, np.int32)
+    n = lib().so_top_c(_p(ids), _p(mu), ids.shape[0], c, _p(out))
+    return out[:n]
+
+
+def verify_node(p, ids, mu, child_tok, omega, onehot=False):
     p, ids, mu = _f32(p), _i32(ids), _f32(mu)
     child_tok, omega = _i32(child_tok), _f32(omega)
     st = NodeState()
-    acc = lib().so_verify_node(_p(p), ids.shape[0], _p(ids), _p(mu), child_tok.shape[0], _p(child_tok), _p(omega), C.byref(st))
+    acc = lib().so_verify_node(_p(p), ids.shape[0], _p(ids), _p(mu), child_tok.shape[0], _p(child_tok), _p(omega), C.byref(st), int(onehot))
     return acc, st
 
 
@@ -255,22 +275,22 @@ def residual_draw(F, S, ids, st, u):
                                       C.byref(st) if st is not None else None, int(u)))
 
 
-def mc_gumbel_topk(ids, mu, c, trials, seed):
+def mc_gumbel_topk(ids, mu, c, trials, seed, mode=DRAFT_GUMBEL_TOPK):
     ids, mu = _i32(ids), _f32(mu)
     K = ids.shape[0]
     counts = np.zeros(K ** c, np.uint64)
-    lib().so_mc_gumbel_topk(_p(ids), _p(mu), K, c, trials, seed, _p(counts))
+    lib().so_mc_draft(_p(ids), _p(mu), K, c, trials, seed, mode, _p(counts))
     return counts
 
 
-def mc_node(p, ids, mu, c, trials, seed):
+def mc_node(p, ids, mu, c, trials, seed, mode=DRAFT_GUMBEL_TOPK):
     p, ids, mu = _f32(p), _i32(ids), _f32(mu)
     counts = np.zeros(p.shape[0], np.uint64)
     acc = C.c_uint64()
     near = C.c_uint64()
     err = C.c_double()
     mn = C.c_double()
-    lib().so_mc_node(_p(p), p.shape[0], ids.shape[0], _p(ids), _p(mu), c, trials, seed, _p(counts),
+    lib().so_mc_node(_p(p), p.shape[0], ids.shape[0], _p(ids), _p(mu), c, trials, seed, mode, _p(counts),
                      C.byref(acc), C.byref(near), C.byref(err), C.byref(mn))
     return counts, acc.value, near.value, err.value, mn.value
 
@@ -288,11 +308,11 @@ class Oracle:
     """One shared n-gram table + B trajectories, driven step by step."""
 
     def __init__(self, vocab, max_batch, order_min, order_max, topk, tree_parent, temperature,
-                 table_capacity, max_probe, seed, logits_dtype, update_mode=0):
+                 table_capacity, max_probe, seed, logits_dtype, update_mode=0, draft_mode=DRAFT_GUMBEL_TOPK):
         self._parent = _i32(tree_parent)
         cfg = _Config(vocab, max_batch, order_min, order_max, topk, self._parent.shape[0],
                       self._parent.ctypes.data_as(C.POINTER(C.c_int32)), temperature, table_capacity,
-                      max_probe, seed, logits_dtype, update_mode)
+                      max_probe, seed, logits_dtype, update_mode, draft_mode)
         self.h = lib().so_create(C.byref(cfg))
         self.B, self.N, self.K, self.V = max_batch, self._parent.shape[0], topk, vocab
         self.D = int(lib().so_depth(self.h))

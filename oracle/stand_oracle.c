@@ -43,6 +43,11 @@
 #define SO_STREAM_ACCEPT 1u
 #define SO_STREAM_BONUS 2u
 
+/* how the children of a node are drawn from its table entry (Sec. 3.1, Sec. 4.2, Table 5) */
+#define SO_DRAFT_GUMBEL_TOPK 0   /* stochastic, Gumbel-Top-K (the method's own)                */
+#define SO_DRAFT_MULTINOMIAL 1   /* stochastic, sequential sampling without replacement        */
+#define SO_DRAFT_DETERMINISTIC 2 /* the most probable stored tokens; proposal treated as one-hot */
+
 /* ------------------------------------------------------------------------------------------
  * Counter-based uniforms: Philox4x32 with 10 rounds (Salmon, Moraes, Dror, Shaw, SC'11).
  * key = 64-bit seed; counter = (token >> 2, node | stream << 24, step low, b | step high << 20);
@@ -352,6 +357,54 @@ int so_gumbel_topk(const int32_t *ids, const float *mu, int K, int c, const floa
     return w;
 }
 
+/* Sequential sampling without replacement (the "basic stochastic drafting" of Table 5): draw j
+ * picks among the candidates not drawn yet with probability proportional to mu.  z = sum of the
+ * remaining mu in stored order; t = U_j * z; the pick is the first remaining candidate, in stored
+ * order, whose running sum exceeds t (the last remaining one if rounding leaves none).  Same law
+ * as Gumbel-Top-K (Plackett-Luce). */
+int so_multinomial_wor(const int32_t *ids, const float *mu, int K, int c, const float *U /* [c] */,
+                       int32_t *tok_out)
+{
+    int left[SO_MAX_K];
+    int n = 0;
+    for (int i = 0; i < K; ++i) { left[i] = mu[i] > 0.0f; n += left[i]; }
+    int w = c < n ? c : n;
+    for (int j = 0; j < w; ++j) {
+        float z = 0.0f;
+        for (int i = 0; i < K; ++i) if (left[i]) z = z + mu[i];
+        float t = U[j] * z;
+        float a = 0.0f;
+        int pick = -1, last = -1;
+        for (int i = 0; i < K; ++i) {
+            if (!left[i]) continue;
+            last = i;
+            a = a + mu[i];
+            if (pick < 0 && t < a) pick = i;
+        }
+        if (pick < 0) pick = last;
+        tok_out[j] = ids[pick];
+        left[pick] = 0;
+    }
+    return w;
+}
+
+/* Deterministic drafting (Sec. 3.1): the c most probable stored tokens, (mu desc, id asc). */
+int so_top_c(const int32_t *ids, const float *mu, int K, int c, int32_t *tok_out)
+{
+    so_pair sc[SO_MAX_K];
+    int n = 0;
+    for (int i = 0; i < K; ++i) {
+        if (!(mu[i] > 0.0f)) continue;
+        sc[n].val = mu[i];
+        sc[n].id = ids[i];
+        ++n;
+    }
+    qsort(sc, (size_t)n, sizeof(so_pair), pair_cmp);
+    int w = c < n ? c : n;
+    for (int j = 0; j < w; ++j) tok_out[j] = sc[j].id;
+    return w;
+}
+
 /* ------------------------------------------------------------------------------------------
  * Verification of the children of one node (Sec. 3.2 applied recursively).
  *   p       dense target distribution of the node's row
@@ -381,8 +434,10 @@ static float support_sum(const float *x, int K)
     return t;
 }
 
+/* onehot != 0 (deterministic drafting, Sec. 3.1): the proposal of round j is the one-hot vector
+ * on child j, so the child is accepted with probability r(x) and a rejection removes only x. */
 int so_verify_node(const float *p, int K, const int32_t *ids, const float *mu,
-                   int nchild, const int32_t *child_tok, const float *omega, so_node_state *st)
+                   int nchild, const int32_t *child_tok, const float *omega, so_node_state *st, int onehot)
 {
     float zw = 0.0f;
     for (int i = 0; i < K; ++i) { st->w[i] = mu[i] > 0.0f ? mu[i] : 0.0f; }
@@ -400,6 +455,7 @@ int so_verify_node(const float *p, int K, const int32_t *ids, const float *mu,
         for (int q = 0; q < K; ++q) if (ids[q] == child_tok[j]) i = q;
         if (i < 0) break; /* cannot happen for a tree drafted from this entry */
         st->rounds++;
+        if (onehot) for (int q = 0; q < K; ++q) st->w[q] = q == i ? 1.0f : 0.0f;
         float lhs = omega[j] * st->w[i];
         if (st->w[i] > 0.0f && fabs((double)omega[j] - (double)st->r[i] / (double)st->w[i]) < 1e-6)
             st->near_threshold = 1;
@@ -415,6 +471,7 @@ int so_verify_node(const float *p, int K, const int32_t *ids, const float *mu,
             st->r[q] = d / Z;
         }
         st->rho = st->rho / Z;
+        if (onehot) continue;
         st->w[i] = 0.0f;
         float zw2 = support_sum(st->w, K);
         for (int q = 0; q < K; ++q) st->w[q] = zw2 > 0.0f ? st->w[q] / zw2 : 0.0f;
@@ -502,6 +559,7 @@ typedef struct {
     uint64_t seed;
     int32_t logits_dtype;
     int32_t update_mode;
+    int32_t draft_mode;
 } so_config;
 
 typedef struct {
@@ -795,10 +853,20 @@ void so_draft(so_handle *h, uint64_t step, int32_t *draft_tok_out /* [B][N] */)
             memcpy(qid, h->ent[e].ids, sizeof(int32_t) * (size_t)K);
             memcpy(qmu, h->ent[e].mu, sizeof(float) * (size_t)K);
             float U[SO_MAX_K];
-            for (int i = 0; i < K; ++i)
-                U[i] = so_uniform(h->cfg.seed, (uint32_t)b, step, (uint32_t)u, (uint32_t)qid[i], SO_STREAM_DRAFT);
             int32_t drawn[SO_MAX_K];
-            int nd = so_gumbel_topk(qid, qmu, K, h->nchild[u], U, drawn);
+            int nd;
+            if (h->cfg.draft_mode == SO_DRAFT_DETERMINISTIC) {
+                nd = so_top_c(qid, qmu, K, h->nchild[u], drawn);
+            } else if (h->cfg.draft_mode == SO_DRAFT_MULTINOMIAL) {
+                /* the uniform of draw j is keyed by j */
+                for (int j = 0; j < h->nchild[u]; ++j)
+                    U[j] = so_uniform(h->cfg.seed, (uint32_t)b, step, (uint32_t)u, (uint32_t)j, SO_STREAM_DRAFT);
+                nd = so_multinomial_wor(qid, qmu, K, h->nchild[u], U, drawn);
+            } else {
+                for (int i = 0; i < K; ++i)
+                    U[i] = so_uniform(h->cfg.seed, (uint32_t)b, step, (uint32_t)u, (uint32_t)qid[i], SO_STREAM_DRAFT);
+                nd = so_gumbel_topk(qid, qmu, K, h->nchild[u], U, drawn);
+            }
             for (int j = 0; j < nd; ++j) tok[h->first_child[u] + j] = drawn[j];
         }
         if (draft_tok_out) memcpy(draft_tok_out + (int64_t)b * N, tok, sizeof(int32_t) * (size_t)N);
@@ -842,7 +910,8 @@ void so_verify(so_handle *h, uint64_t step, const void *logits,
                 float om[SO_MAX_K];
                 for (int j = 0; j < nc; ++j)
                     om[j] = so_uniform(h->cfg.seed, (uint32_t)b, step, (uint32_t)(h->first_child[cur] + j), 0u, SO_STREAM_ACCEPT);
-                acc = so_verify_node(p, K, qid, qmu, nc, tok + h->first_child[cur], om, &st);
+                acc = so_verify_node(p, K, qid, qmu, nc, tok + h->first_child[cur], om, &st,
+                                     h->cfg.draft_mode == SO_DRAFT_DETERMINISTIC);
                 h->st.accept_tests += (uint64_t)st.rounds;
                 h->st.near_threshold += (uint64_t)st.near_threshold;
             }
@@ -955,15 +1024,27 @@ void so_reset_node_counts(so_handle *h) { memset(h->node_count, 0, sizeof(uint64
  * Monte-Carlo drivers used by the statistical pins (they run the functions above in a loop).
  * ======================================================================================== */
 
-/* counts[t0 * K^(c-1) + ...]: frequency of each ordered c-tuple of entry positions. */
-void so_mc_gumbel_topk(const int32_t *ids, const float *mu, int K, int c, uint64_t trials,
-                       uint64_t seed, uint64_t *counts)
+/* the children of node 0 of trial t, drawn the way so_draft draws them */
+static int mc_draft(const int32_t *ids, const float *mu, int K, int c, uint64_t seed, uint64_t t, int mode,
+                    int32_t *drawn)
 {
     float U[SO_MAX_K];
+    if (mode == SO_DRAFT_DETERMINISTIC) return so_top_c(ids, mu, K, c, drawn);
+    if (mode == SO_DRAFT_MULTINOMIAL) {
+        for (int j = 0; j < c; ++j) U[j] = so_uniform(seed, 0, t, 0, (uint32_t)j, SO_STREAM_DRAFT);
+        return so_multinomial_wor(ids, mu, K, c, U, drawn);
+    }
+    for (int i = 0; i < K; ++i) U[i] = so_uniform(seed, 0, t, 0, (uint32_t)ids[i], SO_STREAM_DRAFT);
+    return so_gumbel_topk(ids, mu, K, c, U, drawn);
+}
+
+/* counts[t0 * K^(c-1) + ...]: frequency of each ordered c-tuple of entry positions. */
+void so_mc_draft(const int32_t *ids, const float *mu, int K, int c, uint64_t trials,
+                 uint64_t seed, int mode, uint64_t *counts)
+{
     int32_t drawn[SO_MAX_K];
     for (uint64_t t = 0; t < trials; ++t) {
-        for (int i = 0; i < K; ++i) U[i] = so_uniform(seed, 0, t, 0, (uint32_t)ids[i], SO_STREAM_DRAFT);
-        int nd = so_gumbel_topk(ids, mu, K, c, U, drawn);
+        int nd = mc_draft(ids, mu, K, c, seed, t, mode, drawn);
         uint64_t code = 0;
         for (int j = 0; j < nd; ++j) {
             int pos = 0;
@@ -978,10 +1059,10 @@ void so_mc_gumbel_topk(const int32_t *ids, const float *mu, int K, int c, uint64
  * total rejection.  counts[v] = how often token v was emitted; *accepted = trials in which
  * some child was accepted; resid_err = max over trials of |sum(residual) - 1|. */
 void so_mc_node(const float *p, int V, int K, const int32_t *ids, const float *mu, int c,
-                uint64_t trials, uint64_t seed, uint64_t *counts, uint64_t *accepted,
+                uint64_t trials, uint64_t seed, int mode, uint64_t *counts, uint64_t *accepted,
                 uint64_t *near, double *resid_err, double *resid_min)
 {
-    float U[SO_MAX_K], om[SO_MAX_K];
+    float om[SO_MAX_K];
     int32_t drawn[SO_MAX_K];
     float *r = (float *)malloc(sizeof(float) * (size_t)V);
     /* masses of the given dense p on the grid the row masses live on: F(v) = floor(p(v) 2^40) */
@@ -990,11 +1071,10 @@ void so_mc_node(const float *p, int V, int K, const int32_t *ids, const float *m
     for (int v = 0; v < V; ++v) { F[v] = (uint64_t)floor(ldexp((double)p[v], 40)); S += F[v]; }
     *accepted = 0; *near = 0; *resid_err = 0.0; *resid_min = 0.0;
     for (uint64_t t = 0; t < trials; ++t) {
-        for (int i = 0; i < K; ++i) U[i] = so_uniform(seed, 0, t, 0, (uint32_t)ids[i], SO_STREAM_DRAFT);
-        int nd = so_gumbel_topk(ids, mu, K, c, U, drawn);
+        int nd = mc_draft(ids, mu, K, c, seed, t, mode, drawn);
         for (int j = 0; j < nd; ++j) om[j] = so_uniform(seed, 0, t, (uint32_t)(1 + j), 0, SO_STREAM_ACCEPT);
         so_node_state st;
-        int acc = nd > 0 ? so_verify_node(p, K, ids, mu, nd, drawn, om, &st) : -1;
+        int acc = nd > 0 ? so_verify_node(p, K, ids, mu, nd, drawn, om, &st, mode == SO_DRAFT_DETERMINISTIC) : -1;
         if (nd > 0) *near += (uint64_t)st.near_threshold;
         if (acc >= 0) { counts[drawn[acc]]++; (*accepted)++; continue; }
         so_residual_dense(p, V, K, ids, nd > 0 ? &st : NULL, r);

@@ -353,6 +353,73 @@ def test_q_equal_p_always_accepts_and_one_hot_accepts_with_p():
     assert _chi(counts, p) > 1e-3
 
 
+# ---- drafting variants of the paper's ablation (Sec. 3.1; Table 5: deterministic / multinomial) ----
+def test_multinomial_without_replacement_matches_plackett_luce():
+    """Sequential sampling without replacement has the law Gumbel-Top-K has (Sec. 4.2)."""
+    ids = np.array([11, 3, 7, 20, 5], np.int32)
+    mu = np.array([0.35, 0.05, 0.2, 0.1, 0.02], np.float32)
+    q = mu.astype(np.float64) / mu.astype(np.float64).sum()
+    K, c, trials = 5, 3, 600_000
+    counts = oracle.mc_gumbel_topk(ids, mu, c, trials, seed=44, mode=oracle.DRAFT_MULTINOMIAL)
+    obs, exp = [], []
+    for tup in itertools.permutations(range(K), c):
+        code = 0
+        for i in tup:
+            code = code * K + i
+        obs.append(counts[code])
+        exp.append(trials * _plackett_luce(q, tup))
+    assert sum(obs) == trials and _chi(obs, exp) > 1e-3
+    # by hand: the running sums of (.5, .25, .25) are .5, .75, 1; U = .6 falls on the second, then
+    # (.5, -, .25) has running sums .5, .75 and U = .9 -> t = .675 falls on the third
+    assert list(oracle.multinomial_wor([4, 2, 9], [0.5, 0.25, 0.25], 2, [0.6, 0.9])) == [2, 9]
+    assert list(oracle.multinomial_wor([4, 2, 9], [0.5, 0.0, 0.25], 3, [0.99, 0.5, 0.5])) == [9, 4]   # zero mass never drawn
+
+
+def test_deterministic_drafting():
+    """Sec. 3.1: q one-hot on the most probable stored tokens; a drafted token is accepted with
+    probability r(x), and the emitted token still follows p for any fan-out."""
+    assert list(oracle.top_c([4, 2, 9, 7], [0.2, 0.5, 0.2, 0.0], 3)) == [2, 4, 9]      # (mu desc, id asc), zero mass out
+    r = np.random.default_rng(31)
+    V, K = 8, 5
+    p = _rand_dist(r, V, 1.0)
+    ids = r.permutation(V)[:K].astype(np.int32)
+    mu = (r.dirichlet(np.full(K, 0.7)) * 0.8).astype(np.float32)
+    first = int(oracle.top_c(ids, mu, 1)[0])
+    trials = 400_000
+    counts, acc, *_ = oracle.mc_node(p, ids, mu, 1, trials, seed=9, mode=oracle.DRAFT_DETERMINISTIC)
+    assert abs(acc / trials - p[first]) < 4 * math.sqrt(p[first] * (1 - p[first]) / trials)   # accepted w.p. p(x_draft)
+    assert _chi(counts, p) > 1e-3
+    for fanout in (2, 4):
+        counts, acc, near, err, mn = oracle.mc_node(p, ids, mu, fanout, 600_000, seed=20 + fanout,
+                                                    mode=oracle.DRAFT_DETERMINISTIC)
+        assert _chi(counts, p) > 1e-3 and err < 5e-6 and mn >= 0.0
+        # some child is accepted with probability 1 - prod_j (1 - r_j(x_j)): with one-hot proposals
+        # r_j(x_j) = p(x_j) / (1 - sum_{i<j} p(x_i)), so the product telescopes to 1 - sum_j p(x_j)
+        want = float(sum(p[t] for t in oracle.top_c(ids, mu, fanout)))
+        assert abs(acc / 600_000 - want) < 4 * math.sqrt(want * (1 - want) / 600_000)
+    # by hand, p = (.5, .3, .2), children 1 then 0: reject 1 (omega .4 >= .3) -> r = (.5, 0, .2)/.7;
+    # accept 0 iff omega < .5/.7
+    pp = np.array([0.5, 0.3, 0.2], np.float32)
+    acc, st = oracle.verify_node(pp, [0, 1, 2], [0.1, 0.8, 0.1], [1, 0], [0.4, 0.70], onehot=True)
+    assert acc == 1 and abs(st.r[0] - 0.5 / 0.7) < 1e-6 and st.r[1] == 0.0 and abs(st.rho - 1 / 0.7) < 1e-6
+    acc, st = oracle.verify_node(pp, [0, 1, 2], [0.1, 0.8, 0.1], [1, 0], [0.4, 0.72], onehot=True)
+    assert acc == -1 and np.allclose([st.r[0], st.r[1], st.r[2]], [0.0, 0.0, 1.0], atol=1e-6)
+
+
+def test_stochastic_drafting_is_accepted_more_often_than_deterministic():
+    """The direction of the paper's Fig. 3 / Table 5 on a synthetic node: a proposal close to the
+    target is accepted with probability sum min(p, q) when sampled, max-token p(x) when one-hot."""
+    r = np.random.default_rng(5)
+    V = 8
+    p = _rand_dist(r, V, 2.0)
+    ids = np.arange(V, dtype=np.int32)
+    mu = (0.9 * p + 0.1 * _rand_dist(r, V, 2.0)).astype(np.float32)
+    _, acc_s, *_ = oracle.mc_node(p, ids, mu, 1, 200_000, seed=3, mode=oracle.DRAFT_GUMBEL_TOPK)
+    _, acc_m, *_ = oracle.mc_node(p, ids, mu, 1, 200_000, seed=3, mode=oracle.DRAFT_MULTINOMIAL)
+    _, acc_d, *_ = oracle.mc_node(p, ids, mu, 1, 200_000, seed=3, mode=oracle.DRAFT_DETERMINISTIC)
+    assert acc_s > acc_d * 1.5 and abs(acc_s - acc_m) < 6 * math.sqrt(200_000) 
+
+
 def test_verify_node_rule_by_hand():
     # p = (.5,.3,.2), q = (.2,.8,0): drafting token 1 (q=.8 > p=.3) is accepted iff omega < .375
     p = np.array([0.5, 0.3, 0.2], np.float32)
