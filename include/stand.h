@@ -44,6 +44,15 @@ extern "C" {
 
 #define STAND_UPDATE_ACCEPTED_PATH 0 /* merge the rows that produced committed tokens (paper Sec. 4.1) */
 
+/* How the children of a tree node are drawn from its table entry (paper Sec. 3.1 "deterministic
+ * or stochastic" drafting, Sec. 4.2, and the ablation of Table 5).  All three keep the output
+ * distribution equal to the target's; they differ in how often drafts are accepted. */
+#define STAND_DRAFT_GUMBEL_TOPK 0   /* Gumbel-Top-K: score ln mu - ln(-ln U), the c largest (the method) */
+#define STAND_DRAFT_MULTINOMIAL 1   /* c sequential draws without replacement, proportional to mu;     */
+                                    /* the uniform of draw j is keyed by j; same law as Gumbel-Top-K     */
+#define STAND_DRAFT_DETERMINISTIC 2 /* the c largest mu (ties: lower id); in verification the proposal  */
+                                    /* of each child is one-hot, so it is accepted with probability r(x) */
+
 #define STAND_MAX_TOPK 32
 #define STAND_MAX_ORDER 8
 #define STAND_MAX_NODES 1024
@@ -67,6 +76,7 @@ typedef struct {
     int32_t logits_dtype;       /* STAND_BF16 or STAND_F32                                          */
     int32_t update_mode;        /* STAND_UPDATE_ACCEPTED_PATH                                       */
     int32_t device;             /* HIP device ordinal                                               */
+    int32_t draft_mode;         /* STAND_DRAFT_*                                                    */
 } stand_config;
 
 typedef struct {

@@ -14,6 +14,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libstand.so")
 
 STAND_BF16, STAND_F32 = 0, 1
+DRAFT_GUMBEL_TOPK, DRAFT_MULTINOMIAL, DRAFT_DETERMINISTIC = 0, 1, 2
 MAX_ORDER = 8
 
 EXPORTED = [
@@ -31,6 +32,7 @@ class Config(C.Structure):
         ("topk", C.c_int32), ("tree_nodes", C.c_int32), ("tree_parent", C.POINTER(C.c_int32)),
         ("temperature", C.c_float), ("table_capacity", C.c_uint64), ("max_probe", C.c_int32),
         ("seed", C.c_uint64), ("logits_dtype", C.c_int32), ("update_mode", C.c_int32), ("device", C.c_int32),
+        ("draft_mode", C.c_int32),
     ]
 
 
@@ -148,11 +150,11 @@ class Stand:
     """One n-gram table shared by B trajectories on one GPU; methods carry the C ABI's names."""
 
     def __init__(self, vocab, max_batch, order_min, order_max, topk, tree_parent, temperature, table_capacity,
-                 max_probe, seed, logits_dtype, device=0):
+                 max_probe, seed, logits_dtype, device=0, draft_mode=0):
         par = np.ascontiguousarray(tree_parent, dtype=np.int32)
         cfg = Config(vocab, max_batch, order_min, order_max, topk, par.shape[0],
                      par.ctypes.data_as(C.POINTER(C.c_int32)), temperature, table_capacity, max_probe, seed,
-                     logits_dtype, 0, device)
+                     logits_dtype, 0, device, draft_mode)
         self.h = C.c_void_p()
         _check(lib().stand_create(C.byref(cfg), C.byref(self.h)))
         self.B, self.N, self.K, self.V = max_batch, par.shape[0], topk, vocab

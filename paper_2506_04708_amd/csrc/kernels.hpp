@@ -142,9 +142,11 @@ __device__ __forceinline__ unsigned long long readlane_u64(unsigned long long v,
 struct NodeResult { int accepted; int rounds; bool near; float r; float rho; };
 
 // ch: the token of drafted child `lane` (lanes 0..nchild-1), so that the rounds wait on no memory.
+// onehot (deterministic drafting, paper Sec. 3.1): the proposal of each round is the one-hot
+// vector on that round's child instead of the renormalised stored means.
 __device__ __forceinline__ NodeResult wave_node_outcome(int lane, int K, int32_t my_id, float my_mu, float my_p, int nchild,
                                         int32_t ch, uint64_t seed, uint32_t b, uint64_t step, int first_child,
-                                        bool track_err, float eps)
+                                        bool track_err, float eps, bool onehot)
 {
     NodeResult res;
     res.accepted = -1; res.rounds = 0; res.near = false;
@@ -164,6 +166,7 @@ __device__ __forceinline__ NodeResult wave_node_outcome(int lane, int K, int32_t
         const unsigned long long mask = __ballot(act && my_id == x);
         if (!mask) break;
         const int i = __ffsll((long long)mask) - 1;
+        if (onehot) w = lane == i ? 1.0f : 0.0f;
         const float wi = u2f((uint32_t)__builtin_amdgcn_readlane((int)f2u(w), i));
         const float ri = u2f((uint32_t)__builtin_amdgcn_readlane((int)f2u(r), i));
         const float ei = u2f((uint32_t)__builtin_amdgcn_readlane((int)f2u(err), i));
@@ -190,7 +193,7 @@ __device__ __forceinline__ NodeResult wave_node_outcome(int lane, int K, int32_t
         }
         r = rn;
         rho = rho / Z;
-        w = zw2 > 0.0f ? w_next / zw2 : 0.0f;
+        if (!onehot) w = zw2 > 0.0f ? w_next / zw2 : 0.0f;
     }
     res.r = r;
     res.rho = rho;
@@ -580,6 +583,7 @@ struct RowPassArgs {
     float *top_l, *top_p;       // [B*N][K]
     int32_t *outcome;           // [B*N] accepted child rank or -1
     unsigned long long *stats;
+    bool onehot;                // deterministic drafting: one-hot proposals in the accept tests
 };
 
 template <int DT>
@@ -664,13 +668,13 @@ __global__ __launch_bounds__(kRowThreads) void row_pass_kernel(RowPassArgs a)
     }
     const float e = (lane < a.K && my_id >= 0) ? exact_exp2(scaled_offset(my_l, m, a.c)) : 0.0f;
     NodeResult nr = wave_node_outcome(lane, a.K, my_id, my_mu, e / s, nch, ch, a.seed, (uint32_t)b, a.step, fc,
-                                      true, kFastEps);
+                                      true, kFastEps, a.onehot);
     if (nr.near) {
         // a test fell inside the error bound of the fast normaliser: decide with the exact one
         const unsigned long long S = wave_row_exact_sum<DT>(rowp, a.V, m, a.c, lane);
         const float sx = normaliser_from_fixed(S);
         nr = wave_node_outcome(lane, a.K, my_id, my_mu, e / sx, nch, ch, a.seed, (uint32_t)b, a.step, fc, false,
-                               0.0f);
+                               0.0f, a.onehot);
         if (lane == 0) atomicAdd(&a.stats[kStatNear], 1ull);
     }
     if (lane == 0) a.outcome[row] = nr.accepted;
@@ -720,6 +724,7 @@ struct PathArgs {
     float *obs_p;              // [B][W][K]
     unsigned long long *stats;
     unsigned long long *node_count;  // [N] verifications in which a node lay on the accepted path (mode 0)
+    bool onehot;                     // deterministic drafting: one-hot proposals in the accept tests
 };
 
 // Walks the accepted path of trajectory b and leaves it in path[0..len) (shared memory).  The
@@ -1079,7 +1084,7 @@ __global__ __launch_bounds__(kFinishThreads) void path_finish_kernel(PathArgs a,
         float my_r = 0.0f, rho = 1.0f;
         if (support) {
             const NodeResult nr = wave_node_outcome(lane, a.K, my_id, my_mu, my_e / s, nch, ch, a.seed, (uint32_t)b, a.step,
-                                                    fc, false, 0.0f);
+                                                    fc, false, 0.0f, a.onehot);
             my_r = (lane < a.K && my_id >= 0) ? nr.r : 0.0f;
             rho = nr.rho;
             if (lane == 0 && nr.accepted != -1) atomicAdd(&a.stats[kStatMismatch], 1ull);  // the stop node rejects all
@@ -1365,6 +1370,7 @@ struct DraftArgs {
     float *draft_qmu;
     int32_t *out_tok;  // caller's copy, may be NULL
     unsigned long long *stats;
+    int mode;          // 0: Gumbel-Top-K, 1: sequential multinomial without replacement, 2: largest means
 };
 
 constexpr int kDraftThreads = 1024;  // 16 waves: the nodes of a tree level are looked up side by side
@@ -1484,16 +1490,48 @@ __global__ __launch_bounds__(kDraftThreads) void draft_kernel(DraftArgs a)
                 a.draft_qid[((size_t)b * N + u) * K + lane] = id;
                 a.draft_qmu[((size_t)b * N + u) * K + lane] = mu;
             }
-            // ---- Gumbel-Top-K: score = ln mu - ln(-ln U); children get the largest scores in order
             const bool cand = lane < K && mu > 0.0f;
-            unsigned long long key = 0ull;
-            if (cand) {
-                const float U = uniform(a.seed, (uint32_t)b, a.step, (uint32_t)u, (uint32_t)id, kStreamDraft);
-                const float g = exact_log(-exact_log(U));
-                key = rank_key(exact_log(mu) - g, (uint32_t)id);
+            int rank = kMaxK;  // child rank of this lane's candidate (>= nch: not drafted)
+            if (a.mode == 1) {
+                // ---- sequential sampling without replacement (the ablation's plain stochastic
+                // drafting): draw j takes the first remaining candidate, in stored order, whose
+                // running sum of mu exceeds U_j * (sum of the remaining mu)
+                const float u_l = lane < nch ? uniform(a.seed, (uint32_t)b, a.step, (uint32_t)u, (uint32_t)lane, kStreamDraft) : 0.0f;
+                bool left = cand;
+                const int ncand_all = __popcll(__ballot(cand));
+                const int draws = nch < ncand_all ? nch : ncand_all;
+                for (int j = 0; j < draws; ++j) {
+                    const float mleft = left ? mu : 0.0f;
+                    const float z = wave_ordered_sum(mleft, K);
+                    const float t = u2f((uint32_t)__builtin_amdgcn_readlane((int)f2u(u_l), j)) * z;
+                    float acc = 0.0f;
+                    int pick = -1, last = -1;
+                    const unsigned long long left_mask = __ballot(left);
+                    for (int i = 0; i < K; ++i) {
+                        const float mi = u2f((uint32_t)__builtin_amdgcn_readlane((int)f2u(mleft), i));
+                        if (!((left_mask >> i) & 1ull)) continue;  // uniform
+                        last = i;
+                        acc = acc + mi;
+                        if (pick < 0 && t < acc) pick = i;
+                    }
+                    if (pick < 0) pick = last;
+                    if (lane == pick) { rank = j; left = false; }
+                }
+            } else {
+                // ---- Gumbel-Top-K (paper Sec. 4.2): score = ln mu - ln(-ln U), the largest scores in
+                // order; deterministic drafting (Sec. 3.1): the largest means themselves
+                unsigned long long key = 0ull;
+                if (cand) {
+                    if (a.mode == 2) key = rank_key(mu, (uint32_t)id);
+                    else {
+                        const float U = uniform(a.seed, (uint32_t)b, a.step, (uint32_t)u, (uint32_t)id, kStreamDraft);
+                        const float g = exact_log(-exact_log(U));
+                        key = rank_key(exact_log(mu) - g, (uint32_t)id);
+                    }
+                }
+                rank = 0;
+                for (int q = 0; q < K; ++q) rank += readlane_u64(key, q) > key ? 1 : 0;
             }
-            int rank = 0;
-            for (int q = 0; q < K; ++q) rank += readlane_u64(key, q) > key ? 1 : 0;
             if (cand && rank < nch) {
                 const int child = t_first[u] + rank;
                 tok[child] = id;

@@ -99,6 +99,7 @@ extern "C" int stand_create(const stand_config *cfg, stand_handle **out)
     if (cfg->max_probe < 1) return STAND_EINVAL;
     if (cfg->logits_dtype != STAND_BF16 && cfg->logits_dtype != STAND_F32) return STAND_EINVAL;
     if (cfg->update_mode != STAND_UPDATE_ACCEPTED_PATH) return STAND_EINVAL;
+    if (cfg->draft_mode < STAND_DRAFT_GUMBEL_TOPK || cfg->draft_mode > STAND_DRAFT_DETERMINISTIC) return STAND_EINVAL;
     if ((int64_t)cfg->max_batch * N * (int64_t)cfg->vocab >= ((int64_t)1 << 40)) return STAND_EINVAL;
     // merge records are numbered in 23 bits (kTagMax); max_batch * tree depth * orders stays far below
     if ((int64_t)cfg->max_batch * (kMaxDepth + 1) * STAND_MAX_ORDER > (int64_t)kTagMax) return STAND_EINVAL;
@@ -260,6 +261,7 @@ static int launch_row_pass(stand_handle *h, uint64_t step, const void *d_logits,
     a.draft_tok = h->draft_tok; a.draft_has = h->draft_has; a.draft_qid = h->draft_qid; a.draft_qmu = h->draft_qmu;
     a.row_m = h->row_m; a.row_s = h->row_s; a.top_idx = h->top_idx; a.top_l = h->top_l; a.top_p = h->top_p;
     a.outcome = h->outcome; a.stats = h->stats;
+    a.onehot = h->cfg.draft_mode == STAND_DRAFT_DETERMINISTIC;
     const dim3 grid((unsigned)((h->B * h->N + kRowsPerBlock - 1) / kRowsPerBlock)), block(kRowThreads);
     const bool timed = h->profiling && h->ev_used < h->ev_begin.size();
     if (timed) {
@@ -319,6 +321,7 @@ static int launch_path_pass(stand_handle *h, uint64_t step, const void *d_logits
     a.outcome = h->outcome; a.commit_row = commit_row; a.commit_len = commit_len;
     a.out_tok = out_tok; a.out_node = out_node; a.out_len = out_len;
     a.seg_part = h->seg_part; a.node_count = h->node_count;
+    a.onehot = h->cfg.draft_mode == STAND_DRAFT_DETERMINISTIC;
     a.stop_i = h->stop_i; a.stop_m = h->stop_m; a.stop_qid = h->stop_qid; a.stop_qmu = h->stop_qmu; a.stop_ql = h->stop_ql;
     a.stop_child = h->stop_child;
     a.obs_idx = h->obs_idx; a.obs_p = h->obs_p; a.stats = h->stats;
@@ -364,7 +367,7 @@ static int launch_draft(stand_handle *h, uint64_t step, int32_t *d_draft_tok, co
     a.seed = h->cfg.seed; a.step = step; a.tree = tree_dev(h);
     a.ctx_tail = h->ctx_tail; a.ctx_len = h->ctx_len; a.append_tok = append_tok; a.append_len = append_len;
     a.draft_tok = h->draft_tok; a.draft_has = h->draft_has; a.draft_qid = h->draft_qid; a.draft_qmu = h->draft_qmu;
-    a.out_tok = d_draft_tok; a.stats = h->stats;
+    a.out_tok = d_draft_tok; a.stats = h->stats; a.mode = h->cfg.draft_mode;
     draft_kernel<<<dim3((unsigned)h->B), dim3(kDraftThreads), 0, s>>>(a);
     HIP_TRY(h, hipGetLastError());
     return STAND_OK;

@@ -36,6 +36,10 @@ def _say(msg):
     ("cfg1", dict(V=40, B=4, K=10, rho=0.5), 40, "step", False),               # tiny vocabulary
     ("cfg3", dict(V=5000, B=8, rho=0.7), 25, "step", True),                    # 64-node tree, K=16, shared table
     ("cfg5", dict(V=3000, B=4, rho=0.7), 12, "step", True),                    # 128-node tree, K=32, orders 1-5
+    ("cfg3", dict(V=5000, B=4, rho=0.8, draft_mode=1), 25, "step", True),      # multinomial drafting
+    ("cfg3", dict(V=5000, B=4, rho=0.8, draft_mode=2), 25, "step", True),      # deterministic drafting, one-hot proposals
+    ("cfg1", dict(V=600, B=3, rho=0.6, draft_mode=2), 40, "separate", False),  # deterministic, closed loop
+    ("cfg1", dict(V=600, B=3, rho=0.6, draft_mode=1), 40, "separate", False),  # multinomial, closed loop
 ])
 def test_lockstep_small(gpu, name, over, steps, mode, forced):
     binding, lockstep = gpu
