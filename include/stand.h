@@ -181,6 +181,16 @@ int stand_get_stats(stand_handle *h, stand_stats *out);
 int stand_profile_begin(stand_handle *h, int32_t max_launches);
 int stand_profile_end(stand_handle *h, double *row_pass_ms_total, int32_t *launches);
 
+/* Inputs of the target model's verify pass for the pending drafts (paper Sec. 3.2: the drafted
+ * tree is scored in one pass with tree attention).  d_mask[b][u][v] (uint8, [B][N][N]) = 1 iff
+ * node v lies on the path root -> u (u included) and u carries a drafted token, else 0;
+ * d_pos[b][u] (int64, [B][N]) = position of node u in trajectory b's sequence, i.e.
+ * (committed tokens - 1) + depth(u) with the root = the last committed token; -1 for nodes
+ * without a drafted token.  Reflects the last stand_draft / stand_step.  The rows of the KV
+ * cache to keep after verification are those of d_out_node[b][0 .. d_out_len[b]) of
+ * stand_verify / stand_step; no separate output is needed for them. */
+int stand_tree_packing(stand_handle *h, uint8_t *d_mask, int64_t *d_pos, void *stream);
+
 /* ---- data-driven draft tree (paper Sec. 4.3 and appendix "Initial tree for optimization") ----
  *
  * The paper starts from a large heuristic tree, runs speculative decoding on sample data while

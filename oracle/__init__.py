@@ -126,6 +126,7 @@ def lib():
         L.so_table_export.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64]
         L.so_get_stats.argtypes = [C.c_void_p, C.POINTER(Stats)]
         L.so_get_node_counts.argtypes = [C.c_void_p, C.c_void_p]
+        L.so_tree_packing.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
         L.so_reset_node_counts.argtypes = [C.c_void_p]
         L.so_mc_draft.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_uint64, C.c_uint64, C.c_int, C.c_void_p]
         L.so_mc_node.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_int, C.c_uint64, C.c_uint64, C.c_int,
@@ -405,6 +406,12 @@ class Oracle:
         out = np.zeros(self.N, np.uint64)
         lib().so_get_node_counts(self.h, _p(out))
         return out
+
+    def tree_packing(self):
+        mask = np.zeros((self.B, self.N, self.N), np.uint8)
+        pos = np.zeros((self.B, self.N), np.int64)
+        lib().so_tree_packing(self.h, _p(mask), _p(pos))
+        return mask, pos
 
     def reset_node_counts(self):
         lib().so_reset_node_counts(self.h)

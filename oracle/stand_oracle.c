@@ -875,6 +875,29 @@ void so_draft(so_handle *h, uint64_t step, int32_t *draft_tok_out /* [B][N] */)
 }
 
 /* ------------------------------------------------------------------------------------------
+ * What the target model needs to score the pending tree in one pass (Sec. 3.2: the drafted
+ * tokens are verified "in parallel" by tree attention): node u may attend to node v iff v lies
+ * on the path root -> u (u itself included) and both carry a drafted token; the position of
+ * node u in the sequence is (number of committed tokens - 1) + depth(u), the root being the
+ * last committed token.  mask_out[b][u][v] in {0, 1}; pos_out[b][u] = -1 for undrafted nodes.
+ * ---------------------------------------------------------------------------------------- */
+void so_tree_packing(const so_handle *h, uint8_t *mask_out /* [B][N][N] */, int64_t *pos_out /* [B][N] */)
+{
+    int N = h->N;
+    for (int b = 0; b < h->B; ++b) {
+        const int32_t *tok = h->draft_tok + (int64_t)b * N;
+        for (int u = 0; u < N; ++u) {
+            uint8_t *row = mask_out + ((int64_t)b * N + u) * N;
+            for (int v = 0; v < N; ++v) row[v] = 0;
+            pos_out[(int64_t)b * N + u] = -1;
+            if (tok[u] < 0) continue;
+            for (int v = u; v >= 0; v = h->parent[v]) row[v] = 1;
+            pos_out[(int64_t)b * N + u] = h->ctx_len[b] - 1 + h->depth[u];
+        }
+    }
+}
+
+/* ------------------------------------------------------------------------------------------
  * Verify (Sec. 3.2, Sec. 4.2): from the root, test the children of the current node in rank
  * order; descend on acceptance; when no child is accepted (or there is none) draw one token
  * from the residual of that node and stop.  out_node[j] is the tree node whose logits row

@@ -23,6 +23,7 @@ EXPORTED = [
     "stand_get_context", "stand_get_stats", "stand_strerror", "stand_last_hip_error",
     "stand_profile_begin", "stand_profile_end", "stand_copy_bytes",
     "stand_tree_initial", "stand_tree_select", "stand_get_node_counts", "stand_reset_node_counts",
+    "stand_tree_packing",
 ]
 
 
@@ -71,6 +72,7 @@ def load_library():
     lib.stand_tree_initial.argtypes = [C.c_int32, i32p, C.c_int32, C.POINTER(C.c_int32)]
     lib.stand_tree_select.argtypes = [i32p, vp, C.c_int32, C.c_int32, i32p, i32p]
     lib.stand_get_node_counts.argtypes = [vp, vp]
+    lib.stand_tree_packing.argtypes = [vp, vp, vp, vp]
     lib.stand_reset_node_counts.argtypes = [vp]
     lib.stand_strerror.restype = C.c_char_p
     lib.stand_strerror.argtypes = [C.c_int]
@@ -254,6 +256,13 @@ class Stand:
         s = Stats()
         _check(lib().stand_get_stats(self.h, C.byref(s)), self.h)
         return s
+
+    def tree_packing(self):
+        """(mask [B, N, N] uint8, positions [B, N] int64) of the pending drafts, on the GPU."""
+        mask = torch.empty((self.B, self.N, self.N), dtype=torch.uint8, device=self.device)
+        pos = torch.empty((self.B, self.N), dtype=torch.int64, device=self.device)
+        _check(lib().stand_tree_packing(self.h, _dptr(mask), _dptr(pos), _stream_ptr()), self.h)
+        return mask, pos
 
     def node_counts(self):
         out = np.zeros(self.N, np.uint64)

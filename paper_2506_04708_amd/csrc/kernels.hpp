@@ -1572,6 +1572,25 @@ __global__ void copy_row_results_kernel(int rows, int K, const float *row_m, con
     }
 }
 
+// Attention mask and positions of the pending tree (paper Sec. 3.2: the tree is scored by the
+// target model in one pass).  anc[u] is the set of ancestors-or-self of node u as a bit set of
+// `words` 64-bit words.  One thread per (u, 8 consecutive v): eight mask bytes per store.
+__global__ __launch_bounds__(256) void tree_packing_kernel(int B, int N, int words, const unsigned long long *anc,
+                                                           const int32_t *depth, const int32_t *draft_tok,
+                                                           const long long *ctx_len, uint8_t *mask, long long *pos)
+{
+    const int b = blockIdx.y;
+    const int groups = (N + 7) / 8;                 // groups of 8 columns per row
+    const int item = blockIdx.x * blockDim.x + threadIdx.x;
+    if (item >= N * groups) return;
+    const int u = item / groups, v0 = (item % groups) * 8;
+    const bool drafted = draft_tok[(size_t)b * N + u] >= 0;
+    const unsigned long long bits = drafted ? anc[(size_t)u * words + (v0 >> 6)] >> (v0 & 63) : 0ull;
+    uint8_t *row = mask + ((size_t)b * N + u) * N;
+    for (int q = 0; q < 8 && v0 + q < N; ++q) row[v0 + q] = (uint8_t)((bits >> q) & 1ull);
+    if (v0 == 0) pos[(size_t)b * N + u] = drafted ? ctx_len[b] - 1 + depth[u] : -1;
+}
+
 // plain copy of 16-byte words: the known-size kernel against which HBM traffic counters are scaled
 __global__ __launch_bounds__(256) void copy_words_kernel(const uint4 *src, uint4 *dst, size_t nwords)
 {

@@ -30,7 +30,8 @@ struct stand_handle {
     int32_t *obs_idx;
     float *obs_p;
     long long *rec_slot;
-    unsigned long long *seg_part, *node_count;
+    unsigned long long *seg_part, *node_count, *anc;  // anc: [N][anc_words] ancestor-or-self bit sets
+    int anc_words;
     int32_t *stop_i, *stop_qid, *stop_child;
     float *stop_m, *stop_qmu, *stop_ql;
     float *pr_m, *pr_top_l;
@@ -77,7 +78,7 @@ static void free_all(stand_handle *h)
     if (!h) return;
     void *ptrs[] = {h->d_tree, h->table, h->ctx_tail, h->ctx_len, h->draft_tok, h->draft_has, h->draft_qid, h->draft_qmu,
                     h->row_m, h->row_s, h->top_l, h->top_p, h->top_idx, h->outcome, h->obs_idx, h->obs_p, h->rec_slot,
-                    h->seg_part, h->node_count, h->stop_i, h->stop_qid, h->stop_child, h->stop_m, h->stop_qmu, h->stop_ql, h->pr_m, h->pr_top_l, h->pr_top_idx, h->stats, h->counter};
+                    h->seg_part, h->node_count, h->anc, h->stop_i, h->stop_qid, h->stop_child, h->stop_m, h->stop_qmu, h->stop_ql, h->pr_m, h->pr_top_l, h->pr_top_idx, h->stats, h->counter};
     for (void *p : ptrs) (void)hipFree(p);
     for (hipEvent_t e : h->ev_begin) (void)hipEventDestroy(e);
     for (hipEvent_t e : h->ev_end) (void)hipEventDestroy(e);
@@ -159,6 +160,8 @@ extern "C" int stand_create(const stand_config *cfg, stand_handle **out)
     acc(dmalloc(&h->rec_slot, nrec));
     acc(dmalloc(&h->seg_part, B * h->W * kSegMax));
     acc(dmalloc(&h->node_count, (size_t)N));
+    h->anc_words = (N + 63) / 64;
+    acc(dmalloc(&h->anc, (size_t)N * h->anc_words));
     acc(dmalloc(&h->stop_i, B * 4)); acc(dmalloc(&h->stop_m, B)); acc(dmalloc(&h->stop_qid, B * kMaxK));
     acc(dmalloc(&h->stop_qmu, B * kMaxK)); acc(dmalloc(&h->stop_ql, B * kMaxK)); acc(dmalloc(&h->stop_child, B * kMaxK));
     acc(dmalloc(&h->pr_m, B * h->W)); acc(dmalloc(&h->pr_top_l, B * h->W * K)); acc(dmalloc(&h->pr_top_idx, B * h->W * K));
@@ -182,6 +185,16 @@ extern "C" int stand_create(const stand_config *cfg, stand_handle **out)
     acc(hipMemset(h->draft_qmu, 0, rows * K * sizeof(float)));
     acc(hipMemset(h->outcome, 0xFF, rows * sizeof(int32_t)));
     acc(hipMemset(h->node_count, 0, (size_t)N * sizeof(unsigned long long)));
+    {
+        // a node's set is its parent's set plus itself (parents come first in the numbering)
+        std::vector<unsigned long long> anc((size_t)N * h->anc_words, 0ull);
+        for (int u = 0; u < N; ++u) {
+            if (u > 0)
+                for (int q = 0; q < h->anc_words; ++q) anc[(size_t)u * h->anc_words + q] = anc[(size_t)cfg->tree_parent[u] * h->anc_words + q];
+            anc[(size_t)u * h->anc_words + (u >> 6)] |= 1ull << (u & 63);
+        }
+        acc(hipMemcpy(h->anc, anc.data(), anc.size() * sizeof(unsigned long long), hipMemcpyHostToDevice));
+    }
     acc(hipMemset(h->row_m, 0, rows * sizeof(float))); acc(hipMemset(h->row_s, 0, rows * sizeof(float)));
     acc(hipMemset(h->top_l, 0, rows * K * sizeof(float))); acc(hipMemset(h->top_p, 0, rows * K * sizeof(float)));
     acc(hipMemset(h->top_idx, 0, rows * K * sizeof(int32_t)));
@@ -390,6 +403,18 @@ extern "C" int stand_draft(stand_handle *h, uint64_t step, int32_t *d_draft_tok,
     if (!h) return STAND_EINVAL;
     HIP_TRY(h, hipSetDevice(h->cfg.device));
     return launch_draft(h, step, d_draft_tok, nullptr, nullptr, (hipStream_t)stream);
+}
+
+extern "C" int stand_tree_packing(stand_handle *h, uint8_t *d_mask, int64_t *d_pos, void *stream)
+{
+    if (!h || !d_mask || !d_pos) return STAND_EINVAL;
+    HIP_TRY(h, hipSetDevice(h->cfg.device));
+    const int items = h->N * ((h->N + 7) / 8);
+    const dim3 grid((unsigned)((items + 255) / 256), (unsigned)h->B);
+    tree_packing_kernel<<<grid, dim3(256), 0, (hipStream_t)stream>>>(h->B, h->N, h->anc_words, h->anc, tree_dev(h).depth,
+                                                                     h->draft_tok, h->ctx_len, d_mask, (long long *)d_pos);
+    HIP_TRY(h, hipGetLastError());
+    return STAND_OK;
 }
 
 extern "C" int stand_verify(stand_handle *h, uint64_t step, const void *d_logits, int32_t *d_out_tok, int32_t *d_out_node,

@@ -117,6 +117,10 @@ def run_lockstep(w, steps, mode="separate", capacity=1 << 12, check_rows=True, t
         if check_rows:
             info["worst_rel"] = max(info["worst_rel"], compare_rows(lg, w, g))
         assert np.array_equal(d_draft.cpu().numpy(), od), "step %d: next draft differs" % step
+        if step % 4 == 0:
+            gm, gp = g.tree_packing()
+            om, op = o.tree_packing()
+            assert np.array_equal(gm.cpu().numpy(), om) and np.array_equal(gp.cpu().numpy(), op), "tree mask / positions differ"
         if table_every and (step % table_every == 0 or step == steps - 1):
             info["entries"] = compare_tables(o, g, w.K)
         for b in range(w.B):

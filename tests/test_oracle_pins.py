@@ -585,6 +585,44 @@ def test_draft_contexts_and_invalid_subtrees():
     assert s.hits[2] == 1 and s.misses >= 1
 
 
+def test_tree_packing_is_the_transitive_closure_of_the_parent_relation():
+    """Tree attention (Sec. 3.2): node u sees exactly the nodes on its path from the root.  Checked
+    against the boolean closure (I + P)^D of the parent relation P, and by row sums = depth + 1."""
+    V, K = 50, 4
+    parent = synth.make_tree(16, 4, [4, 2, 1, 1])
+    depth = synth.tree_info(parent)[0]
+    o = oracle.Oracle(V, 2, 1, 2, K, parent, 0.6, 1 << 10, 64, 3, oracle.DT_F32)
+    # teach the table a chain 5 -> 6 -> 7 ... so that trajectory 0 drafts a partial tree
+    ctx = [1, 2, 3, 4, 5]
+    for a in range(5, 12):
+        ids = np.array([a + 1, a + 20, a + 30, 0], np.int32)
+        mu = np.array([0.6, 0.2, 0.1, 0.0], np.float32)
+        o.table_put([a], 1, ids, mu)
+    o.set_context(0, ctx)
+    o.set_context(1, [9, 9, 40])           # nothing known after 40: only the root is drafted
+    tok = o.draft(0)
+    mask, pos = o.tree_packing()
+    N = len(parent)
+    P = np.zeros((N, N), bool)
+    for u in range(1, N):
+        P[u, parent[u]] = True
+    closure = np.eye(N, dtype=bool)
+    step = np.eye(N, dtype=bool) | P
+    for _ in range(int(depth.max())):
+        closure = (closure.astype(np.int64) @ step.astype(np.int64)) > 0
+    for b in range(2):
+        drafted = tok[b] >= 0
+        assert drafted[0] and (b == 0 and drafted.sum() > 3 or b == 1 and drafted.sum() == 1)
+        want = closure & drafted[:, None]
+        assert np.array_equal(mask[b].astype(bool), want)
+        assert np.array_equal(mask[b].sum(axis=1), np.where(drafted, depth + 1, 0))
+        clen = 5 if b == 0 else 3
+        assert np.array_equal(pos[b], np.where(drafted, clen - 1 + depth, -1))
+        # a drafted node's ancestors are drafted, so no drafted row points at an undrafted column
+        assert not mask[b][:, ~drafted].any()
+    o.close()
+
+
 def test_tree_generator_matches_fixture():
     lines = [l.split() for l in open(os.path.join(GOLD, "cfg1_tree.txt")) if not l.startswith("#")]
     par = [int(x) for x in lines[0][1:]]
