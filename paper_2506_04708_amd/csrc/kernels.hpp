@@ -288,54 +288,90 @@ __device__ __forceinline__ void wave_prune(WaveScan *ws, WaveScanState &st, int 
     if (th) set_theta(st, th);
 }
 
+// While a row is streamed the list holds raw records, (bits of the vector maximum) << 32 | vector
+// index, which cost nothing to build; ranking keys are made from them when the list is pruned.
+__device__ __forceinline__ unsigned long long raw_record(float cm, uint32_t vec)
+{
+    return ((unsigned long long)f2u(cm) << 32) | vec;
+}
+__device__ __forceinline__ unsigned long long key_of_raw(unsigned long long raw)
+{
+    return rank_key(u2f((uint32_t)(raw >> 32)), (uint32_t)raw);
+}
+__device__ __forceinline__ unsigned long long raw_of_key(unsigned long long key)
+{
+    return raw_record(rank_key_value(key), rank_key_id(key));
+}
+
 // Cheap prune: finds, by bisection on the upper key word (the vector maximum) with ballots, a
 // threshold that at least K records reach, and keeps those records (unsorted; records whose
-// maximum equals the threshold all stay).  Used while streaming, where only the threshold and
-// a short list matter.  Falls back to the exact prune when ties leave too many records.
+// maximum equals the threshold all stay).  RAW_IN / KEYS_OUT say whether the list holds raw
+// records or ranking keys before / after.  Falls back to the exact prune when ties leave too
+// many records.
 constexpr int kPruneSlack = 16;
+template <bool RAW_IN, bool KEYS_OUT>
 __device__ __forceinline__ void wave_prune_fast(WaveScan *ws, WaveScanState &st, int lane, int K)
 {
     const int n = st.cnt;  // <= kWaveCap = 3 * 64
-    if (n <= K) return;
-    const unsigned long long e0 = lane < n ? ws->buf[lane] : 0ull;
-    const unsigned long long e1 = 64 + lane < n ? ws->buf[64 + lane] : 0ull;
-    const unsigned long long e2 = 128 + lane < n ? ws->buf[128 + lane] : 0ull;
+    unsigned long long e0 = lane < n ? ws->buf[lane] : 0ull;
+    unsigned long long e1 = 64 + lane < n ? ws->buf[64 + lane] : 0ull;
+    unsigned long long e2 = 128 + lane < n ? ws->buf[128 + lane] : 0ull;
+    if (RAW_IN) {  // ranking keys of existing records are never zero
+        e0 = lane < n ? key_of_raw(e0) : 0ull;
+        e1 = 64 + lane < n ? key_of_raw(e1) : 0ull;
+        e2 = 128 + lane < n ? key_of_raw(e2) : 0ull;
+    }
     const uint32_t h0 = (uint32_t)(e0 >> 32), h1 = (uint32_t)(e1 >> 32), h2 = (uint32_t)(e2 >> 32);
     uint32_t t = 0u;
-    for (int bit = 31; bit >= 0; --bit) {
-        const uint32_t cand = t | (1u << bit);
-        const int c = __popcll(__ballot(h0 >= cand)) + __popcll(__ballot(h1 >= cand)) + __popcll(__ballot(h2 >= cand));
-        if (c >= K) {
-            t = cand;
-            if (c == K) break;
+    if (n > K) {
+        for (int bit = 31; bit >= 0; --bit) {
+            const uint32_t cand = t | (1u << bit);
+            const int c = __popcll(__ballot(h0 >= cand)) + __popcll(__ballot(h1 >= cand)) + __popcll(__ballot(h2 >= cand));
+            if (c >= K) {
+                t = cand;
+                if (c == K) break;
+            }
         }
     }
-    // at least K records have an upper word >= t (t > 0: keys of existing records are not zero)
+    // n > K: at least K records have an upper word >= t > 0; otherwise t = 0 keeps every record
+    const bool k0 = lane < n && h0 >= t, k1 = 64 + lane < n && h1 >= t, k2 = 128 + lane < n && h2 >= t;
     __builtin_amdgcn_wave_barrier();
-    const unsigned long long b0 = __ballot(h0 >= t), b1 = __ballot(h1 >= t), b2 = __ballot(h2 >= t);
+    const unsigned long long b0 = __ballot(k0), b1 = __ballot(k1), b2 = __ballot(k2);
     const int c0 = __popcll(b0), c1 = __popcll(b1);
-    if (h0 >= t) ws->buf[lane_prefix_count(b0)] = e0;
-    if (h1 >= t) ws->buf[c0 + lane_prefix_count(b1)] = e1;
-    if (h2 >= t) ws->buf[c0 + c1 + lane_prefix_count(b2)] = e2;
+    const bool keys_now = KEYS_OUT || !RAW_IN;
+    if (k0) ws->buf[lane_prefix_count(b0)] = (RAW_IN && !KEYS_OUT) ? raw_of_key(e0) : e0;
+    if (k1) ws->buf[c0 + lane_prefix_count(b1)] = (RAW_IN && !KEYS_OUT) ? raw_of_key(e1) : e1;
+    if (k2) ws->buf[c0 + c1 + lane_prefix_count(b2)] = (RAW_IN && !KEYS_OUT) ? raw_of_key(e2) : e2;
     __builtin_amdgcn_wave_barrier();
     st.cnt = c0 + c1 + __popcll(b2);
-    const unsigned long long key = (unsigned long long)t << 32;
-    if (key > st.theta_key) { st.theta_key = key; st.theta_val = order_key_inv(t); }
-    if (st.cnt > K + kPruneSlack) wave_prune(ws, st, lane, K);
+    if (t) {
+        const unsigned long long key = (unsigned long long)t << 32;
+        if (key > st.theta_key) { st.theta_key = key; st.theta_val = order_key_inv(t); }
+    }
+    if (st.cnt > K + kPruneSlack) {
+        // too many ties at the threshold: rank exactly (on keys), then restore the list's form
+        if (!keys_now) {
+            for (int i = lane; i < st.cnt; i += 64) ws->buf[i] = key_of_raw(ws->buf[i]);
+            __builtin_amdgcn_wave_barrier();
+        }
+        wave_prune(ws, st, lane, K);
+        if (!keys_now) {
+            if (lane < st.cnt) ws->buf[lane] = raw_of_key(ws->buf[lane]);
+            __builtin_amdgcn_wave_barrier();
+        }
+    }
 }
 
-// Lanes with `has` append the record (cm, vec) if it beats the threshold; prune above kWavePrune records.
-__device__ __forceinline__ void wave_offer(WaveScan *ws, WaveScanState &st, int lane, int K, bool has, float cm,
+// Lanes with `pred` append the raw record (cm, vec); prune above kWavePrune records.
+__device__ __forceinline__ void wave_offer(WaveScan *ws, WaveScanState &st, int lane, int K, bool pred, float cm,
                                            uint32_t vec)
 {
-    const unsigned long long key = rank_key(cm, vec);
-    const bool pred = has && key > st.theta_key;
     const unsigned long long bal = __ballot(pred);
     if (!bal) return;
-    if (pred) ws->buf[st.cnt + lane_prefix_count(bal)] = key;
+    if (pred) ws->buf[st.cnt + lane_prefix_count(bal)] = raw_record(cm, vec);
     st.cnt += __popcll(bal);
     __builtin_amdgcn_wave_barrier();
-    if (st.cnt > kWavePrune) wave_prune_fast(ws, st, lane, K);
+    if (st.cnt > kWavePrune) wave_prune_fast<true, false>(ws, st, lane, K);
 }
 
 // Leaves the row's K best element keys (value desc, id asc) sorted in ws->top[0..K), returns
@@ -439,8 +475,8 @@ __device__ __forceinline__ WavePartial wave_row_stream(const void *rowp, int V, 
         }
     }
 
-    // leave at most K + kPruneSlack records, the wave's K best among them, in ws->buf
-    wave_prune_fast(ws, st, lane, K);
+    // leave at most K + kPruneSlack ranking keys, the wave's K best among them, in ws->buf
+    wave_prune_fast<true, true>(ws, st, lane, K);
     float s = s_t;
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off);
@@ -469,7 +505,7 @@ __device__ __forceinline__ void wave_row_finish(const void *rowp, int V, int K, 
         WaveScanState st;
         st.cnt = cnt;
         set_theta(st, 0ull);
-        wave_prune_fast(ws, st, lane, K);
+        wave_prune_fast<false, true>(ws, st, lane, K);
         cnt = st.cnt;
     }
     const unsigned long long th_vec = wave_select(ws->buf, ws->top, lane, K, cnt);
