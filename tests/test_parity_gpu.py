@@ -162,6 +162,22 @@ def test_full_shape_step(gpu):
     assert info["emitted"] >= 3 * w.B and info["entries"] > 0
 
 
+@pytest.mark.parametrize("name,over,steps", [
+    ("cfg2", dict(), 32),                                             # configs[1] at its real shape: B=1, 32-node tree
+    ("cfg4", dict(B=16, shared_prefix=64, cross=0.6), 5),             # configs[3] rows (V=128256, 48 nodes, K=10, T=1), 16 of its 64 trajectories
+    ("cfg5", dict(B=8), 4),                                           # configs[4] rows (128 nodes, K=32, orders 1-5, T=0.8), 8 of its 128 beams
+])
+def test_other_configs_at_their_row_shapes(gpu, name, over, steps):
+    """The remaining BASELINE configs with their real vocabulary, tree, K, orders and temperature
+    (fewer trajectories where the full batch would not fit a test's time), whole steps in lock step."""
+    binding, lockstep = gpu
+    w = synth.Workload(name, run_steps=steps, **over)
+    _say("%s %s: %d rows of %d logits, %d steps" % (name, over, w.B * w.N, w.V, steps))
+    info = lockstep.run_lockstep(w, steps, mode="step", capacity=1 << 16, forced=True, check_rows=False)
+    _say("  -> %s" % {k: v for k, v in info.items() if k != "node_counts"})
+    assert info["emitted"] >= steps * w.B
+
+
 def test_tree_optimisation_on_the_initial_tree(gpu):
     """Paper Sec. 4.3 end to end at a small vocabulary: speculate on the 625-node initial tree
     (depth 20), count accepted nodes on both sides, keep the best 80 and speculate on that tree."""
