@@ -21,6 +21,7 @@ DT_BF16 = 0
 DT_F32 = 1
 STREAM_DRAFT, STREAM_ACCEPT, STREAM_BONUS = 0, 1, 2
 DRAFT_GUMBEL_TOPK, DRAFT_MULTINOMIAL, DRAFT_DETERMINISTIC = 0, 1, 2
+UPDATE_ACCEPTED_PATH, UPDATE_ALL_NODES = 0, 1
 
 
 def build(force=False):

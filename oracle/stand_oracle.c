@@ -44,6 +44,10 @@
 #define SO_STREAM_BONUS 2u
 
 /* how the children of a node are drawn from its table entry (Sec. 3.1, Sec. 4.2, Table 5) */
+/* which rows of a verified tree are merged into the table (Sec. 4.1) */
+#define SO_UPDATE_ACCEPTED_PATH 0 /* the rows that produced committed tokens                       */
+#define SO_UPDATE_ALL_NODES 1     /* the row of every drafted node, under the context that node    */
+                                  /* would have if its path were accepted (a table stress variant) */
 #define SO_DRAFT_GUMBEL_TOPK 0   /* stochastic, Gumbel-Top-K (the method's own)                */
 #define SO_DRAFT_MULTINOMIAL 1   /* stochastic, sequential sampling without replacement        */
 #define SO_DRAFT_DETERMINISTIC 2 /* the most probable stored tokens; proposal treated as one-hot */
@@ -975,6 +979,32 @@ void so_update(so_handle *h, uint64_t step, const void *logits, const int32_t *c
     int K = h->K, V = h->V, W = h->D + 1;
     int32_t obs_id[SO_MAX_K];
     float obs_p[SO_MAX_K];
+    if (h->cfg.update_mode == SO_UPDATE_ALL_NODES) {
+        /* Every drafted node u: its row is the distribution of the token after the sequence
+         * context ++ tokens on the path root -> u (the root is the context's last token).
+         * Records in the order b, u, n ascending; the pending draft is the one just verified. */
+        int N = h->N;
+        int32_t path_tok[64];
+        for (int b = 0; b < h->B; ++b) {
+            const int32_t *tok = h->draft_tok + (int64_t)b * N;
+            int64_t base_len = h->ctx_len[b];
+            for (int u = 0; u < N; ++u) {
+                if (tok[u] < 0) continue;
+                so_row_obs(row_ptr(h, logits, b, u), h->cfg.logits_dtype, V, h->cfg.temperature, K, obs_id, obs_p, NULL, NULL);
+                int d = h->depth[u];
+                for (int x = u, i = d; x > 0; x = h->parent[x]) path_tok[--i] = tok[x]; /* tokens below the root */
+                int32_t key[SO_MAX_ORDER];
+                for (int n = h->cfg.order_min; n <= h->cfg.order_max; ++n) {
+                    if (base_len + d < n) continue;
+                    for (int i = 0; i < n; ++i) {
+                        int64_t pos = base_len + d - n + i; /* position in context ++ path */
+                        key[i] = pos < base_len ? h->ctx[b][pos] : path_tok[pos - base_len];
+                    }
+                    table_merge(h, n, key, obs_id, obs_p);
+                }
+            }
+        }
+    } else
     for (int b = 0; b < h->B; ++b) {
         int64_t base_len = h->ctx_len[b];
         for (int j = 0; j < commit_len[b]; ++j) {

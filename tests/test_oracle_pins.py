@@ -240,6 +240,52 @@ def test_table_equals_brute_force_recount():
     assert o.context_len(0) == len(ctx) and list(o.context_tail(0, 3)) == ctx[-3:]
 
 
+def test_all_nodes_update_equals_brute_force_recount():
+    """ALL_NODES update mode: every drafted node's row is merged under the context the node would
+    have if its path were accepted; recounted here from the drafted trees with a dictionary."""
+    V, K, T = 8, 8, 0.6
+    parent = np.array([-1, 0, 0, 1, 1, 2, 3], np.int32)
+    o = oracle.Oracle(V, 2, 1, 3, K, parent, T, 1 << 12, 64, 7, oracle.DT_F32, update_mode=oracle.UPDATE_ALL_NODES)
+    depth = synth.tree_info(parent)[0]
+    r = np.random.default_rng(15)
+    ctx = [[int(x) for x in r.integers(V, size=2)] for _ in range(2)]
+    for b in range(2):
+        o.set_context(b, ctx[b])
+    recount = {}
+    draft = o.draft(0)
+    for step in range(120):
+        lg = r.standard_normal((2, o.N, V)).astype(np.float32)
+        for b in range(2):
+            for u in range(o.N):
+                if draft[b, u] < 0:
+                    continue
+                path, x = [], u
+                while x > 0:
+                    path.append(int(draft[b, x]))
+                    x = parent[x]
+                seq = ctx[b] + path[::-1]
+                p = _softmax64(lg[b, u], T)
+                for order in (1, 2, 3):
+                    if len(seq) >= order:
+                        acc = recount.setdefault(tuple(seq[-order:]), [0, np.zeros(V)])
+                        acc[0] += 1
+                        acc[1] += p
+        otok, onode, olen, draft_next = o.step(step, lg)
+        for b in range(2):
+            ctx[b] += [int(t) for t in otok[b, : olen[b]]]
+        draft = draft_next
+    tab = o.table_export()
+    assert len(tab) == len(recount) and (draft >= 0).sum() > 4      # trees really were drafted
+    byfp = {int(t["fp"]): t for t in tab}
+    for key, (cnt, psum) in recount.items():
+        t = byfp[oracle.fingerprint(key)]
+        assert t["count"] == cnt and t["order"] == len(key)
+        got = np.zeros(V)
+        got[t["ids"]] = t["mu"]
+        assert np.max(np.abs(got - psum / cnt)) < 3e-6
+    o.close()
+
+
 def test_fingerprint_separates_orders_and_permutations():
     fps = {oracle.fingerprint(t) for t in [(1,), (1, 1), (1, 2), (2, 1), (0,), (0, 0), (0, 0, 0), (2 ** 31 - 1,)]}
     assert len(fps) == 8 and 0 not in fps
