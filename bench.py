@@ -61,6 +61,8 @@ def main():
     ap.add_argument("--no-events", action="store_true", help="do not time the row pass with HIP events")
     ap.add_argument("--draft-mode", type=int, default=0,
                     help="0 Gumbel-Top-K (the method), 1 sequential multinomial, 2 deterministic (the paper's ablation)")
+    ap.add_argument("--update-mode", type=int, default=0,
+                    help="0 merge the accepted path's rows (the paper), 1 merge every drafted node's row (table stress)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run a plain copy of one logits tensor (known HBM traffic) for counter calibration")
     args = ap.parse_args()
@@ -88,7 +90,7 @@ def main():
     dt = binding.STAND_BF16 if w.dtype == "bf16" else binding.STAND_F32
     assert w.dtype == "bf16"
     mk = lambda: binding.Stand(w.V, w.B, cfg["order_min"], cfg["order_max"], w.K, w.parent, w.T, cfg["capacity"], 64,
-                               cfg["seed"], dt, draft_mode=args.draft_mode)
+                               cfg["seed"], dt, draft_mode=args.draft_mode, update_mode=args.update_mode)
     gen = torch.Generator(device="cuda").manual_seed(cfg["seed"] & 0x7FFFFFFF)
     h1 = mk()
     for b in range(w.B):
@@ -102,7 +104,8 @@ def main():
     if cpu_n:
         import oracle
         orc = oracle.Oracle(w.V, w.B, cfg["order_min"], cfg["order_max"], w.K, w.parent, w.T, cfg["capacity"], 64,
-                            cfg["seed"], oracle.DT_BF16, draft_mode=args.draft_mode)
+                            cfg["seed"], oracle.DT_BF16, draft_mode=args.draft_mode,
+                            update_mode=args.update_mode)
         for b in range(w.B):
             orc.set_context(b, w.prompt(b))
         od = orc.draft(0)
@@ -227,11 +230,13 @@ def main():
                                "for %d steps" % (args.workload, w.B, w.V, w.N, w.D, cfg["order_min"], cfg["order_max"], w.K,
                                                  w.T, cfg["capacity"], T_warm),
                    "draft_mode": ["gumbel_topk", "multinomial", "deterministic"][args.draft_mode],
+                   "update_mode": ["accepted_path", "all_nodes"][args.update_mode],
                    "acceptance_len": round(acc_len, 3), "table_entries": int(entries0 + st.inserts)},
         "hbm_gbps_algorithmic": round(step_bytes * steps_per_s / 1e9, 1),
         "hbm_frac_of_peak": round(step_bytes * steps_per_s / 1e9 / HBM_PEAK_GBPS, 4),
         "bytes_per_step": step_bytes,
         "roofline": roof, "cpu_baseline": cpu,
+        "table_updates_per_step": round((st.inserts + st.merges) / max(len(rec), 1), 1),
         "near_threshold_fallbacks": int(st.near_threshold), "filter_mismatch": int(st.filter_mismatch),
         "prep_seconds": round(prep_s, 1),
     }

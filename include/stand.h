@@ -43,6 +43,11 @@ extern "C" {
 #define STAND_F32 1
 
 #define STAND_UPDATE_ACCEPTED_PATH 0 /* merge the rows that produced committed tokens (paper Sec. 4.1) */
+#define STAND_UPDATE_ALL_NODES 1     /* merge the row of EVERY drafted node of the verified tree, each under  */
+                                     /* the context it would have if its path were accepted: records in the   */
+                                     /* order b, node, n ascending; commit rows are then ignored by the merge  */
+                                     /* (the committed tokens are still appended).  A stress variant for the   */
+                                     /* table: thousands of records per step instead of hundreds               */
 
 /* How the children of a tree node are drawn from its table entry (paper Sec. 3.1 "deterministic
  * or stochastic" drafting, Sec. 4.2, and the ablation of Table 5).  All three keep the output
@@ -74,7 +79,7 @@ typedef struct {
     int32_t max_probe;          /* linear-probe limit, >= 1; past it an update is dropped+counted   */
     uint64_t seed;              /* key of the counter-based uniforms                                */
     int32_t logits_dtype;       /* STAND_BF16 or STAND_F32                                          */
-    int32_t update_mode;        /* STAND_UPDATE_ACCEPTED_PATH                                       */
+    int32_t update_mode;        /* STAND_UPDATE_*                                                   */
     int32_t device;             /* HIP device ordinal                                               */
     int32_t draft_mode;         /* STAND_DRAFT_*                                                    */
 } stand_config;

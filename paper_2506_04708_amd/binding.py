@@ -152,11 +152,11 @@ class Stand:
     """One n-gram table shared by B trajectories on one GPU; methods carry the C ABI's names."""
 
     def __init__(self, vocab, max_batch, order_min, order_max, topk, tree_parent, temperature, table_capacity,
-                 max_probe, seed, logits_dtype, device=0, draft_mode=0):
+                 max_probe, seed, logits_dtype, device=0, draft_mode=0, update_mode=0):
         par = np.ascontiguousarray(tree_parent, dtype=np.int32)
         cfg = Config(vocab, max_batch, order_min, order_max, topk, par.shape[0],
                      par.ctypes.data_as(C.POINTER(C.c_int32)), temperature, table_capacity, max_probe, seed,
-                     logits_dtype, 0, device, draft_mode)
+                     logits_dtype, update_mode, device, draft_mode)
         self.h = C.c_void_p()
         _check(lib().stand_create(C.byref(cfg), C.byref(self.h)))
         self.B, self.N, self.K, self.V = max_batch, par.shape[0], topk, vocab

@@ -735,6 +735,8 @@ constexpr int kFinishThreads = 1024;  // path_finish_kernel: many waves, so that
 struct PathArgs {
     const void *logits;
     int B, N, V, K, W, mode;   // mode 0: verify (path from outcome), 1: update (rows given)
+    int R;                     // row slots per trajectory: W (slot j = path position j), or N when
+    bool all_nodes;            // every drafted node's row is observed (slot j = node j)
     int nseg;                  // segments per path row (grid.x of path_exact_kernel)
     float c;
     uint64_t seed, step;
@@ -879,16 +881,17 @@ __global__ __launch_bounds__(kPathThreads) void path_exact_kernel(PathArgs a)
     }
     // ---- partial sum of segment seg of path row j; the root row needs no walk
     int node;
-    if (a.mode != 0) node = commit_row_of(a, b, j);
+    if (a.all_nodes) node = a.draft_tok[(size_t)b * a.N + j] >= 0 ? j : -1;
+    else if (a.mode != 0) node = commit_row_of(a, b, j);
     else if (j == 0) node = 0;
     else {
         const int len = resolve_path(a, b, path, oc, &s_len);
         node = j < len ? path[j] : -1;
     }
-    if (node < 0) return;  // block-uniform: no such path row
+    if (node < 0) return;  // block-uniform: no such row
     const int row = b * a.N + node;
     const char *rowp = (const char *)a.logits + (size_t)row * (size_t)a.V * ES;
-    const float m = a.src_m[a.mode == 0 ? row : b * a.W + j];
+    const float m = a.src_m[a.mode == 0 ? row : b * a.R + j];
     const RowGeom g = row_geom<DT>(rowp, a.V);
     const int per = (g.nvec + nseg - 1) / nseg;
     const int v0 = seg * per < g.nvec ? seg * per : g.nvec;
@@ -900,7 +903,7 @@ __global__ __launch_bounds__(kPathThreads) void path_exact_kernel(PathArgs a)
     if (tid == 0) {
         unsigned long long t = 0ull;
         for (int q = 0; q < kPathThreads / 64; ++q) t += s_part[q];
-        a.seg_part[((size_t)b * a.W + j) * kSegMax + seg] = t;
+        a.seg_part[((size_t)b * a.R + j) * kSegMax + seg] = t;
     }
 }
 
@@ -931,7 +934,9 @@ __device__ __forceinline__ void vector_masses(const uint4 &w, int e0, float m, f
 // Update mode: maximum and top-K of the given commit rows (one workgroup of 4 waves per row).
 struct CommitScanArgs {
     const void *logits;
-    int B, N, V, K, W;
+    int B, N, V, K, W, R;
+    bool all_nodes;            // rows = the drafted nodes (slot j = node j) instead of the commit rows
+    const int32_t *draft_tok;
     float c;
     const int32_t *commit_row, *commit_len;
     float *pr_m;          // [B*W]
@@ -946,11 +951,17 @@ __global__ __launch_bounds__(256) void commit_scan_kernel(CommitScanArgs a)
     __shared__ WaveScan wsh[4];
     __shared__ int part_cnt[4];
     const int j = blockIdx.x, b = blockIdx.y, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    int cl = a.commit_len[b];
-    cl = cl < 0 ? 0 : (cl > a.W ? a.W : cl);
-    if (j >= cl) return;
-    const int node = a.commit_row[(size_t)b * a.W + j];
-    if (node < 0 || node >= a.N) return;
+    int node;
+    if (a.all_nodes) {
+        if (a.draft_tok[(size_t)b * a.N + j] < 0) return;
+        node = j;
+    } else {
+        int cl = a.commit_len[b];
+        cl = cl < 0 ? 0 : (cl > a.W ? a.W : cl);
+        if (j >= cl) return;
+        node = a.commit_row[(size_t)b * a.W + j];
+        if (node < 0 || node >= a.N) return;
+    }
     const char *rowp = (const char *)a.logits + ((size_t)b * a.N + node) * (size_t)a.V * ES;
     WaveScan *ws = &wsh[wave];
     const WavePartial wp = wave_row_stream<DT>(rowp, a.V, a.c, a.K, ws, lane, wave, 4);
@@ -965,7 +976,7 @@ __global__ __launch_bounds__(256) void commit_scan_kernel(CommitScanArgs a)
     }
     __builtin_amdgcn_wave_barrier();
     wave_row_finish<DT>(rowp, a.V, a.K, ws, lane, cnt);
-    const size_t src = (size_t)b * a.W + j;
+    const size_t src = (size_t)b * a.R + j;
     if (lane < a.K) {
         a.pr_top_idx[src * a.K + lane] = (int32_t)rank_key_id(ws->top[lane]);
         a.pr_top_l[src * a.K + lane] = rank_key_value(ws->top[lane]);
@@ -988,7 +999,12 @@ struct MergeArgs {
     const int32_t *commit_row;        // [B][W] or NULL (then every j < len is valid)
     const int32_t *commit_len;        // [B]
     int N;
-    long long *rec_slot;              // [B*W*NO]
+    int R;                            // record slots per trajectory: W, or N in all-nodes mode
+    bool all_nodes;                   // record (b, j, n) observes drafted node j under its path's context
+    const int32_t *draft_tok;         // [B][N]
+    const int32_t *depth;             // [N]
+    const int32_t *recent;            // [B][N][kMaxOrder] recent[.][i]: token i positions before the end of node's sequence
+    long long *rec_slot;              // [B*R*NO]
     const int32_t *obs_idx;
     const float *obs_p;
     unsigned long long *stats;
@@ -1003,21 +1019,31 @@ __device__ __forceinline__ int clamp_len(int len, int W) { return len < 0 ? 0 : 
 __device__ __forceinline__ void merge_claim_record(const MergeArgs &a, int rec)
 {
     const int NO = a.omax - a.omin + 1;
-    if (rec >= a.B * a.W * NO) return;
+    if (rec >= a.B * a.R * NO) return;
     const int n = a.omin + rec % NO;
-    const int j = (rec / NO) % a.W;
-    const int b = rec / (NO * a.W);
+    const int j = (rec / NO) % a.R;
+    const int b = rec / (NO * a.R);
     long long slot_out = -1;
-    const int len = clamp_len(a.commit_len[b], a.W);
     const long long base_len = a.ctx_len[b];
-    bool valid = j < len && base_len + j >= n;
-    if (valid && a.commit_row) {
-        const int r = a.commit_row[(size_t)b * a.W + j];
-        valid = r >= 0 && r < a.N;
+    bool valid;
+    if (a.all_nodes) {
+        valid = a.draft_tok[(size_t)b * a.N + j] >= 0 && base_len + a.depth[j] >= n;
+    } else {
+        const int len = clamp_len(a.commit_len[b], a.W);
+        valid = j < len && base_len + j >= n;
+        if (valid && a.commit_row) {
+            const int r = a.commit_row[(size_t)b * a.W + j];
+            valid = r >= 0 && r < a.N;
+        }
     }
     if (valid) {
         int32_t key[kMaxOrder];
         for (int i = 0; i < n; ++i) {
+            if (a.all_nodes) {
+                // the last n tokens of context ++ path to node j, as the draft kernel left them
+                key[i] = a.recent[((size_t)b * a.N + j) * kMaxOrder + (n - 1 - i)];
+                continue;
+            }
             const int back = n - i;  // this token is `back` positions before token j
             // positions before j: commit tokens j-1, j-2, ... then the context tail
             key[i] = (back <= j) ? a.commit_tok[(size_t)b * a.W + (j - back)]
@@ -1057,12 +1083,13 @@ __global__ __launch_bounds__(kFinishThreads) void path_finish_kernel(PathArgs a,
         return;
     }
     __shared__ FinishShared sh;
-    const int j = (int)blockIdx.x % a.W, b = (int)blockIdx.x / a.W;
+    const int j = (int)blockIdx.x % a.R, b = (int)blockIdx.x / a.R;
     // Everything whose address depends on (b, j) only is requested at once: the partial sums and,
     // in verify mode, the stop record of the trajectory (used if this turns out to be its stop row).
     const int nseg = a.nseg;
-    const unsigned long long part = (wave == 0 && lane < nseg) ? a.seg_part[((size_t)b * a.W + j) * kSegMax + lane] : 0ull;
+    const unsigned long long part = (wave == 0 && lane < nseg) ? a.seg_part[((size_t)b * a.R + j) * kSegMax + lane] : 0ull;
     int len = 0, node, nch = 0, fc = -1;
+    bool stop = false;
     int32_t my_id = -1, ch = -1;
     float my_mu = 0.0f, my_l = 0.0f, m;
     if (a.mode == 0) {
@@ -1075,16 +1102,17 @@ __global__ __launch_bounds__(kFinishThreads) void path_finish_kernel(PathArgs a,
             my_id = a.stop_qid[(size_t)b * kMaxK + lane]; my_mu = a.stop_qmu[(size_t)b * kMaxK + lane];
             my_l = a.stop_ql[(size_t)b * kMaxK + lane]; ch = a.stop_child[(size_t)b * kMaxK + lane];
         }
-        node = j < len ? (j == len - 1 ? stop_node : a.out_node[(size_t)b * a.W + j]) : -1;
+        if (a.all_nodes) node = a.draft_tok[(size_t)b * a.N + j] >= 0 ? j : -1;
+        else node = j < len ? (j == len - 1 ? stop_node : a.out_node[(size_t)b * a.W + j]) : -1;
+        stop = node >= 0 && node == stop_node;
     } else {
-        node = commit_row_of(a, b, j);
+        node = a.all_nodes ? (a.draft_tok[(size_t)b * a.N + j] >= 0 ? j : -1) : commit_row_of(a, b, j);
         m = 0.0f;
     }
     if (node < 0) return;  // block-uniform
-    const bool stop = a.mode == 0 && j == len - 1;
     if (!stop && wave != 0) return;
     const int row = b * a.N + node;
-    const int src = a.mode == 0 ? row : b * a.W + j;
+    const int src = a.mode == 0 ? row : b * a.R + j;
     const char *rowp = (const char *)a.logits + (size_t)row * (size_t)a.V * ES;
     if (!stop) m = a.src_m[src];
     const RowGeom g = row_geom<DT>(rowp, a.V);
@@ -1109,8 +1137,8 @@ __global__ __launch_bounds__(kFinishThreads) void path_finish_kernel(PathArgs a,
         if (!stop) {
             // observation of this row (paper Sec. 4.1: top-k ids and probabilities)
             if (lane < a.K) {
-                a.obs_idx[((size_t)b * a.W + j) * a.K + lane] = o_idx;
-                a.obs_p[((size_t)b * a.W + j) * a.K + lane] = exact_exp2(scaled_offset(o_l, m, a.c)) / s;
+                a.obs_idx[((size_t)b * a.R + j) * a.K + lane] = o_idx;
+                a.obs_p[((size_t)b * a.R + j) * a.K + lane] = exact_exp2(scaled_offset(o_l, m, a.c)) / s;
             }
             return;
         }
@@ -1131,8 +1159,8 @@ __global__ __launch_bounds__(kFinishThreads) void path_finish_kernel(PathArgs a,
         }
         // the stop row's observation (its loads have had the replay to arrive)
         if (lane < a.K) {
-            a.obs_idx[((size_t)b * a.W + j) * a.K + lane] = o_idx;
-            a.obs_p[((size_t)b * a.W + j) * a.K + lane] = exact_exp2(scaled_offset(o_l, m, a.c)) / s;
+            a.obs_idx[((size_t)b * a.R + j) * a.K + lane] = o_idx;
+            a.obs_p[((size_t)b * a.R + j) * a.K + lane] = exact_exp2(scaled_offset(o_l, m, a.c)) / s;
         }
         // ---- integer masses (unit 2^-40 / s * rho): support token i weighs floor(r_i * (S / rho)),
         // a token outside the support the term it contributes to S
@@ -1288,7 +1316,7 @@ __global__ __launch_bounds__(64) void merge_apply_kernel(MergeArgs a)
     __shared__ int32_t l_id[2 * kMaxK];
     __shared__ float l_val[2 * kMaxK];
     const int NO = a.omax - a.omin + 1;
-    const int nrec = a.B * a.W * NO;
+    const int nrec = a.B * a.R * NO;
     const int rec = blockIdx.x;
     const int lane = threadIdx.x;
     const int K = a.K;
@@ -1407,6 +1435,7 @@ struct DraftArgs {
     int32_t *out_tok;  // caller's copy, may be NULL
     unsigned long long *stats;
     int mode;          // 0: Gumbel-Top-K, 1: sequential multinomial without replacement, 2: largest means
+    int32_t *recent_out;  // [B][N][kMaxOrder] or NULL: the recent tokens of every drafted node (all-nodes update)
 };
 
 constexpr int kDraftThreads = 1024;  // 16 waves: the nodes of a tree level are looked up side by side
@@ -1584,6 +1613,9 @@ __global__ __launch_bounds__(kDraftThreads) void draft_kernel(DraftArgs a)
         a.draft_tok[(size_t)b * N + u] = tok[u];
         if (a.out_tok) a.out_tok[(size_t)b * N + u] = tok[u];
     }
+    if (a.recent_out)
+        for (int i = tid; i < N * kMaxOrder; i += kDraftThreads)
+            if (tok[i / kMaxOrder] >= 0) a.recent_out[(size_t)b * N * kMaxOrder + i] = recent[i / kMaxOrder][i % kMaxOrder];
 }
 
 // small helpers --------------------------------------------------------------------------------

@@ -30,6 +30,8 @@ struct stand_handle {
     int32_t *obs_idx;
     float *obs_p;
     long long *rec_slot;
+    int R;            // row / record slots per trajectory: W, or N with STAND_UPDATE_ALL_NODES
+    int32_t *recent;  // [B][N][kMaxOrder], all-nodes mode only
     unsigned long long *seg_part, *node_count, *anc;  // anc: [N][anc_words] ancestor-or-self bit sets
     int anc_words;
     int32_t *stop_i, *stop_qid, *stop_child;
@@ -78,7 +80,7 @@ static void free_all(stand_handle *h)
     if (!h) return;
     void *ptrs[] = {h->d_tree, h->table, h->ctx_tail, h->ctx_len, h->draft_tok, h->draft_has, h->draft_qid, h->draft_qmu,
                     h->row_m, h->row_s, h->top_l, h->top_p, h->top_idx, h->outcome, h->obs_idx, h->obs_p, h->rec_slot,
-                    h->seg_part, h->node_count, h->anc, h->stop_i, h->stop_qid, h->stop_child, h->stop_m, h->stop_qmu, h->stop_ql, h->pr_m, h->pr_top_l, h->pr_top_idx, h->stats, h->counter};
+                    h->recent, h->seg_part, h->node_count, h->anc, h->stop_i, h->stop_qid, h->stop_child, h->stop_m, h->stop_qmu, h->stop_ql, h->pr_m, h->pr_top_l, h->pr_top_idx, h->stats, h->counter};
     for (void *p : ptrs) (void)hipFree(p);
     for (hipEvent_t e : h->ev_begin) (void)hipEventDestroy(e);
     for (hipEvent_t e : h->ev_end) (void)hipEventDestroy(e);
@@ -99,11 +101,13 @@ extern "C" int stand_create(const stand_config *cfg, stand_handle **out)
     if (cfg->table_capacity < 16 || (cfg->table_capacity & (cfg->table_capacity - 1))) return STAND_EINVAL;
     if (cfg->max_probe < 1) return STAND_EINVAL;
     if (cfg->logits_dtype != STAND_BF16 && cfg->logits_dtype != STAND_F32) return STAND_EINVAL;
-    if (cfg->update_mode != STAND_UPDATE_ACCEPTED_PATH) return STAND_EINVAL;
+    if (cfg->update_mode != STAND_UPDATE_ACCEPTED_PATH && cfg->update_mode != STAND_UPDATE_ALL_NODES) return STAND_EINVAL;
     if (cfg->draft_mode < STAND_DRAFT_GUMBEL_TOPK || cfg->draft_mode > STAND_DRAFT_DETERMINISTIC) return STAND_EINVAL;
     if ((int64_t)cfg->max_batch * N * (int64_t)cfg->vocab >= ((int64_t)1 << 40)) return STAND_EINVAL;
     // merge records are numbered in 23 bits (kTagMax); max_batch * tree depth * orders stays far below
-    if ((int64_t)cfg->max_batch * (kMaxDepth + 1) * STAND_MAX_ORDER > (int64_t)kTagMax) return STAND_EINVAL;
+    if ((int64_t)cfg->max_batch * (cfg->update_mode == STAND_UPDATE_ALL_NODES ? (int64_t)N : (int64_t)(kMaxDepth + 1)) * STAND_MAX_ORDER >
+        (int64_t)kTagMax)
+        return STAND_EINVAL;
     int ndev = 0;
     if (hipGetDeviceCount(&ndev) != hipSuccess || cfg->device < 0 || cfg->device >= ndev) return STAND_EINVAL;
 
@@ -139,12 +143,13 @@ extern "C" int stand_create(const stand_config *cfg, stand_handle **out)
     if (!ok || h->D > STAND_MAX_DEPTH) { delete h; return STAND_EINVAL; }
     h->cfg.tree_parent = nullptr;
     h->W = h->D + 1;
+    h->R = cfg->update_mode == STAND_UPDATE_ALL_NODES ? N : h->W;
     h->level_start.assign(h->D + 2, N);
     for (int u = N - 1; u >= 0; --u) h->level_start[h->depth[u]] = u;
 
     if (hipSetDevice(cfg->device) != hipSuccess) { delete h; return STAND_EHIP; }
     const size_t B = h->B, rows = B * N;
-    const size_t nrec = B * h->W * h->NO;
+    const size_t nrec = B * h->R * h->NO;
     hipError_t e = hipSuccess;
     auto acc = [&](hipError_t x) { if (e == hipSuccess) e = x; };
     acc(dmalloc(&h->d_tree, 4 * (size_t)N + h->D + 2));
@@ -156,15 +161,16 @@ extern "C" int stand_create(const stand_config *cfg, stand_handle **out)
     acc(dmalloc(&h->row_m, rows)); acc(dmalloc(&h->row_s, rows));
     acc(dmalloc(&h->top_l, rows * K)); acc(dmalloc(&h->top_p, rows * K)); acc(dmalloc(&h->top_idx, rows * K));
     acc(dmalloc(&h->outcome, rows));
-    acc(dmalloc(&h->obs_idx, B * h->W * K)); acc(dmalloc(&h->obs_p, B * h->W * K));
+    acc(dmalloc(&h->obs_idx, B * h->R * K)); acc(dmalloc(&h->obs_p, B * h->R * K));
     acc(dmalloc(&h->rec_slot, nrec));
-    acc(dmalloc(&h->seg_part, B * h->W * kSegMax));
+    acc(dmalloc(&h->seg_part, B * h->R * kSegMax));
+    acc(dmalloc(&h->recent, rows * kMaxOrder));
     acc(dmalloc(&h->node_count, (size_t)N));
     h->anc_words = (N + 63) / 64;
     acc(dmalloc(&h->anc, (size_t)N * h->anc_words));
     acc(dmalloc(&h->stop_i, B * 4)); acc(dmalloc(&h->stop_m, B)); acc(dmalloc(&h->stop_qid, B * kMaxK));
     acc(dmalloc(&h->stop_qmu, B * kMaxK)); acc(dmalloc(&h->stop_ql, B * kMaxK)); acc(dmalloc(&h->stop_child, B * kMaxK));
-    acc(dmalloc(&h->pr_m, B * h->W)); acc(dmalloc(&h->pr_top_l, B * h->W * K)); acc(dmalloc(&h->pr_top_idx, B * h->W * K));
+    acc(dmalloc(&h->pr_m, B * h->R)); acc(dmalloc(&h->pr_top_l, B * h->R * K)); acc(dmalloc(&h->pr_top_idx, B * h->R * K));
     acc(dmalloc(&h->stats, (size_t)kStatCount));
     acc(dmalloc(&h->counter, 1));
     if (e != hipSuccess) { free_all(h); return e == hipErrorOutOfMemory ? STAND_ENOMEM : STAND_EHIP; }
@@ -302,6 +308,8 @@ static MergeArgs merge_args(stand_handle *h, const int32_t *commit_tok, const in
     MergeArgs a;
     a.table = h->table; a.mask = h->cfg.table_capacity - 1; a.slot_bytes = h->slot_bytes; a.K = h->K;
     a.max_probe = h->cfg.max_probe; a.B = h->B; a.W = h->W; a.omin = h->cfg.order_min; a.omax = h->cfg.order_max;
+    a.R = h->R; a.all_nodes = h->cfg.update_mode == STAND_UPDATE_ALL_NODES; a.draft_tok = h->draft_tok;
+    a.depth = tree_dev(h).depth; a.recent = h->recent;
     a.ctx_tail = h->ctx_tail; a.ctx_len = h->ctx_len; a.commit_tok = commit_tok; a.commit_row = commit_row;
     a.commit_len = commit_len; a.N = h->N; a.rec_slot = h->rec_slot; a.obs_idx = h->obs_idx; a.obs_p = h->obs_p;
     a.stats = h->stats;
@@ -318,14 +326,16 @@ static int launch_path_pass(stand_handle *h, uint64_t step, const void *d_logits
     if (mode == 1) {
         CommitScanArgs c;
         c.logits = d_logits; c.B = h->B; c.N = h->N; c.V = h->V; c.K = h->K; c.W = h->W; c.c = h->c;
+        c.R = h->R; c.all_nodes = h->cfg.update_mode == STAND_UPDATE_ALL_NODES; c.draft_tok = h->draft_tok;
         c.commit_row = commit_row; c.commit_len = commit_len;
         c.pr_m = h->pr_m; c.pr_top_idx = h->pr_top_idx; c.pr_top_l = h->pr_top_l;
-        const dim3 grid((unsigned)h->W, (unsigned)h->B);
+        const dim3 grid((unsigned)h->R, (unsigned)h->B);
         if (bf16) commit_scan_kernel<kDtBf16><<<grid, dim3(256), 0, s>>>(c);
         else commit_scan_kernel<kDtF32><<<grid, dim3(256), 0, s>>>(c);
     }
     PathArgs a;
     a.logits = d_logits; a.B = h->B; a.N = h->N; a.V = h->V; a.K = h->K; a.W = h->W; a.mode = mode; a.c = h->c;
+    a.R = h->R; a.all_nodes = h->cfg.update_mode == STAND_UPDATE_ALL_NODES;
     a.seed = h->cfg.seed; a.step = step; a.tree = tree_dev(h);
     a.draft_tok = h->draft_tok; a.draft_has = h->draft_has; a.draft_qid = h->draft_qid; a.draft_qmu = h->draft_qmu;
     a.src_m = mode == 0 ? h->row_m : h->pr_m;
@@ -342,9 +352,9 @@ static int launch_path_pass(stand_handle *h, uint64_t step, const void *d_logits
     // one more block per (row, trajectory) slot for the outputs and the stop record
     const int row_vectors = (int)(((size_t)h->V * (bf16 ? 2 : 4) + 15) / 16);
     a.nseg = clampi((row_vectors + 4 * kPathThreads - 1) / (4 * kPathThreads), 1, kSegMax);
-    const dim3 g1((unsigned)a.nseg + 1, (unsigned)h->W, (unsigned)h->B), block(kPathThreads);
-    const int finish_blocks = h->B * h->W;
-    const int claim_blocks = claim ? (h->B * h->W * h->NO + kFinishThreads - 1) / kFinishThreads : 0;
+    const dim3 g1((unsigned)a.nseg + 1, (unsigned)h->R, (unsigned)h->B), block(kPathThreads);
+    const int finish_blocks = h->B * h->R;
+    const int claim_blocks = claim ? (h->B * h->R * h->NO + kFinishThreads - 1) / kFinishThreads : 0;
     const MergeArgs mg = claim ? *claim : merge_args(h, nullptr, nullptr, nullptr);
     const dim3 g2((unsigned)(finish_blocks + claim_blocks));
     if (bf16) {
@@ -361,7 +371,7 @@ static int launch_path_pass(stand_handle *h, uint64_t step, const void *d_logits
 // applies the records whose slots the path pass claimed
 static int launch_merge_apply(stand_handle *h, const MergeArgs &a, bool append_ctx, hipStream_t s)
 {
-    const int nrec = h->B * h->W * h->NO;
+    const int nrec = h->B * h->R * h->NO;
     merge_apply_kernel<<<dim3((unsigned)nrec), dim3(64), 0, s>>>(a);
     if (append_ctx)
         ctx_append_kernel<<<dim3((unsigned)((h->B + 63) / 64)), dim3(64), 0, s>>>(h->B, h->W, h->ctx_tail, h->ctx_len,
@@ -381,6 +391,7 @@ static int launch_draft(stand_handle *h, uint64_t step, int32_t *d_draft_tok, co
     a.ctx_tail = h->ctx_tail; a.ctx_len = h->ctx_len; a.append_tok = append_tok; a.append_len = append_len;
     a.draft_tok = h->draft_tok; a.draft_has = h->draft_has; a.draft_qid = h->draft_qid; a.draft_qmu = h->draft_qmu;
     a.out_tok = d_draft_tok; a.stats = h->stats; a.mode = h->cfg.draft_mode;
+    a.recent_out = h->cfg.update_mode == STAND_UPDATE_ALL_NODES ? h->recent : nullptr;
     draft_kernel<<<dim3((unsigned)h->B), dim3(kDraftThreads), 0, s>>>(a);
     HIP_TRY(h, hipGetLastError());
     return STAND_OK;

@@ -40,6 +40,9 @@ def _say(msg):
     ("cfg3", dict(V=5000, B=4, rho=0.8, draft_mode=2), 25, "step", True),      # deterministic drafting, one-hot proposals
     ("cfg1", dict(V=600, B=3, rho=0.6, draft_mode=2), 40, "separate", False),  # deterministic, closed loop
     ("cfg1", dict(V=600, B=3, rho=0.6, draft_mode=1), 40, "separate", False),  # multinomial, closed loop
+    ("cfg3", dict(V=5000, B=4, rho=0.8, update_mode=1), 25, "step", True),     # every drafted node's row is merged
+    ("cfg1", dict(V=900, B=3, rho=0.7, update_mode=1), 40, "separate", True),  # the same through stand_update
+    ("cfg5", dict(V=3000, B=2, rho=0.8, update_mode=1), 10, "step", False),    # 128 nodes, K=32, closed loop
 ])
 def test_lockstep_small(gpu, name, over, steps, mode, forced):
     binding, lockstep = gpu
