@@ -29,14 +29,17 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0
 
 
+PEAK = 8.0  # height of the peaked tokens above the noise (--peak)
+
+
 def gen_logits(torch, w, step, draft_tok_host, gen):
-    """[B, N, V] bf16 logits on the GPU: N(0, 3) noise plus +8 on each row's peaked tokens."""
+    """[B, N, V] bf16 logits on the GPU: N(0, 3) noise plus +PEAK on each row's peaked tokens."""
     import numpy as np
     peaks = w.peaks(step, draft_tok_host)                      # [B, N, 4] int64, -1 = none
     x = torch.randn((w.B, w.N, w.V), generator=gen, device="cuda", dtype=torch.float32)
     x.mul_(3.0 ** 0.5)
     pk = torch.from_numpy(peaks).cuda()
-    add = torch.where(pk >= 0, torch.full(pk.shape, 8.0, device="cuda"), torch.zeros(pk.shape, device="cuda"))
+    add = torch.where(pk >= 0, torch.full(pk.shape, PEAK, device="cuda"), torch.zeros(pk.shape, device="cuda"))
     x.scatter_add_(2, pk.clamp(min=0), add)
     return x.to(torch.bfloat16).contiguous()
 
@@ -63,6 +66,12 @@ def main():
                     help="0 Gumbel-Top-K (the method), 1 sequential multinomial, 2 deterministic (the paper's ablation)")
     ap.add_argument("--update-mode", type=int, default=0,
                     help="0 merge the accepted path's rows (the paper), 1 merge every drafted node's row (table stress)")
+    ap.add_argument("--peak", type=float, default=8.0,
+                    help="logit height of the peaked tokens (BASELINE: +8, p about 0.23 each); higher peaks give "
+                         "sharper targets, longer acceptance and deeper drafts")
+    ap.add_argument("--max-peaks", type=int, default=4,
+                    help="each row peaks on 1..max-peaks tokens (BASELINE: 1-4); 1 with a high --peak models a confident "
+                         "target, where acceptance follows the quality of the drafts")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run a plain copy of one logits tensor (known HBM traffic) for counter calibration")
     args = ap.parse_args()
@@ -74,6 +83,8 @@ def main():
     import numpy as np
     import torch
     from paper_2506_04708_amd import binding, synth
+    global PEAK
+    PEAK = args.peak
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     K_steps, W_steps, T_warm = args.steps, args.warmup, args.table_warm
@@ -86,7 +97,7 @@ def main():
         w = synth.Workload(None, run_steps=total + 2, **cfg)
     else:
         cfg = synth.CONFIGS[args.workload]
-        w = synth.Workload(args.workload, run_steps=total + 2)
+        w = synth.Workload(args.workload, run_steps=total + 2, max_peaks=args.max_peaks)
     dt = binding.STAND_BF16 if w.dtype == "bf16" else binding.STAND_F32
     assert w.dtype == "bf16"
     mk = lambda: binding.Stand(w.V, w.B, cfg["order_min"], cfg["order_max"], w.K, w.parent, w.T, cfg["capacity"], 64,
@@ -230,7 +241,7 @@ def main():
                                "for %d steps" % (args.workload, w.B, w.V, w.N, w.D, cfg["order_min"], cfg["order_max"], w.K,
                                                  w.T, cfg["capacity"], T_warm),
                    "draft_mode": ["gumbel_topk", "multinomial", "deterministic"][args.draft_mode],
-                   "update_mode": ["accepted_path", "all_nodes"][args.update_mode],
+                   "update_mode": ["accepted_path", "all_nodes"][args.update_mode], "peak": args.peak, "max_peaks": args.max_peaks,
                    "acceptance_len": round(acc_len, 3), "table_entries": int(entries0 + st.inserts)},
         "hbm_gbps_algorithmic": round(step_bytes * steps_per_s / 1e9, 1),
         "hbm_frac_of_peak": round(step_bytes * steps_per_s / 1e9 / HBM_PEAK_GBPS, 4),

@@ -139,7 +139,10 @@ int stand_draft(stand_handle *h, uint64_t step, int32_t *d_draft_tok, void *stre
  * U < r(x) / w(x) with r the residual target and w the proposal renormalised over the
  * children not yet rejected; on rejection r <- norm(max(0, r - w)).  An accepted child
  * becomes the current node.  When no child is accepted (or there is none) one token is drawn
- * from the residual of the current node and the walk stops.
+ * from the residual of the current node -- the position floor(u T / 2^64) in the residual's
+ * cumulative integer mass T, u = 64 counter-based random bits of (trajectory, step, node) --
+ * and the walk stops.  Each node on the accepted path adds 1 to its acceptance counter
+ * (stand_get_node_counts).
  * Outputs: d_out_tok [B][D+1] emitted tokens, d_out_node [B][D+1] the tree node whose logits
  * row produced each of them (root, then the accepted nodes), d_out_len [B] in 1..D+1; unused
  * entries are -1.  Handle state (table, contexts) is not changed. */

@@ -188,8 +188,8 @@ def bf16_bits_to_f32(b):
     return (np.ascontiguousarray(b, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)
 
 
-def peaked_tokens(seed, step, b, parent, depth, first_child, nchild, draft_tok, stream_next, V):
-    """For every tree node of trajectory b: the 1..4 token ids that receive the +8 peak.
+def peaked_tokens(seed, step, b, parent, depth, first_child, nchild, draft_tok, stream_next, V, max_peaks=4):
+    """For every tree node of trajectory b: the 1..max_peaks token ids that receive the +8 peak.
 
     Order of preference: the stream's next token when the node's path matches the stream,
     then the node's drafted children in rank order, then hash-chosen fillers.  stream_next
@@ -205,7 +205,7 @@ def peaked_tokens(seed, step, b, parent, depth, first_child, nchild, draft_tok, 
         on_stream[u] = (on_stream[parent[u]] and draft_tok[u] >= 0 and d - 1 < len(stream_next)
                         and int(draft_tok[u]) == int(stream_next[d - 1]))
     for u in range(N):
-        r = 1 + int(_h(seed, step, b, u, 77) % np.uint64(4))
+        r = 1 + int(_h(seed, step, b, u, 77) % np.uint64(max_peaks))
         cand = []
         d = depth[u]
         if on_stream[u] and d < len(stream_next):
@@ -275,7 +275,7 @@ class Workload:
         for b in range(self.B):
             nxt = self.streams[b, self.pos[b] + 1: self.pos[b] + self.D + 3]
             out[b] = peaked_tokens(self.seed, step, b, self.parent, self.depth, self.first_child, self.nchild,
-                                   draft_tok[b], nxt, self.V)
+                                   draft_tok[b], nxt, self.V, self.cfg.get("max_peaks", 4))
         return out
 
     def logits(self, step, draft_tok):
