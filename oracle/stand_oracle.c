@@ -361,9 +361,11 @@ int so_gumbel_topk(const int32_t *ids, const float *mu, int K, int c, const floa
     return w;
 }
 
+static float support_sum(const float *x, int K);
+
 /* Sequential sampling without replacement (the "basic stochastic drafting" of Table 5): draw j
  * picks among the candidates not drawn yet with probability proportional to mu.  z = sum of the
- * remaining mu in stored order; t = U_j * z; the pick is the first remaining candidate, in stored
+ * remaining mu (support_sum's order); t = U_j * z; the pick is the first remaining candidate, in stored
  * order, whose running sum exceeds t (the last remaining one if rounding leaves none).  Same law
  * as Gumbel-Top-K (Plackett-Luce). */
 int so_multinomial_wor(const int32_t *ids, const float *mu, int K, int c, const float *U /* [c] */,
@@ -374,8 +376,9 @@ int so_multinomial_wor(const int32_t *ids, const float *mu, int K, int c, const 
     for (int i = 0; i < K; ++i) { left[i] = mu[i] > 0.0f; n += left[i]; }
     int w = c < n ? c : n;
     for (int j = 0; j < w; ++j) {
-        float z = 0.0f;
-        for (int i = 0; i < K; ++i) if (left[i]) z = z + mu[i];
+        float rest[SO_MAX_K];
+        for (int i = 0; i < K; ++i) rest[i] = left[i] ? mu[i] : 0.0f;
+        float z = support_sum(rest, K);
         float t = U[j] * z;
         float a = 0.0f;
         int pick = -1, last = -1;
@@ -431,11 +434,17 @@ typedef struct {
     int near_threshold; /* |omega - r/w| < 1e-6 on some round */
 } so_node_state;
 
+/* Sum over the support as a balanced pairwise tree on SO_MAX_K slots (absent slots are +0):
+ * neighbours first, then groups of 4, 8, 16, 32 -- one binary32 rounding per addition.  The
+ * order is part of the numeric contract (any fixed order would do for the method; this one
+ * needs log2 steps on a machine that adds in parallel). */
 static float support_sum(const float *x, int K)
 {
-    float t = 0.0f;
-    for (int i = 0; i < K; ++i) t = t + x[i];
-    return t;
+    float t[SO_MAX_K];
+    for (int i = 0; i < SO_MAX_K; ++i) t[i] = i < K ? x[i] : 0.0f;
+    for (int n = SO_MAX_K; n > 1; n /= 2)
+        for (int i = 0; i < n / 2; ++i) t[i] = t[2 * i] + t[2 * i + 1];
+    return t[0];
 }
 
 /* onehot != 0 (deterministic drafting, Sec. 3.1): the proposal of round j is the one-hot vector

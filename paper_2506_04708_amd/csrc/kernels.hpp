@@ -112,23 +112,23 @@ __device__ __forceinline__ float fast_exp2(float y) { return __builtin_amdgcn_ex
 // Returns the rank of the accepted child or -1.  With track_err the values r are taken to
 // carry a relative error of at most eps and `near` reports a test that the error could flip.
 // ---------------------------------------------------------------------------------------------
-// Sum of the values of lanes 0..K-1 in lane order (one rounding per addition), the same in
-// every lane.
-__device__ __forceinline__ float wave_ordered_sum(float x, int K)
+// Sum of the values of lanes 0..31 as a balanced pairwise tree: (x0 + x1) + (x2 + x3), then
+// groups of 4, 8, 16 and finally the two rows of 16 lanes -- one rounding per addition, the
+// same in every lane.  Lanes K..31 must hold +0.  Data-parallel-primitive moves only (no LDS).
+template <int CTRL>
+__device__ __forceinline__ float dpp_fetch_f32(float x)
 {
-    float t = 0.0f;
-    for (int i = 0; i < K; ++i) t = t + u2f((uint32_t)__builtin_amdgcn_readlane((int)f2u(x), i));
-    return t;
+    return u2f((uint32_t)__builtin_amdgcn_update_dpp(0, (int)f2u(x), CTRL, 0xF, 0xF, true));
 }
-// two such sums at once (independent chains)
-__device__ __forceinline__ void wave_ordered_sum2(float x, float y, int K, float &sx, float &sy)
+__device__ __forceinline__ float wave_tree_sum(float x)
 {
-    float t = 0.0f, v = 0.0f;
-    for (int i = 0; i < K; ++i) {
-        t = t + u2f((uint32_t)__builtin_amdgcn_readlane((int)f2u(x), i));
-        v = v + u2f((uint32_t)__builtin_amdgcn_readlane((int)f2u(y), i));
-    }
-    sx = t; sy = v;
+    x = x + dpp_fetch_f32<0xB1>(x);   // quad_perm [1,0,3,2]: neighbours
+    x = x + dpp_fetch_f32<0x4E>(x);   // quad_perm [2,3,0,1]: pairs of pairs
+    x = x + dpp_fetch_f32<0x141>(x);  // row_half_mirror: the two quads of 8 lanes
+    x = x + dpp_fetch_f32<0x140>(x);  // row_mirror: the two halves of a row of 16
+    const float lo = u2f((uint32_t)__builtin_amdgcn_readlane((int)f2u(x), 0));
+    const float hi = u2f((uint32_t)__builtin_amdgcn_readlane((int)f2u(x), 16));
+    return lo + hi;
 }
 
 // 64-bit key of lane i (i uniform)
@@ -155,7 +155,7 @@ __device__ __forceinline__ NodeResult wave_node_outcome(int lane, int K, int32_t
     if (lane >= nchild) ch = -1;
     const float om_l = lane < nchild ? uniform(seed, b, step, (uint32_t)(first_child + lane), 0u, kStreamAccept) : 0.0f;
     float w = (act && my_mu > 0.0f) ? my_mu : 0.0f;
-    float zw = wave_ordered_sum(w, K);
+    float zw = wave_tree_sum(w);
     w = zw > 0.0f ? w / zw : 0.0f;
     float r = act ? my_p : 0.0f;
     float rho = 1.0f;
@@ -177,8 +177,7 @@ __device__ __forceinline__ NodeResult wave_node_outcome(int lane, int K, int32_t
         if (lhs < ri) { res.accepted = j; break; }
         const float mn = act ? (r < w ? r : w) : 0.0f;
         const float w_next = lane == i ? 0.0f : w;  // the rejected token leaves the proposal
-        float M, zw2;
-        wave_ordered_sum2(mn, w_next, K, M, zw2);
+        const float M = wave_tree_sum(mn), zw2 = wave_tree_sum(w_next);
         float Z = 1.0f - M;
         if (!(Z > 1e-30f)) Z = 1e-30f;
         float d = r - w;
@@ -1154,7 +1153,7 @@ __global__ __launch_bounds__(kFinishThreads) void path_finish_kernel(PathArgs a,
             if (lane == 0 && nr.accepted != -1) atomicAdd(&a.stats[kStatMismatch], 1ull);  // the stop node rejects all
             // a residual that is not a distribution any more (the normalising mass underflowed)
             // is not used
-            const float rs = wave_ordered_sum(my_r, a.K);
+            const float rs = wave_tree_sum(my_r);
             if (!(rs <= 2.0f) || !(rho < __builtin_inff())) support = false;
         }
         // the stop row's observation (its loads have had the replay to arrive)
@@ -1257,7 +1256,16 @@ __global__ __launch_bounds__(kFinishThreads) void path_finish_kernel(PathArgs a,
         }
     };
     uint4 w0 = make_uint4(0, 0, 0, 0), w1 = w0, w2 = w0, w3 = w0;  // the last round's vectors are kept
-    if (r0 < r1)
+    unsigned long long f1[EPV];  // cpt == 1 (the usual case): the masses of this thread's only vector are kept
+#pragma unroll
+    for (int q = 0; q < EPV; ++q) f1[q] = 0ull;
+    if (cpt == 1) {
+        if (r0 < r1) {
+            vector_masses<DT>(g.vp[r0], g.head + r0 * EPV, m, a.c, sh, f1);
+#pragma unroll
+            for (int q = 0; q < EPV; ++q) mine += f1[q];
+        }
+    } else if (r0 < r1)
         for (int base = r0; base < r1; base += 4) {
             w0 = g.vp[base < rlast ? base : rlast];
             w1 = g.vp[base + 1 < rlast ? base + 1 : rlast];
@@ -1288,6 +1296,15 @@ __global__ __launch_bounds__(kFinishThreads) void path_finish_kernel(PathArgs a,
             }
         };
         const bool single_round = r1 - r0 <= 4;  // then w0..w3 still hold this thread's whole run
+        if (cpt == 1) {
+#pragma unroll
+            for (int q = 0; q < EPV; ++q) {
+                if (token < 0) {
+                    if (left < f1[q]) token = g.head + r0 * EPV + q;
+                    else left -= f1[q];
+                }
+            }
+        } else
         for (int base = r0; base < r1 && token < 0; base += 4) {
             if (!single_round) {
                 w0 = g.vp[base < rlast ? base : rlast];
@@ -1567,7 +1584,7 @@ __global__ __launch_bounds__(kDraftThreads) void draft_kernel(DraftArgs a)
                 const int draws = nch < ncand_all ? nch : ncand_all;
                 for (int j = 0; j < draws; ++j) {
                     const float mleft = left ? mu : 0.0f;
-                    const float z = wave_ordered_sum(mleft, K);
+                    const float z = wave_tree_sum(mleft);
                     const float t = u2f((uint32_t)__builtin_amdgcn_readlane((int)f2u(u_l), j)) * z;
                     float acc = 0.0f;
                     int pick = -1, last = -1;
