@@ -330,11 +330,19 @@ static uint64_t fmix64(uint64_t h)
     return h;
 }
 
+/* h = fmix64(n * C + sum_i M_i * (x_i + 1)) with x_i the token i positions before the end of the
+ * key (x_0 = newest) and M_0..M_7 fixed odd multipliers; 0 is mapped to 1.  The terms do not
+ * depend on each other, and keys that share their newest tokens share their first terms. */
+static const uint64_t fp_mult[SO_MAX_ORDER] = {
+    0x9E3779B97F4A7C15ULL, 0xC2B2AE3D27D4EB4FULL, 0x165667B19E3779F9ULL, 0xD6E8FEB86659FD93ULL,
+    0xA0761D6478BD642FULL, 0xE7037ED1A0B428DBULL, 0x8EBC6AF09C88C6E3ULL, 0x589965CC75374CC3ULL};
+
 uint64_t so_fingerprint(int n, const int32_t *tokens)
 {
-    uint64_t h = (uint64_t)n;
+    uint64_t acc = (uint64_t)n * 0x2545F4914F6CDD1DULL;
     for (int i = 0; i < n; ++i)
-        h = fmix64((h + 0x9E3779B97F4A7C15ULL) ^ (uint64_t)(uint32_t)tokens[i]);
+        acc += fp_mult[i] * ((uint64_t)(uint32_t)tokens[n - 1 - i] + 1u);
+    uint64_t h = fmix64(acc);
     return h ? h : 1;
 }
 

@@ -1512,11 +1512,7 @@ __global__ __launch_bounds__(kDraftThreads) void draft_kernel(DraftArgs a)
             unsigned long long fp = 0ull;
             if (lane < NO) {
                 const int n = a.omax - lane;
-                if (clen + d >= n) {
-                    int32_t key[kMaxOrder];
-                    for (int i = 0; i < n; ++i) key[i] = recent[u][n - 1 - i];
-                    fp = fingerprint(n, key);
-                }
+                if (clen + d >= n) fp = fingerprint_newest_first(n, recent[u]);
             }
             unsigned long long home_fp = 0ull;
             uint32_t home_cnt = 0;
@@ -1555,7 +1551,7 @@ __global__ __launch_bounds__(kDraftThreads) void draft_kernel(DraftArgs a)
                 continue;
             }
             const int win = __ffsll((long long)hits) - 1;  // lowest lane = longest order
-            const long long slot = __shfl(hit_slot, win);
+            const long long slot = (long long)readlane_u64((unsigned long long)hit_slot, win);
             const unsigned long long win_fp = readlane_u64(fp, win);
             if (lane == 0) atomicAdd(&a.stats[kStatHits + (a.omax - win)], 1ull);
             int32_t id = -1;
@@ -1611,8 +1607,9 @@ __global__ __launch_bounds__(kDraftThreads) void draft_kernel(DraftArgs a)
                         key = rank_key(exact_log(mu) - g, (uint32_t)id);
                     }
                 }
-                rank = 0;
-                for (int q = 0; q < K; ++q) rank += readlane_u64(key, q) > key ? 1 : 0;
+                rank = 0;  // lanes without a candidate hold key 0, which is above no key
+#pragma unroll
+                for (int q = 0; q < kMaxK; ++q) rank += readlane_u64(key, q) > key ? 1 : 0;
             }
             if (cand && rank < nch) {
                 const int child = t_first[u] + rank;

@@ -136,11 +136,31 @@ __host__ __device__ inline uint64_t fmix64(uint64_t h)
     h ^= h >> 33;
     return h;
 }
+// Key fingerprint: fmix64(n * C + sum_i M_i * (x_i + 1)), x_i = the token i positions before the
+// end of the key (x_0 = newest); 0 is mapped to 1.  The terms are independent of each other.
+__host__ __device__ inline uint64_t fingerprint_multiplier(int i)
+{
+    constexpr uint64_t m[kMaxOrder] = {0x9E3779B97F4A7C15ULL, 0xC2B2AE3D27D4EB4FULL, 0x165667B19E3779F9ULL,
+                                       0xD6E8FEB86659FD93ULL, 0xA0761D6478BD642FULL, 0xE7037ED1A0B428DBULL,
+                                       0x8EBC6AF09C88C6E3ULL, 0x589965CC75374CC3ULL};
+    return m[i];
+}
+// newest_first[i] = token i positions before the end of the key
+__host__ __device__ inline uint64_t fingerprint_newest_first(int n, const int32_t *newest_first)
+{
+    uint64_t acc = (uint64_t)n * 0x2545F4914F6CDD1DULL;
+#pragma unroll
+    for (int i = 0; i < kMaxOrder; ++i)
+        if (i < n) acc += fingerprint_multiplier(i) * ((uint64_t)(uint32_t)newest_first[i] + 1u);
+    const uint64_t h = fmix64(acc);
+    return h ? h : 1;
+}
 // tokens[0..n) oldest first
 __host__ __device__ inline uint64_t fingerprint(int n, const int32_t *tokens)
 {
-    uint64_t h = (uint64_t)n;
-    for (int i = 0; i < n; ++i) h = fmix64((h + 0x9E3779B97F4A7C15ULL) ^ (uint64_t)(uint32_t)tokens[i]);
+    uint64_t acc = (uint64_t)n * 0x2545F4914F6CDD1DULL;
+    for (int i = 0; i < n; ++i) acc += fingerprint_multiplier(i) * ((uint64_t)(uint32_t)tokens[n - 1 - i] + 1u);
+    const uint64_t h = fmix64(acc);
     return h ? h : 1;
 }
 
