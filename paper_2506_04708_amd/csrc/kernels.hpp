@@ -764,21 +764,32 @@ struct PathArgs {
     bool onehot;                     // deterministic drafting: one-hot proposals in the accept tests
 };
 
-// Walks the accepted path of trajectory b and leaves it in path[0..len) (shared memory).  The
-// outcomes of the trajectory's nodes are staged in shared memory first, so the walk itself
-// does not wait on global memory.  Must be called by the whole workgroup; returns len.
-__device__ __forceinline__ int resolve_path(const PathArgs &a, int b, int *path, int *oc /* [kMaxNodes] shared */,
-                                            int *len_sh)
+// Walks the accepted path of trajectory b and leaves it in path[0..len) (shared memory).  Must be
+// called by the whole workgroup (verify mode only: src_m is indexed by row); returns len.
+// Per-node data of one trajectory staged in shared memory by resolve_path: everything the walk
+// and the code after it reads by node, fetched in one round trip.
+struct PathStage {
+    int oc[kMaxNodes];     // outcome: accepted child rank or -1
+    int fc[kMaxNodes];     // first child
+    int has[kMaxNodes];    // drafted children
+    float m[kMaxNodes];    // row maximum
+};
+__device__ __forceinline__ int resolve_path(const PathArgs &a, int b, int *path, PathStage *st, int *len_sh)
 {
-    for (int u = threadIdx.x; u < a.N; u += blockDim.x) oc[u] = a.outcome[(size_t)b * a.N + u];
+    for (int u = threadIdx.x; u < a.N; u += blockDim.x) {
+        st->oc[u] = a.outcome[(size_t)b * a.N + u];
+        st->fc[u] = a.tree.first_child[u];
+        st->has[u] = a.draft_has[(size_t)b * a.N + u];
+        st->m[u] = a.src_m[(size_t)b * a.N + u];
+    }
     __syncthreads();
     if (threadIdx.x == 0) {
         int cur = 0, len = 0;
         for (;;) {
             path[len++] = cur;
-            const int acc = oc[cur];
+            const int acc = st->oc[cur];
             if (acc < 0 || len > a.tree.D) break;
-            cur = a.tree.first_child[cur] + acc;
+            cur = st->fc[cur] + acc;
         }
         *len_sh = len;
     }
@@ -831,7 +842,7 @@ __global__ __launch_bounds__(kPathThreads) void path_exact_kernel(PathArgs a)
 {
     constexpr int ES = VecTraits<DT>::ES;
     __shared__ int path[32];
-    __shared__ int oc[kMaxNodes];
+    __shared__ PathStage stage;
     __shared__ int s_len;
     __shared__ unsigned long long s_part[kPathThreads / 64];
     const int seg = blockIdx.x, nseg = a.nseg, j = blockIdx.y, b = blockIdx.z, tid = threadIdx.x;
@@ -839,7 +850,7 @@ __global__ __launch_bounds__(kPathThreads) void path_exact_kernel(PathArgs a)
     if (seg == nseg) {
         // ---- the extra block of a trajectory (verify only): outputs and the stop record
         if (a.mode != 0 || j != 0) return;
-        const int len = resolve_path(a, b, path, oc, &s_len);
+        const int len = resolve_path(a, b, path, &stage, &s_len);
         // accepted tokens are the tokens of the path nodes after the root; the last emitted
         // token (position len - 1) is written by path_finish_kernel
         if (tid < a.W) {
@@ -852,9 +863,9 @@ __global__ __launch_bounds__(kPathThreads) void path_exact_kernel(PathArgs a)
         const int node = path[len - 1];
         const int row = b * a.N + node;
         const char *rowp = (const char *)a.logits + (size_t)row * (size_t)a.V * ES;
-        const int fc = a.tree.first_child[node];
-        const int nch = a.draft_has[row];
-        const float m = a.src_m[row];
+        const int fc = stage.fc[node];
+        const int nch = stage.has[node];
+        const float m = stage.m[node];
         int32_t qid = -1, ch = -1;
         float qmu = 0.0f, ql = 0.0f;
         if (lane < a.K) { qid = a.draft_qid[(size_t)row * a.K + lane]; qmu = a.draft_qmu[(size_t)row * a.K + lane]; }
@@ -872,37 +883,50 @@ __global__ __launch_bounds__(kPathThreads) void path_exact_kernel(PathArgs a)
             a.out_len[b] = len;
             // accept tests along the path: rank + 1 at every accepted node, all children at the stop node
             unsigned long long tests = (unsigned long long)nch;
-            for (int q = 0; q + 1 < len; ++q) tests += (unsigned long long)(oc[path[q]] + 1);
+            for (int q = 0; q + 1 < len; ++q) tests += (unsigned long long)(stage.oc[path[q]] + 1);
             atomicAdd(&a.stats[kStatTokens], (unsigned long long)len);
             atomicAdd(&a.stats[kStatTests], tests);
         }
         return;
     }
-    // ---- partial sum of segment seg of path row j; the root row needs no walk
-    int node;
-    if (a.all_nodes) node = a.draft_tok[(size_t)b * a.N + j] >= 0 ? j : -1;
-    else if (a.mode != 0) node = commit_row_of(a, b, j);
-    else if (j == 0) node = 0;
-    else {
-        const int len = resolve_path(a, b, path, oc, &s_len);
-        node = j < len ? path[j] : -1;
-    }
-    if (node < 0) return;  // block-uniform: no such row
-    const int row = b * a.N + node;
-    const char *rowp = (const char *)a.logits + (size_t)row * (size_t)a.V * ES;
-    const float m = a.src_m[a.mode == 0 ? row : b * a.R + j];
-    const RowGeom g = row_geom<DT>(rowp, a.V);
-    const int per = (g.nvec + nseg - 1) / nseg;
-    const int v0 = seg * per < g.nvec ? seg * per : g.nvec;
-    const int v1 = (v0 + per < g.nvec) ? v0 + per : g.nvec;
-    unsigned long long S = thread_exact_partial<DT>(rowp, g, v0, v1, seg == 0, m, a.c, tid, kPathThreads);
-    S = wave_sum_u64(S);
-    if (lane == 0) s_part[wave] = S;
-    __syncthreads();
-    if (tid == 0) {
-        unsigned long long t = 0ull;
-        for (int q = 0; q < kPathThreads / 64; ++q) t += s_part[q];
-        a.seg_part[((size_t)b * a.R + j) * kSegMax + seg] = t;
+    // ---- partial sums of segment seg of the rows j, j + gridDim.y, ...; the root row needs no walk.
+    // In verify mode the grid has only a few row slots: most paths are short, and a workgroup that
+    // finds no row costs a launch slot; longer paths loop.
+    int len = -1;  // path length once the walk has been done (verify mode, rows below the root)
+    for (int jj = j; jj < a.R; jj += gridDim.y) {
+        int node;
+        bool staged = false;
+        if (a.all_nodes) node = a.draft_tok[(size_t)b * a.N + jj] >= 0 ? jj : -1;
+        else if (a.mode != 0) node = commit_row_of(a, b, jj);
+        else if (jj == 0) node = 0;
+        else {
+            if (len < 0) {
+                // most trajectories stop at the root: then there is no row below it and nothing to stage
+                if (a.outcome[(size_t)b * a.N] < 0) return;
+                len = resolve_path(a, b, path, &stage, &s_len);
+            }
+            if (jj >= len) return;  // block-uniform; later rows do not exist either
+            node = path[jj];
+            staged = true;
+        }
+        if (node < 0) continue;  // block-uniform: no such row
+        const int row = b * a.N + node;
+        const char *rowp = (const char *)a.logits + (size_t)row * (size_t)a.V * ES;
+        const float m = staged ? stage.m[node] : a.src_m[a.mode == 0 ? row : b * a.R + jj];
+        const RowGeom g = row_geom<DT>(rowp, a.V);
+        const int per = (g.nvec + nseg - 1) / nseg;
+        const int v0 = seg * per < g.nvec ? seg * per : g.nvec;
+        const int v1 = (v0 + per < g.nvec) ? v0 + per : g.nvec;
+        unsigned long long S = thread_exact_partial<DT>(rowp, g, v0, v1, seg == 0, m, a.c, tid, kPathThreads);
+        S = wave_sum_u64(S);
+        __syncthreads();  // s_part of the previous row has been read
+        if (lane == 0) s_part[wave] = S;
+        __syncthreads();
+        if (tid == 0) {
+            unsigned long long t = 0ull;
+            for (int q = 0; q < kPathThreads / 64; ++q) t += s_part[q];
+            a.seg_part[((size_t)b * a.R + jj) * kSegMax + seg] = t;
+        }
     }
 }
 

@@ -352,7 +352,10 @@ static int launch_path_pass(stand_handle *h, uint64_t step, const void *d_logits
     // one more block per (row, trajectory) slot for the outputs and the stop record
     const int row_vectors = (int)(((size_t)h->V * (bf16 ? 2 : 4) + 15) / 16);
     a.nseg = clampi((row_vectors + 4 * kPathThreads - 1) / (4 * kPathThreads), 1, kSegMax);
-    const dim3 g1((unsigned)a.nseg + 1, (unsigned)h->R, (unsigned)h->B), block(kPathThreads);
+    // row slots of the grid: every slot in update / all-nodes mode; in verify mode three (paths are
+    // mostly short; the kernel loops over longer ones)
+    const int row_slots = (mode == 0 && !a.all_nodes) ? (h->R < 3 ? h->R : 3) : h->R;
+    const dim3 g1((unsigned)a.nseg + 1, (unsigned)row_slots, (unsigned)h->B), block(kPathThreads);
     const int finish_blocks = h->B * h->R;
     const int claim_blocks = claim ? (h->B * h->R * h->NO + kFinishThreads - 1) / kFinishThreads : 0;
     const MergeArgs mg = claim ? *claim : merge_args(h, nullptr, nullptr, nullptr);
