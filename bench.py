@@ -66,6 +66,9 @@ def main():
                     help="0 Gumbel-Top-K (the method), 1 sequential multinomial, 2 deterministic (the paper's ablation)")
     ap.add_argument("--update-mode", type=int, default=0,
                     help="0 merge the accepted path's rows (the paper), 1 merge every drafted node's row (table stress)")
+    ap.add_argument("--merge-policy", type=int, default=0,
+                    help="0 running mean over all observations of a context (the method), 1 keep only the newest "
+                         "observation (the replace policy the paper compares against)")
     ap.add_argument("--peak", type=float, default=8.0,
                     help="logit height of the peaked tokens (BASELINE: +8, p about 0.23 each); higher peaks give "
                          "sharper targets, longer acceptance and deeper drafts")
@@ -101,7 +104,8 @@ def main():
     dt = binding.STAND_BF16 if w.dtype == "bf16" else binding.STAND_F32
     assert w.dtype == "bf16"
     mk = lambda: binding.Stand(w.V, w.B, cfg["order_min"], cfg["order_max"], w.K, w.parent, w.T, cfg["capacity"], 64,
-                               cfg["seed"], dt, draft_mode=args.draft_mode, update_mode=args.update_mode)
+                               cfg["seed"], dt, draft_mode=args.draft_mode, update_mode=args.update_mode,
+                               merge_policy=args.merge_policy)
     gen = torch.Generator(device="cuda").manual_seed(cfg["seed"] & 0x7FFFFFFF)
     h1 = mk()
     for b in range(w.B):
@@ -112,11 +116,12 @@ def main():
     # one step at a time, so no more than one logits tensor is ever held on the host
     cpu_n = 0 if args.no_cpu else min(args.cpu_steps, T_warm)
     cpu_s = 0.0
+    cpu_rows = None
     if cpu_n:
         import oracle
         orc = oracle.Oracle(w.V, w.B, cfg["order_min"], cfg["order_max"], w.K, w.parent, w.T, cfg["capacity"], 64,
                             cfg["seed"], oracle.DT_BF16, draft_mode=args.draft_mode,
-                            update_mode=args.update_mode)
+                            update_mode=args.update_mode, merge_policy=args.merge_policy)
         for b in range(w.B):
             orc.set_context(b, w.prompt(b))
         od = orc.draft(0)
@@ -142,6 +147,20 @@ def main():
             od = orc.draft(step + 1)
             cpu_s += time.perf_counter() - c0
             assert np.array_equal(olen, ln) and np.array_equal(otok, g_tok), "oracle and GPU outputs differ"
+            if step == 0:
+                # the oracle's row function (softmax statistics + top-K of one row) over EVERY row of this
+                # step's tensor, rows spread over the host's cores: what the full-tensor pass costs on the CPU
+                from concurrent.futures import ThreadPoolExecutor
+                cores = min(len(os.sched_getaffinity(0)), int(os.environ.get("OMP_NUM_THREADS", "16")), 16)
+                flat = lg_host.reshape(w.B * w.N, w.V)
+                r0 = time.perf_counter()
+                with ThreadPoolExecutor(cores) as pool:
+                    res = list(pool.map(lambda r: oracle.row_obs(flat[r], w.T, w.K)[0], range(flat.shape[0])))
+                rows_s = time.perf_counter() - r0
+                g_idx = h1.row_results()[2].cpu().numpy()
+                assert np.array_equal(np.stack(res), g_idx), "oracle and GPU top-K ids differ on the full tensor"
+                cpu_rows = {"value": round(1.0 / rows_s, 4), "unit": "row passes/s (all %d rows of one step)" % flat.shape[0],
+                            "cores": cores, "kind": "oracle row function, rows in parallel", "seconds": round(rows_s, 2)}
             del lg_host
         w.commit(ln)
         lens.append(ln.mean())
@@ -198,6 +217,19 @@ def main():
     for i, (lg, force, r_tok, r_len, r_draft) in enumerate(rec):
         assert torch.equal(o_len[i], r_len) and torch.equal(o_tok[i], r_tok) and torch.equal(o_draft[i], r_draft), \
             "replay diverged from the recorded run at step %d" % i
+    # floor of a kernel that only fetches one step's logits, in the row pass's launch shape
+    read_us = None
+    if (w.V * 2) % 16 == 0:
+        sink = torch.zeros(4 * w.B * w.N, dtype=torch.int32, device="cuda")
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        reps = 20
+        for r in range(3 + reps):
+            if r == 3:
+                ev[0].record()
+            binding.read_rows(rec[r % len(rec)][0], w.V * 2, w.B * w.N, sink, torch.cuda.current_stream().cuda_stream)
+        ev[1].record()
+        torch.cuda.synchronize()
+        read_us = ev[0].elapsed_time(ev[1]) * 1e3 / reps
     st = h2.stats()
     ms_per_step = (t2 - t1) * 1e3 / K_steps
     steps_per_s = K_steps / (t2 - t1)
@@ -223,6 +255,11 @@ def main():
         roof = {"bound": "hbm", "kernel": "row_pass_kernel", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
                 "avg_launch_us": round(row_us, 2), "bytes_per_launch": row_bytes}
+        if read_us:
+            # the same bytes fetched by a kernel that does nothing else (stand_read_rows), back to back
+            roof["read_only_us"] = round(read_us, 2)
+            roof["read_only_GBps"] = round(logits_bytes / (read_us * 1e-6) / 1e9, 1)
+            roof["frac_of_read_only"] = round(read_us / row_us, 4)
 
     cpu = None
     if cpu_n:
@@ -230,6 +267,8 @@ def main():
                "sample": "first %d steps of the same workload (table filling up from empty), %.1f s of CPU time; the "
                          "oracle evaluates only the rows its walk visits, the GPU all %d rows; outputs checked equal"
                          % (cpu_n, cpu_s, rows)}
+        if cpu_rows:
+            cpu["row_pass_all_cores"] = cpu_rows
 
     out = {
         "metric": "speculation steps/s (stand_step: verify + table merge + draft), B=%d, V=%d, %d-node tree" % (w.B, w.V, w.N),
@@ -241,7 +280,8 @@ def main():
                                "for %d steps" % (args.workload, w.B, w.V, w.N, w.D, cfg["order_min"], cfg["order_max"], w.K,
                                                  w.T, cfg["capacity"], T_warm),
                    "draft_mode": ["gumbel_topk", "multinomial", "deterministic"][args.draft_mode],
-                   "update_mode": ["accepted_path", "all_nodes"][args.update_mode], "peak": args.peak, "max_peaks": args.max_peaks,
+                   "update_mode": ["accepted_path", "all_nodes"][args.update_mode],
+                   "merge_policy": ["running_mean", "replace"][args.merge_policy], "peak": args.peak, "max_peaks": args.max_peaks,
                    "acceptance_len": round(acc_len, 3), "table_entries": int(entries0 + st.inserts)},
         "hbm_gbps_algorithmic": round(step_bytes * steps_per_s / 1e9, 1),
         "hbm_frac_of_peak": round(step_bytes * steps_per_s / 1e9 / HBM_PEAK_GBPS, 4),

@@ -49,6 +49,14 @@ extern "C" {
                                      /* (the committed tokens are still appended).  A stress variant for the   */
                                      /* table: thousands of records per step instead of hundreds               */
 
+/* What an update does to an entry that already exists.  The method keeps the running mean of all
+ * observations of a context (paper Sec. 4.1).  REPLACE keeps only the newest observation, the
+ * policy of the lookup table the paper compares against and argues loses information as
+ * trajectories accumulate (Sec. 5.1, discussion of Table 1); the occurrence count is still
+ * kept.  Records of one step apply in record order, so the last record of a key wins. */
+#define STAND_MERGE_MEAN 0
+#define STAND_MERGE_REPLACE 1
+
 /* How the children of a tree node are drawn from its table entry (paper Sec. 3.1 "deterministic
  * or stochastic" drafting, Sec. 4.2, and the ablation of Table 5).  All three keep the output
  * distribution equal to the target's; they differ in how often drafts are accepted. */
@@ -82,6 +90,7 @@ typedef struct {
     int32_t update_mode;        /* STAND_UPDATE_*                                                   */
     int32_t device;             /* HIP device ordinal                                               */
     int32_t draft_mode;         /* STAND_DRAFT_*                                                    */
+    int32_t merge_policy;       /* STAND_MERGE_*                                                    */
 } stand_config;
 
 typedef struct {
@@ -234,6 +243,14 @@ int stand_tree_select(const int32_t *host_parent, const uint64_t *host_counts, i
  * the kernels above can be scaled by what they read for this one.  STAND_EINVAL on a bad
  * size or alignment. */
 int stand_copy_bytes(void *d_dst, const void *d_src, uint64_t bytes, void *stream);
+
+/* Measurement aid, not part of the method: reads `rows` consecutive rows of `row_bytes` bytes
+ * (a multiple of 16; d_src 16-byte aligned, device memory) with one 256-thread workgroup per
+ * row, the launch shape of the row pass, doing nothing with the data but a checksum.  Its
+ * duration is the floor of any kernel that fetches the logits once on this device.  d_sink
+ * (device, 4 * rows words) receives one word per wave.  STAND_EINVAL on a bad size or
+ * alignment. */
+int stand_read_rows(const void *d_src, uint64_t row_bytes, uint64_t rows, uint32_t *d_sink, void *stream);
 
 const char *stand_strerror(int code);
 int stand_last_hip_error(const stand_handle *h);

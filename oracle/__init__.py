@@ -22,6 +22,7 @@ DT_F32 = 1
 STREAM_DRAFT, STREAM_ACCEPT, STREAM_BONUS = 0, 1, 2
 DRAFT_GUMBEL_TOPK, DRAFT_MULTINOMIAL, DRAFT_DETERMINISTIC = 0, 1, 2
 UPDATE_ACCEPTED_PATH, UPDATE_ALL_NODES = 0, 1
+MERGE_MEAN, MERGE_REPLACE = 0, 1
 
 
 def build(force=False):
@@ -46,6 +47,7 @@ class _Config(C.Structure):
         ("logits_dtype", C.c_int32),
         ("update_mode", C.c_int32),
         ("draft_mode", C.c_int32),
+        ("merge_policy", C.c_int32),
     ]
 
 
@@ -310,11 +312,12 @@ class Oracle:
     """One shared n-gram table + B trajectories, driven step by step."""
 
     def __init__(self, vocab, max_batch, order_min, order_max, topk, tree_parent, temperature,
-                 table_capacity, max_probe, seed, logits_dtype, update_mode=0, draft_mode=DRAFT_GUMBEL_TOPK):
+                 table_capacity, max_probe, seed, logits_dtype, update_mode=0, draft_mode=DRAFT_GUMBEL_TOPK,
+                 merge_policy=MERGE_MEAN):
         self._parent = _i32(tree_parent)
         cfg = _Config(vocab, max_batch, order_min, order_max, topk, self._parent.shape[0],
                       self._parent.ctypes.data_as(C.POINTER(C.c_int32)), temperature, table_capacity,
-                      max_probe, seed, logits_dtype, update_mode, draft_mode)
+                      max_probe, seed, logits_dtype, update_mode, draft_mode, merge_policy)
         self.h = lib().so_create(C.byref(cfg))
         self.B, self.N, self.K, self.V = max_batch, self._parent.shape[0], topk, vocab
         self.D = int(lib().so_depth(self.h))

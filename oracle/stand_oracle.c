@@ -48,6 +48,9 @@
 #define SO_UPDATE_ACCEPTED_PATH 0 /* the rows that produced committed tokens                       */
 #define SO_UPDATE_ALL_NODES 1     /* the row of every drafted node, under the context that node    */
                                   /* would have if its path were accepted (a table stress variant) */
+/* what a table update does to an entry that exists (Sec. 4.1; Sec. 5.1 on replacing) */
+#define SO_MERGE_MEAN 0    /* running mean of all observations (the method)      */
+#define SO_MERGE_REPLACE 1 /* the newest observation only (comparison policy)   */
 #define SO_DRAFT_GUMBEL_TOPK 0   /* stochastic, Gumbel-Top-K (the method's own)                */
 #define SO_DRAFT_MULTINOMIAL 1   /* stochastic, sequential sampling without replacement        */
 #define SO_DRAFT_DETERMINISTIC 2 /* the most probable stored tokens; proposal treated as one-hot */
@@ -581,6 +584,7 @@ typedef struct {
     int32_t logits_dtype;
     int32_t update_mode;
     int32_t draft_mode;
+    int32_t merge_policy;
 } so_config;
 
 typedef struct {
@@ -782,7 +786,9 @@ static void table_merge(so_handle *h, int n, const int32_t *tok, const int32_t *
     so_entry *en = &h->ent[e];
     int32_t ids2[SO_MAX_K];
     float mu2[SO_MAX_K];
-    so_merge(en->count, en->ids, en->mu, h->K, obs_ids, obs_p, ids2, mu2);
+    /* SO_MERGE_REPLACE: the comparison policy the paper argues against in Sec. 5.1 (a table that
+     * keeps only the newest observation of a context); the occurrence count is still kept */
+    so_merge(h->cfg.merge_policy == SO_MERGE_REPLACE ? 0u : en->count, en->ids, en->mu, h->K, obs_ids, obs_p, ids2, mu2);
     memcpy(en->ids, ids2, sizeof(int32_t) * (size_t)h->K);
     memcpy(en->mu, mu2, sizeof(float) * (size_t)h->K);
     en->count++;

@@ -15,13 +15,14 @@ LIB_PATH = os.path.join(_HERE, "libstand.so")
 
 STAND_BF16, STAND_F32 = 0, 1
 DRAFT_GUMBEL_TOPK, DRAFT_MULTINOMIAL, DRAFT_DETERMINISTIC = 0, 1, 2
+MERGE_MEAN, MERGE_REPLACE = 0, 1
 MAX_ORDER = 8
 
 EXPORTED = [
     "stand_create", "stand_destroy", "stand_depth", "stand_set_context", "stand_reorder", "stand_update",
     "stand_draft", "stand_verify", "stand_step", "stand_row_results", "stand_table_export", "stand_table_import",
     "stand_get_context", "stand_get_stats", "stand_strerror", "stand_last_hip_error",
-    "stand_profile_begin", "stand_profile_end", "stand_copy_bytes",
+    "stand_profile_begin", "stand_profile_end", "stand_copy_bytes", "stand_read_rows",
     "stand_tree_initial", "stand_tree_select", "stand_get_node_counts", "stand_reset_node_counts",
     "stand_tree_packing",
 ]
@@ -33,7 +34,7 @@ class Config(C.Structure):
         ("topk", C.c_int32), ("tree_nodes", C.c_int32), ("tree_parent", C.POINTER(C.c_int32)),
         ("temperature", C.c_float), ("table_capacity", C.c_uint64), ("max_probe", C.c_int32),
         ("seed", C.c_uint64), ("logits_dtype", C.c_int32), ("update_mode", C.c_int32), ("device", C.c_int32),
-        ("draft_mode", C.c_int32),
+        ("draft_mode", C.c_int32), ("merge_policy", C.c_int32),
     ]
 
 
@@ -69,6 +70,7 @@ def load_library():
     lib.stand_profile_begin.argtypes = [vp, C.c_int32]
     lib.stand_profile_end.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_int32)]
     lib.stand_copy_bytes.argtypes = [vp, vp, C.c_uint64, vp]
+    lib.stand_read_rows.argtypes = [vp, C.c_uint64, C.c_uint64, vp, vp]
     lib.stand_tree_initial.argtypes = [C.c_int32, i32p, C.c_int32, C.POINTER(C.c_int32)]
     lib.stand_tree_select.argtypes = [i32p, vp, C.c_int32, C.c_int32, i32p, i32p]
     lib.stand_get_node_counts.argtypes = [vp, vp]
@@ -88,6 +90,13 @@ def copy_bytes(dst, src, nbytes, stream=None):
     rc = lib().stand_copy_bytes(dst.data_ptr(), src.data_ptr(), nbytes, stream)
     if rc:
         raise RuntimeError("stand_copy_bytes: %s" % lib().stand_strerror(rc).decode())
+
+
+def read_rows(src, row_bytes, rows, sink, stream=None):
+    """Bare read of `rows` rows in the row pass's launch shape (measurement aid); sink: int32 tensor of 4 * rows."""
+    rc = lib().stand_read_rows(src.data_ptr(), row_bytes, rows, sink.data_ptr(), stream)
+    if rc:
+        raise RuntimeError("stand_read_rows: %s" % lib().stand_strerror(rc).decode())
 
 
 def tree_initial(levels=20):
@@ -152,11 +161,11 @@ class Stand:
     """One n-gram table shared by B trajectories on one GPU; methods carry the C ABI's names."""
 
     def __init__(self, vocab, max_batch, order_min, order_max, topk, tree_parent, temperature, table_capacity,
-                 max_probe, seed, logits_dtype, device=0, draft_mode=0, update_mode=0):
+                 max_probe, seed, logits_dtype, device=0, draft_mode=0, update_mode=0, merge_policy=0):
         par = np.ascontiguousarray(tree_parent, dtype=np.int32)
         cfg = Config(vocab, max_batch, order_min, order_max, topk, par.shape[0],
                      par.ctypes.data_as(C.POINTER(C.c_int32)), temperature, table_capacity, max_probe, seed,
-                     logits_dtype, update_mode, device, draft_mode)
+                     logits_dtype, update_mode, device, draft_mode, merge_policy)
         self.h = C.c_void_p()
         _check(lib().stand_create(C.byref(cfg), C.byref(self.h)))
         self.B, self.N, self.K, self.V = max_batch, par.shape[0], topk, vocab

@@ -1024,6 +1024,7 @@ struct MergeArgs {
     int N;
     int R;                            // record slots per trajectory: W, or N in all-nodes mode
     bool all_nodes;                   // record (b, j, n) observes drafted node j under its path's context
+    bool replace;                     // an existing entry becomes the newest observation (no running mean)
     const int32_t *draft_tok;         // [B][N]
     const int32_t *depth;             // [N]
     const int32_t *recent;            // [B][N][kMaxOrder] recent[.][i]: token i positions before the end of node's sequence
@@ -1385,8 +1386,8 @@ __global__ __launch_bounds__(64) void merge_apply_kernel(MergeArgs a)
     if (count == 0) { e_id = -1; e_mu = 0.0f; }
 
     auto apply = [&](int32_t o_id, float o_p) {
-        if (count == 0) {
-            // first sight: the entry is the observation
+        if (count == 0 || a.replace) {
+            // first sight, or a table that keeps only the newest observation: the entry is the observation
             const int32_t id2 = __shfl(o_id, 32 + (lane & 31));
             const float p2 = __shfl(o_p, 32 + (lane & 31));
             if (lane < K) { e_id = id2; e_mu = p2; }
@@ -1702,6 +1703,40 @@ __global__ __launch_bounds__(256) void copy_words_kernel(const uint4 *src, uint4
 {
     const size_t stride = (size_t)gridDim.x * blockDim.x;
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < nwords; i += stride) dst[i] = src[i];
+}
+
+// Bare read of `rows` rows of `vpr` 16-byte words in the row pass's launch shape (one workgroup
+// of 256 threads per row, two batches of two loads per thread in flight): what a kernel that only
+// fetches the logits takes on this device.  Each wave leaves one word so the loads are not removed.
+__global__ __launch_bounds__(256) void read_rows_kernel(const uint4 *src, size_t vpr, uint32_t *sink)
+{
+    const uint4 *r = src + (size_t)blockIdx.x * vpr;
+    const size_t t = threadIdx.x, last = vpr - 1;
+    constexpr int U = 2, PF = 2;
+    const size_t per_batch = 256 * U;
+    const size_t nbatch = (vpr + per_batch - 1) / per_batch;
+    uint4 ring[PF][U];
+    auto load = [&](uint4 (&w)[U], size_t k) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const size_t i = (k * U + u) * 256 + t;
+            w[u] = r[i < last ? i : last];
+        }
+    };
+#pragma unroll
+    for (int s = 0; s < PF; ++s) load(ring[s], s);
+    uint32_t acc = 0;
+    for (size_t k0 = 0; k0 < nbatch; k0 += PF) {
+#pragma unroll
+        for (int s = 0; s < PF; ++s) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) acc += ring[s][u].x ^ ring[s][u].y ^ ring[s][u].z ^ ring[s][u].w;
+            load(ring[s], k0 + s + PF);
+        }
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) acc += __shfl_xor(acc, off);
+    if ((threadIdx.x & 63) == 0) sink[(size_t)blockIdx.x * 4 + (threadIdx.x >> 6)] = acc;
 }
 
 // export support: count and compact the occupied slots

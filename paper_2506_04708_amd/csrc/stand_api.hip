@@ -103,6 +103,7 @@ extern "C" int stand_create(const stand_config *cfg, stand_handle **out)
     if (cfg->logits_dtype != STAND_BF16 && cfg->logits_dtype != STAND_F32) return STAND_EINVAL;
     if (cfg->update_mode != STAND_UPDATE_ACCEPTED_PATH && cfg->update_mode != STAND_UPDATE_ALL_NODES) return STAND_EINVAL;
     if (cfg->draft_mode < STAND_DRAFT_GUMBEL_TOPK || cfg->draft_mode > STAND_DRAFT_DETERMINISTIC) return STAND_EINVAL;
+    if (cfg->merge_policy != STAND_MERGE_MEAN && cfg->merge_policy != STAND_MERGE_REPLACE) return STAND_EINVAL;
     if ((int64_t)cfg->max_batch * N * (int64_t)cfg->vocab >= ((int64_t)1 << 40)) return STAND_EINVAL;
     // merge records are numbered in 23 bits (kTagMax); max_batch * tree depth * orders stays far below
     if ((int64_t)cfg->max_batch * (cfg->update_mode == STAND_UPDATE_ALL_NODES ? (int64_t)N : (int64_t)(kMaxDepth + 1)) * STAND_MAX_ORDER >
@@ -309,6 +310,7 @@ static MergeArgs merge_args(stand_handle *h, const int32_t *commit_tok, const in
     a.table = h->table; a.mask = h->cfg.table_capacity - 1; a.slot_bytes = h->slot_bytes; a.K = h->K;
     a.max_probe = h->cfg.max_probe; a.B = h->B; a.W = h->W; a.omin = h->cfg.order_min; a.omax = h->cfg.order_max;
     a.R = h->R; a.all_nodes = h->cfg.update_mode == STAND_UPDATE_ALL_NODES; a.draft_tok = h->draft_tok;
+    a.replace = h->cfg.merge_policy == STAND_MERGE_REPLACE;
     a.depth = tree_dev(h).depth; a.recent = h->recent;
     a.ctx_tail = h->ctx_tail; a.ctx_len = h->ctx_len; a.commit_tok = commit_tok; a.commit_row = commit_row;
     a.commit_len = commit_len; a.N = h->N; a.rec_slot = h->rec_slot; a.obs_idx = h->obs_idx; a.obs_p = h->obs_p;
@@ -736,6 +738,16 @@ extern "C" int stand_copy_bytes(void *d_dst, const void *d_src, uint64_t bytes, 
     const size_t want = (nwords + 255) / 256;
     const unsigned blocks = (unsigned)(want < 16384 ? want : 16384);
     copy_words_kernel<<<dim3(blocks), dim3(256), 0, (hipStream_t)stream>>>((const uint4 *)d_src, (uint4 *)d_dst, nwords);
+    return hipGetLastError() == hipSuccess ? STAND_OK : STAND_EHIP;
+}
+
+extern "C" int stand_read_rows(const void *d_src, uint64_t row_bytes, uint64_t rows, uint32_t *d_sink, void *stream)
+{
+    if (!d_src || !d_sink || row_bytes == 0 || (row_bytes & 15u) || ((uintptr_t)d_src & 15u) || rows == 0 ||
+        rows > 0x7FFFFFFFull)
+        return STAND_EINVAL;
+    read_rows_kernel<<<dim3((unsigned)rows), dim3(256), 0, (hipStream_t)stream>>>((const uint4 *)d_src, (size_t)(row_bytes / 16),
+                                                                                 d_sink);
     return hipGetLastError() == hipSuccess ? STAND_OK : STAND_EHIP;
 }
 

@@ -27,10 +27,11 @@ def make_pair(w, capacity, max_probe=64, seed=None, order_min=None, order_max=No
     dt_g = binding.STAND_F32 if w.dtype == "f32" else binding.STAND_BF16
     mode = cfg.get("draft_mode", 0)  # same numbering on both sides (0 Gumbel-Top-K, 1 multinomial, 2 deterministic)
     upd = cfg.get("update_mode", 0)  # 0 accepted path, 1 all drafted nodes
+    pol = cfg.get("merge_policy", 0)  # 0 running mean, 1 replace
     o = oracle.Oracle(w.V, w.B, omin, omax, w.K, w.parent, w.T, capacity, max_probe, seed, dt_o, draft_mode=mode,
-                      update_mode=upd)
+                      update_mode=upd, merge_policy=pol)
     g = binding.Stand(w.V, w.B, omin, omax, w.K, w.parent, w.T, capacity, max_probe, seed, dt_g, draft_mode=mode,
-                      update_mode=upd)
+                      update_mode=upd, merge_policy=pol)
     return o, g
 
 

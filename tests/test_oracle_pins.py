@@ -240,6 +240,49 @@ def test_table_equals_brute_force_recount():
     assert o.context_len(0) == len(ctx) and list(o.context_tail(0, 3)) == ctx[-3:]
 
 
+def test_replace_policy_keeps_the_newest_observation():
+    """MERGE_REPLACE (the table policy the paper contrasts with its own in Sec. 5.1): an entry holds the
+    distribution of the newest occurrence of its context, in update order, and still counts occurrences."""
+    V, K, T = 8, 8, 0.6
+    o = oracle.Oracle(V, 1, 1, 3, K, np.array((-1, 0, 0, 1), np.int32), T, 1 << 12, 64, 7, oracle.DT_F32,
+                      merge_policy=oracle.MERGE_REPLACE)
+    W = o.W
+    r = np.random.default_rng(6)
+    ctx = [int(x) for x in r.integers(V, size=3)]
+    o.set_context(0, ctx)
+    newest = {}
+    for step in range(150):
+        lg = r.standard_normal((1, o.N, V)).astype(np.float32)
+        n = int(r.integers(1, W + 1))
+        toks = r.integers(V, size=n)
+        rows = r.integers(o.N, size=n)
+        ct = np.full((1, W), -1, np.int32)
+        cr = np.full((1, W), -1, np.int32)
+        ct[0, :n], cr[0, :n] = toks, rows
+        for j in range(n):
+            p = _softmax64(lg[0, rows[j]], T)
+            for order in (1, 2, 3):
+                if len(ctx) >= order:
+                    acc = newest.setdefault(tuple(ctx[-order:]), [0, None])
+                    acc[0] += 1
+                    acc[1] = p
+            ctx.append(int(toks[j]))
+        o.update(step, lg, ct, cr, np.array([n], np.int32))
+    tab = o.table_export()
+    assert len(tab) == len(newest)
+    byfp = {int(t["fp"]): t for t in tab}
+    differs_from_mean = 0
+    for key, (cnt, p) in newest.items():
+        t = byfp[oracle.fingerprint(key)]
+        assert t["count"] == cnt and t["order"] == len(key)
+        got = np.zeros(V)
+        got[t["ids"]] = t["mu"]
+        assert np.max(np.abs(got - p)) < 2e-6
+        differs_from_mean += cnt > 1
+    assert differs_from_mean > 20        # contexts seen several times: a mean would have failed above
+    o.close()
+
+
 def test_all_nodes_update_equals_brute_force_recount():
     """ALL_NODES update mode: every drafted node's row is merged under the context the node would
     have if its path were accepted; recounted here from the drafted trees with a dictionary."""

@@ -43,6 +43,8 @@ def _say(msg):
     ("cfg3", dict(V=5000, B=4, rho=0.8, update_mode=1), 25, "step", True),     # every drafted node's row is merged
     ("cfg1", dict(V=900, B=3, rho=0.7, update_mode=1), 40, "separate", True),  # the same through stand_update
     ("cfg5", dict(V=3000, B=2, rho=0.8, update_mode=1), 10, "step", False),    # 128 nodes, K=32, closed loop
+    ("cfg3", dict(V=5000, B=8, rho=0.8, merge_policy=1), 25, "step", True),    # entries replaced, not averaged
+    ("cfg1", dict(V=900, B=3, rho=0.7, merge_policy=1, update_mode=1), 40, "separate", True),  # replace, many records per key
 ])
 def test_lockstep_small(gpu, name, over, steps, mode, forced):
     binding, lockstep = gpu
@@ -224,6 +226,23 @@ def test_row_pass_timing_and_copy(gpu):
     assert torch.equal(dst, src)
     with pytest.raises(RuntimeError):
         binding.copy_bytes(dst, src, 24)       # not a multiple of 16
+    # stand_read_rows: the checksum it leaves is the sum over each row's words of (x ^ y ^ z ^ w)
+    for rows, words in [(3, 1), (5, 515), (2, 2048), (7, 4099)]:
+        host = np.random.default_rng(rows * 131 + words).integers(0, 1 << 32, size=(rows, words, 4), dtype=np.uint64)
+        srcw = torch.from_numpy(host.astype(np.uint32).view(np.int32)).cuda()
+        sink = torch.zeros(4 * rows, dtype=torch.int32, device="cuda")
+        binding.read_rows(srcw, words * 16, rows, sink)
+        torch.cuda.synchronize()
+        want = (host[..., 0] ^ host[..., 1] ^ host[..., 2] ^ host[..., 3]).sum(axis=1) & 0xFFFFFFFF
+        got = (sink.cpu().numpy().view(np.uint32).astype(np.uint64).reshape(rows, 4).sum(axis=1)) & 0xFFFFFFFF
+        # lanes past the row's end re-read its last word (clamped index): add those duplicates
+        per_pass = 256 * 4
+        padded = ((words + per_pass - 1) // per_pass) * per_pass
+        lastw = host[:, -1, 0] ^ host[:, -1, 1] ^ host[:, -1, 2] ^ host[:, -1, 3]
+        want = (want + (padded - words) * lastw) & 0xFFFFFFFF
+        assert np.array_equal(got, want), (rows, words)
+    with pytest.raises(RuntimeError):
+        binding.read_rows(srcw, 24, 1, sink)
 
 
 # ---- state handling ------------------------------------------------------------------------------
