@@ -330,9 +330,14 @@ __device__ __forceinline__ unsigned long long raw_of_key(unsigned long long key)
 // maximum equals the threshold all stay).  RAW_IN / KEYS_OUT say whether the list holds raw
 // records or ranking keys before / after.  Falls back to the exact prune when ties leave too
 // many records.
+// Every record's upper key word lies in [lo_word, hi_word] (the current threshold and the key of
+// the largest value seen; 0 and ~0 if unknown), so the bits the two bounds share are not searched;
+// LOWBIT is the lowest bit that can differ between two values of the logits' type (16 for bf16,
+// whose binary32 images have sixteen constant low bits per sign).
 constexpr int kPruneSlack = 16;
-template <bool RAW_IN, bool KEYS_OUT>
-__device__ __forceinline__ void wave_prune_fast(WaveScan *ws, WaveScanState &st, int lane, int K)
+template <bool RAW_IN, bool KEYS_OUT, int LOWBIT>
+__device__ __forceinline__ void wave_prune_fast(WaveScan *ws, WaveScanState &st, int lane, int K, uint32_t lo_word,
+                                                uint32_t hi_word)
 {
     const int n = st.cnt;  // <= kWaveCap = 3 * 64
     unsigned long long e0 = lane < n ? ws->buf[lane] : 0ull;
@@ -346,7 +351,15 @@ __device__ __forceinline__ void wave_prune_fast(WaveScan *ws, WaveScanState &st,
     const uint32_t h0 = (uint32_t)(e0 >> 32), h1 = (uint32_t)(e1 >> 32), h2 = (uint32_t)(e2 >> 32);
     uint32_t t = 0u;
     if (n > K) {
-        for (int bit = 31; bit >= 0; --bit) {
+        const uint32_t diff = lo_word ^ hi_word;
+        int top = -1;  // highest bit in which the bounds differ
+        if (diff) {
+            top = 31 - __builtin_clz(diff);
+            t = top == 31 ? 0u : (hi_word & ~((2u << top) - 1u));
+        } else {
+            t = hi_word;
+        }
+        for (int bit = top; bit >= LOWBIT; --bit) {
             const uint32_t cand = t | (1u << bit);
             const int c = __popcll(__ballot(h0 >= cand)) + __popcll(__ballot(h1 >= cand)) + __popcll(__ballot(h2 >= cand));
             if (c >= K) {
@@ -385,15 +398,17 @@ __device__ __forceinline__ void wave_prune_fast(WaveScan *ws, WaveScanState &st,
 }
 
 // Lanes with `pred` append the raw record (cm, vec); prune above kWavePrune records.
+template <int LOWBIT>
 __device__ __forceinline__ void wave_offer(WaveScan *ws, WaveScanState &st, int lane, int K, bool pred, float cm,
-                                           uint32_t vec)
+                                           uint32_t vec, float seen_max)
 {
     const unsigned long long bal = __ballot(pred);
     if (!bal) return;
     if (pred) ws->buf[st.cnt + lane_prefix_count(bal)] = raw_record(cm, vec);
     st.cnt = __builtin_amdgcn_readfirstlane(st.cnt + __popcll(bal));
     __builtin_amdgcn_wave_barrier();
-    if (st.cnt > kWavePrune) wave_prune_fast<true, false>(ws, st, lane, K);
+    if (st.cnt > kWavePrune)
+        wave_prune_fast<true, false, LOWBIT>(ws, st, lane, K, (uint32_t)(st.theta_key >> 32), order_key(seen_max));
 }
 
 // Leaves the row's K best element keys (value desc, id asc) sorted in ws->top[0..K), returns
@@ -414,6 +429,7 @@ __device__ __forceinline__ WavePartial wave_row_stream(const void *rowp, int V, 
 {
     constexpr int EPV = VecTraits<DT>::EPV;
     constexpr int U = kRowU, PF = kRowPF;
+    constexpr int LOWBIT = DT == kDtBf16 ? 16 : 0;
     // the row and the wave's share of it are the same in every lane: keep them in scalar registers
     rowp = (const void *)readlane_u64((unsigned long long)rowp, 0);
     wsub = __builtin_amdgcn_readfirstlane(wsub);
@@ -483,7 +499,8 @@ __device__ __forceinline__ WavePartial wave_row_stream(const void *rowp, int V, 
 #pragma unroll
         for (int j = 0; j < EPV; ++j) e += fast_exp2(__builtin_fmaf(x[j], c, nb));
         s_t += valid ? e : 0.0f;
-        if (__ballot(valid && cm >= st.theta_val)) wave_offer(ws, st, lane, K, valid && cm >= st.theta_val, cm, (uint32_t)idx);
+        if (__ballot(valid && cm >= st.theta_val))
+            wave_offer<LOWBIT>(ws, st, lane, K, valid && cm >= st.theta_val, cm, (uint32_t)idx, m_ref);
     };
     auto do_batch = [&](uint4 (&w)[U], int k) {
         const int kb = k * wpr + wsub;        // batch of the row
@@ -510,7 +527,7 @@ __device__ __forceinline__ WavePartial wave_row_stream(const void *rowp, int V, 
     }
 
     // leave at most K + kPruneSlack ranking keys, the wave's K best among them, in ws->buf
-    wave_prune_fast<true, true>(ws, st, lane, K);
+    wave_prune_fast<true, true, LOWBIT>(ws, st, lane, K, (uint32_t)(st.theta_key >> 32), order_key(m_ref));
     float s = s_t;
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off);
@@ -539,7 +556,7 @@ __device__ __forceinline__ void wave_row_finish(const void *rowp, int V, int K, 
         WaveScanState st;
         st.cnt = cnt;
         set_theta(st, 0ull);
-        wave_prune_fast<false, true>(ws, st, lane, K);
+        wave_prune_fast<false, true, DT == kDtBf16 ? 16 : 0>(ws, st, lane, K, 0u, ~0u);
         cnt = st.cnt;
     }
     const unsigned long long th_vec = wave_select(ws->buf, ws->top, lane, K, cnt);
@@ -905,7 +922,7 @@ __global__ __launch_bounds__(kPathThreads) void path_exact_kernel(PathArgs a)
     __shared__ int s_len;
     __shared__ unsigned long long s_part[kPathThreads / 64];
     const int seg = blockIdx.x, nseg = a.nseg, j = blockIdx.y, b = blockIdx.z, tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
+    const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // scalar: the same in every lane
     if (seg == nseg) {
         // ---- the extra block of a trajectory (verify only): outputs and the stop record
         if (a.mode != 0 || j != 0) return;
@@ -1032,7 +1049,7 @@ __global__ __launch_bounds__(256) void commit_scan_kernel(CommitScanArgs a)
     constexpr int ES = VecTraits<DT>::ES;
     __shared__ WaveScan wsh[4];
     __shared__ int part_cnt[4];
-    const int j = blockIdx.x, b = blockIdx.y, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int j = blockIdx.x, b = blockIdx.y, lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     int node;
     if (a.all_nodes) {
         if (a.draft_tok[(size_t)b * a.N + j] < 0) return;
@@ -1160,7 +1177,7 @@ template <int DT>
 __global__ __launch_bounds__(kFinishThreads) void path_finish_kernel(PathArgs a, MergeArgs mg, int finish_blocks)
 {
     constexpr int ES = VecTraits<DT>::ES, EPV = VecTraits<DT>::EPV;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     if ((int)blockIdx.x >= finish_blocks) {
         merge_claim_record(mg, ((int)blockIdx.x - finish_blocks) * kFinishThreads + tid);
         return;
@@ -1550,7 +1567,7 @@ __global__ __launch_bounds__(kDraftThreads) void draft_kernel(DraftArgs a)
     __shared__ int32_t t_first[kMaxNodes], t_nchild[kMaxNodes];
     __shared__ int32_t t_level[kMaxDepth + 3];
     __shared__ long long s_clen;
-    const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int N = a.tree.N, K = a.K;
     for (int u = tid; u < N; u += kDraftThreads) {
         t_first[u] = a.tree.first_child[u];
@@ -1579,17 +1596,18 @@ __global__ __launch_bounds__(kDraftThreads) void draft_kernel(DraftArgs a)
         s_clen = len;
     }
     __syncthreads();
-    const long long clen = s_clen;
+    const long long clen = (long long)readlane_u64((unsigned long long)s_clen, 0);
     const int NO = a.omax - a.omin + 1;
     for (int d = 0; d < a.tree.D; ++d) {
-        const int lo = t_level[d], hi = t_level[d + 1];
+        // values read from shared memory that are the same in every lane go to scalar registers
+        const int lo = __builtin_amdgcn_readfirstlane(t_level[d]), hi = __builtin_amdgcn_readfirstlane(t_level[d + 1]);
         // a level without a drafted node ends the tree (tok is stable here: barrier below)
         bool any = false;
         for (int u = lo + lane; u < hi; u += 64) any |= tok[u] >= 0;
         if (!__ballot(any)) break;  // the same in every wave
         for (int u = lo + wave; u < hi; u += kDraftThreads / 64) {
-            const int nch = t_nchild[u];
-            if (nch == 0 || tok[u] < 0) continue;  // uniform per wave
+            const int nch = __builtin_amdgcn_readfirstlane(t_nchild[u]);
+            if (nch == 0 || __builtin_amdgcn_readfirstlane(tok[u]) < 0) continue;
             // ---- multi-level lookup (paper Sec. 4.2): lane q < NO takes order n = omax - q.
             // The home slot of every order is read together with its payload in one round
             // trip; only a key that was displaced by linear probing needs further probes.
