@@ -156,6 +156,46 @@ def test_full_shape_rows_sampled(gpu):
     g.close()
 
 
+def test_largest_config_rows_sampled(gpu):
+    """BASELINE configs[4] at its full size (B=128, N=128, V=152064, bf16, K=32, T=0.8: 16384 rows, 4.98 GB of
+    logits) in one verify; the oracle checks sampled rows one by one, torch checks every row's maximum."""
+    binding, lockstep = gpu
+    w = synth.Workload("cfg5", run_steps=1)
+    assert (w.B, w.N, w.K) == (128, 128, 32)
+    g = binding.Stand(w.V, w.B, 1, 5, w.K, w.parent, w.T, 1 << 16, 64, 13, binding.STAND_BF16)
+    gen = torch.Generator(device="cuda").manual_seed(4321)
+    lg = torch.empty((w.B, w.N, w.V), device="cuda", dtype=torch.bfloat16)
+    for b0 in range(0, w.B, 16):                       # generated in slices: the float32 noise of all rows would be 10 GB
+        x = torch.randn((16, w.N, w.V), generator=gen, device="cuda", dtype=torch.float32) * (3 ** 0.5)
+        peak = torch.randint(0, w.V, (16, w.N, 3), generator=gen, device="cuda")
+        x.scatter_add_(2, peak, torch.full(peak.shape, 8.0, device="cuda"))
+        lg[b0:b0 + 16] = x.to(torch.bfloat16)
+        del x
+    out_tok, out_node, out_len, d = g.new_outputs()
+    _say("largest config: verify over %d rows" % (w.B * w.N))
+    g.verify(0, lg, out_tok, out_node, out_len)
+    torch.cuda.synchronize()
+    m, s, idx, p = g.row_results()
+    assert torch.equal(m, lg.view(w.B * w.N, w.V).max(dim=1).values.float())
+    assert bool(((idx >= 0) & (idx < w.V)).all()) and bool((p[:, 1:] <= p[:, :-1]).all())
+    m, s, idx, p = (t.cpu().numpy() for t in (m, s, idx, p))
+    flat = lg.view(torch.int16).view(w.B * w.N, w.V)
+    rows = [0, 127, 128, 8191, 16383] + [int(x) for x in np.random.default_rng(1).integers(0, w.B * w.N, 7)]
+    for r in rows:
+        row = flat[r].cpu().numpy().view(np.uint16)
+        oi, op, om, os_ = oracle.row_obs(row, w.T, w.K)
+        assert np.array_equal(idx[r], oi) and m[r] == om
+        assert np.all(np.abs(p[r] / op - 1) < 1e-5) and abs(s[r] / os_ - 1) < 1e-5
+    for b in (0, 77, 127):                              # no drafts pending: one token resampled from the root row
+        row = flat[b * w.N].cpu().numpy().view(np.uint16)
+        F = oracle.row_masses(row, w.T)
+        u = oracle.uniform_u64(13, b, 0, 0, oracle.STREAM_BONUS)
+        assert out_tok.cpu().numpy()[b, 0] == oracle.residual_draw(F, int(F.sum()), np.zeros(0, np.int32), None, u)
+    assert np.all(out_len.cpu().numpy() == 1)
+    g.close()
+    del lg
+
+
 def test_full_shape_step(gpu):
     """The configuration bench.py times (B=32, N=64, V=152064, bf16, K=16, orders 1-4), three whole
     stand_step calls in lock step with the oracle: tokens, nodes, lengths, next drafts, table."""
