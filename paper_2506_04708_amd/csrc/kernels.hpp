@@ -1487,7 +1487,17 @@ __global__ __launch_bounds__(64) void merge_apply_kernel(MergeArgs a)
             const unsigned long long key = act ? rank_key(val, (uint32_t)id) : 0ull;
             int rank = 0;
 #pragma unroll
-            for (int q = 0; q < 64; ++q) rank += readlane_u64(key, q) > key ? 1 : 0;
+            for (int q = 0; q < 16; ++q) {
+                rank += readlane_u64(key, q) > key ? 1 : 0;
+                rank += readlane_u64(key, 32 + q) > key ? 1 : 0;
+            }
+            if (K > 16) {  // the other lanes are inactive (key 0) for K <= 16
+#pragma unroll
+                for (int q = 16; q < 32; ++q) {
+                    rank += readlane_u64(key, q) > key ? 1 : 0;
+                    rank += readlane_u64(key, 32 + q) > key ? 1 : 0;
+                }
+            }
             if (act && rank < K) { l_id[rank] = id; l_val[rank] = val; }
             __syncthreads();
             if (lane < K) { e_id = l_id[lane]; e_mu = l_val[lane]; }
@@ -1711,7 +1721,11 @@ __global__ __launch_bounds__(kDraftThreads) void draft_kernel(DraftArgs a)
                 }
                 rank = 0;  // lanes without a candidate hold key 0, which is above no key
 #pragma unroll
-                for (int q = 0; q < kMaxK; ++q) rank += readlane_u64(key, q) > key ? 1 : 0;
+                for (int q = 0; q < kMaxK / 2; ++q) rank += readlane_u64(key, q) > key ? 1 : 0;
+                if (K > kMaxK / 2) {  // lanes K.. hold key 0: the upper half is needed for large K only
+#pragma unroll
+                    for (int q = kMaxK / 2; q < kMaxK; ++q) rank += readlane_u64(key, q) > key ? 1 : 0;
+                }
             }
             if (cand && rank < nch) {
                 const int child = t_first[u] + rank;
