@@ -1573,7 +1573,7 @@ __global__ __launch_bounds__(kDraftThreads) void draft_kernel(DraftArgs a)
     __shared__ int32_t tok[kMaxNodes];
     // recent[u][i]: the token i positions before the end of the sequence that ends at node u
     // (recent[u][0] is the node's own token), so a key is read without walking up the tree
-    __shared__ int32_t recent[kMaxNodes][kMaxOrder];
+    __shared__ __align__(16) int32_t recent[kMaxNodes][kMaxOrder];
     __shared__ int32_t t_first[kMaxNodes], t_nchild[kMaxNodes];
     __shared__ int32_t t_level[kMaxDepth + 3];
     __shared__ long long s_clen;
@@ -1621,10 +1621,23 @@ __global__ __launch_bounds__(kDraftThreads) void draft_kernel(DraftArgs a)
             // ---- multi-level lookup (paper Sec. 4.2): lane q < NO takes order n = omax - q.
             // The home slot of every order is read together with its payload in one round
             // trip; only a key that was displaced by linear probing needs further probes.
+            // The node's recent tokens are the same for every lane: they are read once (two 16-byte
+            // reads), their terms of the fingerprint are formed in scalar registers, and each lane adds
+            // the first n of them by selects -- no lane-dependent branches or dependent reads.
             unsigned long long fp = 0ull;
-            if (lane < NO) {
+            {
+                const int4 r_lo = *(const int4 *)&recent[u][0], r_hi = *(const int4 *)&recent[u][4];
+                const int32_t rt[kMaxOrder] = {r_lo.x, r_lo.y, r_lo.z, r_lo.w, r_hi.x, r_hi.y, r_hi.z, r_hi.w};
                 const int n = a.omax - lane;
-                if (clen + d >= n) fp = fingerprint_newest_first(n, recent[u]);
+                unsigned long long acc = (unsigned long long)(uint32_t)n * 0x2545F4914F6CDD1DULL;
+#pragma unroll
+                for (int i = 0; i < kMaxOrder; ++i) {
+                    const uint32_t x = (uint32_t)__builtin_amdgcn_readfirstlane(rt[i]);
+                    const unsigned long long term = fingerprint_multiplier(i) * ((unsigned long long)x + 1u);
+                    acc += i < n ? term : 0ull;
+                }
+                const unsigned long long hsh = fmix64(acc);
+                if (lane < NO && clen + d >= n) fp = hsh ? hsh : 1ull;
             }
             unsigned long long home_fp = 0ull;
             uint32_t home_cnt = 0;
