@@ -200,10 +200,13 @@ __device__ __forceinline__ NodeResult wave_node_outcome(int lane, int K, int32_t
 }
 
 // ---------------------------------------------------------------------------------------------
-// Row pass: one wave per logits row, no workgroup barriers.  The wave streams its row with
-// kRowPF batches of kRowU 16-byte vectors per lane in flight, keeps a wave-uniform running
-// maximum as the reference of the fast exponentials, and collects top-K candidates (elements
-// not below the current K-th best) in a small per-wave list that is pruned by rank counting.
+// Row pass: kRowWPR waves share one logits row, each streaming every kRowWPR-th batch of it with
+// no synchronisation until the row's end.  A wave keeps kRowPF batches of kRowU 16-byte vectors
+// per lane in flight (non-temporal buffer loads), a wave-uniform running maximum as the reference
+// of the fast exponentials, and a small list of top-K candidates: one (maximum, index) record per
+// vector whose maximum is not below the wave's current threshold, pruned by a ballot bisection.
+// Everything that is the same in all lanes of a wave (reference, threshold, list length, loop
+// counters, the buffer descriptor) is kept in scalar registers.
 // ---------------------------------------------------------------------------------------------
 #ifndef STAND_ROW_U
 #define STAND_ROW_U 3
