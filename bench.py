@@ -269,6 +269,11 @@ def main():
                          % (cpu_n, cpu_s, rows)}
         if cpu_rows:
             cpu["row_pass_all_cores"] = cpu_rows
+        try:
+            model = [l.split(":", 1)[1].strip() for l in open("/proc/cpuinfo") if l.startswith("model name")]
+            cpu["host"] = "%s, %d logical CPUs, %d usable by this process" % (model[0], len(model), len(os.sched_getaffinity(0)))
+        except (OSError, IndexError):
+            pass
 
     out = {
         "metric": "speculation steps/s (stand_step: verify + table merge + draft), B=%d, V=%d, %d-node tree" % (w.B, w.V, w.N),

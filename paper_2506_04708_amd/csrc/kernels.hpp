@@ -24,11 +24,11 @@
 namespace stand {
 
 constexpr int kDtBf16 = 0, kDtF32 = 1;
-#ifndef STAND_ROW_WPR
-#define STAND_ROW_WPR 4
-#endif
-constexpr int kRowWPR = STAND_ROW_WPR;      // waves that share one logits row (1, 2 or 4)
-constexpr int kRowThreads = 64 * kRowWPR;   // row pass: one row per workgroup
+// Row pass: one row per workgroup of WPR waves.  Four waves per row fill the device when there
+// are thousands of rows; with few rows (one or a few trajectories) a row is spread over sixteen
+// waves so that the pass is not limited by what four waves can keep in flight.
+constexpr int kRowWPR = 4, kRowWPRFewRows = 16;
+constexpr int kRowsFew = 768;               // at most this many rows: kRowWPRFewRows waves per row
 constexpr int kMaxNodes = 1024;
 constexpr int kMaxDepth = 31;
 constexpr int kPathThreads = 256;
@@ -218,14 +218,12 @@ constexpr int kRowU = STAND_ROW_U;     // vectors per lane per batch
 constexpr int kRowPF = STAND_ROW_PF;   // batches in flight per wave
 constexpr int kWaveCap = 192;          // vector records per wave (pruned when above kWavePrune)
 constexpr int kWavePrune = 128;
-constexpr int kRowsPerBlock = 1;
 
 constexpr int kElemCap = 8 * kMaxK + 64;  // element candidates at the end of a row (<= 8 per kept vector + edges)
 
 struct WaveScan {
     unsigned long long buf[kWaveCap + 8];   // vector records: (maximum of the vector, vector index)
     unsigned long long top[kMaxK];      // pruned / final keys, best first
-    unsigned long long ebuf[kElemCap + 8];  // element keys offered to the final selection
 };
 
 // 16-byte load of data that is read once: marked non-temporal so that it does not displace
@@ -545,7 +543,8 @@ __device__ __forceinline__ WavePartial wave_row_stream(const void *rowp, int V, 
 // the largest maxima contain the K best elements; their elements and the row's edge elements
 // are ranked exactly.  Leaves the K best element keys sorted in ws->top[0..K).
 template <int DT>
-__device__ __forceinline__ void wave_row_finish(const void *rowp, int V, int K, WaveScan *ws, int lane, int cnt)
+__device__ __forceinline__ void wave_row_finish(const void *rowp, int V, int K, WaveScan *ws, unsigned long long *ebuf,
+                                                int lane, int cnt)
 {
     constexpr int EPV = VecTraits<DT>::EPV;
     const RowGeom g = row_geom<DT>(rowp, V);
@@ -568,7 +567,7 @@ __device__ __forceinline__ void wave_row_finish(const void *rowp, int V, int K, 
     int ne = 0;
     {
         const unsigned long long eb = __ballot(edge_id >= 0 && edge_val >= th_val);
-        if (edge_id >= 0 && edge_val >= th_val) ws->ebuf[lane_prefix_count(eb)] = rank_key(edge_val, (uint32_t)edge_id);
+        if (edge_id >= 0 && edge_val >= th_val) ebuf[lane_prefix_count(eb)] = rank_key(edge_val, (uint32_t)edge_id);
         ne = __popcll(eb);
         float x[EPV];
         uint32_t vec = 0;
@@ -581,12 +580,12 @@ __device__ __forceinline__ void wave_row_finish(const void *rowp, int V, int K, 
         for (int j = 0; j < EPV; ++j) {
             const bool pred = own && x[j] >= th_val;
             const unsigned long long bal = __ballot(pred);
-            if (pred) ws->ebuf[ne + lane_prefix_count(bal)] = rank_key(x[j], (uint32_t)(g.head + (int)vec * EPV + j));
+            if (pred) ebuf[ne + lane_prefix_count(bal)] = rank_key(x[j], (uint32_t)(g.head + (int)vec * EPV + j));
             ne += __popcll(bal);
         }
     }
     __builtin_amdgcn_wave_barrier();
-    wave_select(ws->ebuf, ws->top, lane, K, ne);
+    wave_select(ebuf, ws->top, lane, K, ne);
 }
 
 // floor(e * 2^40) for e in [0, 1] as hi * 2^20 + lo with hi = floor(e * 2^20) <= 2^20 and
@@ -676,22 +675,23 @@ struct RowPassArgs {
     bool onehot;                // deterministic drafting: one-hot proposals in the accept tests
 };
 
-template <int DT>
-__global__ __launch_bounds__(kRowThreads) void row_pass_kernel(RowPassArgs a)
+template <int DT, int WPR>
+__global__ __launch_bounds__(64 * WPR) void row_pass_kernel(RowPassArgs a)
 {
     constexpr int ES = VecTraits<DT>::ES;
-    __shared__ WaveScan wsh[kRowThreads / 64];
-    __shared__ float part_m[kRowThreads / 64], part_s[kRowThreads / 64];
-    __shared__ int part_cnt[kRowThreads / 64];
+    __shared__ WaveScan wsh[WPR];
+    __shared__ unsigned long long ebuf[kElemCap + 8];  // element keys offered to the row's final selection
+    __shared__ float part_m[WPR], part_s[WPR];
+    __shared__ int part_cnt[WPR];
     // the wave's number is the same in all its lanes: say so, so that everything derived from it
     // (its share of the row, the loop over its batches) is kept in scalar registers
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    const int wsub = wave % kRowWPR;
+    const int wsub = wave;
     // Workgroups are numbered node-major (all trajectories' rows of node 0, then of node 1, ...).
     // The nodes near the root carry drafted children, whose accept tests make the end of their
     // row the longest; started first, those ends overlap with the streaming of later rows, and the
     // rows that finish the kernel are leaves.
-    const int slot = blockIdx.x * kRowsPerBlock + wave / kRowWPR;
+    const int slot = blockIdx.x;
     const int row = slot < a.B * a.N ? (slot % a.B) * a.N + slot / a.B : slot;
     const bool live = row < a.B * a.N;
     WaveScan *ws = &wsh[wave];
@@ -738,18 +738,18 @@ __global__ __launch_bounds__(kRowThreads) void row_pass_kernel(RowPassArgs a)
         if (lane == 0) a.outcome[row] = nr.accepted;
     };
     // the wave of a row that runs the accept tests: the second one where a row has several
-    constexpr int kTestWave = kRowWPR >= 2 ? 1 : 0;
-    if constexpr (kRowWPR == 1) {
+    constexpr int kTestWave = WPR >= 2 ? 1 : 0;
+    if constexpr (WPR == 1) {
         if (!live) return;  // whole wave; no workgroup barrier in this configuration
         const WavePartial wp = wave_row_stream<DT>(rowp, a.V, a.c, a.K, ws, lane, 0, 1);
         request_proposal();
         request_proposal_logits();
-        wave_row_finish<DT>(rowp, a.V, a.K, ws, lane, wp.cnt);
+        wave_row_finish<DT>(rowp, a.V, a.K, ws, ebuf, lane, wp.cnt);
         m = rank_key_value(ws->top[0]);
         s = wp.s * fast_exp2((wp.m_ref - m) * a.c);  // m_ref equals m: the factor is 1
     } else {
         if (live) {
-            const WavePartial wp = wave_row_stream<DT>(rowp, a.V, a.c, a.K, ws, lane, wsub, kRowWPR);
+            const WavePartial wp = wave_row_stream<DT>(rowp, a.V, a.c, a.K, ws, lane, wsub, WPR);
             if (lane == 0) { part_m[wave] = wp.m_ref; part_s[wave] = wp.s; part_cnt[wave] = wp.cnt; }
             if (wsub == kTestWave) request_proposal();
         }
@@ -760,27 +760,36 @@ __global__ __launch_bounds__(kRowThreads) void row_pass_kernel(RowPassArgs a)
             // them while the first wave ranks.  Same expressions as below, so both waves hold the same m, s.
             request_proposal_logits();
             float mt = part_m[wave - kTestWave];
-            for (int q = 1; q < kRowWPR; ++q) mt = fmaxf(mt, part_m[wave - kTestWave + q]);
+            for (int q = 1; q < WPR; ++q) mt = fmaxf(mt, part_m[wave - kTestWave + q]);
             mt = mt + 0.0f;  // the ranking's maximum has no negative zero
             float st = 0.0f;
-            for (int q = 0; q < kRowWPR; ++q) st += part_s[wave - kTestWave + q] * fast_exp2((part_m[wave - kTestWave + q] - mt) * a.c);
+            for (int q = 0; q < WPR; ++q) st += part_s[wave - kTestWave + q] * fast_exp2((part_m[wave - kTestWave + q] - mt) * a.c);
             node_tests(mt, st);
             return;
         }
         if (wsub != 0) return;
         if (kTestWave == 0) request_proposal_logits();
-        // gather the partner waves' records behind this wave's own (each list holds at most K + kPruneSlack)
+        // gather the partner waves' records behind this wave's own (each list holds at most
+        // K + kPruneSlack ranking keys); with many partners the list is cut down on the way
         int cnt = part_cnt[wave];
-        for (int q = 1; q < kRowWPR; ++q) {
+        for (int q = 1; q < WPR; ++q) {
             const int cq = part_cnt[wave + q];
+            if (cnt + cq > kWavePrune) {
+                WaveScanState gs;
+                gs.cnt = cnt;
+                set_theta(gs, 0ull);
+                __builtin_amdgcn_wave_barrier();
+                wave_prune_fast<false, true, DT == kDtBf16 ? 16 : 0>(ws, gs, lane, a.K, 0u, ~0u);
+                cnt = gs.cnt;
+            }
             if (lane < cq) ws->buf[cnt + lane] = wsh[wave + q].buf[lane];
             cnt += cq;
         }
         __builtin_amdgcn_wave_barrier();
-        wave_row_finish<DT>(rowp, a.V, a.K, ws, lane, cnt);
+        wave_row_finish<DT>(rowp, a.V, a.K, ws, ebuf, lane, cnt);
         m = rank_key_value(ws->top[0]);
         s = 0.0f;
-        for (int q = 0; q < kRowWPR; ++q) s += part_s[wave + q] * fast_exp2((part_m[wave + q] - m) * a.c);
+        for (int q = 0; q < WPR; ++q) s += part_s[wave + q] * fast_exp2((part_m[wave + q] - m) * a.c);
     }
 
     if (lane < a.K) {
@@ -1051,6 +1060,7 @@ __global__ __launch_bounds__(256) void commit_scan_kernel(CommitScanArgs a)
 {
     constexpr int ES = VecTraits<DT>::ES;
     __shared__ WaveScan wsh[4];
+    __shared__ unsigned long long ebuf[kElemCap + 8];
     __shared__ int part_cnt[4];
     const int j = blockIdx.x, b = blockIdx.y, lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     int node;
@@ -1077,7 +1087,7 @@ __global__ __launch_bounds__(256) void commit_scan_kernel(CommitScanArgs a)
         cnt += cq;
     }
     __builtin_amdgcn_wave_barrier();
-    wave_row_finish<DT>(rowp, a.V, a.K, ws, lane, cnt);
+    wave_row_finish<DT>(rowp, a.V, a.K, ws, ebuf, lane, cnt);
     const size_t src = (size_t)b * a.R + j;
     if (lane < a.K) {
         a.pr_top_idx[src * a.K + lane] = (int32_t)rank_key_id(ws->top[lane]);

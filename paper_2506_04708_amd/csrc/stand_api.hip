@@ -282,21 +282,22 @@ static int launch_row_pass(stand_handle *h, uint64_t step, const void *d_logits,
     a.row_m = h->row_m; a.row_s = h->row_s; a.top_idx = h->top_idx; a.top_l = h->top_l; a.top_p = h->top_p;
     a.outcome = h->outcome; a.stats = h->stats;
     a.onehot = h->cfg.draft_mode == STAND_DRAFT_DETERMINISTIC;
-    const dim3 grid((unsigned)((h->B * h->N + kRowsPerBlock - 1) / kRowsPerBlock)), block(kRowThreads);
+    const int rows = h->B * h->N;
+    const bool few = rows <= kRowsFew;  // one workgroup per row; more waves per row when rows are few
+    const bool bf16 = h->cfg.logits_dtype == STAND_BF16;
+    const dim3 grid((unsigned)rows), block(64u * (unsigned)(few ? kRowWPRFewRows : kRowWPR));
+    const void *fn = bf16 ? (few ? (const void *)row_pass_kernel<kDtBf16, kRowWPRFewRows> : (const void *)row_pass_kernel<kDtBf16, kRowWPR>)
+                          : (few ? (const void *)row_pass_kernel<kDtF32, kRowWPRFewRows> : (const void *)row_pass_kernel<kDtF32, kRowWPR>);
+    void *args[] = {&a};
     const bool timed = h->profiling && h->ev_used < h->ev_begin.size();
     if (timed) {
         // the events are attached to the dispatch itself: their difference is the kernel's own
         // start-to-end time, without the marker packets a hipEventRecord pair would add
         hipEvent_t e0 = h->ev_begin[h->ev_used], e1 = h->ev_end[h->ev_used];
         h->ev_used++;
-        void *args[] = {&a};
-        const void *fn = h->cfg.logits_dtype == STAND_BF16 ? (const void *)row_pass_kernel<kDtBf16>
-                                                           : (const void *)row_pass_kernel<kDtF32>;
         HIP_TRY(h, hipExtLaunchKernel(fn, grid, block, args, 0, s, e0, e1, 0));
-    } else if (h->cfg.logits_dtype == STAND_BF16) {
-        row_pass_kernel<kDtBf16><<<grid, block, 0, s>>>(a);
     } else {
-        row_pass_kernel<kDtF32><<<grid, block, 0, s>>>(a);
+        HIP_TRY(h, hipLaunchKernel(fn, grid, block, args, 0, s));
     }
     HIP_TRY(h, hipGetLastError());
     return STAND_OK;
