@@ -375,7 +375,8 @@ def test_bad_arguments_are_rejected(gpu):
               table_capacity=64, max_probe=8, seed=1, logits_dtype=binding.STAND_F32)
     for bad in [dict(temperature=0.0), dict(topk=1), dict(topk=33), dict(table_capacity=100), dict(order_max=9),
                 dict(tree_parent=np.array([-1, 1, 0], np.int32)), dict(tree_parent=np.array([-1, 0, 1, 0], np.int32)),
-                dict(vocab=3), dict(max_probe=0), dict(logits_dtype=7)]:
+                dict(vocab=3), dict(max_probe=0), dict(logits_dtype=7), dict(draft_mode=3), dict(update_mode=2),
+                dict(merge_policy=2), dict(vocab=1 << 22)]:
         with pytest.raises(binding.StandError):
             binding.Stand(**{**ok, **bad})
     g = binding.Stand(**ok)
