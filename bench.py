@@ -11,7 +11,10 @@ Procedure (all inputs are generated on the GPU before the timed region):
   2. record: the next warmup+steps steps are run once while their logits stay resident in HBM;
   3. timed: a second handle that starts from a copy of the state reached after (1) replays the
      recorded steps back to back; the wall clock around the last `--steps` of them is the
-     result, and its outputs must equal the recorded ones.
+     result, and its outputs must equal the recorded ones.  (2) and (3) alternate in chunks of
+     as many steps as fit the free memory (one chunk at the defaults: 200 x 623 MB); the second
+     handle repeats exactly what the first did, so the next chunk continues from equal states,
+     and the timed spans of the chunks are added.
 Also printed: the row pass's achieved HBM bandwidth from HIP events recorded inside the
 library around that kernel (same timed region), and the CPU oracle timed on the first steps
 of the same workload on the host.
@@ -55,7 +58,7 @@ def force_tokens(np, w):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=48)
+    ap.add_argument("--steps", type=int, default=192)
     ap.add_argument("--warmup", type=int, default=8)
     ap.add_argument("--table-warm", type=int, default=200)
     ap.add_argument("--workload", default="cfg3")
@@ -175,64 +178,87 @@ def main():
     for b in range(w.B):
         tail, ln_ctx = h1.get_context(b, binding.MAX_ORDER)
         h2.set_context(b, tail)
-    # ---- 2. record ------------------------------------------------------------------------------------
-    rec = []
-    for step in range(T_warm, total):
-        d_host = draft.cpu().numpy()
-        lg = gen_logits(torch, w, step, d_host, gen)
-        force = torch.from_numpy(force_tokens(np, w)).cuda()
-        h1.step(step, lg, out_tok, out_node, out_len, draft, force)
-        ln = out_len.cpu().numpy()
-        w.commit(ln)
-        lens.append(ln.mean())
-        rec.append((lg, force, out_tok.clone(), out_len.clone(), draft.clone()))
-    torch.cuda.synchronize()
-    prep_s = time.time() - t0
-    # ---- 3. timed replay ----------------------------------------------------------------------------------
-    o_tok = [torch.empty_like(out_tok) for _ in rec]
-    o_node = [torch.empty_like(out_node) for _ in rec]
-    o_len = [torch.empty_like(out_len) for _ in rec]
-    o_draft = [torch.empty_like(draft) for _ in rec]
-    if args.calib_copy:
-        src = rec[0][0]
-        dst = torch.empty_like(src)
-        for _ in range(3):
-            binding.copy_bytes(dst, src, src.numel() * src.element_size())
-        torch.cuda.synchronize()
-        del dst
-    h2.draft(T_warm, draft)
-    for i in range(W_steps):
-        lg, force, *_ = rec[i]
-        h2.step(T_warm + i, lg, o_tok[i], o_node[i], o_len[i], o_draft[i], force)
-    if not args.no_events:
-        h2.profile_begin(K_steps)
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    for i in range(W_steps, W_steps + K_steps):
-        lg, force, *_ = rec[i]
-        h2.step(T_warm + i, lg, o_tok[i], o_node[i], o_len[i], o_draft[i], force)
-    torch.cuda.synchronize()
-    t2 = time.perf_counter()
-    row_ms, row_n = (0.0, 0) if args.no_events else h2.profile_end()
-    for i, (lg, force, r_tok, r_len, r_draft) in enumerate(rec):
-        assert torch.equal(o_len[i], r_len) and torch.equal(o_tok[i], r_tok) and torch.equal(o_draft[i], r_draft), \
-            "replay diverged from the recorded run at step %d" % i
-    # floor of a kernel that only fetches one step's logits, in the row pass's launch shape
+    # ---- 2./3. record a chunk of steps with their logits resident in HBM, then replay it on the second
+    # handle; the replay of the steps after the warm-up is what is timed.  The steps are taken in chunks
+    # so that any --steps fits the memory: the second handle repeats exactly what the first did, so after
+    # a chunk both hold the same state and the next chunk continues from it.  One chunk at the defaults.
+    logits_bytes_1 = w.B * w.N * w.V * 2
+    free_b = torch.cuda.mem_get_info()[0]
+    chunk_cap = max(8, int(0.45 * free_b / logits_bytes_1))
+    n_after = W_steps + K_steps
+    h2.draft(T_warm, draft2 := torch.empty_like(draft))
+    timed_s = issue_s = 0.0
+    done = 0
+    n_chunks = 0
     read_us = None
-    if (w.V * 2) % 16 == 0:
-        sink = torch.zeros(4 * w.B * w.N, dtype=torch.int32, device="cuda")
-        ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
-        reps = 20
-        for r in range(3 + reps):
-            if r == 3:
-                ev[0].record()
-            binding.read_rows(rec[r % len(rec)][0], w.V * 2, w.B * w.N, sink, torch.cuda.current_stream().cuda_stream)
-        ev[1].record()
+    prep_s = time.time() - t0
+    while done < n_after:
+        n = min(chunk_cap, n_after - done)
+        c0 = time.time()
+        rec = []
+        for i in range(n):
+            step = T_warm + done + i
+            d_host = draft.cpu().numpy()
+            lg = gen_logits(torch, w, step, d_host, gen)
+            force = torch.from_numpy(force_tokens(np, w)).cuda()
+            h1.step(step, lg, out_tok, out_node, out_len, draft, force)
+            ln = out_len.cpu().numpy()
+            w.commit(ln)
+            lens.append(ln.mean())
+            rec.append((lg, force, out_tok.clone(), out_len.clone(), draft.clone()))
         torch.cuda.synchronize()
-        read_us = ev[0].elapsed_time(ev[1]) * 1e3 / reps
+        prep_s += time.time() - c0
+        o_tok = [torch.empty_like(out_tok) for _ in rec]
+        o_node = [torch.empty_like(out_node) for _ in rec]
+        o_len = [torch.empty_like(out_len) for _ in rec]
+        o_draft = [torch.empty_like(draft) for _ in rec]
+        if args.calib_copy and done == 0:
+            src = rec[0][0]
+            dst = torch.empty_like(src)
+            for _ in range(3):
+                binding.copy_bytes(dst, src, src.numel() * src.element_size())
+            torch.cuda.synchronize()
+            del dst
+        n_untimed = max(0, min(n, W_steps - done))      # warm-up steps that fall into this chunk
+        for i in range(n_untimed):
+            lg, force, *_ = rec[i]
+            h2.step(T_warm + done + i, lg, o_tok[i], o_node[i], o_len[i], o_draft[i], force)
+        if n > n_untimed:
+            if not args.no_events and done + n_untimed == W_steps:
+                h2.profile_begin(K_steps)
+            torch.cuda.synchronize()
+            t1 = time.perf_counter()
+            for i in range(n_untimed, n):
+                lg, force, *_ = rec[i]
+                h2.step(T_warm + done + i, lg, o_tok[i], o_node[i], o_len[i], o_draft[i], force)
+            t_issued = time.perf_counter()
+            torch.cuda.synchronize()
+            t2 = time.perf_counter()
+            timed_s += t2 - t1
+            issue_s += t_issued - t1
+            n_chunks += 1
+        for i, (lg, force, r_tok, r_len, r_draft) in enumerate(rec):
+            assert torch.equal(o_len[i], r_len) and torch.equal(o_tok[i], r_tok) and torch.equal(o_draft[i], r_draft), \
+                "replay diverged from the recorded run at step %d" % (done + i)
+        done += n
+        if done >= n_after and (w.V * 2) % 16 == 0:
+            # floor of a kernel that only fetches one step's logits, in the row pass's launch shape
+            sink = torch.zeros(4 * w.B * w.N, dtype=torch.int32, device="cuda")
+            ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+            reps = 20
+            for r in range(3 + reps):
+                if r == 3:
+                    ev[0].record()
+                binding.read_rows(rec[r % len(rec)][0], w.V * 2, w.B * w.N, sink, torch.cuda.current_stream().cuda_stream)
+            ev[1].record()
+            torch.cuda.synchronize()
+            read_us = ev[0].elapsed_time(ev[1]) * 1e3 / reps
+        del rec, o_tok, o_node, o_len, o_draft
+    row_ms, row_n = (0.0, 0) if args.no_events else h2.profile_end()
+    n_rec = n_after
     st = h2.stats()
-    ms_per_step = (t2 - t1) * 1e3 / K_steps
-    steps_per_s = K_steps / (t2 - t1)
+    ms_per_step = timed_s * 1e3 / K_steps
+    steps_per_s = K_steps / timed_s
 
     rows = w.B * w.N
     logits_bytes = rows * w.V * 2
@@ -292,8 +318,9 @@ def main():
         "hbm_frac_of_peak": round(step_bytes * steps_per_s / 1e9 / HBM_PEAK_GBPS, 4),
         "bytes_per_step": step_bytes,
         "roofline": roof, "cpu_baseline": cpu,
-        "table_updates_per_step": round((st.inserts + st.merges) / max(len(rec), 1), 1),
+        "table_updates_per_step": round((st.inserts + st.merges) / max(n_rec, 1), 1),
         "near_threshold_fallbacks": int(st.near_threshold), "filter_mismatch": int(st.filter_mismatch),
+        "host_issue_ms_per_step": round(issue_s * 1e3 / K_steps, 4), "timed_chunks": n_chunks,
         "prep_seconds": round(prep_s, 1),
     }
     print(json.dumps(out))

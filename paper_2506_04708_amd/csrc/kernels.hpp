@@ -686,7 +686,6 @@ __global__ __launch_bounds__(64 * WPR) void row_pass_kernel(RowPassArgs a)
     // the wave's number is the same in all its lanes: say so, so that everything derived from it
     // (its share of the row, the loop over its batches) is kept in scalar registers
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    const int wsub = wave;
     // Workgroups are numbered node-major (all trajectories' rows of node 0, then of node 1, ...).
     // The nodes near the root carry drafted children, whose accept tests make the end of their
     // row the longest; started first, those ends overlap with the streaming of later rows, and the
@@ -737,60 +736,48 @@ __global__ __launch_bounds__(64 * WPR) void row_pass_kernel(RowPassArgs a)
         }
         if (lane == 0) a.outcome[row] = nr.accepted;
     };
-    // the wave of a row that runs the accept tests: the second one where a row has several
-    constexpr int kTestWave = WPR >= 2 ? 1 : 0;
-    if constexpr (WPR == 1) {
-        if (!live) return;  // whole wave; no workgroup barrier in this configuration
-        const WavePartial wp = wave_row_stream<DT>(rowp, a.V, a.c, a.K, ws, lane, 0, 1);
-        request_proposal();
-        request_proposal_logits();
-        wave_row_finish<DT>(rowp, a.V, a.K, ws, ebuf, lane, wp.cnt);
-        m = rank_key_value(ws->top[0]);
-        s = wp.s * fast_exp2((wp.m_ref - m) * a.c);  // m_ref equals m: the factor is 1
-    } else {
-        if (live) {
-            const WavePartial wp = wave_row_stream<DT>(rowp, a.V, a.c, a.K, ws, lane, wsub, WPR);
-            if (lane == 0) { part_m[wave] = wp.m_ref; part_s[wave] = wp.s; part_cnt[wave] = wp.cnt; }
-            if (wsub == kTestWave) request_proposal();
-        }
-        __syncthreads();
-        if (!live) return;
-        if (kTestWave != 0 && wsub == kTestWave) {
-            // the accept tests need the row's maximum and normaliser, not its ranking: this wave runs
-            // them while the first wave ranks.  Same expressions as below, so both waves hold the same m, s.
-            request_proposal_logits();
-            float mt = part_m[wave - kTestWave];
-            for (int q = 1; q < WPR; ++q) mt = fmaxf(mt, part_m[wave - kTestWave + q]);
-            mt = mt + 0.0f;  // the ranking's maximum has no negative zero
-            float st = 0.0f;
-            for (int q = 0; q < WPR; ++q) st += part_s[wave - kTestWave + q] * fast_exp2((part_m[wave - kTestWave + q] - mt) * a.c);
-            node_tests(mt, st);
-            return;
-        }
-        if (wsub != 0) return;
-        if (kTestWave == 0) request_proposal_logits();
-        // gather the partner waves' records behind this wave's own (each list holds at most
-        // K + kPruneSlack ranking keys); with many partners the list is cut down on the way
-        int cnt = part_cnt[wave];
-        for (int q = 1; q < WPR; ++q) {
-            const int cq = part_cnt[wave + q];
-            if (cnt + cq > kWavePrune) {
-                WaveScanState gs;
-                gs.cnt = cnt;
-                set_theta(gs, 0ull);
-                __builtin_amdgcn_wave_barrier();
-                wave_prune_fast<false, true, DT == kDtBf16 ? 16 : 0>(ws, gs, lane, a.K, 0u, ~0u);
-                cnt = gs.cnt;
-            }
-            if (lane < cq) ws->buf[cnt + lane] = wsh[wave + q].buf[lane];
-            cnt += cq;
-        }
-        __builtin_amdgcn_wave_barrier();
-        wave_row_finish<DT>(rowp, a.V, a.K, ws, ebuf, lane, cnt);
-        m = rank_key_value(ws->top[0]);
-        s = 0.0f;
-        for (int q = 0; q < WPR; ++q) s += part_s[wave + q] * fast_exp2((part_m[wave + q] - m) * a.c);
+    // Wave 0 ranks the row at its end, wave 1 runs the accept tests meanwhile.
+    static_assert(WPR >= 2, "a row is shared by at least two waves");
+    constexpr int kTestWave = 1;
+    if (live) {
+        const WavePartial wp = wave_row_stream<DT>(rowp, a.V, a.c, a.K, ws, lane, wave, WPR);
+        if (lane == 0) { part_m[wave] = wp.m_ref; part_s[wave] = wp.s; part_cnt[wave] = wp.cnt; }
+        if (wave == kTestWave) request_proposal();
     }
+    __syncthreads();
+    if (!live) return;
+    // both finishing waves form the row's maximum and normaliser with the same expressions, so
+    // they hold the same m and s (the ranking's maximum, top[0], has no negative zero either)
+    m = part_m[0];
+    for (int q = 1; q < WPR; ++q) m = fmaxf(m, part_m[q]);
+    m = m + 0.0f;
+    s = 0.0f;
+    for (int q = 0; q < WPR; ++q) s += part_s[q] * fast_exp2((part_m[q] - m) * a.c);
+    if (wave == kTestWave) {
+        // the accept tests need the row's maximum and normaliser, not its ranking
+        request_proposal_logits();
+        node_tests(m, s);
+        return;
+    }
+    if (wave != 0) return;
+    // gather the partner waves' records behind this wave's own (each list holds at most
+    // K + kPruneSlack ranking keys); with many partners the list is cut down on the way
+    int cnt = part_cnt[0];
+    for (int q = 1; q < WPR; ++q) {
+        const int cq = part_cnt[q];
+        if (cnt + cq > kWavePrune) {
+            WaveScanState gs;
+            gs.cnt = cnt;
+            set_theta(gs, 0ull);
+            __builtin_amdgcn_wave_barrier();
+            wave_prune_fast<false, true, DT == kDtBf16 ? 16 : 0>(ws, gs, lane, a.K, 0u, ~0u);
+            cnt = gs.cnt;
+        }
+        if (lane < cq) ws->buf[cnt + lane] = wsh[q].buf[lane];
+        cnt += cq;
+    }
+    __builtin_amdgcn_wave_barrier();
+    wave_row_finish<DT>(rowp, a.V, a.K, ws, ebuf, lane, cnt);
 
     if (lane < a.K) {
         const unsigned long long key = ws->top[lane];
@@ -800,7 +787,6 @@ __global__ __launch_bounds__(64 * WPR) void row_pass_kernel(RowPassArgs a)
         a.top_p[(size_t)row * a.K + lane] = exact_exp2(scaled_offset(l, m, a.c)) / s;
     }
     if (lane == 0) { a.row_m[row] = m; a.row_s[row] = s; }
-    if (kTestWave == 0) node_tests(m, s);
 }
 
 // ---------------------------------------------------------------------------------------------
