@@ -195,6 +195,13 @@ int stand_get_stats(stand_handle *h, stand_stats *out);
  * stand_verify / stand_step is bracketed by a pair of HIP events on the caller's stream.
  * stand_profile_end synchronises the device, returns the summed event time in milliseconds
  * and the number of launches measured, and switches the timing off. */
+/* Accept tests are first decided with a fast normaliser of the row whose relative error is below
+ * 5e-5; a test whose margin is smaller than the assumed error is decided again with the exact
+ * normaliser (counted in stand_stats.near_threshold), so results never depend on this value.
+ * `margin` in [5e-5, 1] replaces the assumed error for later calls: a larger value only sends
+ * more tests to the exact path (1 sends practically all of them).  STAND_EINVAL outside the range. */
+int stand_set_filter_margin(stand_handle *h, float margin);
+
 int stand_profile_begin(stand_handle *h, int32_t max_launches);
 int stand_profile_end(stand_handle *h, double *row_pass_ms_total, int32_t *launches);
 

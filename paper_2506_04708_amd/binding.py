@@ -22,7 +22,7 @@ EXPORTED = [
     "stand_create", "stand_destroy", "stand_depth", "stand_set_context", "stand_reorder", "stand_update",
     "stand_draft", "stand_verify", "stand_step", "stand_row_results", "stand_table_export", "stand_table_import",
     "stand_get_context", "stand_get_stats", "stand_strerror", "stand_last_hip_error",
-    "stand_profile_begin", "stand_profile_end", "stand_copy_bytes", "stand_read_rows",
+    "stand_profile_begin", "stand_profile_end", "stand_copy_bytes", "stand_read_rows", "stand_set_filter_margin",
     "stand_tree_initial", "stand_tree_select", "stand_get_node_counts", "stand_reset_node_counts",
     "stand_tree_packing",
 ]
@@ -67,6 +67,7 @@ def load_library():
     lib.stand_table_import.argtypes = [vp, vp, C.c_uint64]
     lib.stand_get_context.argtypes = [vp, C.c_int32, i32p, C.c_int32, C.POINTER(C.c_int64), vp]
     lib.stand_get_stats.argtypes = [vp, C.POINTER(Stats)]
+    lib.stand_set_filter_margin.argtypes = [vp, C.c_float]
     lib.stand_profile_begin.argtypes = [vp, C.c_int32]
     lib.stand_profile_end.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_int32)]
     lib.stand_copy_bytes.argtypes = [vp, vp, C.c_uint64, vp]
@@ -251,6 +252,9 @@ class Stand:
         ln = C.c_int64(0)
         _check(lib().stand_get_context(self.h, b, out.ctypes.data_as(C.c_void_p), n, C.byref(ln), _stream_ptr()), self.h)
         return out[:n], int(ln.value)
+
+    def set_filter_margin(self, margin):
+        _check(lib().stand_set_filter_margin(self.h, margin), self.h)
 
     def profile_begin(self, max_launches):
         _check(lib().stand_profile_begin(self.h, max_launches), self.h)

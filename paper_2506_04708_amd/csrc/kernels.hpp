@@ -673,6 +673,7 @@ struct RowPassArgs {
     int32_t *outcome;           // [B*N] accepted child rank or -1
     unsigned long long *stats;
     bool onehot;                // deterministic drafting: one-hot proposals in the accept tests
+    float eps;                  // relative error assumed for the fast normaliser (>= kFastEps)
 };
 
 template <int DT, int WPR>
@@ -725,7 +726,7 @@ __global__ __launch_bounds__(64 * WPR) void row_pass_kernel(RowPassArgs a)
         }
         const float e = (lane < a.K && my_id >= 0) ? exact_exp2(scaled_offset(my_l, m, a.c)) : 0.0f;
         NodeResult nr = wave_node_outcome(lane, a.K, my_id, my_mu, e / s, nch, ch, a.seed, (uint32_t)b, a.step, fc,
-                                          true, kFastEps, a.onehot);
+                                          true, a.eps, a.onehot);
         if (nr.near) {
             // a test fell inside the error bound of the fast normaliser: decide with the exact one
             const unsigned long long S = wave_row_exact_sum<DT>(rowp, a.V, m, a.c, lane);

@@ -43,6 +43,7 @@ struct stand_handle {
     bool table_used;
     // optional timing of the row pass: event pairs recorded on the caller's stream
     bool profiling;
+    float filter_margin;  // relative error assumed for the fast normaliser in the accept tests
     std::vector<hipEvent_t> ev_begin, ev_end;
     size_t ev_used;
 };
@@ -122,6 +123,7 @@ extern "C" int stand_create(const stand_config *cfg, stand_handle **out)
     h->last_hip = 0;
     h->table_used = false;
     h->profiling = false;
+    h->filter_margin = kFastEps;
     h->ev_used = 0;
 
     // tree: breadth-first numbering with contiguous siblings <=> parents non-decreasing
@@ -282,6 +284,7 @@ static int launch_row_pass(stand_handle *h, uint64_t step, const void *d_logits,
     a.row_m = h->row_m; a.row_s = h->row_s; a.top_idx = h->top_idx; a.top_l = h->top_l; a.top_p = h->top_p;
     a.outcome = h->outcome; a.stats = h->stats;
     a.onehot = h->cfg.draft_mode == STAND_DRAFT_DETERMINISTIC;
+    a.eps = h->filter_margin;
     const int rows = h->B * h->N;
     const bool few = rows <= kRowsFew;  // one workgroup per row; more waves per row when rows are few
     const bool bf16 = h->cfg.logits_dtype == STAND_BF16;
@@ -578,6 +581,13 @@ extern "C" int stand_get_stats(stand_handle *h, stand_stats *out)
     out->misses = st[kStatMisses]; out->inserts = st[kStatInserts]; out->merges = st[kStatMerges];
     out->drops = st[kStatDrops]; out->near_threshold = st[kStatNear]; out->tokens_emitted = st[kStatTokens];
     out->accept_tests = st[kStatTests]; out->filter_mismatch = st[kStatMismatch];
+    return STAND_OK;
+}
+
+extern "C" int stand_set_filter_margin(stand_handle *h, float margin)
+{
+    if (!h || !(margin >= kFastEps) || !(margin <= 1.0f)) return STAND_EINVAL;
+    h->filter_margin = margin;
     return STAND_OK;
 }
 

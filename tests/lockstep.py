@@ -70,6 +70,8 @@ def run_lockstep(w, steps, mode="separate", capacity=1 << 12, check_rows=True, t
     """mode "separate": stand_verify / stand_update / stand_draft; mode "step": stand_step.
     forced=True commits the workload's stream tokens (open-loop replay); False commits what was emitted."""
     o, g = make_pair(w, capacity, max_probe)
+    if w.cfg.get("filter_margin") is not None:
+        g.set_filter_margin(w.cfg["filter_margin"])   # GPU only: how many accept tests take the exact path
     for b in range(w.B):
         o.set_context(b, w.prompt(b))
         g.set_context(b, w.prompt(b))

@@ -43,6 +43,8 @@ def _say(msg):
     ("cfg3", dict(V=5000, B=4, rho=0.8, update_mode=1), 25, "step", True),     # every drafted node's row is merged
     ("cfg1", dict(V=900, B=3, rho=0.7, update_mode=1), 40, "separate", True),  # the same through stand_update
     ("cfg5", dict(V=3000, B=2, rho=0.8, update_mode=1), 10, "step", False),    # 128 nodes, K=32, closed loop
+    ("cfg3", dict(V=48, B=4, rho=0.5), 40, "step", False),                     # 64-node tree, closed loop on a tiny vocabulary: deep acceptance, many rejections
+    ("cfg5", dict(V=64, B=2, rho=0.5), 30, "step", False),                     # 128-node tree, K=32, the same
     ("cfg3", dict(V=5000, B=8, rho=0.8, merge_policy=1), 25, "step", True),    # entries replaced, not averaged
     ("cfg1", dict(V=900, B=3, rho=0.7, merge_policy=1, update_mode=1), 40, "separate", True),  # replace, many records per key
 ])
@@ -54,6 +56,23 @@ def test_lockstep_small(gpu, name, over, steps, mode, forced):
     _say("  -> %s" % info)
     assert info["emitted"] >= steps * w.B
     assert info["worst_rel"] < 1e-5
+
+
+@pytest.mark.parametrize("name,over,steps,mode", [
+    ("cfg3", dict(V=48, B=4, rho=0.5, filter_margin=1.0), 40, "step"),                      # practically every test decided exactly
+    ("cfg3", dict(V=51, B=4, rho=0.5, filter_margin=0.05), 40, "step"),                     # a mix, misaligned rows
+    ("cfg1", dict(V=40, B=4, K=10, rho=0.5, filter_margin=1.0, draft_mode=2), 40, "separate"),  # one-hot proposals, f32
+    ("cfg5", dict(V=3000, B=2, rho=0.8, filter_margin=1.0), 10, "step"),                    # K=32, rows of several batches
+])
+def test_exact_fallback_of_the_accept_tests(gpu, name, over, steps, mode):
+    """Accept tests whose margin is inside the fast normaliser's error bound are decided again with the
+    exact normaliser.  With real inputs that is rare (the lock-step cases above count 0), so the bound is
+    inflated here: the second decision path then runs for most tests and must give the oracle's results."""
+    binding, lockstep = gpu
+    w = synth.Workload(name, run_steps=steps, **over)
+    info = lockstep.run_lockstep(w, steps, mode=mode, capacity=1 << 14, forced=False)
+    _say("exact fallback %s %s -> %s" % (name, over, {k: v for k, v in info.items() if k != "node_counts"}))
+    assert info["near_gpu"] > 10 and info["emitted"] >= steps * w.B
 
 
 def test_lockstep_cfg1_full(gpu):
@@ -382,4 +401,8 @@ def test_bad_arguments_are_rejected(gpu):
     g = binding.Stand(**ok)
     with pytest.raises(binding.StandError):
         g.set_context(5, [1, 2])
+    for bad_margin in (0.0, 1e-6, 1.5, float("nan")):
+        with pytest.raises(binding.StandError):
+            g.set_filter_margin(bad_margin)
+    g.set_filter_margin(0.01)
     g.close()
