@@ -85,6 +85,8 @@ typedef struct {
     float temperature;          /* T > 0; rows are softmax(logits / T) (paper Sec. 5: 0.6)          */
     uint64_t table_capacity;    /* slots, a power of two >= 16                                      */
     int32_t max_probe;          /* linear-probe limit, >= 1; past it an update is dropped+counted   */
+                                /* (which updates of a step are dropped at a nearly full table      */
+                                /* depends on the order in which the step's keys claim their slots) */
     uint64_t seed;              /* key of the counter-based uniforms                                */
     int32_t logits_dtype;       /* STAND_BF16 or STAND_F32                                          */
     int32_t update_mode;        /* STAND_UPDATE_*                                                   */

@@ -38,7 +38,8 @@ def make_pair(w, capacity, max_probe=64, seed=None, order_min=None, order_max=No
 def compare_tables(o, g, K):
     to = o.table_export()
     tg = oracle.parse_table_export(g.table_export(), K)
-    assert len(to) == len(tg), "table sizes differ: oracle %d gpu %d" % (len(to), len(tg))
+    assert len(to) == len(tg), "table sizes differ: oracle %d gpu %d (dropped updates: oracle %d gpu %d)" % (
+        len(to), len(tg), o.stats().drops, g.stats().drops)
     assert np.array_equal(to["fp"], tg["fp"]), "key fingerprints differ"
     assert np.array_equal(to["count"], tg["count"]), "counts differ"
     assert np.array_equal(to["order"], tg["order"]), "orders differ"

@@ -75,6 +75,44 @@ def test_exact_fallback_of_the_accept_tests(gpu, name, over, steps, mode):
     assert info["near_gpu"] > 10 and info["emitted"] >= steps * w.B
 
 
+def _random_config(seed):
+    """A small configuration drawn at random: tree shape, K, vocabulary, orders, temperature, dtype, batch,
+    drafting / update / merge variants."""
+    r = np.random.default_rng(seed)
+    D = int(r.integers(1, 7))
+    caps = [int(r.integers(1, 6))] + [int(r.integers(1, 4)) for _ in range(int(r.integers(0, 3)))]
+    total, width = 1, 1
+    for d in range(D):
+        width *= caps[d] if d < len(caps) else caps[-1]
+        total += width
+    lo = len({()} | {(q,) for q in range(caps[0])} | {tuple([0] * d) for d in range(1, D + 1)})
+    N = int(r.integers(lo, min(total, 48) + 1))
+    K = int(r.integers(max(caps), 33))
+    V = int(r.integers(K, 400))
+    omin = int(r.integers(1, 3))
+    return dict(B=int(r.integers(1, 5)), V=V, dtype=["f32", "bf16"][int(r.integers(2))], N=N, D=D, caps=caps,
+                order_min=omin, order_max=int(r.integers(omin, 7)), K=K, T=float(r.uniform(0.3, 1.5)),
+                rho=float(r.uniform(0.3, 0.9)), seed=1000 + seed, draft_mode=int(r.integers(3)),
+                update_mode=int(r.integers(2)), merge_policy=int(r.integers(2)),
+                filter_margin=[None, 0.05, 1.0][int(r.integers(3))])
+
+
+@pytest.mark.parametrize("seed", range(32))
+def test_lockstep_random_configs(gpu, seed):
+    """Whole steps in lock step with the oracle on configurations drawn at random (closed loop, so that
+    acceptance, rejection and resampling all occur), alternating stand_step and the separate entry points."""
+    binding, lockstep = gpu
+    cfg = _random_config(seed)
+    steps = 24
+    w = synth.Workload(None, run_steps=steps, **cfg)
+    _say("random config %d: %s" % (seed, {k: v for k, v in cfg.items() if k != "seed"}))
+    # capacity far above the number of keys: once updates are dropped at a nearly full table, WHICH keys are
+    # dropped depends on the order of the claims, which is sequential in the oracle and parallel on the GPU
+    info = lockstep.run_lockstep(w, steps, mode=["step", "separate"][seed % 2], capacity=1 << 16, forced=bool(seed % 3 == 0))
+    _say("  -> %s" % {k: v for k, v in info.items() if k != "node_counts"})
+    assert info["emitted"] >= steps * w.B and info["worst_rel"] < 1e-5
+
+
 def test_lockstep_cfg1_full(gpu):
     """BASELINE configs[0] at its real shape: B=1, V=32000, fp32, 16-node tree, 64 steps."""
     binding, lockstep = gpu
