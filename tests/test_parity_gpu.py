@@ -45,6 +45,8 @@ def _say(msg):
     ("cfg5", dict(V=3000, B=2, rho=0.8, update_mode=1), 10, "step", False),    # 128 nodes, K=32, closed loop
     ("cfg3", dict(V=1003, B=13, rho=0.8), 8, "step", True),                    # 832 rows: four waves per row (as at full size), misaligned bf16 rows
     ("cfg3", dict(V=777, B=13, rho=0.8, dtype="f32"), 6, "step", False),       # the same with f32 rows, closed loop
+    ("cfg3", dict(V=48, B=13, rho=0.5), 30, "step", False),                    # 832 rows (four waves per row) and deep acceptance
+    ("cfg5", dict(V=64, B=7, rho=0.5), 16, "step", False),                     # the same on the 128-node tree (896 rows)
     ("cfg3", dict(V=48, B=4, rho=0.5), 40, "step", False),                     # 64-node tree, closed loop on a tiny vocabulary: deep acceptance, many rejections
     ("cfg5", dict(V=64, B=2, rho=0.5), 30, "step", False),                     # 128-node tree, K=32, the same
     ("cfg3", dict(V=5000, B=8, rho=0.8, merge_policy=1), 25, "step", True),    # entries replaced, not averaged
