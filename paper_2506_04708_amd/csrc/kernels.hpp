@@ -920,7 +920,9 @@ __global__ __launch_bounds__(kPathThreads) void path_exact_kernel(PathArgs a)
     __shared__ PathStage stage;
     __shared__ int s_len;
     __shared__ unsigned long long s_part[kPathThreads / 64];
-    const int seg = blockIdx.x, nseg = a.nseg, j = blockIdx.y, b = blockIdx.z, tid = threadIdx.x;
+    // row slots are the slowest grid dimension: the workgroups of slot 0 (every trajectory has that
+    // row) are dispatched before those of the later slots, most of which find no row
+    const int seg = blockIdx.x, nseg = a.nseg, j = blockIdx.z, b = blockIdx.y, tid = threadIdx.x;
     const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // scalar: the same in every lane
     if (seg == nseg) {
         // ---- the extra block of a trajectory (verify only): outputs and the stop record
@@ -964,11 +966,11 @@ __global__ __launch_bounds__(kPathThreads) void path_exact_kernel(PathArgs a)
         }
         return;
     }
-    // ---- partial sums of segment seg of the rows j, j + gridDim.y, ...; the root row needs no walk.
+    // ---- partial sums of segment seg of the rows j, j + gridDim.z, ...; the root row needs no walk.
     // In verify mode the grid has only a few row slots: most paths are short, and a workgroup that
     // finds no row costs a launch slot; longer paths loop.
     int len = -1;  // path length once the walk has been done (verify mode, rows below the root)
-    for (int jj = j; jj < a.R; jj += gridDim.y) {
+    for (int jj = j; jj < a.R; jj += gridDim.z) {
         int node;
         bool staged = false;
         if (a.all_nodes) node = a.draft_tok[(size_t)b * a.N + jj] >= 0 ? jj : -1;
@@ -1183,7 +1185,7 @@ __global__ __launch_bounds__(kFinishThreads) void path_finish_kernel(PathArgs a,
         return;
     }
     __shared__ FinishShared sh;
-    const int j = (int)blockIdx.x % a.R, b = (int)blockIdx.x / a.R;
+    const int j = (int)blockIdx.x / a.B, b = (int)blockIdx.x % a.B;  // slot-major, as in path_exact_kernel
     // Everything whose address depends on (b, j) only is requested at once: the partial sums and,
     // in verify mode, the stop record of the trajectory (used if this turns out to be its stop row).
     const int nseg = a.nseg;
@@ -1426,17 +1428,24 @@ __global__ __launch_bounds__(kFinishThreads) void path_finish_kernel(PathArgs a,
     }
 }
 
-// One wave per record.  The lowest record that claimed a slot (its leader, named in the slot
-// header by the claim) applies all records of that slot in record order; the other records'
-// waves leave at once.  A slot claimed by one record only needs no search for followers.
-__global__ __launch_bounds__(64) void merge_apply_kernel(MergeArgs a)
+// One wave per record, kMergeWaves records per workgroup (most records of a step do not exist --
+// paths are short -- and a launch of one small workgroup per record spends its time dispatching
+// them).  The lowest record that claimed a slot (its leader, named in the slot header by the
+// claim) applies all records of that slot in record order; the other records' waves leave at
+// once.  A slot claimed by one record only needs no search for followers.  The waves of a
+// workgroup do not interact.
+constexpr int kMergeWaves = 16;
+__global__ __launch_bounds__(64 * kMergeWaves) void merge_apply_kernel(MergeArgs a)
 {
-    __shared__ int32_t l_id[2 * kMaxK];
-    __shared__ float l_val[2 * kMaxK];
+    __shared__ int32_t l_id_all[kMergeWaves][2 * kMaxK];
+    __shared__ float l_val_all[kMergeWaves][2 * kMaxK];
     const int NO = a.omax - a.omin + 1;
     const int nrec = a.B * a.R * NO;
-    const int rec = blockIdx.x;
-    const int lane = threadIdx.x;
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int rec = (int)blockIdx.x * kMergeWaves + wave;
+    if (rec >= nrec) return;
+    int32_t *l_id = l_id_all[wave];
+    float *l_val = l_val_all[wave];
     const int K = a.K;
     const long long slot = a.rec_slot[rec];
     if (slot < 0) return;
@@ -1499,9 +1508,9 @@ __global__ __launch_bounds__(64) void merge_apply_kernel(MergeArgs a)
                 }
             }
             if (act && rank < K) { l_id[rank] = id; l_val[rank] = val; }
-            __syncthreads();
+            __builtin_amdgcn_wave_barrier();  // the wave's own part of shared memory: no other wave is involved
             if (lane < K) { e_id = l_id[lane]; e_mu = l_val[lane]; }
-            __syncthreads();
+            __builtin_amdgcn_wave_barrier();
         }
         count++;
     };

@@ -361,7 +361,7 @@ static int launch_path_pass(stand_handle *h, uint64_t step, const void *d_logits
     // row slots of the grid: every slot in update / all-nodes mode; in verify mode three (paths are
     // mostly short; the kernel loops over longer ones)
     const int row_slots = (mode == 0 && !a.all_nodes) ? (h->R < 3 ? h->R : 3) : h->R;
-    const dim3 g1((unsigned)a.nseg + 1, (unsigned)row_slots, (unsigned)h->B), block(kPathThreads);
+    const dim3 g1((unsigned)a.nseg + 1, (unsigned)h->B, (unsigned)row_slots), block(kPathThreads);
     const int finish_blocks = h->B * h->R;
     const int claim_blocks = claim ? (h->B * h->R * h->NO + kFinishThreads - 1) / kFinishThreads : 0;
     const MergeArgs mg = claim ? *claim : merge_args(h, nullptr, nullptr, nullptr);
@@ -381,7 +381,7 @@ static int launch_path_pass(stand_handle *h, uint64_t step, const void *d_logits
 static int launch_merge_apply(stand_handle *h, const MergeArgs &a, bool append_ctx, hipStream_t s)
 {
     const int nrec = h->B * h->R * h->NO;
-    merge_apply_kernel<<<dim3((unsigned)nrec), dim3(64), 0, s>>>(a);
+    merge_apply_kernel<<<dim3((unsigned)((nrec + kMergeWaves - 1) / kMergeWaves)), dim3(64 * kMergeWaves), 0, s>>>(a);
     if (append_ctx)
         ctx_append_kernel<<<dim3((unsigned)((h->B + 63) / 64)), dim3(64), 0, s>>>(h->B, h->W, h->ctx_tail, h->ctx_len,
                                                                                 a.commit_tok, a.commit_len);
