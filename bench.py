@@ -168,7 +168,12 @@ def main():
         w.commit(ln)
         lens.append(ln.mean())
         del lg
+    near_1e6 = None
     if cpu_n:
+        ost = orc.stats()
+        # decisions whose uniform lay within 1e-6 of the acceptance ratio, among all accept tests of the
+        # sample (counted by the oracle; both sides take the same decisions, which the sample asserts)
+        near_1e6 = {"count": int(ost.near_threshold), "accept_tests": int(ost.accept_tests), "steps": cpu_n}
         orc.close()
     # ---- state copy for the replay handle ---------------------------------------------------------
     h2 = mk()
@@ -320,6 +325,7 @@ def main():
         "roofline": roof, "cpu_baseline": cpu,
         "table_updates_per_step": round((st.inserts + st.merges) / max(n_rec, 1), 1),
         "near_threshold_fallbacks": int(st.near_threshold), "filter_mismatch": int(st.filter_mismatch),
+        "decisions_within_1e-6_of_threshold": near_1e6,
         "host_issue_ms_per_step": round(issue_s * 1e3 / K_steps, 4), "timed_chunks": n_chunks,
         "prep_seconds": round(prep_s, 1),
     }
