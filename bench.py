@@ -62,7 +62,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=8)
     ap.add_argument("--table-warm", type=int, default=200)
     ap.add_argument("--workload", default="cfg3")
-    ap.add_argument("--cpu-steps", type=int, default=20)
+    ap.add_argument("--cpu-steps", type=int, default=40)
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-events", action="store_true", help="do not time the row pass with HIP events")
     ap.add_argument("--draft-mode", type=int, default=0,
