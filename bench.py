@@ -286,6 +286,9 @@ def main():
         roof = {"bound": "hbm", "kernel": "row_pass_kernel", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
                 "avg_launch_us": round(row_us, 2), "bytes_per_launch": row_bytes}
+        if traffic:
+            # the same launch priced by the bytes the profiler's counters saw it move
+            roof["achieved_by_traffic"] = round(traffic / (row_us * 1e-6) / 1e9, 1)
         if read_us:
             # the same bytes fetched by a kernel that does nothing else (stand_read_rows), back to back
             roof["read_only_us"] = round(read_us, 2)
