@@ -410,6 +410,45 @@ def test_reorder_matches_oracle(gpu):
     g.close()
 
 
+def test_empty_contexts_and_empty_commits(gpu):
+    """Edge cases of the state: a trajectory without any context (nothing can be drafted, its root row still
+    yields a token), contexts shorter than the orders, an update that commits nothing, and a closed loop
+    started from that state."""
+    binding, lockstep = gpu
+    w = synth.Workload("cfg1", run_steps=12, V=300, B=3, rho=0.5)
+    o, g = lockstep.make_pair(w, 1 << 12)
+    o.set_context(1, [7])                      # trajectory 0: no context at all, 1: one token, 2: two tokens
+    g.set_context(1, [7])
+    o.set_context(2, [7, 9])
+    g.set_context(2, [7, 9])
+    out_tok, out_node, out_len, d = g.new_outputs()
+    od = o.draft(0)
+    g.draft(0, d)
+    torch.cuda.synchronize()
+    assert np.array_equal(d.cpu().numpy(), od) and np.all(od[0] == -1) and np.all(od[:, 1:] == -1)
+    lg = w.logits(0, od)
+    dl = lockstep._logits_to_device(lg, w.dtype)
+    # an update that commits nothing leaves table and contexts as they are
+    none = np.zeros(w.B, np.int32)
+    ct = np.full((w.B, g.W), -1, np.int32)
+    o.update(0, lg, ct, ct, none)
+    g.update(0, dl, torch.from_numpy(ct).cuda(), torch.from_numpy(ct).cuda(), torch.from_numpy(none).cuda())
+    assert len(o.table_export()) == 0 and g.table_export().shape[0] == 0
+    for b in range(w.B):
+        assert g.get_context(b, 1)[1] == o.context_len(b) == b
+    # closed loop from there: every emitted token is committed
+    for step in range(12):
+        lg = w.logits(step, od)
+        otok, onode, olen, od = o.step(step, lg)
+        g.step(step, lockstep._logits_to_device(lg, w.dtype), out_tok, out_node, out_len, d)
+        torch.cuda.synchronize()
+        assert np.array_equal(out_len.cpu().numpy(), olen) and np.array_equal(out_tok.cpu().numpy(), otok)
+        assert np.array_equal(out_node.cpu().numpy(), onode) and np.array_equal(d.cpu().numpy(), od)
+    assert lockstep.compare_tables(o, g, w.K) > 0
+    o.close()
+    g.close()
+
+
 def test_tiny_capacity_drops_are_counted(gpu):
     binding, lockstep = gpu
     w = synth.Workload("cfg1", run_steps=30, V=2000, B=2, rho=0.3)
