@@ -410,6 +410,19 @@ def test_reorder_matches_oracle(gpu):
     g.close()
 
 
+@pytest.mark.parametrize("update_mode", [0, 1])
+def test_largest_tree(gpu, update_mode):
+    """The limits of the tree: 1024 nodes (STAND_MAX_NODES) and depth 31, orders 1-8, K=32, in lock step
+    (closed loop on a tiny vocabulary so that long paths are accepted)."""
+    binding, lockstep = gpu
+    w = synth.Workload(None, B=2, V=40, dtype="bf16", N=1024, D=31, caps=[4, 3, 2, 2, 1], order_min=1, order_max=8,
+                       K=32, T=0.7, rho=0.5, seed=4242, run_steps=10, update_mode=update_mode)
+    assert len(w.parent) == 1024 and w.D == 31
+    info = lockstep.run_lockstep(w, 10, mode="step", capacity=1 << 16, forced=False, check_rows=False)
+    _say("largest tree, update mode %d -> %s" % (update_mode, {k: v for k, v in info.items() if k != "node_counts"}))
+    assert info["emitted"] >= 10 * w.B
+
+
 def test_empty_contexts_and_empty_commits(gpu):
     """Edge cases of the state: a trajectory without any context (nothing can be drafted, its root row still
     yields a token), contexts shorter than the orders, an update that commits nothing, and a closed loop
