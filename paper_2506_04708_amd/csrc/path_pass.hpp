@@ -194,8 +194,8 @@ __global__ __launch_bounds__(kPathThreads) void path_exact_kernel(PathArgs a)
         else if (jj == 0) node = 0;
         else {
             if (len < 0) {
-                // most trajectories stop at the root: then there is no row below it and nothing to stage
-                if (a.outcome[(size_t)b * a.N] < 0) return;
+                // (no separate look at the root's outcome first: that would be one more dependent round
+                // trip to memory in front of the staging for every path that does go on)
                 len = resolve_path(a, b, path, &stage, &s_len);
             }
             if (jj >= len) return;  // block-uniform; later rows do not exist either
