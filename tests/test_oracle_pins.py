@@ -745,3 +745,214 @@ def test_acceptance_length_rises_with_repetition():
     lo = _run_accept_len(0.0, 1)
     hi = _run_accept_len(0.9, 1)
     assert hi > lo
+
+
+def _run_shared_vs_separate(shared, steps=160, B=4, V=2048):
+    """Acceptance length of the same B streams (heavy reuse of each other's spans) when the trajectories share one
+    table and when each has a table of its own."""
+    w = synth.Workload("cfg1", run_steps=steps, V=V, rho=0.7, B=B, cross=0.9, shared_prefix=32, prompt_len=32)
+    if shared:
+        tables = [oracle.Oracle(w.V, B, 1, 3, w.K, w.parent, w.T, 1 << 14, 64, 1, oracle.DT_F32)]
+    else:
+        tables = [oracle.Oracle(w.V, 1, 1, 3, w.K, w.parent, w.T, 1 << 14, 64, 1, oracle.DT_F32) for _ in range(B)]
+    for b in range(B):
+        (tables[0] if shared else tables[b]).set_context(b if shared else 0, w.prompt(b))
+    draft = lambda step: np.concatenate([t.draft(step) for t in tables], axis=0)
+    d = draft(0)
+    tot = 0
+    for step in range(steps):
+        lg = w.logits(step, d)
+        if shared:
+            tok, node, ln = tables[0].verify(step, lg)
+            tables[0].update(step, lg, w.commit(ln), node, ln)
+        else:
+            res = [t.verify(step, np.ascontiguousarray(lg[b:b + 1])) for b, t in enumerate(tables)]
+            ln = np.concatenate([r[2] for r in res])
+            commit = w.commit(ln)
+            for b, t in enumerate(tables):
+                t.update(step, np.ascontiguousarray(lg[b:b + 1]), commit[b:b + 1], res[b][1], res[b][2])
+        d = draft(step + 1)
+        if step >= steps // 2:
+            tot += int(ln.sum())
+    return tot / (B * (steps - steps // 2))
+
+
+def test_acceptance_length_rises_with_trajectories_sharing_the_table():
+    """Sec. 5.1 (discussion of Table 1): the more trajectories feed one table, the longer the accepted drafts,
+    because n-grams recur across trajectories.  Same streams, one shared table against one table each."""
+    assert _run_shared_vs_separate(True) > _run_shared_vs_separate(False) + 0.05
+
+
+# ---- state handling: beam copies, capacity, near-threshold counter ----------------------------
+@pytest.mark.parametrize("src_of", [[1, 1, 3, 0], [1, 2, 0], [0, 0, 0, 0, 4], [2, 1, 0]])
+def test_reorder_copies_contexts_and_drops_pending_drafts(src_of):
+    """Beam copy (the tree-search setting of Sec. 5.2: parents copied, table shared): afterwards trajectory b holds
+    the whole context of src_of[b] as it was BEFORE the call (maps with duplicates and cycles), no draft is
+    pending, and the table is untouched."""
+    B = len(src_of)
+    r = np.random.default_rng(11)
+    o = oracle.Oracle(50, B, 1, 3, 8, np.array([-1, 0, 0, 1], np.int32), 0.6, 1 << 10, 64, 3, oracle.DT_F32)
+    ctx = [[int(x) for x in r.integers(50, size=int(r.integers(1, 12)))] for _ in range(B)]
+    ctx[0] = []                                  # an empty context is copied as well
+    for b in range(B):
+        o.set_context(b, ctx[b])
+    o.table_put([ctx[1][-1]], 3, np.arange(8), np.full(8, 0.125, np.float32))
+    d = o.draft(0)
+    assert (d[1] >= 0).sum() > 1                 # a draft is pending for trajectory 1
+    before = o.table_export().copy()
+    o.reorder(src_of)
+    want = [list(ctx[s]) for s in src_of]        # plain copy from the old state
+    for b in range(B):
+        assert o.context_len(b) == len(want[b])
+        assert list(o.context_tail(b, len(want[b]))) == want[b]
+    mask, pos = o.tree_packing()
+    assert not mask.any() and (pos == -1).all()  # nothing is drafted any more, not even the roots
+    after = o.table_export()
+    assert before.tobytes() == after.tobytes()
+    # the copies are independent: committing to one does not change its source
+    lg = r.standard_normal((B, 4, 50)).astype(np.float32)
+    ct = np.full((B, o.W), -1, np.int32)
+    ct[0, 0] = 7
+    ln = np.zeros(B, np.int32)
+    ln[0] = 1
+    o.update(0, lg, ct, np.zeros((B, o.W), np.int32), ln)
+    assert list(o.context_tail(0, len(want[0]) + 1)) == want[0] + [7]
+    for b in range(1, B):
+        assert o.context_len(b) == len(want[b])
+
+
+def _capacity_run(capacity, max_probe, steps=60, seed=5):
+    """Updates of one trajectory in record order (position, then order ascending) as (key tuple, float64 softmax)."""
+    V, K, T = 8, 8, 0.6
+    o = oracle.Oracle(V, 1, 1, 2, K, np.array([-1, 0, 0, 1], np.int32), T, capacity, max_probe, 9, oracle.DT_F32)
+    r = np.random.default_rng(seed)
+    ctx = [int(x) for x in r.integers(V, size=2)]
+    o.set_context(0, ctx)
+    records = []
+    for step in range(steps):
+        lg = r.standard_normal((1, o.N, V)).astype(np.float32)
+        n = int(r.integers(1, o.W + 1))
+        toks, rows = r.integers(V, size=n), r.integers(o.N, size=n)
+        ct = np.full((1, o.W), -1, np.int32)
+        cr = np.full((1, o.W), -1, np.int32)
+        ct[0, :n], cr[0, :n] = toks, rows
+        for j in range(n):
+            for order in (1, 2):
+                records.append((tuple(ctx[-order:]), _softmax64(lg[0, rows[j]], T)))
+            ctx.append(int(toks[j]))
+        o.update(step, lg, ct, cr, np.array([n], np.int32))
+    return o, records
+
+
+def _check_stored(o, applied, V=8):
+    tab = o.table_export()
+    assert sorted(int(t["fp"]) for t in tab) == sorted(oracle.fingerprint(k) for k in applied)
+    byfp = {int(t["fp"]): t for t in tab}
+    for key, (cnt, psum) in applied.items():
+        t = byfp[oracle.fingerprint(key)]
+        assert t["count"] == cnt and t["order"] == len(key)
+        got = np.zeros(V)
+        got[t["ids"]] = t["mu"]
+        assert np.max(np.abs(got - psum / cnt)) < 2e-6
+
+
+def test_full_table_keeps_the_first_keys_and_counts_every_later_one_as_a_drop():
+    """Fixed capacity without eviction: with the probe limit equal to the capacity every free slot is in reach, so
+    exactly the first `capacity` distinct keys in update order are stored, every update of any later key is a
+    counted drop, and what is stored is the recount of the updates that were applied."""
+    cap = 16
+    o, records = _capacity_run(cap, cap)
+    applied, drops = {}, 0
+    for key, p in records:
+        if key not in applied and len(applied) == cap:
+            drops += 1
+            continue
+        acc = applied.setdefault(key, [0, np.zeros(8)])
+        acc[0] += 1
+        acc[1] += p
+    assert len({k for k, _ in records}) > 2 * cap and drops > 50      # the stream has far more keys than slots
+    st = o.stats()
+    assert st.drops == drops and st.inserts == cap and st.inserts + st.merges + st.drops == len(records)
+    _check_stored(o, applied)
+
+
+def test_probe_limit_drops_keys_whose_window_is_full():
+    """Linear probing with a limit: a key may only live in the max_probe slots that start at its home slot
+    (fingerprint mod capacity); it is dropped, and counted, while they are all taken by other keys, although the
+    table still has free slots elsewhere."""
+    cap, probe = 64, 2
+    o, records = _capacity_run(cap, probe, steps=40)
+    slots, applied, drops = {}, {}, 0
+    for key, p in records:
+        fp = oracle.fingerprint(key)
+        home = fp % cap
+        window = [(home + i) % cap for i in range(probe)]
+        if key not in applied:
+            free = [s for s in window if s not in slots]
+            if not free:
+                drops += 1
+                continue
+            slots[free[0]] = key
+        acc = applied.setdefault(key, [0, np.zeros(8)])
+        acc[0] += 1
+        acc[1] += p
+    st = o.stats()
+    assert drops > 0 and len(applied) < cap                          # dropped although slots were free
+    assert st.drops == drops and st.inserts == len(applied)
+    _check_stored(o, applied)
+
+
+def test_near_threshold_counts_tests_within_1e6_of_the_acceptance_ratio():
+    """The counter of accept decisions that a rounding difference could flip: a test is counted iff its uniform
+    lies within 1e-6 (absolute) of the ratio residual / proposal of the tested child -- in whichever round of the
+    recursion that is -- and the decision itself is not affected."""
+    ids = np.array([0, 1, 2, 3], np.int32)
+    mu = np.array([0.5, 0.25, 0.125, 0.125], np.float32)
+    p = np.array([0.25, 0.25, 0.25, 0.25], np.float32)
+    ratio = 0.5                                                       # r / w of child 0 in the first round
+    for delta, near in [(5e-7, 1), (-5e-7, 1), (2e-6, 0), (-2e-6, 0)]:
+        acc, st = oracle.verify_node(p, ids, mu, [0], [np.float32(ratio + delta)])
+        assert st.near_threshold == near and acc == (0 if delta < 0 else -1)
+    # a small ratio: the distance is absolute, not relative
+    p2 = np.array([0.005, 0.495, 0.25, 0.25], np.float32)             # r / w = 0.01
+    for delta, near in [(5e-7, 1), (2e-6, 0)]:
+        _, st = oracle.verify_node(p2, ids, mu, [0], [np.float32(np.float32(0.005) / np.float32(0.5)) + np.float32(delta)])
+        assert st.near_threshold == near
+    # second round: after child 0 is rejected, child 1 is tested on the residual and the renormalised proposal;
+    # its ratio is computed here by hand in float64 from the rule of Sec. 3.2
+    p3 = np.array([0.1, 0.3, 0.3, 0.3], np.float32)
+    w = mu.astype(np.float64) / mu.astype(np.float64).sum()
+    r = p3.astype(np.float64)
+    Z = 1.0 - np.minimum(r, w).sum()
+    r2 = np.maximum(r - w, 0.0) / Z
+    w2 = w.copy()
+    w2[0] = 0.0
+    w2 /= w2.sum()
+    ratio2 = r2[1] / w2[1]
+    assert abs(ratio2 - 0.25) < 1e-6
+    for delta, near in [(4e-7, 1), (-4e-7, 1), (3e-6, 0), (-3e-6, 0)]:
+        om2 = np.float32(ratio2 + delta)
+        acc, st = oracle.verify_node(p3, ids, mu, [0, 1], [np.float32(0.9), om2])
+        assert st.rounds == 2 and st.near_threshold == near and acc == (1 if delta < 0 else -1), (delta, acc)
+    # the first round's uniform is far from its ratio (0.2): a near hit in round one must not be reported for it
+    acc, st = oracle.verify_node(p3, ids, mu, [0], [np.float32(0.9)])
+    assert st.near_threshold == 0 and acc == -1
+    # the stateful path: so_verify draws the uniform itself (stream ACCEPT, node = the child); the target row is
+    # built around that uniform so that the test lands 5e-7 / 2e-6 away from its ratio, and the statistics count it
+    for delta, near in [(5e-7, 1), (2e-6, 0)]:
+        o = oracle.Oracle(4, 1, 1, 1, 4, np.array([-1, 0], np.int32), 1.0, 64, 8, 3, oracle.DT_F32)
+        o.set_context(0, [2])
+        o.table_put([2], 1, ids, mu)
+        t = int(o.draft(0)[0, 1])
+        om = oracle.uniform(3, 0, 0, 1, 0, oracle.STREAM_ACCEPT)
+        w_t = float(mu[t]) / float(mu.sum())
+        pt = w_t * (om + delta)
+        if not 0.02 < pt < 0.9:
+            continue
+        row = np.full(4, (1.0 - pt) / 3.0)
+        row[t] = pt
+        lg = np.log(np.stack([row, row])[None]).astype(np.float32)
+        got = oracle.row_softmax(lg[0, 0], 1.0)[0][t]
+        assert abs(float(got) / w_t - (om + delta)) < 2e-7            # the row really gives that ratio
+        o.verify(0, lg)
+        assert o.stats().accept_tests == 1 and o.stats().near_threshold == near
