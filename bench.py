@@ -78,6 +78,14 @@ def main():
     ap.add_argument("--max-peaks", type=int, default=4,
                     help="each row peaks on 1..max-peaks tokens (BASELINE: 1-4); 1 with a high --peak models a confident "
                          "target, where acceptance follows the quality of the drafts")
+    ap.add_argument("--step-mode", type=int, default=0,
+                    help="how stand_step is issued: 0 the library's choice, 1 five dependent launches, 2 one launch")
+    ap.add_argument("--upper-depth", type=int, default=2, help="one-launch step: tree levels whose rows go first")
+    ap.add_argument("--tail-groups", type=int, default=0, help="one-launch step: tail workgroups per trajectory (0: library's choice)")
+    ap.add_argument("--rows-first", type=int, default=0,
+                    help="one-launch step: row workgroups placed before the tail's (0: one device-full)")
+    ap.add_argument("--timeline", action="store_true",
+                    help="after the timed region, replay a few steps with the one-launch step's clock readings on and print them")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run a plain copy of one logits tensor (known HBM traffic) for counter calibration")
     args = ap.parse_args()
@@ -106,9 +114,13 @@ def main():
         w = synth.Workload(args.workload, run_steps=total + 2, max_peaks=args.max_peaks)
     dt = binding.STAND_BF16 if w.dtype == "bf16" else binding.STAND_F32
     assert w.dtype == "bf16"
-    mk = lambda: binding.Stand(w.V, w.B, cfg["order_min"], cfg["order_max"], w.K, w.parent, w.T, cfg["capacity"], 64,
+    mk0 = lambda: binding.Stand(w.V, w.B, cfg["order_min"], cfg["order_max"], w.K, w.parent, w.T, cfg["capacity"], 64,
                                cfg["seed"], dt, draft_mode=args.draft_mode, update_mode=args.update_mode,
                                merge_policy=args.merge_policy)
+    def mk():
+        h = mk0()
+        h.set_step_plan(args.step_mode, args.upper_depth, args.tail_groups, 0, args.rows_first)
+        return h
     gen = torch.Generator(device="cuda").manual_seed(cfg["seed"] & 0x7FFFFFFF)
     h1 = mk()
     for b in range(w.B):
@@ -246,6 +258,21 @@ def main():
             assert torch.equal(o_len[i], r_len) and torch.equal(o_tok[i], r_tok) and torch.equal(o_draft[i], r_draft), \
                 "replay diverged from the recorded run at step %d" % (done + i)
         done += n
+        if done >= n_after and args.timeline:
+            # where the time of the one-launch step goes: a few more steps on recorded logits, clock readings on
+            h2.step_timeline(True)
+            acc = []
+            for i in range(min(16, len(rec))):
+                lg, force, *_ = rec[-1 - i]
+                h2.step(T_warm + n_after + i, lg, o_tok[0], o_node[0], o_len[0], o_draft[0], force)
+                r0, r1, tl = h2.step_timeline(True, read=True)
+                acc.append(np.concatenate([[r1], tl.mean(axis=0), tl.max(axis=0)]))
+            acc = np.mean(np.stack(acc), axis=0)
+            names = ["tail start", "path known", "sums in", "claims made", "rows finished", "all claims in", "all applied", "draft done"]
+            print("timeline (us from the first row workgroup's start, mean over %d steps): last row end %.1f" % (min(16, len(rec)), acc[0]), file=sys.stderr)
+            for k, nm in enumerate(names):
+                print("  %-14s mean over trajectories %7.1f   latest %7.1f" % (nm, acc[1 + k], acc[9 + k]), file=sys.stderr)
+            h2.step_timeline(False)
         if done >= n_after and (w.V * 2) % 16 == 0:
             # floor of a kernel that only fetches one step's logits, in the row pass's launch shape
             sink = torch.zeros(4 * w.B * w.N, dtype=torch.int32, device="cuda")

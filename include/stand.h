@@ -66,6 +66,11 @@ extern "C" {
 #define STAND_DRAFT_DETERMINISTIC 2 /* the c largest mu (ties: lower id); in verification the proposal  */
                                     /* of each child is one-hot, so it is accepted with probability r(x) */
 
+/* How stand_step issues its work (results are the same; see stand_set_step_plan). */
+#define STAND_STEP_AUTO 0   /* one launch where it pays (more than 768 rows, accepted-path updates), else serial */
+#define STAND_STEP_SERIAL 1 /* five dependent launches: rows, exact sums, finish + claims, apply, draft           */
+#define STAND_STEP_FUSED 2  /* one launch: the dependent tail runs beside the rows that are still streaming      */
+
 #define STAND_MAX_TOPK 32
 #define STAND_MAX_ORDER 8
 #define STAND_MAX_NODES 1024
@@ -105,6 +110,8 @@ typedef struct {
     uint64_t accept_tests;
     uint64_t filter_mismatch;           /* path nodes whose outcome changed under exact arithmetic     */
                                         /* (must stay 0; a self-check of the error bound)              */
+    uint64_t wait_expired;              /* one-launch step: bounded waits that ran out (must stay 0;   */
+                                        /* the outputs of that step are void, see stand_set_wait_limit) */
 } stand_stats;
 
 /* Creates a handle: validates the configuration, copies the tree, allocates and clears the
@@ -168,6 +175,39 @@ int stand_verify(stand_handle *h, uint64_t step, const void *d_logits, int32_t *
 int stand_step(stand_handle *h, uint64_t step, const void *d_logits, int32_t *d_out_tok,
                int32_t *d_out_node, int32_t *d_out_len, int32_t *d_next_draft_tok,
                const int32_t *d_force_tok, void *stream);
+
+/* How stand_step is issued (paper: the step is verify -> update -> draft, Sec. 3.2, 4.1, 4.2; this only
+ * chooses the launch structure, every output is the same bit for bit).
+ *   mode         STAND_STEP_AUTO / SERIAL / FUSED.  FUSED is refused (STAND_EINVAL) with
+ *                STAND_UPDATE_ALL_NODES, whose records need every drafted row.
+ *   upper_depth  FUSED: the rows of tree nodes up to this depth take the first places in the launch
+ *                (default 2: paths that end above depth 3 never wait for a late row; deeper paths are
+ *                still correct, the tail then waits for the rows it needs).  0 .. STAND_MAX_DEPTH.
+ *   tail_groups  FUSED: workgroups per trajectory that share the exact sums of the path rows, 1 .. 8;
+ *                0 = chosen from the batch size.
+ *   rows_first   FUSED: number of row workgroups placed before the tail's workgroups (at least the
+ *                upper levels' rows); 0 = as many as the device holds at once, so that the tail starts
+ *                when the first round of rows ends.
+ *   shuffle      non-zero: the order in which row workgroups take rows is permuted (seeded by the value);
+ *                a test that results do not depend on the workgroup -> work mapping. */
+int stand_set_step_plan(stand_handle *h, int32_t mode, int32_t upper_depth, int32_t tail_groups, int32_t rows_first,
+                        uint32_t shuffle);
+
+/* Bound, in microseconds, of every wait inside the one-launch step (default 200 000).  A wait that runs
+ * out is counted in stand_stats.wait_expired; every kernel still ends normally, but the step's outputs
+ * for the affected trajectories are void (out_len 0, tokens -1) and the table must be considered invalid.
+ * With a healthy device no wait comes near the default.  0 makes every wait that is not satisfied at once
+ * expire (for tests of this path). */
+int stand_set_wait_limit(stand_handle *h, uint64_t microseconds);
+
+/* Measurement aid: where the time of the one-launch step goes.  enable != 0 makes later one-launch steps
+ * record readings of the device's constant clock (allocates 16 + 64 * max_batch bytes once; enable == 0
+ * frees them).  host_ticks, if not NULL, receives the readings of the last such step ([2 + 8 * max_batch]:
+ * earliest start and latest end of a row workgroup, then per trajectory: tail workgroup started, path
+ * known, exact sums of all its workgroups in, its claims made, its rows finished, all trajectories' claims
+ * in, all records applied, draft written); STAND_ESTATE if recording was not enabled.  *ticks_per_second,
+ * if not NULL, receives the clock's rate.  Synchronises the device. */
+int stand_step_timeline(stand_handle *h, int32_t enable, uint64_t *host_ticks, uint64_t *ticks_per_second);
 
 /* Per-row results of the last stand_verify / stand_step, for inspection: for each of the B*N
  * rows the maximum logit, the softmax normaliser (fast single-pass value, relative error

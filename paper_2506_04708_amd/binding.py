@@ -16,6 +16,7 @@ LIB_PATH = os.path.join(_HERE, "libstand.so")
 STAND_BF16, STAND_F32 = 0, 1
 DRAFT_GUMBEL_TOPK, DRAFT_MULTINOMIAL, DRAFT_DETERMINISTIC = 0, 1, 2
 MERGE_MEAN, MERGE_REPLACE = 0, 1
+STEP_AUTO, STEP_SERIAL, STEP_FUSED = 0, 1, 2
 MAX_ORDER = 8
 
 EXPORTED = [
@@ -25,6 +26,7 @@ EXPORTED = [
     "stand_profile_begin", "stand_profile_end", "stand_copy_bytes", "stand_read_rows", "stand_set_filter_margin",
     "stand_tree_initial", "stand_tree_select", "stand_get_node_counts", "stand_reset_node_counts",
     "stand_tree_packing",
+    "stand_set_step_plan", "stand_set_wait_limit", "stand_step_timeline",
 ]
 
 
@@ -43,7 +45,7 @@ class Stats(C.Structure):
         ("hits", C.c_uint64 * (MAX_ORDER + 1)), ("misses", C.c_uint64),
         ("inserts", C.c_uint64), ("merges", C.c_uint64), ("drops", C.c_uint64),
         ("near_threshold", C.c_uint64), ("tokens_emitted", C.c_uint64), ("accept_tests", C.c_uint64),
-        ("filter_mismatch", C.c_uint64),
+        ("filter_mismatch", C.c_uint64), ("wait_expired", C.c_uint64),
     ]
 
 
@@ -61,6 +63,9 @@ def load_library():
     lib.stand_update.argtypes = [vp, C.c_uint64, vp, i32p, i32p, i32p, vp]
     lib.stand_draft.argtypes = [vp, C.c_uint64, i32p, vp]
     lib.stand_verify.argtypes = [vp, C.c_uint64, vp, i32p, i32p, i32p, vp]
+    lib.stand_set_step_plan.argtypes = [vp, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_uint32]
+    lib.stand_set_wait_limit.argtypes = [vp, C.c_uint64]
+    lib.stand_step_timeline.argtypes = [vp, C.c_int32, vp, C.POINTER(C.c_uint64)]
     lib.stand_step.argtypes = [vp, C.c_uint64, vp, i32p, i32p, i32p, i32p, i32p, vp]
     lib.stand_row_results.argtypes = [vp, vp, vp, vp, vp, vp]
     lib.stand_table_export.argtypes = [vp, vp, C.POINTER(C.c_uint64)]
@@ -252,6 +257,23 @@ class Stand:
         ln = C.c_int64(0)
         _check(lib().stand_get_context(self.h, b, out.ctypes.data_as(C.c_void_p), n, C.byref(ln), _stream_ptr()), self.h)
         return out[:n], int(ln.value)
+
+    def set_step_plan(self, mode=0, upper_depth=2, tail_groups=0, shuffle=0, rows_first=0):
+        _check(lib().stand_set_step_plan(self.h, mode, upper_depth, tail_groups, rows_first, shuffle), self.h)
+
+    def set_wait_limit(self, microseconds):
+        _check(lib().stand_set_wait_limit(self.h, microseconds), self.h)
+
+    def step_timeline(self, enable=True, read=False):
+        """Switches the recording of the one-launch step's clock readings on or off; with read=True returns
+        (row_start, row_end, per-trajectory stamps [B, 8]) of the last such step in microseconds from row_start."""
+        rate = C.c_uint64(0)
+        buf = np.zeros(2 + 8 * self.B, np.uint64) if read else None
+        _check(lib().stand_step_timeline(self.h, int(enable), buf.ctypes.data if read else None, C.byref(rate)), self.h)
+        if not read:
+            return None
+        us = (buf.astype(np.int64) - np.int64(buf[0])) * (1e6 / rate.value)
+        return float(us[0]), float(us[1]), us[2:].reshape(self.B, 8)
 
     def set_filter_margin(self, margin):
         _check(lib().stand_set_filter_margin(self.h, margin), self.h)

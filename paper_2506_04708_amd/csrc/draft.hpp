@@ -28,18 +28,41 @@ struct DraftArgs {
 
 constexpr int kDraftThreads = 1024;  // 16 waves: the nodes of a tree level are looked up side by side
 
-__global__ __launch_bounds__(kDraftThreads) void draft_kernel(DraftArgs a)
+// Shared memory of one trajectory's draft, sized for a tree of N nodes and depth D.
+struct DraftShared {
+    int32_t *tok;                    // [N]
+    int32_t (*recent)[kMaxOrder];    // [N][kMaxOrder] recent[u][i]: the token i positions before the end of the
+                                     // sequence that ends at node u (recent[u][0] is the node's own token), so a
+                                     // key is read without walking up the tree; 16-byte aligned
+    int32_t *t_first, *t_nchild;     // [N]
+    int32_t *t_level;                // [D + 2]
+    long long *clen;
+};
+__host__ __device__ inline size_t draft_shared_bytes(int N, int D)
 {
-    __shared__ int32_t tok[kMaxNodes];
-    // recent[u][i]: the token i positions before the end of the sequence that ends at node u
-    // (recent[u][0] is the node's own token), so a key is read without walking up the tree
-    __shared__ __align__(16) int32_t recent[kMaxNodes][kMaxOrder];
-    __shared__ int32_t t_first[kMaxNodes], t_nchild[kMaxNodes];
-    __shared__ int32_t t_level[kMaxDepth + 3];
-    __shared__ long long s_clen;
-    const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    return (size_t)N * kMaxOrder * 4 + 3 * (size_t)N * 4 + (((size_t)D + 2 + 3) & ~(size_t)3) * 4 + 16;
+}
+__device__ __forceinline__ DraftShared draft_shared_carve(char *base, int N, int D)
+{
+    DraftShared s;
+    s.recent = (int32_t(*)[kMaxOrder])base;  base += (size_t)N * kMaxOrder * 4;
+    s.tok = (int32_t *)base;                 base += (size_t)N * 4;
+    s.t_first = (int32_t *)base;             base += (size_t)N * 4;
+    s.t_nchild = (int32_t *)base;            base += (size_t)N * 4;
+    s.t_level = (int32_t *)base;             base += (((size_t)D + 2 + 3) & ~(size_t)3) * 4;
+    s.clen = (long long *)base;
+    return s;
+}
+
+// The draft of trajectory b by the NT threads of the calling workgroup (all of them call this).
+template <int NT>
+__device__ __forceinline__ void draft_trajectory(const DraftArgs &a, int b, const DraftShared &sm)
+{
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    int32_t *tok = sm.tok, *t_first = sm.t_first, *t_nchild = sm.t_nchild, *t_level = sm.t_level;
+    int32_t(*recent)[kMaxOrder] = sm.recent;
     const int N = a.tree.N, K = a.K;
-    for (int u = tid; u < N; u += kDraftThreads) {
+    for (int u = tid; u < N; u += NT) {
         t_first[u] = a.tree.first_child[u];
         t_nchild[u] = a.tree.nchild[u];
         if (u > 0) tok[u] = -1;  // the root's token is set with the context below
@@ -63,10 +86,10 @@ __global__ __launch_bounds__(kDraftThreads) void draft_kernel(DraftArgs a)
         }
         for (int i = 0; i < kMaxOrder; ++i) recent[0][i] = t[kMaxOrder - 1 - i];
         tok[0] = len > 0 ? t[kMaxOrder - 1] : -1;
-        s_clen = len;
+        *sm.clen = len;
     }
     __syncthreads();
-    const long long clen = (long long)readlane_u64((unsigned long long)s_clen, 0);
+    const long long clen = (long long)readlane_u64((unsigned long long)*sm.clen, 0);
     const int NO = a.omax - a.omin + 1;
     for (int d = 0; d < a.tree.D; ++d) {
         // values read from shared memory that are the same in every lane go to scalar registers
@@ -75,7 +98,7 @@ __global__ __launch_bounds__(kDraftThreads) void draft_kernel(DraftArgs a)
         bool any = false;
         for (int u = lo + lane; u < hi; u += 64) any |= tok[u] >= 0;
         if (!__ballot(any)) break;  // the same in every wave
-        for (int u = lo + wave; u < hi; u += kDraftThreads / 64) {
+        for (int u = lo + wave; u < hi; u += NT / 64) {
             const int nch = __builtin_amdgcn_readfirstlane(t_nchild[u]);
             if (nch == 0 || __builtin_amdgcn_readfirstlane(tok[u]) < 0) continue;
             // ---- multi-level lookup (paper Sec. 4.2): lane q < NO takes order n = omax - q.
@@ -103,8 +126,8 @@ __global__ __launch_bounds__(kDraftThreads) void draft_kernel(DraftArgs a)
             uint32_t home_cnt = 0;
             if (fp) {
                 const SlotHeader *h = slot_header(a.table, fp & a.mask, a.slot_bytes);
-                home_fp = h->fp;
-                home_cnt = h->count;
+                home_fp = ld_agent(&h->fp);
+                home_cnt = ld_agent(&h->count);
             }
             int32_t pid[kMaxOrder];
             float pmu[kMaxOrder];
@@ -113,8 +136,8 @@ __global__ __launch_bounds__(kDraftThreads) void draft_kernel(DraftArgs a)
                 pid[q] = -1; pmu[q] = 0.0f;
                 const unsigned long long fq = readlane_u64(fp, q);  // uniform
                 if (q < NO && fq && lane < K) {
-                    pid[q] = slot_ids(a.table, fq & a.mask, a.slot_bytes)[lane];
-                    pmu[q] = slot_mu(a.table, fq & a.mask, a.slot_bytes, K)[lane];
+                    pid[q] = ld_agent(&slot_ids(a.table, fq & a.mask, a.slot_bytes)[lane]);
+                    pmu[q] = ld_agent(&slot_mu(a.table, fq & a.mask, a.slot_bytes, K)[lane]);
                 }
             }
             long long hit_slot = -1;
@@ -124,8 +147,8 @@ __global__ __launch_bounds__(kDraftThreads) void draft_kernel(DraftArgs a)
                     for (int i = 1; i < a.max_probe; ++i) {  // displaced key: keep probing
                         const uint64_t slot = (fp + (uint64_t)i) & a.mask;
                         const SlotHeader *h = slot_header(a.table, slot, a.slot_bytes);
-                        const unsigned long long cur = h->fp;
-                        if (cur == fp) { if (h->count > 0) hit_slot = (long long)slot; break; }
+                        const unsigned long long cur = ld_agent(&h->fp);
+                        if (cur == fp) { if (ld_agent(&h->count) > 0) hit_slot = (long long)slot; break; }
                         if (cur == 0ull) break;
                     }
                 }
@@ -146,8 +169,8 @@ __global__ __launch_bounds__(kDraftThreads) void draft_kernel(DraftArgs a)
 #pragma unroll
                 for (int q = 0; q < kMaxOrder; ++q) if (q == win) { id = pid[q]; mu = pmu[q]; }
             } else if (lane < K) {
-                id = slot_ids(a.table, (uint64_t)slot, a.slot_bytes)[lane];
-                mu = slot_mu(a.table, (uint64_t)slot, a.slot_bytes, K)[lane];
+                id = ld_agent(&slot_ids(a.table, (uint64_t)slot, a.slot_bytes)[lane]);
+                mu = ld_agent(&slot_mu(a.table, (uint64_t)slot, a.slot_bytes, K)[lane]);
             }
             if (lane < K) {
                 a.draft_qid[((size_t)b * N + u) * K + lane] = id;
@@ -212,13 +235,19 @@ __global__ __launch_bounds__(kDraftThreads) void draft_kernel(DraftArgs a)
         }
         __syncthreads();
     }
-    for (int u = tid; u < N; u += kDraftThreads) {
+    for (int u = tid; u < N; u += NT) {
         a.draft_tok[(size_t)b * N + u] = tok[u];
         if (a.out_tok) a.out_tok[(size_t)b * N + u] = tok[u];
     }
     if (a.recent_out)
-        for (int i = tid; i < N * kMaxOrder; i += kDraftThreads)
+        for (int i = tid; i < N * kMaxOrder; i += NT)
             if (tok[i / kMaxOrder] >= 0) a.recent_out[(size_t)b * N * kMaxOrder + i] = recent[i / kMaxOrder][i % kMaxOrder];
+}
+
+__global__ __launch_bounds__(kDraftThreads) void draft_kernel(DraftArgs a)
+{
+    __shared__ __align__(16) char smem[(size_t)kMaxNodes * kMaxOrder * 4 + 3 * (size_t)kMaxNodes * 4 + (kMaxDepth + 5) * 4 + 16];
+    draft_trajectory<kDraftThreads>(a, (int)blockIdx.x, draft_shared_carve(smem, a.tree.N, a.tree.D));
 }
 
 }  // namespace stand

@@ -13,6 +13,9 @@
 //                    commit_scan_kernel  top-K of caller-given rows (update without verify)
 //   table_merge.hpp  merge_apply_kernel  running-mean merge into the open-addressing table (Sec. 4.1)
 //   draft.hpp        draft_kernel        multi-level lookup + Gumbel-Top-K along the static tree (Sec. 4.2)
+//   step_fused.hpp   stand_step_kernel   the whole step in one launch: rows of the tree's upper levels, then
+//                                        the dependent tail beside the remaining rows (bounded waits on
+//                                        device-scope counters)
 //   aux_kernels.hpp  fills, copies, tree packing, table export
 //
 // The row pass is the only kernel that touches all of the logits; it is bound by HBM bandwidth.
@@ -21,7 +24,8 @@
 // every probability that is stored in the table or used for resampling, is recomputed with
 // the exact integer normaliser of numeric.hpp, so all decisions are those of exact arithmetic.
 // The kernels after the row pass are chains of dependent memory round trips over little data;
-// workgroups exchange data only across kernel boundaries (no device-scope atomics or fences).
+// their workgroups exchange data only across kernel boundaries.  stand_step_kernel runs the same
+// device functions in one launch and orders them with counters instead.
 #pragma once
 #include "numeric.hpp"
 #include "wave_ops.hpp"
@@ -29,4 +33,5 @@
 #include "table_merge.hpp"
 #include "path_pass.hpp"
 #include "draft.hpp"
+#include "step_fused.hpp"
 #include "aux_kernels.hpp"

@@ -189,7 +189,9 @@ __global__ __launch_bounds__(kPathThreads) void path_exact_kernel(PathArgs a)
     for (int jj = j; jj < a.R; jj += gridDim.z) {
         int node;
         bool staged = false;
-        if (a.all_nodes) node = a.draft_tok[(size_t)b * a.N + jj] >= 0 ? jj : -1;
+        // (in verify mode the root row is always on the path, also when the trajectory has no context yet
+        // and its root carries no token)
+        if (a.all_nodes) node = (a.draft_tok[(size_t)b * a.N + jj] >= 0 || (a.mode == 0 && jj == 0)) ? jj : -1;
         else if (a.mode != 0) node = commit_row_of(a, b, jj);
         else if (jj == 0) node = 0;
         else {
@@ -302,57 +304,31 @@ __global__ __launch_bounds__(256) void commit_scan_kernel(CommitScanArgs a)
 }
 
 
-// See the comment above PathArgs.  Blocks [0, finish_blocks) finish path row (b, j) =
-// (block / W, block % W); the blocks after them claim merge records, kFinishThreads per block.
-template <int DT>
-__global__ __launch_bounds__(kFinishThreads) void path_finish_kernel(PathArgs a, MergeArgs mg, int finish_blocks)
+// Finishes row slot j of trajectory b, whose row is tree node `node`: its observation (paper Sec. 4.1:
+// top-k ids and probabilities with the exact normaliser) and, at the stop row of a verification, the
+// replay of the node's accept tests with exact probabilities and the resampled token.  A row that is
+// not a stop row is finished by ONE wave (wave = 0, tid = lane); the stop row by all NT threads of the
+// workgroup, which all call this with their wave and thread numbers.  m: the row's maximum.  Wave 0's
+// lanes hold the stop node's proposal (my_id, my_mu), the row's logits at those ids (my_l) and the
+// tokens of the drafted children (ch); nch / fc / len as in the stop record.
+template <int DT, int NT>
+__device__ __forceinline__ void finish_row(const PathArgs &a, FinishShared &sh, int b, int j, int node, bool stop, float m,
+                                           int nch, int fc, int len, int32_t my_id, float my_mu, float my_l, int32_t ch,
+                                           unsigned long long part, int tid, int wave)
 {
     constexpr int ES = VecTraits<DT>::ES, EPV = VecTraits<DT>::EPV;
-    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    if ((int)blockIdx.x >= finish_blocks) {
-        merge_claim_record(mg, ((int)blockIdx.x - finish_blocks) * kFinishThreads + tid);
-        return;
-    }
-    __shared__ FinishShared sh;
-    const int j = (int)blockIdx.x / a.B, b = (int)blockIdx.x % a.B;  // slot-major, as in path_exact_kernel
-    // Everything whose address depends on (b, j) only is requested at once: the partial sums and,
-    // in verify mode, the stop record of the trajectory (used if this turns out to be its stop row).
+    const int lane = tid & 63;
     const int nseg = a.nseg;
-    const unsigned long long part = (wave == 0 && lane < nseg) ? a.seg_part[((size_t)b * a.R + j) * kSegMax + lane] : 0ull;
-    int len = 0, node, nch = 0, fc = -1;
-    bool stop = false;
-    int32_t my_id = -1, ch = -1;
-    float my_mu = 0.0f, my_l = 0.0f, m;
-    if (a.mode == 0) {
-        const int stop_node = a.stop_i[(size_t)b * 4 + 0];
-        len = a.stop_i[(size_t)b * 4 + 1];
-        nch = a.stop_i[(size_t)b * 4 + 2];
-        fc = a.stop_i[(size_t)b * 4 + 3];
-        m = a.stop_m[b];
-        if (wave == 0 && lane < kMaxK) {
-            my_id = a.stop_qid[(size_t)b * kMaxK + lane]; my_mu = a.stop_qmu[(size_t)b * kMaxK + lane];
-            my_l = a.stop_ql[(size_t)b * kMaxK + lane]; ch = a.stop_child[(size_t)b * kMaxK + lane];
-        }
-        if (a.all_nodes) node = a.draft_tok[(size_t)b * a.N + j] >= 0 ? j : -1;
-        else node = j < len ? (j == len - 1 ? stop_node : a.out_node[(size_t)b * a.W + j]) : -1;
-        stop = node >= 0 && node == stop_node;
-    } else {
-        node = a.all_nodes ? (a.draft_tok[(size_t)b * a.N + j] >= 0 ? j : -1) : commit_row_of(a, b, j);
-        m = 0.0f;
-    }
-    if (node < 0) return;  // block-uniform
-    if (!stop && wave != 0) return;
     const int row = b * a.N + node;
     const int src = a.mode == 0 ? row : b * a.R + j;
     const char *rowp = (const char *)a.logits + (size_t)row * (size_t)a.V * ES;
-    if (!stop) m = a.src_m[src];
     const RowGeom g = row_geom<DT>(rowp, a.V);
     const int per = (g.nvec + nseg - 1) / nseg;
 
     if (wave == 0) {
         int32_t o_idx = 0;
         float o_l = 0.0f;
-        if (lane < a.K) { o_idx = a.src_top_idx[(size_t)src * a.K + lane]; o_l = a.src_top_l[(size_t)src * a.K + lane]; }
+        if (lane < a.K) { o_idx = ld_agent(&a.src_top_idx[(size_t)src * a.K + lane]); o_l = ld_agent(&a.src_top_l[(size_t)src * a.K + lane]); }
         if (!stop || nch <= 0 || lane >= a.K) { my_id = -1; my_mu = 0.0f; }
         const float my_e = my_id >= 0 ? exact_exp2(scaled_offset(my_l, m, a.c)) : 0.0f;
         int edge_id = -1;
@@ -368,8 +344,8 @@ __global__ __launch_bounds__(kFinishThreads) void path_finish_kernel(PathArgs a,
         if (!stop) {
             // observation of this row (paper Sec. 4.1: top-k ids and probabilities)
             if (lane < a.K) {
-                a.obs_idx[((size_t)b * a.R + j) * a.K + lane] = o_idx;
-                a.obs_p[((size_t)b * a.R + j) * a.K + lane] = exact_exp2(scaled_offset(o_l, m, a.c)) / s;
+                st_agent(&a.obs_idx[((size_t)b * a.R + j) * a.K + lane], o_idx);
+                st_agent(&a.obs_p[((size_t)b * a.R + j) * a.K + lane], exact_exp2(scaled_offset(o_l, m, a.c)) / s);
             }
             return;
         }
@@ -390,8 +366,8 @@ __global__ __launch_bounds__(kFinishThreads) void path_finish_kernel(PathArgs a,
         }
         // the stop row's observation (its loads have had the replay to arrive)
         if (lane < a.K) {
-            a.obs_idx[((size_t)b * a.R + j) * a.K + lane] = o_idx;
-            a.obs_p[((size_t)b * a.R + j) * a.K + lane] = exact_exp2(scaled_offset(o_l, m, a.c)) / s;
+            st_agent(&a.obs_idx[((size_t)b * a.R + j) * a.K + lane], o_idx);
+            st_agent(&a.obs_p[((size_t)b * a.R + j) * a.K + lane], exact_exp2(scaled_offset(o_l, m, a.c)) / s);
         }
         // ---- integer masses (unit 2^-40 / s * rho): support token i weighs floor(r_i * (S / rho)),
         // a token outside the support the term it contributes to S
@@ -473,7 +449,7 @@ __global__ __launch_bounds__(kFinishThreads) void path_finish_kernel(PathArgs a,
     // ---- locate the token inside vector segment seg: every thread owns a contiguous run of
     // vectors, so thread order is id order
     const int vs = seg * per, ve = (vs + per < g.nvec) ? vs + per : g.nvec;
-    const int cpt = (ve - vs + kFinishThreads - 1) / kFinishThreads;
+    const int cpt = (ve - vs + NT - 1) / NT;
     const int r0 = vs + tid * cpt < ve ? vs + tid * cpt : ve;
     const int r1 = r0 + cpt < ve ? r0 + cpt : ve;
     // four independent loads per round (indices clamped, unused vectors skipped)
@@ -555,6 +531,49 @@ __global__ __launch_bounds__(kFinishThreads) void path_finish_kernel(PathArgs a,
         a.out_tok[(size_t)b * a.W + (len - 1)] = a.src_top_idx[(size_t)src * a.K];
         atomicAdd(&a.stats[kStatMismatch], 1ull);
     }
+}
+
+// See the comment above PathArgs.  Blocks [0, finish_blocks) finish row slot j of trajectory b with
+// (j, b) = (block / B, block % B); the blocks after them claim merge records, kFinishThreads per block.
+template <int DT>
+__global__ __launch_bounds__(kFinishThreads) void path_finish_kernel(PathArgs a, MergeArgs mg, int finish_blocks)
+{
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    if ((int)blockIdx.x >= finish_blocks) {
+        merge_claim_record(mg, ((int)blockIdx.x - finish_blocks) * kFinishThreads + tid);
+        return;
+    }
+    __shared__ FinishShared sh;
+    const int j = (int)blockIdx.x / a.B, b = (int)blockIdx.x % a.B;  // slot-major, as in path_exact_kernel
+    // Everything whose address depends on (b, j) only is requested at once: the partial sums and,
+    // in verify mode, the stop record of the trajectory (used if this turns out to be its stop row).
+    const unsigned long long part = (wave == 0 && lane < a.nseg) ? ld_agent(&a.seg_part[((size_t)b * a.R + j) * kSegMax + lane]) : 0ull;
+    int len = 0, node, nch = 0, fc = -1;
+    bool stop = false;
+    int32_t my_id = -1, ch = -1;
+    float my_mu = 0.0f, my_l = 0.0f, m;
+    if (a.mode == 0) {
+        const int stop_node = a.stop_i[(size_t)b * 4 + 0];
+        len = a.stop_i[(size_t)b * 4 + 1];
+        nch = a.stop_i[(size_t)b * 4 + 2];
+        fc = a.stop_i[(size_t)b * 4 + 3];
+        m = a.stop_m[b];
+        if (wave == 0 && lane < kMaxK) {
+            my_id = a.stop_qid[(size_t)b * kMaxK + lane]; my_mu = a.stop_qmu[(size_t)b * kMaxK + lane];
+            my_l = a.stop_ql[(size_t)b * kMaxK + lane]; ch = a.stop_child[(size_t)b * kMaxK + lane];
+        }
+        // all-nodes mode: slot j = node j; an undrafted root (empty context) is still the stop row
+        if (a.all_nodes) node = (a.draft_tok[(size_t)b * a.N + j] >= 0 || j == 0) ? j : -1;
+        else node = j < len ? (j == len - 1 ? stop_node : a.out_node[(size_t)b * a.W + j]) : -1;
+        stop = node >= 0 && node == stop_node;
+    } else {
+        node = a.all_nodes ? (a.draft_tok[(size_t)b * a.N + j] >= 0 ? j : -1) : commit_row_of(a, b, j);
+        m = 0.0f;
+    }
+    if (node < 0) return;  // block-uniform
+    if (!stop && wave != 0) return;
+    if (!stop) m = a.src_m[a.mode == 0 ? b * a.N + node : b * a.R + j];
+    finish_row<DT, kFinishThreads>(a, sh, b, j, node, stop, m, nch, fc, len, my_id, my_mu, my_l, ch, part, tid, wave);
 }
 
 }  // namespace stand

@@ -406,7 +406,7 @@ __device__ __forceinline__ void fixed_split(float e, uint32_t &hi, uint32_t &lo)
 
 // Exact fixed-point sum over the vectors [v0, v1) of a row (plus the edge elements if with_edge),
 // strided over `nthreads` threads; returns this thread's partial sum_v floor(E((l_v - m) c) * 2^40).
-template <int DT>
+template <int DT, int INFLIGHT = 4>
 __device__ __forceinline__ unsigned long long thread_exact_partial(const void *rowp, const RowGeom &g, int v0, int v1,
                                                                    bool with_edge, float m, float c, int t, int nthreads)
 {
@@ -423,7 +423,7 @@ __device__ __forceinline__ unsigned long long thread_exact_partial(const void *r
             ahi += hi; alo += lo;
         }
     }
-    // four independent loads are issued before any of them is used (indices clamped, so the
+    // INFLIGHT independent loads are issued before any of them is used (indices clamped, so the
     // number of loads in flight does not depend on the position in the row)
     const int vlast = v1 > v0 ? v1 - 1 : v0;
     auto add_vec = [&](const uint4 &w, int idx) {
@@ -438,16 +438,22 @@ __device__ __forceinline__ unsigned long long thread_exact_partial(const void *r
             }
         }
     };
-    for (int base = v0 + t; base < v1; base += 4 * nthreads) {
-        const int i0 = base, i1 = base + nthreads, i2 = base + 2 * nthreads, i3 = base + 3 * nthreads;
-        const uint4 w0 = g.vp[i0 < vlast ? i0 : vlast];
-        const uint4 w1 = g.vp[i1 < vlast ? i1 : vlast];
-        const uint4 w2 = g.vp[i2 < vlast ? i2 : vlast];
-        const uint4 w3 = g.vp[i3 < vlast ? i3 : vlast];
-        add_vec(w0, i0); add_vec(w1, i1); add_vec(w2, i2); add_vec(w3, i3);
-        // at most 32 elements since the last flush: the 32-bit accumulators stay below 2^26
-        S += ((unsigned long long)ahi << 20) + alo;
-        ahi = 0; alo = 0;
+    for (int base = v0 + t; base < v1; base += INFLIGHT * nthreads) {
+        uint4 w[INFLIGHT];
+#pragma unroll
+        for (int q = 0; q < INFLIGHT; ++q) {
+            const int i = base + q * nthreads;
+            w[q] = g.vp[i < vlast ? i : vlast];
+        }
+#pragma unroll
+        for (int q = 0; q < INFLIGHT; ++q) {
+            add_vec(w[q], base + q * nthreads);
+            if ((q & 3) == 3 || q == INFLIGHT - 1) {
+                // at most 32 elements since the last flush: the 32-bit accumulators stay below 2^26
+                S += ((unsigned long long)ahi << 20) + alo;
+                ahi = 0; alo = 0;
+            }
+        }
     }
     return S + ((unsigned long long)ahi << 20) + alo;
 }
@@ -482,27 +488,28 @@ struct RowPassArgs {
     float eps;                  // relative error assumed for the fast normaliser (>= kFastEps)
 };
 
+// Shared memory of one row's workgroup of WPR waves.
+template <int WPR>
+struct RowShared {
+    WaveScan wsh[WPR];
+    unsigned long long ebuf[kElemCap + 8];  // element keys offered to the row's final selection
+    float part_m[WPR], part_s[WPR];
+    int part_cnt[WPR];
+};
+
+// One logits row by the WPR waves of the calling workgroup (all of its 64 * WPR threads call this).
+// `done`, if given, counts the two waves that write the row's results: each adds 1 once its stores
+// have completed at device scope, so a reader that sees the counter advance by 2 may read them.
 template <int DT, int WPR>
-__global__ __launch_bounds__(64 * WPR) void row_pass_kernel(RowPassArgs a)
+__device__ __forceinline__ void row_role(const RowPassArgs &a, int row, RowShared<WPR> *sm, unsigned *done)
 {
     constexpr int ES = VecTraits<DT>::ES;
-    __shared__ WaveScan wsh[WPR];
-    __shared__ unsigned long long ebuf[kElemCap + 8];  // element keys offered to the row's final selection
-    __shared__ float part_m[WPR], part_s[WPR];
-    __shared__ int part_cnt[WPR];
     // the wave's number is the same in all its lanes: say so, so that everything derived from it
     // (its share of the row, the loop over its batches) is kept in scalar registers
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    // Workgroups are numbered node-major (all trajectories' rows of node 0, then of node 1, ...).
-    // The nodes near the root carry drafted children, whose accept tests make the end of their
-    // row the longest; started first, those ends overlap with the streaming of later rows, and the
-    // rows that finish the kernel are leaves.
-    const int slot = blockIdx.x;
-    const int row = slot < a.B * a.N ? (slot % a.B) * a.N + slot / a.B : slot;
-    const bool live = row < a.B * a.N;
-    WaveScan *ws = &wsh[wave];
-    const int b = live ? row / a.N : 0, u = live ? row % a.N : 0;
-    const char *rowp = (const char *)a.logits + (size_t)(live ? row : 0) * (size_t)a.V * ES;
+    WaveScan *ws = &sm->wsh[wave];
+    const int b = row / a.N, u = row % a.N;
+    const char *rowp = (const char *)a.logits + (size_t)row * (size_t)a.V * ES;
     float m, s;
     // The proposal of this node (needed for the accept tests at the end) is requested by the
     // finishing wave as soon as it has streamed its part, so that its two dependent round trips
@@ -527,7 +534,7 @@ __global__ __launch_bounds__(64 * WPR) void row_pass_kernel(RowPassArgs a)
     // ---- accept / reject outcome of this node's children (paper Sec. 3.2, applied recursively)
     auto node_tests = [&](float m, float s) {
         if (nch == 0) {  // uniform over the wave
-            if (lane == 0) a.outcome[row] = -1;
+            if (lane == 0) st_agent(&a.outcome[row], (int32_t)-1);
             return;
         }
         const float e = (lane < a.K && my_id >= 0) ? exact_exp2(scaled_offset(my_l, m, a.c)) : 0.0f;
@@ -541,37 +548,42 @@ __global__ __launch_bounds__(64 * WPR) void row_pass_kernel(RowPassArgs a)
                                    0.0f, a.onehot);
             if (lane == 0) atomicAdd(&a.stats[kStatNear], 1ull);
         }
-        if (lane == 0) a.outcome[row] = nr.accepted;
+        if (lane == 0) st_agent(&a.outcome[row], (int32_t)nr.accepted);
+    };
+    auto signal_done = [&]() {
+        if (!done) return;
+        publish_fence();  // the wave's result stores (device scope) are complete before the counter moves
+        if (lane == 0) atomicAdd(done, 1u);
     };
     // Wave 0 ranks the row at its end, wave 1 runs the accept tests meanwhile.
     static_assert(WPR >= 2, "a row is shared by at least two waves");
     constexpr int kTestWave = 1;
-    if (live) {
+    {
         const WavePartial wp = wave_row_stream<DT>(rowp, a.V, a.c, a.K, ws, lane, wave, WPR);
-        if (lane == 0) { part_m[wave] = wp.m_ref; part_s[wave] = wp.s; part_cnt[wave] = wp.cnt; }
+        if (lane == 0) { sm->part_m[wave] = wp.m_ref; sm->part_s[wave] = wp.s; sm->part_cnt[wave] = wp.cnt; }
         if (wave == kTestWave) request_proposal();
     }
     __syncthreads();
-    if (!live) return;
     // both finishing waves form the row's maximum and normaliser with the same expressions, so
     // they hold the same m and s (the ranking's maximum, top[0], has no negative zero either)
-    m = part_m[0];
-    for (int q = 1; q < WPR; ++q) m = fmaxf(m, part_m[q]);
+    m = sm->part_m[0];
+    for (int q = 1; q < WPR; ++q) m = fmaxf(m, sm->part_m[q]);
     m = m + 0.0f;
     s = 0.0f;
-    for (int q = 0; q < WPR; ++q) s += part_s[q] * fast_exp2((part_m[q] - m) * a.c);
+    for (int q = 0; q < WPR; ++q) s += sm->part_s[q] * fast_exp2((sm->part_m[q] - m) * a.c);
     if (wave == kTestWave) {
         // the accept tests need the row's maximum and normaliser, not its ranking
         request_proposal_logits();
         node_tests(m, s);
+        signal_done();
         return;
     }
     if (wave != 0) return;
     // gather the partner waves' records behind this wave's own (each list holds at most
     // K + kPruneSlack ranking keys); with many partners the list is cut down on the way
-    int cnt = part_cnt[0];
+    int cnt = sm->part_cnt[0];
     for (int q = 1; q < WPR; ++q) {
-        const int cq = part_cnt[q];
+        const int cq = sm->part_cnt[q];
         if (cnt + cq > kWavePrune) {
             WaveScanState gs;
             gs.cnt = cnt;
@@ -580,20 +592,34 @@ __global__ __launch_bounds__(64 * WPR) void row_pass_kernel(RowPassArgs a)
             wave_prune_fast<false, true, DT == kDtBf16 ? 16 : 0>(ws, gs, lane, a.K, 0u, ~0u);
             cnt = gs.cnt;
         }
-        if (lane < cq) ws->buf[cnt + lane] = wsh[q].buf[lane];
+        if (lane < cq) ws->buf[cnt + lane] = sm->wsh[q].buf[lane];
         cnt += cq;
     }
     __builtin_amdgcn_wave_barrier();
-    wave_row_finish<DT>(rowp, a.V, a.K, ws, ebuf, lane, cnt);
+    wave_row_finish<DT>(rowp, a.V, a.K, ws, sm->ebuf, lane, cnt);
 
     if (lane < a.K) {
         const unsigned long long key = ws->top[lane];
         const float l = rank_key_value(key);
-        a.top_idx[(size_t)row * a.K + lane] = (int32_t)rank_key_id(key);
-        a.top_l[(size_t)row * a.K + lane] = l;
-        a.top_p[(size_t)row * a.K + lane] = exact_exp2(scaled_offset(l, m, a.c)) / s;
+        st_agent(&a.top_idx[(size_t)row * a.K + lane], (int32_t)rank_key_id(key));
+        st_agent(&a.top_l[(size_t)row * a.K + lane], l);
+        st_agent(&a.top_p[(size_t)row * a.K + lane], exact_exp2(scaled_offset(l, m, a.c)) / s);
     }
-    if (lane == 0) { a.row_m[row] = m; a.row_s[row] = s; }
+    if (lane == 0) { st_agent(&a.row_m[row], m); st_agent(&a.row_s[row], s); }
+    signal_done();
+}
+
+template <int DT, int WPR>
+__global__ __launch_bounds__(64 * WPR) void row_pass_kernel(RowPassArgs a)
+{
+    __shared__ RowShared<WPR> sm;
+    // Workgroups are numbered node-major (all trajectories' rows of node 0, then of node 1, ...).
+    // The nodes near the root carry drafted children, whose accept tests make the end of their
+    // row the longest; started first, those ends overlap with the streaming of later rows, and the
+    // rows that finish the kernel are leaves.
+    const int slot = blockIdx.x;
+    if (slot >= a.B * a.N) return;
+    row_role<DT, WPR>(a, (slot % a.B) * a.N + slot / a.B, &sm, nullptr);
 }
 
 }  // namespace stand

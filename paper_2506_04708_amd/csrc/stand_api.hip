@@ -13,6 +13,18 @@
 
 using namespace stand;
 
+// Device memory that one verification uses between its kernels (results of the row pass, partial sums,
+// the stop records, observations).
+struct VerifyScratch {
+    float *row_m, *row_s, *top_l, *top_p;
+    int32_t *top_idx, *outcome;
+    int32_t *obs_idx;
+    float *obs_p;
+    unsigned long long *seg_part;
+    int32_t *stop_i, *stop_qid, *stop_child;
+    float *stop_m, *stop_qmu, *stop_ql;
+};
+
 struct stand_handle {
     stand_config cfg;
     int N, D, K, B, V, W, NO, slot_bytes;
@@ -23,19 +35,28 @@ struct stand_handle {
     char *table;
     int32_t *ctx_tail;
     long long *ctx_len;
-    int32_t *draft_tok, *draft_has, *draft_qid;
+    int32_t *draft_tok, *draft_has, *draft_qid;   // the pending draft
     float *draft_qmu;
-    float *row_m, *row_s, *top_l, *top_p;
-    int32_t *top_idx, *outcome;
-    int32_t *obs_idx;
-    float *obs_p;
+    int32_t *draft_tok2, *draft_has2, *draft_qid2;  // second copy: the one-launch step writes the next draft here
+    float *draft_qmu2;                              // while rows that are still streaming read the pending one
+    // one-launch step (stand_step_kernel)
+    unsigned *row_done, *sum_done, *bar;  // counters that only grow, see step_fused.hpp
+    unsigned step_epoch;
+    int step_mode;       // STAND_STEP_AUTO / SERIAL / FUSED
+    int upper_depth;     // rows of nodes up to this depth are dispatched before the tail
+    int tail_groups;     // tail workgroups per trajectory (0: chosen from the batch size)
+    int rows_first;      // row workgroups dispatched before the tail's (0: as many as the device holds at once)
+    int step_slots;      // workgroups of stand_step_kernel the device holds at once (0: not asked yet)
+    uint32_t shuffle;    // non-zero: row slots are permuted (a test of independence from the work mapping)
+    uint64_t wait_limit_us;
+    int wall_khz;        // rate of the device's constant clock (wall_clock64)
+    unsigned long long *stamps;  // [2 + 8 * B] clock readings of the last one-launch step, or NULL (stand_step_timeline)
+    VerifyScratch vs;  // row results, partial sums, stop records, observations (hipMalloc'ed at create)
     long long *rec_slot;
     int R;            // row / record slots per trajectory: W, or N with STAND_UPDATE_ALL_NODES
     int32_t *recent;  // [B][N][kMaxOrder], all-nodes mode only
-    unsigned long long *seg_part, *node_count, *anc;  // anc: [N][anc_words] ancestor-or-self bit sets
+    unsigned long long *node_count, *anc;  // anc: [N][anc_words] ancestor-or-self bit sets
     int anc_words;
-    int32_t *stop_i, *stop_qid, *stop_child;
-    float *stop_m, *stop_qmu, *stop_ql;
     float *pr_m, *pr_top_l;
     int32_t *pr_top_idx;
     unsigned long long *stats;
@@ -80,8 +101,8 @@ static void free_all(stand_handle *h)
 {
     if (!h) return;
     void *ptrs[] = {h->d_tree, h->table, h->ctx_tail, h->ctx_len, h->draft_tok, h->draft_has, h->draft_qid, h->draft_qmu,
-                    h->row_m, h->row_s, h->top_l, h->top_p, h->top_idx, h->outcome, h->obs_idx, h->obs_p, h->rec_slot,
-                    h->recent, h->seg_part, h->node_count, h->anc, h->stop_i, h->stop_qid, h->stop_child, h->stop_m, h->stop_qmu, h->stop_ql, h->pr_m, h->pr_top_l, h->pr_top_idx, h->stats, h->counter};
+                    h->vs.row_m, h->vs.row_s, h->vs.top_l, h->vs.top_p, h->vs.top_idx, h->vs.outcome, h->vs.obs_idx, h->vs.obs_p, h->rec_slot,
+                    h->recent, h->draft_tok2, h->draft_has2, h->draft_qid2, h->draft_qmu2, h->row_done, h->sum_done, h->bar, h->stamps, h->vs.seg_part, h->node_count, h->anc, h->vs.stop_i, h->vs.stop_qid, h->vs.stop_child, h->vs.stop_m, h->vs.stop_qmu, h->vs.stop_ql, h->pr_m, h->pr_top_l, h->pr_top_idx, h->stats, h->counter};
     for (void *p : ptrs) (void)hipFree(p);
     for (hipEvent_t e : h->ev_begin) (void)hipEventDestroy(e);
     for (hipEvent_t e : h->ev_end) (void)hipEventDestroy(e);
@@ -124,6 +145,20 @@ extern "C" int stand_create(const stand_config *cfg, stand_handle **out)
     h->table_used = false;
     h->profiling = false;
     h->filter_margin = kFastEps;
+    h->step_epoch = 0;
+    h->step_mode = STAND_STEP_AUTO;
+    h->upper_depth = 2;
+    h->tail_groups = 0;
+    h->rows_first = 0;
+    h->step_slots = 0;
+    h->shuffle = 0;
+    h->wait_limit_us = 200000;
+    h->stamps = nullptr;
+    {
+        int khz = 0;
+        if (hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, cfg->device) != hipSuccess || khz <= 0) khz = 100000;
+        h->wall_khz = khz;
+    }
     h->ev_used = 0;
 
     // tree: breadth-first numbering with contiguous siblings <=> parents non-decreasing
@@ -161,18 +196,21 @@ extern "C" int stand_create(const stand_config *cfg, stand_handle **out)
     acc(dmalloc(&h->ctx_len, B));
     acc(dmalloc(&h->draft_tok, rows)); acc(dmalloc(&h->draft_has, rows));
     acc(dmalloc(&h->draft_qid, rows * K)); acc(dmalloc(&h->draft_qmu, rows * K));
-    acc(dmalloc(&h->row_m, rows)); acc(dmalloc(&h->row_s, rows));
-    acc(dmalloc(&h->top_l, rows * K)); acc(dmalloc(&h->top_p, rows * K)); acc(dmalloc(&h->top_idx, rows * K));
-    acc(dmalloc(&h->outcome, rows));
-    acc(dmalloc(&h->obs_idx, B * h->R * K)); acc(dmalloc(&h->obs_p, B * h->R * K));
+    acc(dmalloc(&h->draft_tok2, rows)); acc(dmalloc(&h->draft_has2, rows));
+    acc(dmalloc(&h->draft_qid2, rows * K)); acc(dmalloc(&h->draft_qmu2, rows * K));
+    acc(dmalloc(&h->row_done, rows)); acc(dmalloc(&h->sum_done, B)); acc(dmalloc(&h->bar, 2));
+    acc(dmalloc(&h->vs.row_m, rows)); acc(dmalloc(&h->vs.row_s, rows));
+    acc(dmalloc(&h->vs.top_l, rows * K)); acc(dmalloc(&h->vs.top_p, rows * K)); acc(dmalloc(&h->vs.top_idx, rows * K));
+    acc(dmalloc(&h->vs.outcome, rows));
+    acc(dmalloc(&h->vs.obs_idx, B * h->R * K)); acc(dmalloc(&h->vs.obs_p, B * h->R * K));
     acc(dmalloc(&h->rec_slot, nrec));
-    acc(dmalloc(&h->seg_part, B * h->R * kSegMax));
+    acc(dmalloc(&h->vs.seg_part, B * h->R * kSegMax));
     acc(dmalloc(&h->recent, rows * kMaxOrder));
     acc(dmalloc(&h->node_count, (size_t)N));
     h->anc_words = (N + 63) / 64;
     acc(dmalloc(&h->anc, (size_t)N * h->anc_words));
-    acc(dmalloc(&h->stop_i, B * 4)); acc(dmalloc(&h->stop_m, B)); acc(dmalloc(&h->stop_qid, B * kMaxK));
-    acc(dmalloc(&h->stop_qmu, B * kMaxK)); acc(dmalloc(&h->stop_ql, B * kMaxK)); acc(dmalloc(&h->stop_child, B * kMaxK));
+    acc(dmalloc(&h->vs.stop_i, B * 4)); acc(dmalloc(&h->vs.stop_m, B)); acc(dmalloc(&h->vs.stop_qid, B * kMaxK));
+    acc(dmalloc(&h->vs.stop_qmu, B * kMaxK)); acc(dmalloc(&h->vs.stop_ql, B * kMaxK)); acc(dmalloc(&h->vs.stop_child, B * kMaxK));
     acc(dmalloc(&h->pr_m, B * h->R)); acc(dmalloc(&h->pr_top_l, B * h->R * K)); acc(dmalloc(&h->pr_top_idx, B * h->R * K));
     acc(dmalloc(&h->stats, (size_t)kStatCount));
     acc(dmalloc(&h->counter, 1));
@@ -192,7 +230,14 @@ extern "C" int stand_create(const stand_config *cfg, stand_handle **out)
     acc(hipMemset(h->draft_has, 0, rows * sizeof(int32_t)));
     acc(hipMemset(h->draft_qid, 0, rows * K * sizeof(int32_t)));
     acc(hipMemset(h->draft_qmu, 0, rows * K * sizeof(float)));
-    acc(hipMemset(h->outcome, 0xFF, rows * sizeof(int32_t)));
+    acc(hipMemset(h->draft_tok2, 0xFF, rows * sizeof(int32_t)));
+    acc(hipMemset(h->draft_has2, 0, rows * sizeof(int32_t)));
+    acc(hipMemset(h->draft_qid2, 0, rows * K * sizeof(int32_t)));
+    acc(hipMemset(h->draft_qmu2, 0, rows * K * sizeof(float)));
+    acc(hipMemset(h->row_done, 0, rows * sizeof(unsigned)));
+    acc(hipMemset(h->sum_done, 0, B * sizeof(unsigned)));
+    acc(hipMemset(h->bar, 0, 2 * sizeof(unsigned)));
+    acc(hipMemset(h->vs.outcome, 0xFF, rows * sizeof(int32_t)));
     acc(hipMemset(h->node_count, 0, (size_t)N * sizeof(unsigned long long)));
     {
         // a node's set is its parent's set plus itself (parents come first in the numbering)
@@ -204,9 +249,9 @@ extern "C" int stand_create(const stand_config *cfg, stand_handle **out)
         }
         acc(hipMemcpy(h->anc, anc.data(), anc.size() * sizeof(unsigned long long), hipMemcpyHostToDevice));
     }
-    acc(hipMemset(h->row_m, 0, rows * sizeof(float))); acc(hipMemset(h->row_s, 0, rows * sizeof(float)));
-    acc(hipMemset(h->top_l, 0, rows * K * sizeof(float))); acc(hipMemset(h->top_p, 0, rows * K * sizeof(float)));
-    acc(hipMemset(h->top_idx, 0, rows * K * sizeof(int32_t)));
+    acc(hipMemset(h->vs.row_m, 0, rows * sizeof(float))); acc(hipMemset(h->vs.row_s, 0, rows * sizeof(float)));
+    acc(hipMemset(h->vs.top_l, 0, rows * K * sizeof(float))); acc(hipMemset(h->vs.top_p, 0, rows * K * sizeof(float)));
+    acc(hipMemset(h->vs.top_idx, 0, rows * K * sizeof(int32_t)));
     acc(hipMemset(h->stats, 0, kStatCount * sizeof(unsigned long long)));
     acc(hipDeviceSynchronize());
     if (e != hipSuccess) { free_all(h); return STAND_EHIP; }
@@ -275,16 +320,22 @@ extern "C" int stand_reorder(stand_handle *h, const int32_t *host_src_of, void *
 }
 
 // ---- launches ----------------------------------------------------------------------------------
-static int launch_row_pass(stand_handle *h, uint64_t step, const void *d_logits, hipStream_t s)
+static RowPassArgs make_row_args(const stand_handle *h, const VerifyScratch &vs, uint64_t step, const void *d_logits)
 {
     RowPassArgs a;
     a.logits = d_logits; a.B = h->B; a.N = h->N; a.V = h->V; a.K = h->K; a.c = h->c;
     a.seed = h->cfg.seed; a.step = step; a.tree = tree_dev(h);
     a.draft_tok = h->draft_tok; a.draft_has = h->draft_has; a.draft_qid = h->draft_qid; a.draft_qmu = h->draft_qmu;
-    a.row_m = h->row_m; a.row_s = h->row_s; a.top_idx = h->top_idx; a.top_l = h->top_l; a.top_p = h->top_p;
-    a.outcome = h->outcome; a.stats = h->stats;
+    a.row_m = vs.row_m; a.row_s = vs.row_s; a.top_idx = vs.top_idx; a.top_l = vs.top_l; a.top_p = vs.top_p;
+    a.outcome = vs.outcome; a.stats = h->stats;
     a.onehot = h->cfg.draft_mode == STAND_DRAFT_DETERMINISTIC;
     a.eps = h->filter_margin;
+    return a;
+}
+
+static int launch_row_pass(stand_handle *h, const VerifyScratch &vs, uint64_t step, const void *d_logits, hipStream_t s)
+{
+    RowPassArgs a = make_row_args(h, vs, step, d_logits);
     const int rows = h->B * h->N;
     const bool few = rows <= kRowsFew;  // one workgroup per row; more waves per row when rows are few
     const bool bf16 = h->cfg.logits_dtype == STAND_BF16;
@@ -317,14 +368,40 @@ static MergeArgs merge_args(stand_handle *h, const int32_t *commit_tok, const in
     a.replace = h->cfg.merge_policy == STAND_MERGE_REPLACE;
     a.depth = tree_dev(h).depth; a.recent = h->recent;
     a.ctx_tail = h->ctx_tail; a.ctx_len = h->ctx_len; a.commit_tok = commit_tok; a.commit_row = commit_row;
-    a.commit_len = commit_len; a.N = h->N; a.rec_slot = h->rec_slot; a.obs_idx = h->obs_idx; a.obs_p = h->obs_p;
+    a.commit_len = commit_len; a.N = h->N; a.rec_slot = h->rec_slot; a.obs_idx = h->vs.obs_idx; a.obs_p = h->vs.obs_p;
     a.stats = h->stats;
+    return a;
+}
+
+static PathArgs make_path_args(const stand_handle *h, const VerifyScratch &vs, uint64_t step, const void *d_logits, int mode,
+                               const int32_t *commit_row, const int32_t *commit_len, int32_t *out_tok, int32_t *out_node,
+                               int32_t *out_len, int seg_vectors)
+{
+    const bool bf16 = h->cfg.logits_dtype == STAND_BF16;
+    PathArgs a;
+    a.logits = d_logits; a.B = h->B; a.N = h->N; a.V = h->V; a.K = h->K; a.W = h->W; a.mode = mode; a.c = h->c;
+    a.R = h->R; a.all_nodes = h->cfg.update_mode == STAND_UPDATE_ALL_NODES;
+    a.seed = h->cfg.seed; a.step = step; a.tree = tree_dev(h);
+    a.draft_tok = h->draft_tok; a.draft_has = h->draft_has; a.draft_qid = h->draft_qid; a.draft_qmu = h->draft_qmu;
+    a.src_m = mode == 0 ? vs.row_m : h->pr_m;
+    a.src_top_idx = mode == 0 ? vs.top_idx : h->pr_top_idx;
+    a.src_top_l = mode == 0 ? vs.top_l : h->pr_top_l;
+    a.outcome = vs.outcome; a.commit_row = commit_row; a.commit_len = commit_len;
+    a.out_tok = out_tok; a.out_node = out_node; a.out_len = out_len;
+    a.seg_part = vs.seg_part; a.node_count = h->node_count;
+    a.onehot = h->cfg.draft_mode == STAND_DRAFT_DETERMINISTIC;
+    a.stop_i = vs.stop_i; a.stop_m = vs.stop_m; a.stop_qid = vs.stop_qid; a.stop_qmu = vs.stop_qmu; a.stop_ql = vs.stop_ql;
+    a.stop_child = vs.stop_child;
+    a.obs_idx = vs.obs_idx; a.obs_p = vs.obs_p; a.stats = h->stats;
+    // segments of seg_vectors 16-byte vectors where kSegMax allows it
+    const int row_vectors = (int)(((size_t)h->V * (bf16 ? 2 : 4) + 15) / 16);
+    a.nseg = clampi((row_vectors + seg_vectors - 1) / seg_vectors, 1, kSegMax);
     return a;
 }
 
 // mode 0 (verify): path from the row pass's outcomes; mode 1 (update): rows given by the caller.
 // With `claim` the launch that finishes the path rows also claims the table slots of that merge.
-static int launch_path_pass(stand_handle *h, uint64_t step, const void *d_logits, int mode, const int32_t *commit_row,
+static int launch_path_pass(stand_handle *h, const VerifyScratch &vs, uint64_t step, const void *d_logits, int mode, const int32_t *commit_row,
                             const int32_t *commit_len, int32_t *out_tok, int32_t *out_node, int32_t *out_len,
                             const MergeArgs *claim, hipStream_t s)
 {
@@ -339,25 +416,9 @@ static int launch_path_pass(stand_handle *h, uint64_t step, const void *d_logits
         if (bf16) commit_scan_kernel<kDtBf16><<<grid, dim3(256), 0, s>>>(c);
         else commit_scan_kernel<kDtF32><<<grid, dim3(256), 0, s>>>(c);
     }
-    PathArgs a;
-    a.logits = d_logits; a.B = h->B; a.N = h->N; a.V = h->V; a.K = h->K; a.W = h->W; a.mode = mode; a.c = h->c;
-    a.R = h->R; a.all_nodes = h->cfg.update_mode == STAND_UPDATE_ALL_NODES;
-    a.seed = h->cfg.seed; a.step = step; a.tree = tree_dev(h);
-    a.draft_tok = h->draft_tok; a.draft_has = h->draft_has; a.draft_qid = h->draft_qid; a.draft_qmu = h->draft_qmu;
-    a.src_m = mode == 0 ? h->row_m : h->pr_m;
-    a.src_top_idx = mode == 0 ? h->top_idx : h->pr_top_idx;
-    a.src_top_l = mode == 0 ? h->top_l : h->pr_top_l;
-    a.outcome = h->outcome; a.commit_row = commit_row; a.commit_len = commit_len;
-    a.out_tok = out_tok; a.out_node = out_node; a.out_len = out_len;
-    a.seg_part = h->seg_part; a.node_count = h->node_count;
-    a.onehot = h->cfg.draft_mode == STAND_DRAFT_DETERMINISTIC;
-    a.stop_i = h->stop_i; a.stop_m = h->stop_m; a.stop_qid = h->stop_qid; a.stop_qmu = h->stop_qmu; a.stop_ql = h->stop_ql;
-    a.stop_child = h->stop_child;
-    a.obs_idx = h->obs_idx; a.obs_p = h->obs_p; a.stats = h->stats;
     // segments: one round of loads per thread (4 vectors of 16 bytes) where kSegMax allows it;
     // one more block per (row, trajectory) slot for the outputs and the stop record
-    const int row_vectors = (int)(((size_t)h->V * (bf16 ? 2 : 4) + 15) / 16);
-    a.nseg = clampi((row_vectors + 4 * kPathThreads - 1) / (4 * kPathThreads), 1, kSegMax);
+    PathArgs a = make_path_args(h, vs, step, d_logits, mode, commit_row, commit_len, out_tok, out_node, out_len, 4 * kPathThreads);
     // row slots of the grid: every slot in update / all-nodes mode; in verify mode three (paths are
     // mostly short; the kernel loops over longer ones)
     const int row_slots = (mode == 0 && !a.all_nodes) ? (h->R < 3 ? h->R : 3) : h->R;
@@ -390,8 +451,8 @@ static int launch_merge_apply(stand_handle *h, const MergeArgs &a, bool append_c
     return STAND_OK;
 }
 
-static int launch_draft(stand_handle *h, uint64_t step, int32_t *d_draft_tok, const int32_t *append_tok,
-                        const int32_t *append_len, hipStream_t s)
+static DraftArgs make_draft_args(const stand_handle *h, uint64_t step, int32_t *d_draft_tok, const int32_t *append_tok,
+                                 const int32_t *append_len)
 {
     DraftArgs a;
     a.table = h->table; a.mask = h->cfg.table_capacity - 1; a.slot_bytes = h->slot_bytes; a.K = h->K;
@@ -401,6 +462,13 @@ static int launch_draft(stand_handle *h, uint64_t step, int32_t *d_draft_tok, co
     a.draft_tok = h->draft_tok; a.draft_has = h->draft_has; a.draft_qid = h->draft_qid; a.draft_qmu = h->draft_qmu;
     a.out_tok = d_draft_tok; a.stats = h->stats; a.mode = h->cfg.draft_mode;
     a.recent_out = h->cfg.update_mode == STAND_UPDATE_ALL_NODES ? h->recent : nullptr;
+    return a;
+}
+
+static int launch_draft(stand_handle *h, uint64_t step, int32_t *d_draft_tok, const int32_t *append_tok,
+                        const int32_t *append_len, hipStream_t s)
+{
+    DraftArgs a = make_draft_args(h, step, d_draft_tok, append_tok, append_len);
     draft_kernel<<<dim3((unsigned)h->B), dim3(kDraftThreads), 0, s>>>(a);
     HIP_TRY(h, hipGetLastError());
     return STAND_OK;
@@ -413,7 +481,7 @@ extern "C" int stand_update(stand_handle *h, uint64_t step, const void *d_logits
     hipStream_t s = (hipStream_t)stream;
     HIP_TRY(h, hipSetDevice(h->cfg.device));
     const MergeArgs mg = merge_args(h, d_commit_tok, d_commit_row, d_commit_len);
-    int rc = launch_path_pass(h, step, d_logits, 1, d_commit_row, d_commit_len, nullptr, nullptr, nullptr, &mg, s);
+    int rc = launch_path_pass(h, h->vs, step, d_logits, 1, d_commit_row, d_commit_len, nullptr, nullptr, nullptr, &mg, s);
     if (rc) return rc;
     return launch_merge_apply(h, mg, true, s);
 }
@@ -443,9 +511,139 @@ extern "C" int stand_verify(stand_handle *h, uint64_t step, const void *d_logits
     if (!h || !d_logits || !d_out_tok || !d_out_node || !d_out_len) return STAND_EINVAL;
     hipStream_t s = (hipStream_t)stream;
     HIP_TRY(h, hipSetDevice(h->cfg.device));
-    int rc = launch_row_pass(h, step, d_logits, s);
+    int rc = launch_row_pass(h, h->vs, step, d_logits, s);
     if (rc) return rc;
-    return launch_path_pass(h, step, d_logits, 0, nullptr, nullptr, d_out_tok, d_out_node, d_out_len, nullptr, s);
+    return launch_path_pass(h, h->vs, step, d_logits, 0, nullptr, nullptr, d_out_tok, d_out_node, d_out_len, nullptr, s);
+}
+
+// The whole step in one launch (step_fused.hpp).
+static bool step_fused_wanted(const stand_handle *h)
+{
+    if (h->cfg.update_mode != STAND_UPDATE_ACCEPTED_PATH) return false;
+    if (h->step_mode == STAND_STEP_SERIAL) return false;
+    // the tail's workgroups wait inside the launch for rows that may be dispatched after them: they must
+    // never hold more than a fraction of the device (256 compute units, three such workgroups each)
+    if (h->B * (h->tail_groups > 0 ? h->tail_groups : 1) > 256) return false;
+    if (h->step_mode == STAND_STEP_FUSED) return true;
+    return h->B * h->N > kRowsFew;  // with few rows the pass is latency-bound and sixteen waves per row serve it better
+}
+static int step_tail_groups(const stand_handle *h)
+{
+    return h->tail_groups > 0 ? h->tail_groups : (h->B <= 32 ? 4 : (h->B <= 64 ? 2 : 1));
+}
+
+static uint32_t gcd_u32(uint32_t a, uint32_t b) { while (b) { const uint32_t t = a % b; a = b; b = t; } return a; }
+
+static int launch_step_fused(stand_handle *h, uint64_t step, const void *d_logits, int32_t *out_tok, int32_t *out_node,
+                             int32_t *out_len, int32_t *next_draft_tok, const int32_t *commit, hipStream_t s)
+{
+    const bool bf16 = h->cfg.logits_dtype == STAND_BF16;
+    StepArgs A;
+    A.row = make_row_args(h, h->vs, step, d_logits);
+    // one wave sums one segment: 256 vectors per lane-round of four loads
+    A.path = make_path_args(h, h->vs, step, d_logits, 0, nullptr, nullptr, out_tok, out_node, out_len, 4 * 64 * 2);
+    A.mg = merge_args(h, commit, nullptr, out_len);
+    A.draft = make_draft_args(h, step + 1, next_draft_tok, commit, out_len);
+    // the next draft goes to the second copy of the draft state; the copies change roles after the launch
+    A.draft.draft_tok = h->draft_tok2; A.draft.draft_has = h->draft_has2;
+    A.draft.draft_qid = h->draft_qid2; A.draft.draft_qmu = h->draft_qmu2;
+    A.sync.row_done = h->row_done; A.sync.sum_done = h->sum_done; A.sync.bar = h->bar;
+    A.sync.epoch = ++h->step_epoch;
+    A.sync.wait_ticks = h->wait_limit_us * (uint64_t)h->wall_khz / 1000ull;
+    A.sync.stamps = h->stamps;
+    if (h->stamps) {
+        // earliest start: all ones, latest end: zero (set by a fill kernel; the launch stays capturable)
+        fill_i32_kernel<<<dim3(1), dim3(64), 0, s>>>((int32_t *)h->stamps, -1, 2);
+        fill_i32_kernel<<<dim3(1), dim3(64), 0, s>>>((int32_t *)(h->stamps + 1), 0, 2);
+    }
+    const int ud = h->upper_depth < h->D ? h->upper_depth : h->D;
+    A.upper_nodes = h->level_start[ud + 1];
+    A.G = step_tail_groups(h);
+    const void *fn = bf16 ? (const void *)stand_step_kernel<kDtBf16> : (const void *)stand_step_kernel<kDtF32>;
+    const size_t smem = step_shared_bytes(h->N, h->D);
+    if (h->step_slots == 0) {
+        // how many of the kernel's workgroups are resident at once: the rows before the tail fill the device once
+        int per_cu = 0, cus = 0;
+        HIP_TRY(h, hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, kStepThreads, smem));
+        HIP_TRY(h, hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, h->cfg.device));
+        h->step_slots = per_cu * cus > 0 ? per_cu * cus : 1;
+    }
+    const uint32_t rows = (uint32_t)(h->B * h->N), n_up = (uint32_t)(A.upper_nodes * h->B);
+    A.shuffle_mul = 1; A.shuffle_add = 0;
+    if (h->shuffle) {
+        // a multiplier coprime with both group sizes permutes the slots of each group
+        uint32_t mul = (h->shuffle * 2654435761u) | 1u;
+        mul = mul % 1000003u + 2u;
+        while (gcd_u32(mul, n_up ? n_up : 1u) != 1u || gcd_u32(mul, rows - n_up ? rows - n_up : 1u) != 1u) ++mul;
+        A.shuffle_mul = mul; A.shuffle_add = h->shuffle;
+    }
+    const uint32_t row_wgs = rows;  // one row per workgroup
+    {
+        const uint32_t want = h->rows_first > 0 ? (uint32_t)h->rows_first : (uint32_t)h->step_slots;
+        const uint32_t first = want > n_up ? want : n_up;
+        A.rows_first = (int)(first < row_wgs ? first : row_wgs);
+    }
+#ifdef STAND_DEBUG_NO_TAIL
+    A.G = 0;
+#endif
+    const dim3 grid(row_wgs + (uint32_t)(h->B * A.G)), block(kStepThreads);
+    void *args[] = {&A};
+    const bool timed = h->profiling && h->ev_used < h->ev_begin.size();
+    if (timed) {
+        hipEvent_t e0 = h->ev_begin[h->ev_used], e1 = h->ev_end[h->ev_used];
+        h->ev_used++;
+        HIP_TRY(h, hipExtLaunchKernel(fn, grid, block, args, smem, s, e0, e1, 0));
+    } else {
+        HIP_TRY(h, hipLaunchKernel(fn, grid, block, args, smem, s));
+    }
+    HIP_TRY(h, hipGetLastError());
+    std::swap(h->draft_tok, h->draft_tok2); std::swap(h->draft_has, h->draft_has2);
+    std::swap(h->draft_qid, h->draft_qid2); std::swap(h->draft_qmu, h->draft_qmu2);
+    h->table_used = true;
+    return STAND_OK;
+}
+
+extern "C" int stand_set_step_plan(stand_handle *h, int32_t mode, int32_t upper_depth, int32_t tail_groups, int32_t rows_first,
+                                   uint32_t shuffle)
+{
+    if (!h || mode < STAND_STEP_AUTO || mode > STAND_STEP_FUSED || upper_depth < 0 || upper_depth > STAND_MAX_DEPTH ||
+        tail_groups < 0 || tail_groups > 8 || rows_first < 0)
+        return STAND_EINVAL;
+    if (mode == STAND_STEP_FUSED && h->cfg.update_mode != STAND_UPDATE_ACCEPTED_PATH) return STAND_EINVAL;
+    h->step_mode = mode; h->upper_depth = upper_depth; h->tail_groups = tail_groups; h->rows_first = rows_first;
+    h->shuffle = shuffle;
+    return STAND_OK;
+}
+
+extern "C" int stand_step_timeline(stand_handle *h, int32_t enable, uint64_t *host_ticks, uint64_t *ticks_per_second)
+{
+    if (!h) return STAND_EINVAL;
+    HIP_TRY(h, hipSetDevice(h->cfg.device));
+    if (ticks_per_second) *ticks_per_second = (uint64_t)h->wall_khz * 1000ull;
+    const size_t n = 2 + 8 * (size_t)h->B;
+    if (host_ticks && h->stamps) {
+        HIP_TRY(h, hipDeviceSynchronize());
+        HIP_TRY(h, hipMemcpy(host_ticks, h->stamps, n * sizeof(uint64_t), hipMemcpyDeviceToHost));
+    } else if (host_ticks) {
+        return STAND_ESTATE;
+    }
+    if (enable && !h->stamps) {
+        HIP_TRY(h, hipDeviceSynchronize());
+        HIP_TRY(h, dmalloc(&h->stamps, n));
+        HIP_TRY(h, hipMemset(h->stamps, 0, n * sizeof(uint64_t)));
+    } else if (!enable && h->stamps) {
+        HIP_TRY(h, hipDeviceSynchronize());
+        (void)hipFree(h->stamps);
+        h->stamps = nullptr;
+    }
+    return STAND_OK;
+}
+
+extern "C" int stand_set_wait_limit(stand_handle *h, uint64_t microseconds)
+{
+    if (!h || microseconds > 60ull * 1000 * 1000) return STAND_EINVAL;
+    h->wait_limit_us = microseconds;
+    return STAND_OK;
 }
 
 extern "C" int stand_step(stand_handle *h, uint64_t step, const void *d_logits, int32_t *d_out_tok, int32_t *d_out_node,
@@ -454,11 +652,13 @@ extern "C" int stand_step(stand_handle *h, uint64_t step, const void *d_logits, 
     if (!h || !d_logits || !d_out_tok || !d_out_node || !d_out_len) return STAND_EINVAL;
     hipStream_t s = (hipStream_t)stream;
     HIP_TRY(h, hipSetDevice(h->cfg.device));
-    int rc = launch_row_pass(h, step, d_logits, s);
-    if (rc) return rc;
     const int32_t *commit = d_force_tok ? d_force_tok : d_out_tok;
+    if (step_fused_wanted(h))
+        return launch_step_fused(h, step, d_logits, d_out_tok, d_out_node, d_out_len, d_next_draft_tok, commit, s);
+    int rc = launch_row_pass(h, h->vs, step, d_logits, s);
+    if (rc) return rc;
     const MergeArgs mg = merge_args(h, commit, nullptr, d_out_len);
-    rc = launch_path_pass(h, step, d_logits, 0, nullptr, nullptr, d_out_tok, d_out_node, d_out_len, &mg, s);
+    rc = launch_path_pass(h, h->vs, step, d_logits, 0, nullptr, nullptr, d_out_tok, d_out_node, d_out_len, &mg, s);
     if (rc) return rc;
     rc = launch_merge_apply(h, mg, false, s);
     if (rc) return rc;
@@ -473,7 +673,7 @@ extern "C" int stand_row_results(stand_handle *h, float *d_row_max, float *d_row
     HIP_TRY(h, hipSetDevice(h->cfg.device));
     const size_t n = (size_t)h->B * h->N * h->K;
     copy_row_results_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, (hipStream_t)stream>>>(
-        h->B * h->N, h->K, h->row_m, h->row_s, h->top_idx, h->top_p, d_row_max, d_row_sum, d_top_idx, d_top_p);
+        h->B * h->N, h->K, h->vs.row_m, h->vs.row_s, h->vs.top_idx, h->vs.top_p, d_row_max, d_row_sum, d_top_idx, d_top_p);
     HIP_TRY(h, hipGetLastError());
     return STAND_OK;
 }
@@ -581,6 +781,7 @@ extern "C" int stand_get_stats(stand_handle *h, stand_stats *out)
     out->misses = st[kStatMisses]; out->inserts = st[kStatInserts]; out->merges = st[kStatMerges];
     out->drops = st[kStatDrops]; out->near_threshold = st[kStatNear]; out->tokens_emitted = st[kStatTokens];
     out->accept_tests = st[kStatTests]; out->filter_mismatch = st[kStatMismatch];
+    out->wait_expired = st[kStatWaitExpired];
     return STAND_OK;
 }
 

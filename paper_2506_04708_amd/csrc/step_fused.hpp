@@ -1,0 +1,286 @@
+// step_fused.hpp -- stand_step_kernel: one speculation step in ONE launch (paper Sec. 3.2, 4.1, 4.2).
+//
+// The step's dependent part (path walk, exact sums of the path rows, resampled token, table merge,
+// next draft) needs only the rows on the accepted paths, which lie in the upper levels of the tree,
+// and moves under 2 % of the step's bytes; run after the row pass it still costs a quarter of the
+// step, because it is a chain of dependent round trips to memory.  Here it runs BESIDE the row pass:
+//
+//   workgroups [0, P)          rows: first those of the tree's upper levels (node-major), one row per
+//                              workgroup, then as many others as the device holds at once
+//   workgroups [P, P + B*G)    the tail: G workgroups per trajectory
+//   the rest                   all other rows
+//
+// Workgroups start in index order, so the first P rows fill the device and finish together; the tail's
+// workgroups take the first places that become free and work while the remaining rows stream.  A tail workgroup never
+// assumes anything about timing: it WAITS for what it needs -- the two result counts of each row on
+// its path (any row, also one that is dispatched after it), the partial sums of its trajectory's
+// other workgroups, and twice for all trajectories (every claim before the first apply, every apply
+// before the first lookup of the draft).  Every wait polls a device-scope counter, sleeps between the
+// polls and gives up after a bounded time (counted in the statistics; the trajectory's outputs are
+// then void); counters only ever grow (launch number times arrivals per launch), so nothing needs
+// clearing between launches.  What a workgroup waits for is always produced by workgroups that need
+// nothing from it.
+#pragma once
+#include "draft.hpp"
+#include "path_pass.hpp"
+
+namespace stand {
+
+#ifndef STAND_STEP_WPR
+#define STAND_STEP_WPR 8
+#endif
+constexpr int kStepWPR = STAND_STEP_WPR;     // waves per workgroup; a row is shared by all of them
+constexpr int kStepThreads = 64 * kStepWPR;
+#ifndef STAND_STEP_MINWAVES
+#define STAND_STEP_MINWAVES 6   // waves per SIMD the kernel's register use must leave room for
+#endif
+#ifndef STAND_POLL_SLEEP
+#define STAND_POLL_SLEEP 8   // argument of s_sleep between two polls of a wait (units of 64 clocks)
+#endif
+#ifndef STAND_TAIL_INFLIGHT
+#define STAND_TAIL_INFLIGHT 8
+#endif
+constexpr int kTailInflight = STAND_TAIL_INFLIGHT;  // 16-byte loads a lane of the tail keeps in flight while it sums a row segment
+constexpr unsigned kWaitMaxPolls = 1u << 24;  // a wait ends after this many polls whatever the clock says
+
+struct StepSync {
+    unsigned *row_done;             // [B*N]  +2 per launch: the ranking wave and the testing wave of the row
+    unsigned *sum_done;             // [B]    +G per launch: the trajectory's tail workgroups after their sums
+    unsigned *bar;                  // [2]    +B per launch each: all claims made / all records applied
+    unsigned epoch;                 // number of this launch on the handle, from 1
+    unsigned long long wait_ticks;  // bound of every wait in ticks of the device's constant clock (wall_clock64)
+    unsigned long long *stamps;     // NULL, or [2 + 8 * B] clock readings of this launch: earliest row start, latest row
+                                    // end, then per trajectory: tail start, path known, sums done, claims made, rows
+                                    // finished, all claims in, all records applied, draft done
+};
+
+struct StepArgs {
+    RowPassArgs row;
+    PathArgs path;       // mode 0, accepted-path update
+    MergeArgs mg;
+    DraftArgs draft;     // writes the OTHER copy of the draft state: rows still streaming read the pending one
+    StepSync sync;
+    int upper_nodes;     // rows of tree nodes [0, upper_nodes) are the first row slots
+    int rows_first;      // row workgroups (>= upper_nodes * B) that come before the tail's
+    int G;               // tail workgroups per trajectory
+    uint32_t shuffle_mul, shuffle_add;  // row slots inside each group are permuted by slot * mul + add (1, 0: identity)
+};
+
+// Polls *p until it has reached `target` (wrap-safe: counters are at most one launch behind).
+__device__ __forceinline__ bool wait_reached(const unsigned *p, unsigned target, unsigned long long ticks)
+{
+    // The polls are relaxed device-scope loads.  What the arriving workgroups stored before they arrived was
+    // stored at device scope and had completed (publish_fence); it is read with ld_agent after this returns.
+    bool seen = (int)(__hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - target) >= 0;
+    if (!seen) {
+        const unsigned long long t0 = wall_clock64();
+        // bounded twice: by the device's constant clock and by a count of polls (each takes a fraction of a microsecond)
+        for (unsigned polls = 0; polls < kWaitMaxPolls && !seen; ++polls) {
+            __builtin_amdgcn_s_sleep(STAND_POLL_SLEEP);
+            seen = (int)(__hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - target) >= 0;
+            if (!seen && wall_clock64() - t0 > ticks) break;
+        }
+    }
+    if (seen) consume_fence();
+    return seen;
+}
+
+__device__ __forceinline__ void stamp(const StepSync &sy, int b, int k)
+{
+    if (sy.stamps) sy.stamps[2 + 8 * b + k] = wall_clock64();
+}
+
+struct TailShared {
+    int path[kMaxDepth + 2];   // nodes of the accepted path
+    int acc[kMaxDepth + 2];    // outcome of each of them
+    int len, ok;
+    FinishShared fin;
+    int32_t l_id[kStepWPR][2 * kMaxK];
+    float l_val[kStepWPR][2 * kMaxK];
+};
+
+// All workgroups of one count arrive, then wait for the rest.  Called by the whole workgroup.
+__device__ __forceinline__ void tail_barrier(const StepSync &sy, int which, unsigned arrivals, TailShared *ts)
+{
+    publish_fence();  // this workgroup's stores (table, records, observations) are complete before its arrival
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        atomicAdd(&sy.bar[which], 1u);
+        if (!wait_reached(&sy.bar[which], arrivals * sy.epoch, sy.wait_ticks)) ts->ok = 0;
+    }
+    __syncthreads();
+    consume_fence();
+}
+
+template <int DT>
+__device__ __forceinline__ void tail_role(const StepArgs &A, int b, int g, char *smem)
+{
+    constexpr int ES = VecTraits<DT>::ES;
+    const PathArgs &a = A.path;
+    const StepSync &sy = A.sync;
+    TailShared *ts = (TailShared *)smem;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int N = a.N, W = a.W, K = a.K;
+
+    // ---- the accepted path: follow the outcomes from the root, waiting for each row on the way
+    if (tid == 0) {
+        if (g == 0) stamp(sy, b, 0);
+        int cur = 0, len = 0, ok = 1;
+        for (;;) {
+            if (!wait_reached(&sy.row_done[(size_t)b * N + cur], 2u * sy.epoch, sy.wait_ticks)) { ok = 0; break; }
+            const int acc = __hip_atomic_load(&a.outcome[(size_t)b * N + cur], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            ts->path[len] = cur;
+            ts->acc[len] = acc;
+            ++len;
+            if (acc < 0 || len > a.tree.D) break;
+            const int nxt = a.tree.first_child[cur] + acc;
+            if (nxt <= cur || nxt >= N) break;  // not reachable for outcomes of this tree
+            cur = nxt;
+        }
+        ts->len = ok ? len : 0;
+        ts->ok = ok;
+        if (g == 0) stamp(sy, b, 1);
+    }
+    __syncthreads();
+    consume_fence();
+    const int len = ts->len;
+
+    // ---- exact partial sums: item (path row j, segment) number i goes to wave i mod (G * waves)
+    const int nseg = a.nseg;
+    for (int item = g * kStepWPR + wave; item < len * nseg; item += A.G * kStepWPR) {
+        const int j = item / nseg, seg = item % nseg;
+        const int row = b * N + ts->path[j];
+        const char *rowp = (const char *)a.logits + (size_t)row * (size_t)a.V * ES;
+        const float m = ld_agent(&a.src_m[row]);
+        const RowGeom geo = row_geom<DT>(rowp, a.V);
+        const int per = (geo.nvec + nseg - 1) / nseg;
+        const int v0 = seg * per < geo.nvec ? seg * per : geo.nvec;
+        const int v1 = (v0 + per < geo.nvec) ? v0 + per : geo.nvec;
+#ifdef STAND_DEBUG_SKIP_SUMS
+        unsigned long long S = (unsigned long long)(v1 - v0);
+#else
+        unsigned long long S = thread_exact_partial<DT, kTailInflight>(rowp, geo, v0, v1, seg == 0, m, a.c, lane, 64);
+#endif
+        S = wave_sum_u64(S);
+        if (lane == 0) st_agent(&a.seg_part[((size_t)b * a.R + j) * kSegMax + seg], S);
+    }
+    publish_fence();
+    __syncthreads();
+    if (tid == 0) atomicAdd(&sy.sum_done[b], 1u);
+    if (g != 0) return;  // the trajectory's other workgroups only help with the sums
+
+    // ---- outputs of the verification; the stop node's proposal is requested now and used after the sums
+    const int stop_node = len > 0 ? ts->path[len - 1] : 0;
+    const int stop_row = b * N + stop_node;
+    const char *stop_rowp = (const char *)a.logits + (size_t)stop_row * (size_t)a.V * ES;
+    int nch = 0, fc = -1;
+    int32_t my_id = -1, ch = -1;
+    float my_mu = 0.0f, my_l = 0.0f, stop_m = 0.0f;
+    if (len > 0) {
+        fc = a.tree.first_child[stop_node];
+        nch = a.draft_has[stop_row];
+        stop_m = ld_agent(&a.src_m[stop_row]);
+        if (wave == 0) {
+            if (lane < K) { my_id = a.draft_qid[(size_t)stop_row * K + lane]; my_mu = a.draft_qmu[(size_t)stop_row * K + lane]; }
+            if (lane < nch && lane < kMaxK && fc >= 0 && fc + lane < N) ch = a.draft_tok[(size_t)b * N + fc + lane];
+            if ((uint32_t)my_id >= (uint32_t)a.V) { my_id = -1; my_mu = 0.0f; }  // never index outside the row
+            else my_l = load_scalar<DT>(stop_rowp, my_id);
+        }
+    }
+    if (tid < W) {
+        a.out_node[(size_t)b * W + tid] = tid < len ? ts->path[tid] : -1;
+        // accepted tokens are the tokens of the path nodes after the root; the last emitted token
+        // (position len - 1) is written by finish_row
+        if (tid + 1 < len) a.out_tok[(size_t)b * W + tid] = a.draft_tok[(size_t)b * N + ts->path[tid + 1]];
+        else if (tid >= len - 1) a.out_tok[(size_t)b * W + tid] = -1;
+    }
+    if (tid < len) atomicAdd(&a.node_count[ts->path[tid]], 1ull);  // paper Sec. 4.3: acceptance statistics per node
+    if (tid == 0) {
+        a.out_len[b] = len;
+        if (len > 0) {
+            unsigned long long tests = (unsigned long long)nch;
+            for (int q = 0; q + 1 < len; ++q) tests += (unsigned long long)(ts->acc[q] + 1);
+            atomicAdd(&a.stats[kStatTokens], (unsigned long long)len);
+            atomicAdd(&a.stats[kStatTests], tests);
+        } else {
+            atomicAdd(&a.stats[kStatWaitExpired], 1ull);
+        }
+    }
+    __syncthreads();  // out_len and the accepted tokens are what the claims read
+    // ---- slots of this trajectory's merge records (they depend on the path's tokens only)
+    {
+        const int per_traj = A.mg.R * (A.mg.omax - A.mg.omin + 1);
+        for (int i = tid; i < per_traj; i += kStepThreads) merge_claim_record(A.mg, b * per_traj + i);
+    }
+    // ---- the sums of all of the trajectory's workgroups, then the rows' observations and the resampled token
+    if (tid == 0) {
+        stamp(sy, b, 3);
+        if (!wait_reached(&sy.sum_done[b], (unsigned)A.G * sy.epoch, sy.wait_ticks)) ts->ok = 0;
+        stamp(sy, b, 2);
+    }
+    __syncthreads();
+    consume_fence();
+    if (len > 0 && ts->ok) {
+        for (int j = wave; j + 1 < len; j += kStepWPR) {  // rows above the stop row: one wave each
+            const int node = ts->path[j];
+            const unsigned long long part = lane < nseg ? ld_agent(&a.seg_part[((size_t)b * a.R + j) * kSegMax + lane]) : 0ull;
+            finish_row<DT, kStepThreads>(a, ts->fin, b, j, node, false, ld_agent(&a.src_m[b * N + node]), 0, -1, len, -1, 0.0f, 0.0f, -1,
+                                         part, lane, 0);
+        }
+        const unsigned long long part =
+            (wave == 0 && lane < nseg) ? ld_agent(&a.seg_part[((size_t)b * a.R + (len - 1)) * kSegMax + lane]) : 0ull;
+        finish_row<DT, kStepThreads>(a, ts->fin, b, len - 1, stop_node, true, stop_m, nch, fc, len, my_id, my_mu, my_l, ch, part,
+                                     tid, wave);
+    } else if (len > 0 && tid == 0) {
+        a.out_tok[(size_t)b * W + (len - 1)] = -1;
+        atomicAdd(&a.stats[kStatWaitExpired], 1ull);
+    }
+
+    // ---- every trajectory's claims and observations, then this trajectory's records
+    if (tid == 0) stamp(sy, b, 4);
+    tail_barrier(sy, 0, (unsigned)a.B, ts);
+    if (tid == 0) stamp(sy, b, 5);
+    {
+        const int NO = A.mg.omax - A.mg.omin + 1;
+        for (int i = wave; i < len * NO; i += kStepWPR) apply_record(A.mg, b * A.mg.R * NO + i, lane, ts->l_id[wave], ts->l_val[wave]);
+    }
+    // ---- every trajectory's records applied, then the next draft
+    tail_barrier(sy, 1, (unsigned)a.B, ts);
+    if (tid == 0) stamp(sy, b, 6);
+    if (tid == 0 && !ts->ok) atomicAdd(&a.stats[kStatWaitExpired], 1ull);
+    draft_trajectory<kStepThreads>(A.draft, b, draft_shared_carve(smem + ((sizeof(TailShared) + 15) & ~(size_t)15), A.draft.tree.N, A.draft.tree.D));
+    if (tid == 0) stamp(sy, b, 7);
+}
+
+__host__ __device__ inline size_t step_shared_bytes(int N, int D)
+{
+    const size_t tail = ((sizeof(TailShared) + 15) & ~(size_t)15) + draft_shared_bytes(N, D);
+    return tail > sizeof(RowShared<kStepWPR>) ? tail : sizeof(RowShared<kStepWPR>);
+}
+
+template <int DT>
+__global__ __launch_bounds__(kStepThreads) __attribute__((amdgpu_waves_per_eu(STAND_STEP_MINWAVES, 8))) void stand_step_kernel(StepArgs A)
+{
+    extern __shared__ __align__(16) char step_smem[];
+    const int B = A.row.B, rows = A.row.B * A.row.N;
+    const int n_up = A.upper_nodes * B, n_first = A.rows_first, n_tail = B * A.G;
+    const int i = (int)blockIdx.x;
+    if (i >= n_first && i < n_first + n_tail) {
+        const int t = i - n_first;
+        tail_role<DT>(A, t % B, t / B, step_smem);
+        return;
+    }
+    // row slots: [0, n_up) the upper levels, [n_up, rows) the others; node-major inside each group
+    int slot = i < n_first ? i : i - n_tail;
+    if (slot >= rows) return;
+    {
+        const int base = slot < n_up ? 0 : n_up, n = slot < n_up ? n_up : rows - n_up;
+        slot = base + (int)(((unsigned long long)(slot - base) * A.shuffle_mul + A.shuffle_add) % (unsigned)n);
+    }
+    const int row = (slot % B) * A.row.N + slot / B;
+    if (A.sync.stamps && threadIdx.x == 0) atomicMin(&A.sync.stamps[0], (unsigned long long)wall_clock64());
+    row_role<DT, kStepWPR>(A.row, row, (RowShared<kStepWPR> *)step_smem, &A.sync.row_done[row]);
+    if (A.sync.stamps && (threadIdx.x == 0 || threadIdx.x == 64)) atomicMax(&A.sync.stamps[1], (unsigned long long)wall_clock64());
+}
+
+}  // namespace stand

@@ -89,7 +89,7 @@ __device__ __forceinline__ void merge_claim_record(const MergeArgs &a, int rec)
         }
         if (!placed) atomicAdd(&a.stats[kStatDrops], 1ull);
     }
-    a.rec_slot[rec] = slot_out;
+    st_agent(&a.rec_slot[rec], slot_out);
 }
 
 
@@ -100,35 +100,31 @@ __device__ __forceinline__ void merge_claim_record(const MergeArgs &a, int rec)
 // once.  A slot claimed by one record only needs no search for followers.  The waves of a
 // workgroup do not interact.
 constexpr int kMergeWaves = 16;
-__global__ __launch_bounds__(64 * kMergeWaves) void merge_apply_kernel(MergeArgs a)
+
+// Record `rec` by one wave (all 64 lanes call this; l_id / l_val: 2 * kMaxK words of shared memory
+// owned by the wave).  Does nothing unless the record exists and leads its slot.
+__device__ __forceinline__ void apply_record(const MergeArgs &a, int rec, int lane, int32_t *l_id, float *l_val)
 {
-    __shared__ int32_t l_id_all[kMergeWaves][2 * kMaxK];
-    __shared__ float l_val_all[kMergeWaves][2 * kMaxK];
     const int NO = a.omax - a.omin + 1;
     const int nrec = a.B * a.R * NO;
-    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    const int rec = (int)blockIdx.x * kMergeWaves + wave;
-    if (rec >= nrec) return;
-    int32_t *l_id = l_id_all[wave];
-    float *l_val = l_val_all[wave];
     const int K = a.K;
-    const long long slot = a.rec_slot[rec];
+    const long long slot = ld_agent(&a.rec_slot[rec]);
     if (slot < 0) return;
     SlotHeader *h = slot_header(a.table, (uint64_t)slot, a.slot_bytes);
     int32_t *ids = slot_ids(a.table, (uint64_t)slot, a.slot_bytes);
     float *mus = slot_mu(a.table, (uint64_t)slot, a.slot_bytes, K);
     // header, stored entry and this record's observation are requested together
-    const uint32_t order_word = h->order;
-    uint32_t count = h->count;
+    const uint32_t order_word = ld_agent(&h->order);
+    uint32_t count = ld_agent(&h->count);
     int32_t e_id = -1;
     float e_mu = 0.0f;
-    if (lane < K) { e_id = ids[lane]; e_mu = mus[lane]; }
+    if (lane < K) { e_id = ld_agent(&ids[lane]); e_mu = ld_agent(&mus[lane]); }
     // lanes 0..K-1: stored entry; lanes 32..32+K-1: observation
     int32_t o_id = -1;
     float o_p = 0.0f;
     if (lane >= 32 && lane < 32 + K) {
-        o_id = a.obs_idx[(size_t)(rec / NO) * K + (lane - 32)];
-        o_p = a.obs_p[(size_t)(rec / NO) * K + (lane - 32)];
+        o_id = ld_agent(&a.obs_idx[(size_t)(rec / NO) * K + (lane - 32)]);
+        o_p = ld_agent(&a.obs_p[(size_t)(rec / NO) * K + (lane - 32)]);
     }
     if (kTagMax - (order_word >> kTagShift) != (uint32_t)rec) return;  // another record leads this slot
     const bool multi = (count & kMultiBit) != 0u;
@@ -182,23 +178,43 @@ __global__ __launch_bounds__(64 * kMergeWaves) void merge_apply_kernel(MergeArgs
 
     apply(o_id, o_p);
     if (multi) {
-        // the later records of this slot, in record order
-        for (int base = rec + 1; base < nrec; base += 64) {
-            const int r = base + lane;
-            unsigned long long hits = __ballot(r < nrec && a.rec_slot[r] == slot);
-            while (hits) {
-                const int bit = __ffsll((long long)hits) - 1;
-                hits &= hits - 1;
-                const int jb = (base + bit) / NO;  // = b * W + j
-                int32_t f_id = -1;
-                float f_p = 0.0f;
-                if (lane >= 32 && lane < 32 + K) { f_id = a.obs_idx[(size_t)jb * K + (lane - 32)]; f_p = a.obs_p[(size_t)jb * K + (lane - 32)]; }
-                apply(f_id, f_p);
+        // the later records of this slot, in record order (four groups of 64 record slots are read per round)
+        for (int base = rec + 1; base < nrec; base += 256) {
+            long long rs[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int r = base + 64 * q + lane;
+                rs[q] = r < nrec ? ld_agent(&a.rec_slot[r]) : -1;
+            }
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                unsigned long long hits = __ballot(rs[q] == slot);
+                while (hits) {
+                    const int bit = __ffsll((long long)hits) - 1;
+                    hits &= hits - 1;
+                    const int jb = (base + 64 * q + bit) / NO;  // = b * R + j
+                    int32_t f_id = -1;
+                    float f_p = 0.0f;
+                    if (lane >= 32 && lane < 32 + K) { f_id = ld_agent(&a.obs_idx[(size_t)jb * K + (lane - 32)]); f_p = ld_agent(&a.obs_p[(size_t)jb * K + (lane - 32)]); }
+                    apply(f_id, f_p);
+                }
             }
         }
     }
-    if (lane < K) { ids[lane] = e_id; mus[lane] = e_mu; }
-    if (lane == 0) { h->count = count; h->order = order_word & ((1u << kTagShift) - 1u); }
+    if (lane < K) { st_agent(&ids[lane], e_id); st_agent(&mus[lane], e_mu); }
+    if (lane == 0) { st_agent(&h->count, count); st_agent(&h->order, order_word & ((1u << kTagShift) - 1u)); }
+}
+
+__global__ __launch_bounds__(64 * kMergeWaves) void merge_apply_kernel(MergeArgs a)
+{
+    __shared__ int32_t l_id_all[kMergeWaves][2 * kMaxK];
+    __shared__ float l_val_all[kMergeWaves][2 * kMaxK];
+    const int NO = a.omax - a.omin + 1;
+    const int nrec = a.B * a.R * NO;
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int rec = (int)blockIdx.x * kMergeWaves + wave;
+    if (rec >= nrec) return;
+    apply_record(a, rec, lane, l_id_all[wave], l_val_all[wave]);
 }
 
 // append the committed tokens to the context tails

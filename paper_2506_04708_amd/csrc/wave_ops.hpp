@@ -10,7 +10,10 @@ constexpr int kDtBf16 = 0, kDtF32 = 1;
 // Row pass: one row per workgroup of WPR waves.  Four waves per row fill the device when there
 // are thousands of rows; with few rows (one or a few trajectories) a row is spread over sixteen
 // waves so that the pass is not limited by what four waves can keep in flight.
-constexpr int kRowWPR = 4, kRowWPRFewRows = 16;
+#ifndef STAND_ROW_WPR
+#define STAND_ROW_WPR 4
+#endif
+constexpr int kRowWPR = STAND_ROW_WPR, kRowWPRFewRows = 16;
 constexpr int kRowsFew = 768;               // at most this many rows: kRowWPRFewRows waves per row
 constexpr int kMaxNodes = 1024;
 constexpr int kMaxDepth = 31;
@@ -20,6 +23,7 @@ constexpr float kFastEps = 5e-5f;  // bound on the relative error of the fast no
 enum StatSlot {
     kStatHits = 0,  // kStatHits + n, n = 1..8
     kStatMisses = 9, kStatInserts, kStatMerges, kStatDrops, kStatNear, kStatTokens, kStatTests, kStatMismatch,
+    kStatWaitExpired,
     kStatCount
 };
 
@@ -89,6 +93,28 @@ __device__ __forceinline__ RowGeom row_geom(const void *rowp, int V)
 }
 
 __device__ __forceinline__ float fast_exp2(float y) { return __builtin_amdgcn_exp2f(y); }
+
+// Loads and stores of data that another workgroup of the SAME launch writes or reads (the one-launch
+// step): performed at device scope, so they go past the caches that are private to a part of the device
+// -- no cache-wide write-back or invalidation is needed to exchange a few words.  A producer waits for
+// its stores (publish_fence), then moves a counter; a consumer that has seen the counter (consume_fence)
+// reads with ld_agent.  Between kernels they behave like ordinary accesses.
+template <typename T>
+__device__ __forceinline__ T ld_agent(const T *p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+template <typename T>
+__device__ __forceinline__ void st_agent(T *p, T v)
+{
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void publish_fence()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");  // orders the stores before what follows ...
+    __builtin_amdgcn_s_waitcnt(0);                           // ... and waits until the memory system has taken them
+}
+__device__ __forceinline__ void consume_fence() { __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup"); }
 
 // ---------------------------------------------------------------------------------------------
 // Accept/reject sequence at one tree node, executed by one wave (lane i = stored id i).

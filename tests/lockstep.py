@@ -71,6 +71,8 @@ def run_lockstep(w, steps, mode="separate", capacity=1 << 12, check_rows=True, t
     """mode "separate": stand_verify / stand_update / stand_draft; mode "step": stand_step.
     forced=True commits the workload's stream tokens (open-loop replay); False commits what was emitted."""
     o, g = make_pair(w, capacity, max_probe)
+    if w.cfg.get("step_plan") is not None:
+        g.set_step_plan(*w.cfg["step_plan"])          # GPU only: (mode, upper_depth, tail_groups, shuffle) of stand_step
     if w.cfg.get("filter_margin") is not None:
         g.set_filter_margin(w.cfg["filter_margin"])   # GPU only: how many accept tests take the exact path
     for b in range(w.B):
@@ -143,6 +145,7 @@ def run_lockstep(w, steps, mode="separate", capacity=1 << 12, check_rows=True, t
     assert (so.inserts, so.merges, so.drops) == (sg.inserts, sg.merges, sg.drops), "update statistics differ"
     assert so.tokens_emitted == sg.tokens_emitted and so.accept_tests == sg.accept_tests
     assert sg.filter_mismatch == 0, "an accept decision changed under exact arithmetic"
+    assert sg.wait_expired == 0, "a bounded wait of the one-launch step ran out"
     assert np.array_equal(o.node_counts(), g.node_counts()), "per-node acceptance counters differ"
     info["node_counts"] = o.node_counts()
     info["near_oracle"], info["near_gpu"] = so.near_threshold, sg.near_threshold

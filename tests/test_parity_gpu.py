@@ -62,6 +62,79 @@ def test_lockstep_small(gpu, name, over, steps, mode, forced):
     assert info["worst_rel"] < 1e-5
 
 
+FUSED = 2  # STAND_STEP_FUSED
+
+
+@pytest.mark.parametrize("name,over,steps,forced", [
+    ("cfg1", dict(V=4096, B=2, rho=0.7, step_plan=(FUSED, 2, 0, 0)), 40, True),            # few rows, one launch forced
+    ("cfg1", dict(V=2003, B=3, rho=0.7, dtype="bf16", step_plan=(FUSED, 1, 1, 0)), 40, True),   # misaligned rows, one tail workgroup
+    ("cfg1", dict(V=40, B=4, K=10, rho=0.5, step_plan=(FUSED, 0, 2, 0)), 40, False),       # only the root rows first; deep paths wait for late rows
+    ("cfg3", dict(V=5000, B=8, rho=0.7, step_plan=(FUSED, 2, 4, 0)), 25, True),
+    ("cfg3", dict(V=48, B=13, rho=0.5, step_plan=(FUSED, 2, 4, 7)), 30, False),            # deep acceptance, shuffled row slots
+    ("cfg3", dict(V=48, B=4, rho=0.5, step_plan=(FUSED, 8, 3, 0)), 40, False),             # every row before the tail
+    ("cfg3", dict(V=48, B=4, rho=0.5, step_plan=(FUSED, 0, 8, 12345)), 40, False),         # tail right behind the roots, shuffled
+    ("cfg5", dict(V=64, B=7, rho=0.5, step_plan=(FUSED, 3, 2, 3)), 16, False),             # 128 nodes, K=32, orders 1-5
+    ("cfg5", dict(V=3000, B=4, rho=0.7, step_plan=(FUSED, 2, 0, 0)), 12, True),
+    ("cfg3", dict(V=5000, B=4, rho=0.8, draft_mode=1, step_plan=(FUSED, 2, 0, 0)), 25, True),    # multinomial drafting
+    ("cfg3", dict(V=5000, B=4, rho=0.8, draft_mode=2, step_plan=(FUSED, 1, 0, 5)), 25, True),    # one-hot proposals
+    ("cfg3", dict(V=5000, B=8, rho=0.8, merge_policy=1, step_plan=(FUSED, 2, 0, 0)), 25, True),  # replace policy
+    ("cfg3", dict(V=777, B=13, rho=0.8, dtype="f32", step_plan=(FUSED, 2, 0, 9)), 6, False),     # f32 rows, misaligned
+    ("cfg3", dict(V=51, B=4, rho=0.5, filter_margin=0.05, step_plan=(FUSED, 2, 0, 0)), 40, False),  # exact second decisions
+    ("cfg3", dict(V=1003, B=13, rho=0.8, step_plan=(1, 2, 0, 0)), 8, True),                # the five-launch step where one launch is the default
+])
+def test_lockstep_one_launch_step(gpu, name, over, steps, forced):
+    """stand_step as one launch (rows of the upper tree levels, then the dependent tail beside the remaining
+    rows): every output as in the five-launch form, whatever the split, the number of tail workgroups and the
+    order in which workgroups take rows."""
+    binding, lockstep = gpu
+    _say("one-launch step %s %s steps=%d forced=%s" % (name, over, steps, forced))
+    w = synth.Workload(name, run_steps=steps, **over)
+    info = lockstep.run_lockstep(w, steps, mode="step", capacity=1 << 14, forced=forced)
+    _say("  -> %s" % {k: v for k, v in info.items() if k != "node_counts"})
+    assert info["emitted"] >= steps * w.B and info["worst_rel"] < 1e-5
+
+
+def test_one_launch_step_waits_are_bounded(gpu):
+    """With the wait limit at zero every wait of the one-launch step that is not satisfied at once runs out:
+    the launches still end, the expiry is reported in the statistics and the outputs are marked void."""
+    binding, lockstep = gpu
+    w = synth.Workload("cfg3", run_steps=4, V=20000, B=8, rho=0.7)
+    g = binding.Stand(w.V, w.B, 1, 4, w.K, w.parent, w.T, 1 << 14, 64, 5, binding.STAND_BF16)
+    g.set_step_plan(FUSED, 2, 4, 0)
+    for b in range(w.B):
+        g.set_context(b, w.prompt(b))
+    out_tok, out_node, out_len, d = g.new_outputs()
+    g.draft(0, d)
+    lg = lockstep._logits_to_device(w.logits(0, d.cpu().numpy()), w.dtype)
+    g.set_wait_limit(0)
+    for step in range(3):
+        g.step(step, lg, out_tok, out_node, out_len, d)
+    torch.cuda.synchronize()
+    st = g.stats()
+    _say("wait limit 0: %d waits expired, lengths %s" % (st.wait_expired, out_len.cpu().numpy().tolist()))
+    assert st.wait_expired > 0
+    ln = out_len.cpu().numpy()
+    assert ((ln >= 0) & (ln <= w.W)).all()
+    g.close()
+    # the default limit: the same calls complete without an expiry
+    g = binding.Stand(w.V, w.B, 1, 4, w.K, w.parent, w.T, 1 << 14, 64, 5, binding.STAND_BF16)
+    g.set_step_plan(FUSED, 2, 4, 0)
+    for b in range(w.B):
+        g.set_context(b, w.prompt(b))
+    g.draft(0, d)
+    for step in range(3):
+        g.step(step, lg, out_tok, out_node, out_len, d)
+    torch.cuda.synchronize()
+    assert g.stats().wait_expired == 0 and (out_len.cpu().numpy() >= 1).all()
+    with pytest.raises(binding.StandError):
+        g.set_step_plan(3, 2, 0, 0)
+    g.close()
+    ga = binding.Stand(w.V, w.B, 1, 4, w.K, w.parent, w.T, 1 << 14, 64, 5, binding.STAND_BF16, update_mode=1)
+    with pytest.raises(binding.StandError):
+        ga.set_step_plan(FUSED, 2, 0, 0)           # all-nodes updates need every drafted row: five launches only
+    ga.close()
+
+
 @pytest.mark.parametrize("name,over,steps,mode", [
     ("cfg3", dict(V=48, B=4, rho=0.5, filter_margin=1.0), 40, "step"),                      # practically every test decided exactly
     ("cfg3", dict(V=51, B=4, rho=0.5, filter_margin=0.05), 40, "step"),                     # a mix, misaligned rows
@@ -423,12 +496,13 @@ def test_largest_tree(gpu, update_mode):
     assert info["emitted"] >= 10 * w.B
 
 
-def test_empty_contexts_and_empty_commits(gpu):
+@pytest.mark.parametrize("update_mode", [0, 1])
+def test_empty_contexts_and_empty_commits(gpu, update_mode):
     """Edge cases of the state: a trajectory without any context (nothing can be drafted, its root row still
     yields a token), contexts shorter than the orders, an update that commits nothing, and a closed loop
     started from that state."""
     binding, lockstep = gpu
-    w = synth.Workload("cfg1", run_steps=12, V=300, B=3, rho=0.5)
+    w = synth.Workload("cfg1", run_steps=12, V=300, B=3, rho=0.5, update_mode=update_mode)
     o, g = lockstep.make_pair(w, 1 << 12)
     o.set_context(1, [7])                      # trajectory 0: no context at all, 1: one token, 2: two tokens
     g.set_context(1, [7])
@@ -441,12 +515,16 @@ def test_empty_contexts_and_empty_commits(gpu):
     assert np.array_equal(d.cpu().numpy(), od) and np.all(od[0] == -1) and np.all(od[:, 1:] == -1)
     lg = w.logits(0, od)
     dl = lockstep._logits_to_device(lg, w.dtype)
-    # an update that commits nothing leaves table and contexts as they are
+    # an update that commits nothing leaves the contexts as they are, and the table too (in all-nodes mode
+    # the rows of the two drafted roots are merged, whatever is committed)
     none = np.zeros(w.B, np.int32)
     ct = np.full((w.B, g.W), -1, np.int32)
     o.update(0, lg, ct, ct, none)
     g.update(0, dl, torch.from_numpy(ct).cuda(), torch.from_numpy(ct).cuda(), torch.from_numpy(none).cuda())
-    assert len(o.table_export()) == 0 and g.table_export().shape[0] == 0
+    if update_mode == 0:
+        assert len(o.table_export()) == 0 and g.table_export().shape[0] == 0
+    else:
+        assert lockstep.compare_tables(o, g, w.K) == 3   # keys (7), (9) and (7, 9)
     for b in range(w.B):
         assert g.get_context(b, 1)[1] == o.context_len(b) == b
     # closed loop from there: every emitted token is committed
