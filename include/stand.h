@@ -38,6 +38,7 @@ extern "C" {
 #define STAND_ENOMEM (-2) /* host or device allocation failed                     */
 #define STAND_EHIP (-3)   /* a HIP call failed; stand_last_hip_error() has its code */
 #define STAND_ESTATE (-4) /* call order violated (e.g. import into a used table)   */
+#define STAND_ELIMIT (-5) /* the request exceeds a fixed limit of the library        */
 
 #define STAND_BF16 0
 #define STAND_F32 1
@@ -75,6 +76,7 @@ extern "C" {
 #define STAND_MAX_ORDER 8
 #define STAND_MAX_NODES 1024
 #define STAND_MAX_DEPTH 31
+#define STAND_STATIC_SCRATCH_BYTES (8u << 20) /* scratch of stand_verify_static: 8 MiB per GPU */
 
 typedef struct stand_handle stand_handle;
 
@@ -166,6 +168,25 @@ int stand_draft(stand_handle *h, uint64_t step, int32_t *d_draft_tok, void *stre
  * entries are -1.  Handle state (table, contexts) is not changed. */
 int stand_verify(stand_handle *h, uint64_t step, const void *d_logits, int32_t *d_out_tok,
                  int32_t *d_out_node, int32_t *d_out_len, void *stream);
+
+/* stand_verify for callers that cannot allocate device memory or tolerate a library that does: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same
+ * results and same error behaviour as stand_verify, but everything the kernels keep between them (the
+ * row pass's per-row results, the partial sums, stop records and observations of the path rows) lives in
+ * a fixed array of STAND_STATIC_SCRATCH_BYTES that is part of the library's device image -- one copy
+ * per GPU, held until the process ends -- instead of the handle's own buffers.  The call allocates and
+ * frees nothing (no hipMalloc, hipFree or allocating library routine).
+ *   - Limit: stand_static_scratch_need(h) bytes must fit the array (about max_batch * tree_nodes *
+ *     (12 * topk + 12) bytes plus the path rows' share: 0.6 MB for 32 x 64 rows with topk 16, 7.5 MB for
+ *     128 x 128 rows with topk 32); otherwise STAND_ELIMIT and nothing is launched.
+ *   - All handles on one GPU share that GPU's array and a call leaves its contents behind: calls that
+ *     overlap on one GPU (different streams or host threads) race; calls ordered by one stream do not.
+ *     Nothing in the array needs to be cleared between calls.
+ *   - stand_row_results keeps reporting the last stand_verify / stand_step, not this call. */
+int stand_verify_static(stand_handle *h, uint64_t step, const void *d_logits, int32_t *d_out_tok,
+                        int32_t *d_out_node, int32_t *d_out_len, void *stream);
+/* Scratch bytes stand_verify_static needs for this handle's shape (0 for a NULL handle). */
+uint64_t stand_static_scratch_need(const stand_handle *h);
 
 /* One speculation step = stand_verify(step) -> stand_update with the emitted tokens and their
  * rows -> stand_draft(step + 1) into d_next_draft_tok [B][N].

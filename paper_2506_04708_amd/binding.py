@@ -25,7 +25,7 @@ EXPORTED = [
     "stand_get_context", "stand_get_stats", "stand_strerror", "stand_last_hip_error",
     "stand_profile_begin", "stand_profile_end", "stand_copy_bytes", "stand_read_rows", "stand_set_filter_margin",
     "stand_tree_initial", "stand_tree_select", "stand_get_node_counts", "stand_reset_node_counts",
-    "stand_tree_packing",
+    "stand_tree_packing", "stand_verify_static", "stand_static_scratch_need",
     "stand_set_step_plan", "stand_set_wait_limit", "stand_step_timeline",
 ]
 
@@ -63,6 +63,9 @@ def load_library():
     lib.stand_update.argtypes = [vp, C.c_uint64, vp, i32p, i32p, i32p, vp]
     lib.stand_draft.argtypes = [vp, C.c_uint64, i32p, vp]
     lib.stand_verify.argtypes = [vp, C.c_uint64, vp, i32p, i32p, i32p, vp]
+    lib.stand_verify_static.argtypes = [vp, C.c_uint64, vp, i32p, i32p, i32p, vp]
+    lib.stand_static_scratch_need.argtypes = [vp]
+    lib.stand_static_scratch_need.restype = C.c_uint64
     lib.stand_set_step_plan.argtypes = [vp, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_uint32]
     lib.stand_set_wait_limit.argtypes = [vp, C.c_uint64]
     lib.stand_step_timeline.argtypes = [vp, C.c_int32, vp, C.POINTER(C.c_uint64)]
@@ -225,6 +228,13 @@ class Stand:
     def verify(self, step, logits, out_tok, out_node, out_len):
         _check(lib().stand_verify(self.h, step, self._logits_ptr(logits), _dptr(out_tok, torch.int32),
                                   _dptr(out_node, torch.int32), _dptr(out_len, torch.int32), _stream_ptr()), self.h)
+
+    def verify_static(self, step, logits, out_tok, out_node, out_len):
+        _check(lib().stand_verify_static(self.h, step, self._logits_ptr(logits), _dptr(out_tok, torch.int32),
+                                         _dptr(out_node, torch.int32), _dptr(out_len, torch.int32), _stream_ptr()), self.h)
+
+    def static_scratch_need(self):
+        return int(lib().stand_static_scratch_need(self.h))
 
     def step(self, step, logits, out_tok, out_node, out_len, next_draft_tok, force_tok=None):
         _check(lib().stand_step(self.h, step, self._logits_ptr(logits), _dptr(out_tok, torch.int32),

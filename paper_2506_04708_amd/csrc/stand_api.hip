@@ -14,7 +14,8 @@
 using namespace stand;
 
 // Device memory that one verification uses between its kernels (results of the row pass, partial sums,
-// the stop records, observations).
+// the stop records, observations).  A handle owns one set; the entry point that must not allocate carves
+// the same set out of the file-scope array below.
 struct VerifyScratch {
     float *row_m, *row_s, *top_l, *top_p;
     int32_t *top_idx, *outcome;
@@ -68,6 +69,29 @@ struct stand_handle {
     std::vector<hipEvent_t> ev_begin, ev_end;
     size_t ev_used;
 };
+
+// Scratch of stand_verify_static: one copy per GPU, held until the process ends.  In host code this
+// name is only a handle for hipGetSymbolAddress, never an address: every use goes through the
+// per-device pointer resolved in static_scratch_ptr().
+static __device__ __align__(256) unsigned char scratch[STAND_STATIC_SCRATCH_BYTES];
+constexpr int kMaxDevices = 64;
+static void *g_scratch_ptr[kMaxDevices];  // device address of `scratch` on each GPU (NULL: not resolved yet)
+
+// Resolves the array's address on `device` (which must be the current device).  Called from
+// stand_create, i.e. once per device before any entry point can need it; no allocation involved.
+static hipError_t static_scratch_ptr(int device, void **out)
+{
+    if (device < 0 || device >= kMaxDevices) return hipErrorInvalidDevice;
+    if (!g_scratch_ptr[device]) {
+        void *p = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        g_scratch_ptr[device] = p;
+    }
+    *out = g_scratch_ptr[device];
+    return hipSuccess;
+}
 
 #define HIP_TRY(h, expr)                                   \
     do {                                                   \
@@ -186,6 +210,12 @@ extern "C" int stand_create(const stand_config *cfg, stand_handle **out)
     for (int u = N - 1; u >= 0; --u) h->level_start[h->depth[u]] = u;
 
     if (hipSetDevice(cfg->device) != hipSuccess) { delete h; return STAND_EHIP; }
+    {
+        // address of the static scratch array on this device, for stand_verify_static
+        void *sp = nullptr;
+        const hipError_t se = static_scratch_ptr(cfg->device, &sp);
+        if (se != hipSuccess) { h->last_hip = (int)se; delete h; return STAND_EHIP; }
+    }
     const size_t B = h->B, rows = B * N;
     const size_t nrec = B * h->R * h->NO;
     hipError_t e = hipSuccess;
@@ -514,6 +544,50 @@ extern "C" int stand_verify(stand_handle *h, uint64_t step, const void *d_logits
     int rc = launch_row_pass(h, h->vs, step, d_logits, s);
     if (rc) return rc;
     return launch_path_pass(h, h->vs, step, d_logits, 0, nullptr, nullptr, d_out_tok, d_out_node, d_out_len, nullptr, s);
+}
+
+// Bytes of scratch a verification of this handle's shape needs, laid out as carve_scratch does.
+static size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+static size_t carve_scratch(const stand_handle *h, unsigned char *base, VerifyScratch *out)
+{
+    const size_t B = h->B, rows = B * h->N, K = h->K, R = h->R;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { unsigned char *p = base ? base + off : nullptr; off += align256(bytes); return p; };
+    VerifyScratch v;
+    v.row_m = (float *)take(rows * 4); v.row_s = (float *)take(rows * 4);
+    v.top_l = (float *)take(rows * K * 4); v.top_p = (float *)take(rows * K * 4);
+    v.top_idx = (int32_t *)take(rows * K * 4); v.outcome = (int32_t *)take(rows * 4);
+    v.obs_idx = (int32_t *)take(B * R * K * 4); v.obs_p = (float *)take(B * R * K * 4);
+    v.seg_part = (unsigned long long *)take(B * R * kSegMax * 8);
+    v.stop_i = (int32_t *)take(B * 4 * 4); v.stop_qid = (int32_t *)take(B * kMaxK * 4);
+    v.stop_child = (int32_t *)take(B * kMaxK * 4); v.stop_m = (float *)take(B * 4);
+    v.stop_qmu = (float *)take(B * kMaxK * 4); v.stop_ql = (float *)take(B * kMaxK * 4);
+    if (out) *out = v;
+    return off;
+}
+
+extern "C" int stand_verify_static(stand_handle *h, uint64_t step, const void *d_logits, int32_t *d_out_tok,
+                                   int32_t *d_out_node, int32_t *d_out_len, void *stream)
+{
+    if (!h || !d_logits || !d_out_tok || !d_out_node || !d_out_len) return STAND_EINVAL;
+    if (carve_scratch(h, nullptr, nullptr) > (size_t)STAND_STATIC_SCRATCH_BYTES) return STAND_ELIMIT;
+    hipStream_t s = (hipStream_t)stream;
+    HIP_TRY(h, hipSetDevice(h->cfg.device));
+    void *base = nullptr;
+    HIP_TRY(h, static_scratch_ptr(h->cfg.device, &base));  // resolved by stand_create already; no allocation
+    VerifyScratch vs;
+    carve_scratch(h, (unsigned char *)base, &vs);
+    // Nothing in the scratch has to start at zero: every word a kernel of the verification reads was written
+    // by an earlier kernel of the same call (row results and outcomes for all rows; partial sums, stop records
+    // and observations for exactly the path rows that are read back).
+    int rc = launch_row_pass(h, vs, step, d_logits, s);
+    if (rc) return rc;
+    return launch_path_pass(h, vs, step, d_logits, 0, nullptr, nullptr, d_out_tok, d_out_node, d_out_len, nullptr, s);
+}
+
+extern "C" uint64_t stand_static_scratch_need(const stand_handle *h)
+{
+    return h ? (uint64_t)carve_scratch(h, nullptr, nullptr) : 0;
 }
 
 // The whole step in one launch (step_fused.hpp).
@@ -971,6 +1045,7 @@ extern "C" const char *stand_strerror(int code)
     case STAND_ENOMEM: return "out of memory";
     case STAND_EHIP: return "HIP runtime error (see stand_last_hip_error)";
     case STAND_ESTATE: return "call not allowed in this state";
+    case STAND_ELIMIT: return "request exceeds a fixed limit of the library";
     default: return "unknown error";
     }
 }
