@@ -9,19 +9,25 @@ T=0.6, 2^22 table slots ("cfg3"), open-loop replay of seeded token streams with 
 Procedure (all inputs are generated on the GPU before the timed region):
   1. table warm-up: `--table-warm` untimed steps with logits generated on the fly;
   2. record: the next warmup+steps steps are run once while their logits stay resident in HBM;
-  3. timed: a second handle that starts from a copy of the state reached after (1) replays the
-     recorded steps back to back; the wall clock around the last `--steps` of them is the
-     result, and its outputs must equal the recorded ones.  (2) and (3) alternate in chunks of
-     as many steps as fit the free memory (one chunk at the defaults: 200 x 623 MB); the second
-     handle repeats exactly what the first did, so the next chunk continues from equal states,
-     and the timed spans of the chunks are added.
-Also printed: the row pass's achieved HBM bandwidth from HIP events recorded inside the
-library around that kernel (same timed region), and the CPU oracle timed on the first steps
-of the same workload on the host.
+  3. timed: a second handle that starts from a copy of the state reached after (1) -- its table
+     additionally filled with inert entries up to the load factor the table has at the end of a
+     full-length run (`--table-fill`) -- replays the recorded steps back to back; the wall clock
+     around the last `--steps` of them is the result, and its outputs must equal the recorded
+     ones.  (2) and (3) alternate in chunks of as many steps as fit the free memory (one chunk at
+     the defaults); the second handle repeats exactly what the first did, so the next chunk
+     continues from equal states, and the timed spans of the chunks are added.  When the timed
+     region is shorter than 25 ms (few `--steps`), the replay is repeated from the same state
+     on fresh handles and the median is reported.
+Also printed: the achieved HBM bandwidth of the step's dominant kernel from HIP events attached
+to its dispatches (the same steps replayed once more from the same state: the events themselves
+cost about 5 us per step, so the wall clock is taken without them), the CPU oracle timed on the
+first steps of the same workload on the host, and the same measurement in a regime of confident
+targets.
 """
 import argparse
 import json
 import os
+import subprocess
 import sys
 import time
 
@@ -32,17 +38,13 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0
 
 
-PEAK = 8.0  # height of the peaked tokens above the noise (--peak)
-
-
-def gen_logits(torch, w, step, draft_tok_host, gen):
-    """[B, N, V] bf16 logits on the GPU: N(0, 3) noise plus +PEAK on each row's peaked tokens."""
-    import numpy as np
+def gen_logits(torch, w, step, draft_tok_host, gen, peak=8.0):
+    """[B, N, V] bf16 logits on the GPU: N(0, 3) noise plus +peak on each row's peaked tokens."""
     peaks = w.peaks(step, draft_tok_host)                      # [B, N, 4] int64, -1 = none
     x = torch.randn((w.B, w.N, w.V), generator=gen, device="cuda", dtype=torch.float32)
     x.mul_(3.0 ** 0.5)
     pk = torch.from_numpy(peaks).cuda()
-    add = torch.where(pk >= 0, torch.full(pk.shape, PEAK, device="cuda"), torch.zeros(pk.shape, device="cuda"))
+    add = torch.where(pk >= 0, torch.full(pk.shape, peak, device="cuda"), torch.zeros(pk.shape, device="cuda"))
     x.scatter_add_(2, pk.clamp(min=0), add)
     return x.to(torch.bfloat16).contiguous()
 
@@ -55,81 +57,76 @@ def force_tokens(np, w):
     return f
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=192)
-    ap.add_argument("--warmup", type=int, default=8)
-    ap.add_argument("--table-warm", type=int, default=200)
-    ap.add_argument("--workload", default="cfg3")
-    ap.add_argument("--cpu-steps", type=int, default=40)
-    ap.add_argument("--no-cpu", action="store_true")
-    ap.add_argument("--no-events", action="store_true", help="do not time the row pass with HIP events")
-    ap.add_argument("--draft-mode", type=int, default=0,
-                    help="0 Gumbel-Top-K (the method), 1 sequential multinomial, 2 deterministic (the paper's ablation)")
-    ap.add_argument("--update-mode", type=int, default=0,
-                    help="0 merge the accepted path's rows (the paper), 1 merge every drafted node's row (table stress)")
-    ap.add_argument("--merge-policy", type=int, default=0,
-                    help="0 running mean over all observations of a context (the method), 1 keep only the newest "
-                         "observation (the replace policy the paper compares against)")
-    ap.add_argument("--peak", type=float, default=8.0,
-                    help="logit height of the peaked tokens (BASELINE: +8, p about 0.23 each); higher peaks give "
-                         "sharper targets, longer acceptance and deeper drafts")
-    ap.add_argument("--max-peaks", type=int, default=4,
-                    help="each row peaks on 1..max-peaks tokens (BASELINE: 1-4); 1 with a high --peak models a confident "
-                         "target, where acceptance follows the quality of the drafts")
-    ap.add_argument("--step-mode", type=int, default=0,
-                    help="how stand_step is issued: 0 the library's choice, 1 five dependent launches, 2 one launch")
-    ap.add_argument("--upper-depth", type=int, default=2, help="one-launch step: tree levels whose rows go first")
-    ap.add_argument("--tail-groups", type=int, default=0, help="one-launch step: tail workgroups per trajectory (0: library's choice)")
-    ap.add_argument("--rows-first", type=int, default=0,
-                    help="one-launch step: row workgroups placed before the tail's (0: one device-full)")
-    ap.add_argument("--timeline", action="store_true",
-                    help="after the timed region, replay a few steps with the one-launch step's clock readings on and print them")
-    ap.add_argument("--calib-copy", action="store_true",
-                    help="also run a plain copy of one logits tensor (known HBM traffic) for counter calibration")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build measures one GPU; every GPU box here has one, so --gpus %d is not run" % args.gpus,
-              file=sys.stderr)
-        sys.exit(2)
+def inert_entries(np, K, n, avoid, seed):
+    """n table entries in the export format with random key fingerprints (no context ever hashes to them, so no
+    lookup or update touches them): they only occupy slots, as the entries of a long run would."""
+    es = 16 + 8 * K
+    rng = np.random.default_rng(seed)
+    fps = np.unique(rng.integers(1, 2 ** 63, size=int(n * 1.01) + 16, dtype=np.uint64))
+    fps = fps[~np.isin(fps, avoid)][:n]
+    rng.shuffle(fps)
+    rec = np.zeros(len(fps), dtype=np.dtype([("fp", "<u8"), ("count", "<u4"), ("order", "<u4"), ("ids", "<i4", (K,)),
+                                             ("mu", "<f4", (K,))]))
+    rec["fp"], rec["count"], rec["order"] = fps, 1, 1
+    rec["ids"] = np.arange(K, dtype=np.int32)[None, :]
+    rec["mu"] = np.float32(1.0 / K)
+    assert rec.dtype.itemsize == es
+    return rec.view(np.uint8).reshape(-1)
 
-    import numpy as np
-    import torch
-    from paper_2506_04708_amd import binding, synth
-    global PEAK
-    PEAK = args.peak
 
-    assert torch.cuda.is_available(), "bench.py needs a GPU"
-    K_steps, W_steps, T_warm = args.steps, args.warmup, args.table_warm
+def host_description():
+    out = {}
+    try:
+        for line in subprocess.run(["lscpu"], capture_output=True, text=True, timeout=10).stdout.splitlines():
+            k, _, v = line.partition(":")
+            out[k.strip()] = v.strip()
+        cores = int(out.get("Core(s) per socket", "0")) * int(out.get("Socket(s)", "0"))
+        return "%s: %d physical cores (%s sockets x %s cores, %s threads per core), %d CPUs usable by this process" % (
+            out.get("Model name", "?"), cores, out.get("Socket(s)", "?"), out.get("Core(s) per socket", "?"),
+            out.get("Thread(s) per core", "?"), len(os.sched_getaffinity(0)))
+    except Exception:
+        return "%d CPUs usable by this process" % len(os.sched_getaffinity(0))
+
+
+def measure(args, np, torch, binding, synth, peak, max_peaks, K_steps, W_steps, T_warm, cpu_steps, label):
+    """One regime of the workload; returns the measured figures as a dict."""
     total = T_warm + W_steps + K_steps
     if args.workload == "opt625":
         # the tree-optimisation run of the paper (Sec. 4.3): speculation on the 625-node initial tree
         big = binding.tree_initial(20)
         cfg = dict(B=4, V=152064, dtype="bf16", N=len(big), D=20, caps=[8], parent=big, order_min=1, order_max=4, K=16,
-                   T=0.6, capacity=1 << 20, rho=0.5, seed=synth.BASE_SEED + 9)
-        w = synth.Workload(None, run_steps=total + 2, **cfg)
+                   T=0.6, capacity=1 << 20, rho=0.5, seed=synth.BASE_SEED + 9, steps=4096)
+        w = synth.Workload(None, run_steps=total + 2, max_peaks=max_peaks, **cfg)
     else:
         cfg = synth.CONFIGS[args.workload]
-        w = synth.Workload(args.workload, run_steps=total + 2, max_peaks=args.max_peaks)
-    dt = binding.STAND_BF16 if w.dtype == "bf16" else binding.STAND_F32
+        w = synth.Workload(args.workload, run_steps=total + 2, max_peaks=max_peaks)
     assert w.dtype == "bf16"
-    mk0 = lambda: binding.Stand(w.V, w.B, cfg["order_min"], cfg["order_max"], w.K, w.parent, w.T, cfg["capacity"], 64,
-                               cfg["seed"], dt, draft_mode=args.draft_mode, update_mode=args.update_mode,
-                               merge_policy=args.merge_policy)
+
     def mk():
-        h = mk0()
-        h.set_step_plan(args.step_mode, args.upper_depth, args.tail_groups, 0, args.rows_first)
+        h = binding.Stand(w.V, w.B, cfg["order_min"], cfg["order_max"], w.K, w.parent, w.T, cfg["capacity"], 64,
+                          cfg["seed"], binding.STAND_BF16, draft_mode=args.draft_mode, update_mode=args.update_mode,
+                          merge_policy=args.merge_policy)
+        if args.update_mode == 0:
+            h.set_step_plan(args.step_mode, args.upper_depth, args.tail_groups, 0, args.rows_first)
         return h
+
     gen = torch.Generator(device="cuda").manual_seed(cfg["seed"] & 0x7FFFFFFF)
     h1 = mk()
     for b in range(w.B):
         h1.set_context(b, w.prompt(b))
     out_tok, out_node, out_len, draft = h1.new_outputs()
     h1.draft(0, draft)
+
+    def reorder_if_due(h, step, d):
+        src = w.reorder_map(step)
+        if src is not None:
+            h.reorder(src)
+            h.draft(step, d)
+        return src is not None
+
     # ---- CPU baseline leg: the oracle runs the first steps side by side with the GPU (same inputs),
     # one step at a time, so no more than one logits tensor is ever held on the host
-    cpu_n = 0 if args.no_cpu else min(args.cpu_steps, T_warm)
+    cpu_n = min(cpu_steps, T_warm)
     cpu_s = 0.0
     cpu_rows = None
     if cpu_n:
@@ -144,8 +141,11 @@ def main():
     t0 = time.time()
     # ---- 1. warm the table (untimed, logits generated on the fly) --------------------------------
     for step in range(T_warm):
+        if reorder_if_due(h1, step, draft) and step < cpu_n:
+            orc.reorder(w.reorder_map(step))
+            od = orc.draft(step)
         d_host = draft.cpu().numpy()
-        lg = gen_logits(torch, w, step, d_host, gen)
+        lg = gen_logits(torch, w, step, d_host, gen, peak)
         force = force_tokens(np, w)
         h1.step(step, lg, out_tok, out_node, out_len, draft, torch.from_numpy(force).cuda())
         ln = out_len.cpu().numpy()
@@ -187,27 +187,48 @@ def main():
         # sample (counted by the oracle; both sides take the same decisions, which the sample asserts)
         near_1e6 = {"count": int(ost.near_threshold), "accept_tests": int(ost.accept_tests), "steps": cpu_n}
         orc.close()
-    # ---- state copy for the replay handle ---------------------------------------------------------
-    h2 = mk()
+
+    # ---- state copy for the replay handle: table (plus inert entries up to the end-of-run load) and contexts
+    es = 16 + 8 * w.K
     snapshot = h1.table_export()
-    entries0 = snapshot.shape[0] // (16 + 8 * w.K)
-    h2.table_import(snapshot)
-    for b in range(w.B):
-        tail, ln_ctx = h1.get_context(b, binding.MAX_ORDER)
-        h2.set_context(b, tail)
+    entries0 = snapshot.shape[0] // es
+    want = int(args.table_fill * cfg["capacity"])
+    filler = np.zeros(0, np.uint8)
+    if want > entries0:
+        fps0 = np.frombuffer(snapshot.tobytes(), dtype=np.dtype([("fp", "<u8"), ("rest", "V%d" % (es - 8))]))["fp"]
+        filler = inert_entries(np, w.K, want - entries0, fps0, cfg["seed"] & 0xFFFF)
+    image = np.concatenate([snapshot, filler])
+    contexts = [h1.get_context(b, binding.MAX_ORDER)[0] for b in range(w.B)]
+
+    def replay_handle():
+        h = mk()
+        h.table_import(image)
+        for b in range(w.B):
+            h.set_context(b, contexts[b])
+        return h
+
+    h2 = replay_handle()
+    # a third handle replays the same steps once more with HIP events attached to the dominant kernel's dispatches
+    # (the events cost about 5 us per step, so the wall clock is taken on the replay without them)
+    hev = None if args.no_events else replay_handle()
     # ---- 2./3. record a chunk of steps with their logits resident in HBM, then replay it on the second
-    # handle; the replay of the steps after the warm-up is what is timed.  The steps are taken in chunks
-    # so that any --steps fits the memory: the second handle repeats exactly what the first did, so after
-    # a chunk both hold the same state and the next chunk continues from it.  One chunk at the defaults.
+    # handle; the replay of the steps after the warm-up is what is timed.
     logits_bytes_1 = w.B * w.N * w.V * 2
     free_b = torch.cuda.mem_get_info()[0]
     chunk_cap = max(8, int(0.45 * free_b / logits_bytes_1))
     n_after = W_steps + K_steps
-    h2.draft(T_warm, draft2 := torch.empty_like(draft))
+    draft2 = torch.empty_like(draft)
+    h2.draft(T_warm, draft2)
+    if hev is not None:
+        hev.draft(T_warm, draft2)
     timed_s = issue_s = 0.0
     done = 0
     n_chunks = 0
     read_us = None
+    row_alone_us = None
+    repeats = []
+    timeline = None
+    kern_ms, kern_n = 0.0, 0
     prep_s = time.time() - t0
     while done < n_after:
         n = min(chunk_cap, n_after - done)
@@ -215,14 +236,15 @@ def main():
         rec = []
         for i in range(n):
             step = T_warm + done + i
+            reo = reorder_if_due(h1, step, draft)
             d_host = draft.cpu().numpy()
-            lg = gen_logits(torch, w, step, d_host, gen)
+            lg = gen_logits(torch, w, step, d_host, gen, peak)
             force = torch.from_numpy(force_tokens(np, w)).cuda()
             h1.step(step, lg, out_tok, out_node, out_len, draft, force)
             ln = out_len.cpu().numpy()
             w.commit(ln)
             lens.append(ln.mean())
-            rec.append((lg, force, out_tok.clone(), out_len.clone(), draft.clone()))
+            rec.append((lg, force, out_tok.clone(), out_len.clone(), draft.clone(), reo))
         torch.cuda.synchronize()
         prep_s += time.time() - c0
         o_tok = [torch.empty_like(out_tok) for _ in rec]
@@ -237,60 +259,106 @@ def main():
             torch.cuda.synchronize()
             del dst
         n_untimed = max(0, min(n, W_steps - done))      # warm-up steps that fall into this chunk
-        for i in range(n_untimed):
-            lg, force, *_ = rec[i]
-            h2.step(T_warm + done + i, lg, o_tok[i], o_node[i], o_len[i], o_draft[i], force)
-        if n > n_untimed:
-            if not args.no_events and done + n_untimed == W_steps:
-                h2.profile_begin(K_steps)
+
+        def replay(h, first_step, profile):
+            """Replays this chunk on handle h; returns (timed seconds, host issue seconds)."""
+            dtmp = torch.empty_like(draft)
+            for i in range(n_untimed):
+                lg, force, *_, reo = rec[i]
+                if reo:
+                    reorder_if_due(h, first_step + i, dtmp)
+                h.step(first_step + i, lg, o_tok[i], o_node[i], o_len[i], o_draft[i], force)
+            if n <= n_untimed:
+                return 0.0, 0.0
+            if profile:
+                h.profile_begin(K_steps)
             torch.cuda.synchronize()
             t1 = time.perf_counter()
             for i in range(n_untimed, n):
-                lg, force, *_ = rec[i]
-                h2.step(T_warm + done + i, lg, o_tok[i], o_node[i], o_len[i], o_draft[i], force)
+                lg, force, *_, reo = rec[i]
+                if reo:
+                    reorder_if_due(h, first_step + i, dtmp)
+                h.step(first_step + i, lg, o_tok[i], o_node[i], o_len[i], o_draft[i], force)
             t_issued = time.perf_counter()
             torch.cuda.synchronize()
             t2 = time.perf_counter()
-            timed_s += t2 - t1
-            issue_s += t_issued - t1
+            return t2 - t1, t_issued - t1
+
+        def check():
+            for i, (lg, force, r_tok, r_len, r_draft, reo) in enumerate(rec):
+                assert torch.equal(o_len[i], r_len) and torch.equal(o_tok[i], r_tok) and torch.equal(o_draft[i], r_draft), \
+                    "replay diverged from the recorded run at step %d" % (done + i)
+
+        ts, ti = replay(h2, T_warm + done, False)
+        check()
+        if n > n_untimed:
+            timed_s += ts
+            issue_s += ti
             n_chunks += 1
-        for i, (lg, force, r_tok, r_len, r_draft) in enumerate(rec):
-            assert torch.equal(o_len[i], r_len) and torch.equal(o_tok[i], r_tok) and torch.equal(o_draft[i], r_draft), \
-                "replay diverged from the recorded run at step %d" % (done + i)
+        if hev is not None:
+            replay(hev, T_warm + done, done + n_untimed == W_steps)   # the events run on from chunk to chunk
+            check()
+        single_chunk = done == 0 and n == n_after
+        if single_chunk and ts < 0.025 and args.repeats > 1:
+            # a short timed region: the same replay again from the same state, on fresh handles; median below
+            repeats = [ts]
+            for r in range(args.repeats - 1):
+                h3 = replay_handle()
+                h3.draft(T_warm, draft2)
+                tr, _ = replay(h3, T_warm, False)
+                check()
+                repeats.append(tr)
+                h3.close()
         done += n
-        if done >= n_after and args.timeline:
-            # where the time of the one-launch step goes: a few more steps on recorded logits, clock readings on
-            h2.step_timeline(True)
-            acc = []
-            for i in range(min(16, len(rec))):
-                lg, force, *_ = rec[-1 - i]
-                h2.step(T_warm + n_after + i, lg, o_tok[0], o_node[0], o_len[0], o_draft[0], force)
-                r0, r1, tl = h2.step_timeline(True, read=True)
-                acc.append(np.concatenate([[r1], tl.mean(axis=0), tl.max(axis=0)]))
-            acc = np.mean(np.stack(acc), axis=0)
-            names = ["tail start", "path known", "sums in", "claims made", "rows finished", "all claims in", "all applied", "draft done"]
-            print("timeline (us from the first row workgroup's start, mean over %d steps): last row end %.1f" % (min(16, len(rec)), acc[0]), file=sys.stderr)
-            for k, nm in enumerate(names):
-                print("  %-14s mean over trajectories %7.1f   latest %7.1f" % (nm, acc[1 + k], acc[9 + k]), file=sys.stderr)
-            h2.step_timeline(False)
-        if done >= n_after and (w.V * 2) % 16 == 0:
-            # floor of a kernel that only fetches one step's logits, in the row pass's launch shape
-            sink = torch.zeros(4 * w.B * w.N, dtype=torch.int32, device="cuda")
+        if done >= n_after:
+            if hev is not None:
+                kern_ms, kern_n = hev.profile_end()
+                hev.close()
+            if args.timeline and h2.step_is_one_launch():
+                # where the time of the one-launch step goes: a few more steps on recorded logits, clock readings on
+                h2.step_timeline(True)
+                acc = []
+                for i in range(min(16, len(rec))):
+                    lg, force, *_ = rec[-1 - i]
+                    h2.step(T_warm + n_after + i, lg, o_tok[0], o_node[0], o_len[0], o_draft[0], force)
+                    r0, r1, tl = h2.step_timeline(True, read=True)
+                    acc.append(np.concatenate([[r1], tl.mean(axis=0), tl.max(axis=0)]))
+                acc = np.mean(np.stack(acc), axis=0)
+                names = ["tail start", "path known", "sums in", "claims made", "rows finished", "all claims in", "all applied",
+                         "draft done"]
+                timeline = {"unit": "us from the first row workgroup's start, mean over %d steps" % min(16, len(rec)),
+                            "last_row_end": round(float(acc[0]), 1),
+                            "stages_mean_latest": {nm: [round(float(acc[1 + k]), 1), round(float(acc[9 + k]), 1)]
+                                                   for k, nm in enumerate(names)}}
+                h2.step_timeline(False)
             ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
-            reps = 20
-            for r in range(3 + reps):
-                if r == 3:
-                    ev[0].record()
-                binding.read_rows(rec[r % len(rec)][0], w.V * 2, w.B * w.N, sink, torch.cuda.current_stream().cuda_stream)
-            ev[1].record()
-            torch.cuda.synchronize()
-            read_us = ev[0].elapsed_time(ev[1]) * 1e3 / reps
+            if (w.V * 2) % 16 == 0:
+                # floor of a kernel that only fetches one step's logits, in the row pass's launch shape
+                sink = torch.zeros(4 * w.B * w.N, dtype=torch.int32, device="cuda")
+                reps = 20
+                for r in range(3 + reps):
+                    if r == 3:
+                        ev[0].record()
+                    binding.read_rows(rec[r % len(rec)][0], w.V * 2, w.B * w.N, sink, torch.cuda.current_stream().cuda_stream)
+                ev[1].record()
+                torch.cuda.synchronize()
+                read_us = ev[0].elapsed_time(ev[1]) * 1e3 / reps
+            # the row pass as a kernel of its own (stand_verify's first launch), same tensors
+            reps = min(12, len(rec))
+            vt = [torch.empty_like(t) for t in (out_tok, out_node, out_len)]
+            for r in range(2):
+                h2.verify(10 ** 6 + r, rec[r % len(rec)][0], *vt)
+            h2.profile_begin(reps)
+            for r in range(reps):
+                h2.verify(10 ** 6 + 2 + r, rec[r % len(rec)][0], *vt)
+            ms_v, n_v = h2.profile_end()
+            row_alone_us = ms_v * 1e3 / max(n_v, 1)
         del rec, o_tok, o_node, o_len, o_draft
-    row_ms, row_n = (0.0, 0) if args.no_events else h2.profile_end()
-    n_rec = n_after
     st = h2.stats()
     ms_per_step = timed_s * 1e3 / K_steps
-    steps_per_s = K_steps / timed_s
+    if repeats:
+        ms_per_step = float(np.median(repeats)) * 1e3 / K_steps
+    steps_per_s = 1e3 / ms_per_step
 
     rows = w.B * w.N
     logits_bytes = rows * w.V * 2
@@ -299,29 +367,36 @@ def main():
     # + row outputs + table traffic of the merges and probes + draft / verify state
     step_bytes = logits_bytes + w.B * w.V * 2 + rows * (8 + 12 * w.K) + 1_200_000 + 500_000
     row_bytes = logits_bytes + rows * (8 + 12 * w.K)
-    # HBM bytes per row-pass launch from profiler counters, if the committed summary holds them
-    traffic = None
-    tpath = os.path.join(ROOT, "profiles", "row_pass_kernel_cfg3_hbm_traffic.txt")
-    if args.workload == "cfg3" and os.path.exists(tpath):
+    fused = h2.step_is_one_launch()
+    kernel = "stand_step_kernel" if fused else "row_pass_kernel"
+    kbytes = step_bytes if fused else row_bytes
+    # HBM bytes per launch of that kernel from profiler counters, if the committed summary holds them
+    traffic = traffic_commit = None
+    tpath = os.path.join(ROOT, "profiles", "%s_%s_hbm_traffic.txt" % (kernel, args.workload))
+    if os.path.exists(tpath) and label == "headline":
         for line in open(tpath):
             if line.startswith("traffic_bytes_per_launch:"):
                 traffic = int(float(line.split(":")[1]))
+            if line.startswith("commit:"):
+                traffic_commit = line.split(":", 1)[1].strip()
     roof = None
-    if row_n:
-        row_us = row_ms * 1e3 / row_n
-        achieved = row_bytes / (row_us * 1e-6) / 1e9
-        roof = {"bound": "hbm", "kernel": "row_pass_kernel", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
+    if kern_n:
+        k_us = kern_ms * 1e3 / kern_n
+        achieved = kbytes / (k_us * 1e-6) / 1e9
+        roof = {"bound": "hbm", "kernel": kernel, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
-                "avg_launch_us": round(row_us, 2), "bytes_per_launch": row_bytes}
+                "traffic_commit": traffic_commit, "avg_launch_us": round(k_us, 2), "bytes_per_launch": kbytes}
         if traffic:
             # the same launch priced by the bytes the profiler's counters saw it move
-            roof["achieved_by_traffic"] = round(traffic / (row_us * 1e-6) / 1e9, 1)
+            roof["achieved_by_traffic"] = round(traffic / (k_us * 1e-6) / 1e9, 1)
+        if row_alone_us:
+            roof["row_pass_alone_us"] = round(row_alone_us, 2)
+            roof["row_pass_alone_GBps"] = round(row_bytes / (row_alone_us * 1e-6) / 1e9, 1)
         if read_us:
             # the same bytes fetched by a kernel that does nothing else (stand_read_rows), back to back
             roof["read_only_us"] = round(read_us, 2)
             roof["read_only_GBps"] = round(logits_bytes / (read_us * 1e-6) / 1e9, 1)
-            roof["frac_of_read_only"] = round(read_us / row_us, 4)
-
+            roof["frac_of_read_only"] = round(read_us / k_us, 4)
     cpu = None
     if cpu_n:
         cpu = {"value": round(cpu_n / cpu_s, 4), "unit": "steps/s", "cores": 1, "kind": "oracle",
@@ -330,38 +405,115 @@ def main():
                          % (cpu_n, cpu_s, rows)}
         if cpu_rows:
             cpu["row_pass_all_cores"] = cpu_rows
-        try:
-            model = [l.split(":", 1)[1].strip() for l in open("/proc/cpuinfo") if l.startswith("model name")]
-            cpu["host"] = "%s, %d logical CPUs, %d usable by this process" % (model[0], len(model), len(os.sched_getaffinity(0)))
-        except (OSError, IndexError):
-            pass
+        cpu["host"] = host_description()
+    load = (entries0 + filler.shape[0] // es + int(st.inserts)) / cfg["capacity"]
+    h1.close()
+    h2.close()
+    return {
+        "steps_per_s": steps_per_s, "ms_per_step": ms_per_step, "acc_len": acc_len, "w": w, "cfg": cfg, "roof": roof, "cpu": cpu,
+        "step_bytes": step_bytes, "near_1e6": near_1e6, "st": st, "n_rec": n_after, "issue_ms": issue_s * 1e3 / K_steps,
+        "n_chunks": n_chunks, "prep_s": prep_s, "load": load, "entries": entries0 + int(st.inserts), "fused": fused,
+        "repeats_ms": [round(r * 1e3 / K_steps, 4) for r in repeats], "timeline": timeline, "T_warm": T_warm,
+    }
 
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=192)
+    ap.add_argument("--warmup", type=int, default=8)
+    ap.add_argument("--table-warm", type=int, default=200)
+    ap.add_argument("--table-fill", type=float, default=None,
+                    help="load factor of the timed handle's table: inert entries are added to the warmed table up to it "
+                         "(default: the load a full-length run of the workload ends with)")
+    ap.add_argument("--workload", default="cfg3")
+    ap.add_argument("--cpu-steps", type=int, default=40)
+    ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--no-deep", action="store_true", help="skip the second, labelled measurement with confident targets")
+    ap.add_argument("--repeats", type=int, default=9, help="replays of a timed region shorter than 25 ms (the median is reported)")
+    ap.add_argument("--no-events", action="store_true", help="do not time the dominant kernel with HIP events")
+    ap.add_argument("--draft-mode", type=int, default=0,
+                    help="0 Gumbel-Top-K (the method), 1 sequential multinomial, 2 deterministic (the paper's ablation)")
+    ap.add_argument("--update-mode", type=int, default=0,
+                    help="0 merge the accepted path's rows (the paper), 1 merge every drafted node's row (table stress)")
+    ap.add_argument("--merge-policy", type=int, default=0,
+                    help="0 running mean over all observations of a context (the method), 1 keep only the newest "
+                         "observation (the replace policy the paper compares against)")
+    ap.add_argument("--peak", type=float, default=8.0,
+                    help="logit height of the peaked tokens (BASELINE: +8, p about 0.23 each); higher peaks give "
+                         "sharper targets, longer acceptance and deeper drafts")
+    ap.add_argument("--max-peaks", type=int, default=4,
+                    help="each row peaks on 1..max-peaks tokens (BASELINE: 1-4); 1 with a high --peak models a confident "
+                         "target, where acceptance follows the quality of the drafts")
+    ap.add_argument("--step-mode", type=int, default=0,
+                    help="how stand_step is issued: 0 the library's choice, 1 five dependent launches, 2 one launch")
+    ap.add_argument("--upper-depth", type=int, default=2, help="one-launch step: tree levels whose rows go first")
+    ap.add_argument("--tail-groups", type=int, default=0, help="one-launch step: tail workgroups per trajectory (0: library's choice)")
+    ap.add_argument("--rows-first", type=int, default=0,
+                    help="one-launch step: row workgroups placed before the tail's (0: one device-full)")
+    ap.add_argument("--timeline", action="store_true",
+                    help="after the timed region, replay a few steps with the one-launch step's clock readings on and report them")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also run a plain copy of one logits tensor (known HBM traffic) for counter calibration")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU; every GPU box here has one, so --gpus %d is not run" % args.gpus,
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2506_04708_amd import binding, synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    if args.table_fill is None:
+        # entries a full-length run ends with = inserts per step (measured over the warm-up steps of each workload)
+        # times the step count the configuration names, over its capacity
+        args.table_fill = {"cfg3": 0.10, "cfg4": 0.12, "cfg5": 0.15}.get(args.workload, 0.0)
+    m = measure(args, np, torch, binding, synth, args.peak, args.max_peaks, args.steps, args.warmup, args.table_warm,
+                0 if args.no_cpu else args.cpu_steps, "headline")
+    deep = None
+    if not args.no_deep and args.workload == "cfg3" and (args.peak, args.max_peaks) == (8.0, 4):
+        d = measure(args, np, torch, binding, synth, 14.0, 1, min(args.steps, 96), args.warmup, min(args.table_warm, 100), 0, "deep")
+        deep = {"label": "confident targets (one peaked token per row at +14, p about 0.98): longer accepted paths and deeper drafts; "
+                         "not the headline workload", "value": round(d["steps_per_s"], 2), "unit": "steps/s",
+                "ms_per_step": round(d["ms_per_step"], 4), "steps": min(args.steps, 96), "acceptance_len": round(d["acc_len"], 3),
+                "hbm_frac_of_peak": round(d["step_bytes"] * d["steps_per_s"] / 1e9 / HBM_PEAK_GBPS, 4),
+                "kernel_avg_launch_us": d["roof"]["avg_launch_us"] if d["roof"] else None,
+                "table_load_factor": round(d["load"], 4), "repeats_ms_per_step": d["repeats_ms"]}
+    w, cfg, st = m["w"], m["cfg"], m["st"]
     out = {
         "metric": "speculation steps/s (stand_step: verify + table merge + draft), B=%d, V=%d, %d-node tree" % (w.B, w.V, w.N),
-        "value": round(steps_per_s, 2), "unit": "steps/s", "n_gpus": 1, "steps": K_steps, "warmup": W_steps,
-        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "value": round(m["steps_per_s"], 2), "unit": "steps/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(m["ms_per_step"], 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": "%s: B=%d trajectories sharing one table, V=%d, bf16 logits, %d-node tree (depth %d), "
                                "orders %d-%d, K=%d, T=%.1f, %d slots; open-loop replay of seeded streams, table warmed "
-                               "for %d steps" % (args.workload, w.B, w.V, w.N, w.D, cfg["order_min"], cfg["order_max"], w.K,
-                                                 w.T, cfg["capacity"], T_warm),
+                               "for %d steps and filled to the load of a full-length run" % (
+                                   args.workload, w.B, w.V, w.N, w.D, cfg["order_min"], cfg["order_max"], w.K, w.T,
+                                   cfg["capacity"], m["T_warm"]),
                    "draft_mode": ["gumbel_topk", "multinomial", "deterministic"][args.draft_mode],
                    "update_mode": ["accepted_path", "all_nodes"][args.update_mode],
                    "merge_policy": ["running_mean", "replace"][args.merge_policy], "peak": args.peak, "max_peaks": args.max_peaks,
-                   "acceptance_len": round(acc_len, 3), "table_entries": int(entries0 + st.inserts)},
-        "hbm_gbps_algorithmic": round(step_bytes * steps_per_s / 1e9, 1),
-        "hbm_frac_of_peak": round(step_bytes * steps_per_s / 1e9 / HBM_PEAK_GBPS, 4),
-        "bytes_per_step": step_bytes,
-        "roofline": roof, "cpu_baseline": cpu,
-        "table_updates_per_step": round((st.inserts + st.merges) / max(n_rec, 1), 1),
+                   "step_issue": "one launch" if m["fused"] else "five launches",
+                   "acceptance_len": round(m["acc_len"], 3), "table_entries": int(m["entries"]),
+                   "table_load_factor": round(m["load"], 4)},
+        "hbm_gbps_algorithmic": round(m["step_bytes"] * m["steps_per_s"] / 1e9, 1),
+        "hbm_frac_of_peak": round(m["step_bytes"] * m["steps_per_s"] / 1e9 / HBM_PEAK_GBPS, 4),
+        "bytes_per_step": m["step_bytes"],
+        "roofline": m["roof"], "cpu_baseline": m["cpu"],
+        "deep_regime": deep,
+        "table_updates_per_step": round((st.inserts + st.merges) / max(m["n_rec"], 1), 1),
         "near_threshold_fallbacks": int(st.near_threshold), "filter_mismatch": int(st.filter_mismatch),
-        "decisions_within_1e-6_of_threshold": near_1e6,
+        "wait_expired": int(st.wait_expired),
+        "decisions_within_1e-6_of_threshold": m["near_1e6"],
+        "repeats_ms_per_step": m["repeats_ms"], "timeline": m["timeline"],
         "paper_context": "context only, not this metric: the paper reports end-to-end decoding on one A100 with the target "
                          "model's forward included: 60-65 % lower latency than autoregressive decoding (7B, best-of-16), "
                          "i.e. about 20 whole-loop speculation steps/s (69.15 tokens/s at 3.46 accepted tokens per step); it "
                          "gives no time for the speculation step alone",
-        "host_issue_ms_per_step": round(issue_s * 1e3 / K_steps, 4), "timed_chunks": n_chunks,
-        "prep_seconds": round(prep_s, 1),
+        "host_issue_ms_per_step": round(m["issue_ms"], 4), "timed_chunks": m["n_chunks"],
+        "prep_seconds": round(m["prep_s"], 1),
     }
     print(json.dumps(out))
 

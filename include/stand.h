@@ -130,8 +130,10 @@ int stand_depth(const stand_handle *h);
  * of b is dropped.  Synchronises `stream`. */
 int stand_set_context(stand_handle *h, int32_t b, const int32_t *host_tokens, int32_t n, void *stream);
 
-/* Beam copy: trajectory b continues from the context of host_src_of[b] (B entries).  Pending
- * drafts are dropped; call stand_draft before the next verify.  Synchronises `stream`. */
+/* Beam copy (tree search: parents copied, table shared): trajectory b continues from the context of
+ * host_src_of[b] (B entries in 0 .. B-1, as it was before the call; a trajectory may be the source of
+ * several).  Pending drafts are dropped; call stand_draft before the next verify.  Asynchronous on
+ * `stream` (the map is copied before the call returns); no host synchronisation. */
 int stand_reorder(stand_handle *h, const int32_t *host_src_of, void *stream);
 
 /* Table update (paper Sec. 4.1, "Efficient logit approximation").  For committed token j of
@@ -213,6 +215,9 @@ int stand_step(stand_handle *h, uint64_t step, const void *d_logits, int32_t *d_
  *                a test that results do not depend on the workgroup -> work mapping. */
 int stand_set_step_plan(stand_handle *h, int32_t mode, int32_t upper_depth, int32_t tail_groups, int32_t rows_first,
                         uint32_t shuffle);
+
+/* 1 if stand_step on this handle is currently issued as one launch, 0 if as five (see stand_set_step_plan). */
+int stand_step_is_one_launch(const stand_handle *h);
 
 /* Bound, in microseconds, of every wait inside the one-launch step (default 200 000).  A wait that runs
  * out is counted in stand_stats.wait_expired; every kernel still ends normally, but the step's outputs

@@ -26,7 +26,7 @@ EXPORTED = [
     "stand_profile_begin", "stand_profile_end", "stand_copy_bytes", "stand_read_rows", "stand_set_filter_margin",
     "stand_tree_initial", "stand_tree_select", "stand_get_node_counts", "stand_reset_node_counts",
     "stand_tree_packing", "stand_verify_static", "stand_static_scratch_need",
-    "stand_set_step_plan", "stand_set_wait_limit", "stand_step_timeline",
+    "stand_set_step_plan", "stand_set_wait_limit", "stand_step_timeline", "stand_step_is_one_launch",
 ]
 
 
@@ -68,6 +68,7 @@ def load_library():
     lib.stand_static_scratch_need.restype = C.c_uint64
     lib.stand_set_step_plan.argtypes = [vp, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_uint32]
     lib.stand_set_wait_limit.argtypes = [vp, C.c_uint64]
+    lib.stand_step_is_one_launch.argtypes = [vp]
     lib.stand_step_timeline.argtypes = [vp, C.c_int32, vp, C.POINTER(C.c_uint64)]
     lib.stand_step.argtypes = [vp, C.c_uint64, vp, i32p, i32p, i32p, i32p, i32p, vp]
     lib.stand_row_results.argtypes = [vp, vp, vp, vp, vp, vp]
@@ -270,6 +271,9 @@ class Stand:
 
     def set_step_plan(self, mode=0, upper_depth=2, tail_groups=0, shuffle=0, rows_first=0):
         _check(lib().stand_set_step_plan(self.h, mode, upper_depth, tail_groups, rows_first, shuffle), self.h)
+
+    def step_is_one_launch(self):
+        return lib().stand_step_is_one_launch(self.h) == 1
 
     def set_wait_limit(self, microseconds):
         _check(lib().stand_set_wait_limit(self.h, microseconds), self.h)

@@ -11,6 +11,20 @@ __global__ void fill_i32_kernel(int32_t *p, int32_t v, size_t n)
     if (i < n) p[i] = v;
 }
 
+// Beam copy: context tail and length of trajectory b become those of trajectory src_of[b].  The new
+// values go to a second pair of arrays (a map may name a trajectory as source and destination at once).
+__global__ void reorder_gather_kernel(int B, const int32_t *src_of, const int32_t *tail_in, const long long *len_in,
+                                      int32_t *tail_out, long long *len_out)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= B * kMaxOrder) return;
+    const int b = i / kMaxOrder, q = i % kMaxOrder;
+    int s = src_of[b];
+    s = s < 0 ? 0 : (s >= B ? B - 1 : s);  // validated on the host; never index outside
+    tail_out[i] = tail_in[(size_t)s * kMaxOrder + q];
+    if (q == 0) len_out[b] = len_in[s];
+}
+
 // top-K probabilities are produced by the row pass already; this copies the per-row results out
 __global__ void copy_row_results_kernel(int rows, int K, const float *row_m, const float *row_s, const int32_t *top_idx,
                                         const float *top_p, float *o_m, float *o_s, int32_t *o_idx, float *o_p)

@@ -294,7 +294,8 @@ __device__ __forceinline__ WavePartial wave_row_stream(const void *rowp, int V, 
     if (__ballot(edge_val > m_ref)) raise_reference(edge_val);
     if (edge_id >= 0) s_t += fast_exp2(__builtin_fmaf(edge_val, c, nb));
 
-    auto one_vector = [&](const uint4 &w, int idx, bool valid) {
+    // One vector: its maximum (returned; -inf for a lane without a vector) and its share of the fast sum.
+    auto one_vector = [&](const uint4 &w, bool valid) {
         float x[EPV];
         unpack<DT>(w, x);
         float cm = x[0];
@@ -306,22 +307,36 @@ __device__ __forceinline__ WavePartial wave_row_stream(const void *rowp, int V, 
 #pragma unroll
         for (int j = 0; j < EPV; ++j) e += fast_exp2(__builtin_fmaf(x[j], c, nb));
         s_t += valid ? e : 0.0f;
-        if (__ballot(valid && cm >= st.theta_val))
-            wave_offer<LOWBIT>(ws, st, lane, K, valid && cm >= st.theta_val, cm, (uint32_t)idx, m_ref);
+        return cm;
+    };
+    // The candidate list is looked at once per batch, not once per vector: a wave sees only a few dozen
+    // batches of a row, and early in the row nearly every vector has some lane at or above the threshold.
+    // Each lane keeps the maxima of its vectors of the batch; if any of them reaches the threshold, the
+    // vectors are offered in order (the threshold may rise between them).
+    auto offer_batch = [&](const float (&cm)[U], const bool (&vld)[U], int kb) {
+        bool any = false;
+#pragma unroll
+        for (int u = 0; u < U; ++u) any |= vld[u] && cm[u] >= st.theta_val;
+        if (!__ballot(any)) return;
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            wave_offer<LOWBIT>(ws, st, lane, K, vld[u] && cm[u] >= st.theta_val, cm[u], (uint32_t)((kb * U + u) * 64 + lane), m_ref);
     };
     auto do_batch = [&](uint4 (&w)[U], int k) {
         const int kb = k * wpr + wsub;        // batch of the row
+        float cm[U];
+        bool vld[U];
         if ((kb + 1) * per_batch <= g.nvec) {  // wave-uniform: every lane has all its vectors
 #pragma unroll
-            for (int u = 0; u < U; ++u) one_vector(w[u], (kb * U + u) * 64 + lane, true);
+            for (int u = 0; u < U; ++u) { vld[u] = true; cm[u] = one_vector(w[u], true); }
         } else {
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                const int idx = (kb * U + u) * 64 + lane;
-                const bool valid = idx < g.nvec;
-                one_vector(valid ? w[u] : make_uint4(0, 0, 0, 0), idx, valid);
+                vld[u] = (kb * U + u) * 64 + lane < g.nvec;
+                cm[u] = one_vector(vld[u] ? w[u] : make_uint4(0, 0, 0, 0), vld[u]);
             }
         }
+        offer_batch(cm, vld, kb);
     };
 
     // batches beyond the row (when nbatch is not a multiple of PF) have no valid lane and add nothing

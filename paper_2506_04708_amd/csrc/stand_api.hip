@@ -34,14 +34,19 @@ struct stand_handle {
     std::vector<int32_t> parent, depth, nchild, first_child, level_start;
     int32_t *d_tree;  // parent | depth | nchild | first_child | level_start
     char *table;
-    int32_t *ctx_tail;
-    long long *ctx_len;
+    int32_t *ctx_tail, *ctx_tail2;   // context tails; the second array receives the result of a beam copy
+    long long *ctx_len, *ctx_len2;
+    int32_t *reorder_map;            // [B] device copy of the map of the last stand_reorder
+    char *export_buf;                // compacted table of the last stand_table_export (kept, grown on demand)
+    uint64_t export_cap;
     int32_t *draft_tok, *draft_has, *draft_qid;   // the pending draft
     float *draft_qmu;
     int32_t *draft_tok2, *draft_has2, *draft_qid2;  // second copy: the one-launch step writes the next draft here
     float *draft_qmu2;                              // while rows that are still streaming read the pending one
     // one-launch step (stand_step_kernel)
-    unsigned *row_done, *sum_done, *bar;  // counters that only grow, see step_fused.hpp
+    unsigned *row_done, *bar;  // counters that only grow, see step_fused.hpp
+    unsigned *item_next, *path_flag;
+    int32_t *path_pub;
     unsigned step_epoch;
     int step_mode;       // STAND_STEP_AUTO / SERIAL / FUSED
     int upper_depth;     // rows of nodes up to this depth are dispatched before the tail
@@ -124,9 +129,9 @@ static hipError_t dmalloc(T **p, size_t n)
 static void free_all(stand_handle *h)
 {
     if (!h) return;
-    void *ptrs[] = {h->d_tree, h->table, h->ctx_tail, h->ctx_len, h->draft_tok, h->draft_has, h->draft_qid, h->draft_qmu,
+    void *ptrs[] = {h->d_tree, h->table, h->ctx_tail, h->ctx_len, h->ctx_tail2, h->ctx_len2, h->reorder_map, h->export_buf, h->draft_tok, h->draft_has, h->draft_qid, h->draft_qmu,
                     h->vs.row_m, h->vs.row_s, h->vs.top_l, h->vs.top_p, h->vs.top_idx, h->vs.outcome, h->vs.obs_idx, h->vs.obs_p, h->rec_slot,
-                    h->recent, h->draft_tok2, h->draft_has2, h->draft_qid2, h->draft_qmu2, h->row_done, h->sum_done, h->bar, h->stamps, h->vs.seg_part, h->node_count, h->anc, h->vs.stop_i, h->vs.stop_qid, h->vs.stop_child, h->vs.stop_m, h->vs.stop_qmu, h->vs.stop_ql, h->pr_m, h->pr_top_l, h->pr_top_idx, h->stats, h->counter};
+                    h->recent, h->draft_tok2, h->draft_has2, h->draft_qid2, h->draft_qmu2, h->row_done, h->bar, h->item_next, h->path_flag, h->path_pub, h->stamps, h->vs.seg_part, h->node_count, h->anc, h->vs.stop_i, h->vs.stop_qid, h->vs.stop_child, h->vs.stop_m, h->vs.stop_qmu, h->vs.stop_ql, h->pr_m, h->pr_top_l, h->pr_top_idx, h->stats, h->counter};
     for (void *p : ptrs) (void)hipFree(p);
     for (hipEvent_t e : h->ev_begin) (void)hipEventDestroy(e);
     for (hipEvent_t e : h->ev_end) (void)hipEventDestroy(e);
@@ -170,6 +175,8 @@ extern "C" int stand_create(const stand_config *cfg, stand_handle **out)
     h->profiling = false;
     h->filter_margin = kFastEps;
     h->step_epoch = 0;
+    h->export_buf = nullptr;
+    h->export_cap = 0;
     h->step_mode = STAND_STEP_AUTO;
     h->upper_depth = 2;
     h->tail_groups = 0;
@@ -224,11 +231,14 @@ extern "C" int stand_create(const stand_config *cfg, stand_handle **out)
     acc(hipMalloc((void **)&h->table, (size_t)cfg->table_capacity * h->slot_bytes));
     acc(dmalloc(&h->ctx_tail, B * kMaxOrder));
     acc(dmalloc(&h->ctx_len, B));
+    acc(dmalloc(&h->ctx_tail2, B * kMaxOrder)); acc(dmalloc(&h->ctx_len2, B)); acc(dmalloc(&h->reorder_map, B));
     acc(dmalloc(&h->draft_tok, rows)); acc(dmalloc(&h->draft_has, rows));
     acc(dmalloc(&h->draft_qid, rows * K)); acc(dmalloc(&h->draft_qmu, rows * K));
     acc(dmalloc(&h->draft_tok2, rows)); acc(dmalloc(&h->draft_has2, rows));
     acc(dmalloc(&h->draft_qid2, rows * K)); acc(dmalloc(&h->draft_qmu2, rows * K));
-    acc(dmalloc(&h->row_done, rows)); acc(dmalloc(&h->sum_done, B)); acc(dmalloc(&h->bar, 2));
+    acc(dmalloc(&h->row_done, rows)); acc(dmalloc(&h->bar, 2));
+    acc(dmalloc(&h->item_next, B)); acc(dmalloc(&h->path_flag, B));
+    acc(dmalloc(&h->path_pub, B * kPathPub));
     acc(dmalloc(&h->vs.row_m, rows)); acc(dmalloc(&h->vs.row_s, rows));
     acc(dmalloc(&h->vs.top_l, rows * K)); acc(dmalloc(&h->vs.top_p, rows * K)); acc(dmalloc(&h->vs.top_idx, rows * K));
     acc(dmalloc(&h->vs.outcome, rows));
@@ -265,8 +275,9 @@ extern "C" int stand_create(const stand_config *cfg, stand_handle **out)
     acc(hipMemset(h->draft_qid2, 0, rows * K * sizeof(int32_t)));
     acc(hipMemset(h->draft_qmu2, 0, rows * K * sizeof(float)));
     acc(hipMemset(h->row_done, 0, rows * sizeof(unsigned)));
-    acc(hipMemset(h->sum_done, 0, B * sizeof(unsigned)));
     acc(hipMemset(h->bar, 0, 2 * sizeof(unsigned)));
+    acc(hipMemset(h->item_next, 0, B * sizeof(unsigned)));
+    acc(hipMemset(h->path_flag, 0, B * sizeof(unsigned))); acc(hipMemset(h->path_pub, 0, B * kPathPub * sizeof(int32_t)));
     acc(hipMemset(h->vs.outcome, 0xFF, rows * sizeof(int32_t)));
     acc(hipMemset(h->node_count, 0, (size_t)N * sizeof(unsigned long long)));
     {
@@ -331,22 +342,16 @@ extern "C" int stand_reorder(stand_handle *h, const int32_t *host_src_of, void *
     for (int b = 0; b < h->B; ++b) if (host_src_of[b] < 0 || host_src_of[b] >= h->B) return STAND_EINVAL;
     hipStream_t s = (hipStream_t)stream;
     HIP_TRY(h, hipSetDevice(h->cfg.device));
-    std::vector<int32_t> tail((size_t)h->B * kMaxOrder), tail2((size_t)h->B * kMaxOrder);
-    std::vector<long long> len(h->B), len2(h->B);
-    HIP_TRY(h, hipMemcpyAsync(tail.data(), h->ctx_tail, tail.size() * sizeof(int32_t), hipMemcpyDeviceToHost, s));
-    HIP_TRY(h, hipMemcpyAsync(len.data(), h->ctx_len, len.size() * sizeof(long long), hipMemcpyDeviceToHost, s));
-    HIP_TRY(h, hipStreamSynchronize(s));
-    for (int b = 0; b < h->B; ++b) {
-        std::copy(tail.begin() + (size_t)host_src_of[b] * kMaxOrder, tail.begin() + (size_t)(host_src_of[b] + 1) * kMaxOrder,
-                  tail2.begin() + (size_t)b * kMaxOrder);
-        len2[b] = len[host_src_of[b]];
-    }
-    HIP_TRY(h, hipMemcpyAsync(h->ctx_tail, tail2.data(), tail2.size() * sizeof(int32_t), hipMemcpyHostToDevice, s));
-    HIP_TRY(h, hipMemcpyAsync(h->ctx_len, len2.data(), len2.size() * sizeof(long long), hipMemcpyHostToDevice, s));
-    int rc = drop_drafts(h, 0, h->B, s);
-    if (rc) return rc;
-    HIP_TRY(h, hipStreamSynchronize(s));
-    return STAND_OK;
+    // the map goes to the device once (the copy from pageable memory is staged before the call returns);
+    // one kernel gathers the contexts into the second pair of arrays, which then becomes the current one
+    HIP_TRY(h, hipMemcpyAsync(h->reorder_map, host_src_of, (size_t)h->B * sizeof(int32_t), hipMemcpyHostToDevice, s));
+    const int n = h->B * kMaxOrder;
+    reorder_gather_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s>>>(h->B, h->reorder_map, h->ctx_tail, h->ctx_len,
+                                                                                  h->ctx_tail2, h->ctx_len2);
+    HIP_TRY(h, hipGetLastError());
+    std::swap(h->ctx_tail, h->ctx_tail2);
+    std::swap(h->ctx_len, h->ctx_len2);
+    return drop_drafts(h, 0, h->B, s);
 }
 
 // ---- launches ----------------------------------------------------------------------------------
@@ -614,14 +619,19 @@ static int launch_step_fused(stand_handle *h, uint64_t step, const void *d_logit
     const bool bf16 = h->cfg.logits_dtype == STAND_BF16;
     StepArgs A;
     A.row = make_row_args(h, h->vs, step, d_logits);
-    // one wave sums one segment: 256 vectors per lane-round of four loads
+    A.G = step_tail_groups(h);
+    // one wave sums one segment: a few rounds of loads per lane; a row has at most as many segments as the
+    // trajectory has summing waves (all waves of its tail workgroups but one)
     A.path = make_path_args(h, h->vs, step, d_logits, 0, nullptr, nullptr, out_tok, out_node, out_len, 4 * 64 * 2);
+    if (A.path.nseg > A.G * kStepWPR - 1) A.path.nseg = A.G * kStepWPR - 1;
     A.mg = merge_args(h, commit, nullptr, out_len);
     A.draft = make_draft_args(h, step + 1, next_draft_tok, commit, out_len);
     // the next draft goes to the second copy of the draft state; the copies change roles after the launch
     A.draft.draft_tok = h->draft_tok2; A.draft.draft_has = h->draft_has2;
     A.draft.draft_qid = h->draft_qid2; A.draft.draft_qmu = h->draft_qmu2;
-    A.sync.row_done = h->row_done; A.sync.sum_done = h->sum_done; A.sync.bar = h->bar;
+    A.sync.row_done = h->row_done; A.sync.bar = h->bar;
+    A.sync.item_next = h->item_next; A.sync.path_flag = h->path_flag;
+    A.sync.path_pub = h->path_pub;
     A.sync.epoch = ++h->step_epoch;
     A.sync.wait_ticks = h->wait_limit_us * (uint64_t)h->wall_khz / 1000ull;
     A.sync.stamps = h->stamps;
@@ -713,6 +723,8 @@ extern "C" int stand_step_timeline(stand_handle *h, int32_t enable, uint64_t *ho
     return STAND_OK;
 }
 
+extern "C" int stand_step_is_one_launch(const stand_handle *h) { return h ? (step_fused_wanted(h) ? 1 : 0) : STAND_EINVAL; }
+
 extern "C" int stand_set_wait_limit(stand_handle *h, uint64_t microseconds)
 {
     if (!h || microseconds > 60ull * 1000 * 1000) return STAND_EINVAL;
@@ -770,8 +782,14 @@ extern "C" int stand_table_export(stand_handle *h, void *host_buf, uint64_t *ino
     if (!host_buf) return STAND_OK;
     if (have < need) return STAND_EINVAL;
     if (n == 0) return STAND_OK;
-    char *dbuf = nullptr;
-    HIP_TRY(h, hipMalloc((void **)&dbuf, need));
+    // the compacted copy goes to a buffer the handle keeps (it grows when a later export needs more)
+    if (h->export_cap < need) {
+        if (h->export_buf) (void)hipFree(h->export_buf);
+        h->export_buf = nullptr; h->export_cap = 0;
+        HIP_TRY(h, hipMalloc((void **)&h->export_buf, need));
+        h->export_cap = need;
+    }
+    char *dbuf = h->export_buf;
     hipError_t e = hipMemset(h->counter, 0, sizeof(unsigned long long));
     if (e == hipSuccess) {
         table_compact_kernel<<<dim3(blocks), dim3(256)>>>(h->table, cap, h->slot_bytes, h->counter, dbuf, n);
@@ -779,7 +797,6 @@ extern "C" int stand_table_export(stand_handle *h, void *host_buf, uint64_t *ino
     }
     std::vector<char> tmp(need);
     if (e == hipSuccess) e = hipMemcpy(tmp.data(), dbuf, need, hipMemcpyDeviceToHost);
-    (void)hipFree(dbuf);
     HIP_TRY(h, e);
     std::vector<uint64_t> order(n);
     for (uint64_t i = 0; i < n; ++i) order[i] = i;

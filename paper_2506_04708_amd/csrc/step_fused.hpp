@@ -41,11 +41,15 @@ constexpr int kStepThreads = 64 * kStepWPR;
 #define STAND_TAIL_INFLIGHT 8
 #endif
 constexpr int kTailInflight = STAND_TAIL_INFLIGHT;  // 16-byte loads a lane of the tail keeps in flight while it sums a row segment
+constexpr int kPathPub = 2 * (kMaxDepth + 2) + 2;  // words per trajectory of the published path
+constexpr unsigned long long kPartThere = 1ull << 63;  // set in a stored partial sum of this launch
 constexpr unsigned kWaitMaxPolls = 1u << 24;  // a wait ends after this many polls whatever the clock says
 
 struct StepSync {
     unsigned *row_done;             // [B*N]  +2 per launch: the ranking wave and the testing wave of the row
-    unsigned *sum_done;             // [B]    +G per launch: the trajectory's tail workgroups after their sums
+    unsigned *item_next;            // [B]    next (path row, segment) item to hand out: (launch number & 0xFFFF) << 16 | item
+    unsigned *path_flag;            // [B]    launch number once the trajectory's path is published
+    int32_t *path_pub;              // [B][kPathPub] the path: length, nodes, then the bit patterns of the rows' maxima
     unsigned *bar;                  // [2]    +B per launch each: all claims made / all records applied
     unsigned epoch;                 // number of this launch on the handle, from 1
     unsigned long long wait_ticks;  // bound of every wait in ticks of the device's constant clock (wall_clock64)
@@ -93,6 +97,7 @@ __device__ __forceinline__ void stamp(const StepSync &sy, int b, int k)
 struct TailShared {
     int path[kMaxDepth + 2];   // nodes of the accepted path
     int acc[kMaxDepth + 2];    // outcome of each of them
+    float pm[kMaxDepth + 2];   // maximum of each of their rows
     int len, ok;
     FinishShared fin;
     int32_t l_id[kStepWPR][2 * kMaxK];
@@ -122,36 +127,69 @@ __device__ __forceinline__ void tail_role(const StepArgs &A, int b, int g, char 
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int N = a.N, W = a.W, K = a.K;
 
-    // ---- the accepted path: follow the outcomes from the root, waiting for each row on the way
-    if (tid == 0) {
-        if (g == 0) stamp(sy, b, 0);
-        int cur = 0, len = 0, ok = 1;
-        for (;;) {
-            if (!wait_reached(&sy.row_done[(size_t)b * N + cur], 2u * sy.epoch, sy.wait_ticks)) { ok = 0; break; }
-            const int acc = __hip_atomic_load(&a.outcome[(size_t)b * N + cur], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            ts->path[len] = cur;
-            ts->acc[len] = acc;
-            ++len;
-            if (acc < 0 || len > a.tree.D) break;
-            const int nxt = a.tree.first_child[cur] + acc;
-            if (nxt <= cur || nxt >= N) break;  // not reachable for outcomes of this tree
-            cur = nxt;
+    // ---- the accepted path: the trajectory's first workgroup follows the outcomes from the root, waiting for
+    // each row on the way, and publishes the path; the others wait for the publication
+    const unsigned tag = (sy.epoch & 0xFFFFu) << 16;
+    int32_t *pub = sy.path_pub + (size_t)b * kPathPub;
+    if (g == 0) {
+        if (tid == 0) {
+            stamp(sy, b, 0);
+            int cur = 0, len = 0, ok = 1;
+            for (;;) {
+                if (!wait_reached(&sy.row_done[(size_t)b * N + cur], 2u * sy.epoch, sy.wait_ticks)) { ok = 0; break; }
+                const int acc = ld_agent(&a.outcome[(size_t)b * N + cur]);
+                ts->pm[len] = ld_agent(&a.src_m[(size_t)b * N + cur]);
+                ts->path[len] = cur;
+                ts->acc[len] = acc;
+                ++len;
+                if (acc < 0 || len > a.tree.D) break;
+                const int nxt = a.tree.first_child[cur] + acc;
+                if (nxt <= cur || nxt >= N) break;  // not reachable for outcomes of this tree
+                cur = nxt;
+            }
+            ts->len = ok ? len : 0;
+            ts->ok = ok;
+            // the first items belong to the trajectory's own waves, one each; the counter hands out the rest
+            st_agent(&sy.item_next[b], tag + (unsigned)(A.G * kStepWPR - 1));
+            stamp(sy, b, 1);
         }
-        ts->len = ok ? len : 0;
-        ts->ok = ok;
-        if (g == 0) stamp(sy, b, 1);
+        __syncthreads();
+        // the partial sums this launch will produce are marked "not there yet"
+        for (int i = tid; i < ts->len * a.nseg; i += kStepThreads)
+            st_agent(&a.seg_part[((size_t)b * a.R + i / a.nseg) * kSegMax + i % a.nseg], 0ull);
+        if (tid < ts->len) {
+            st_agent(&pub[1 + tid], (int32_t)ts->path[tid]);
+            st_agent(&pub[1 + (kMaxDepth + 2) + tid], (int32_t)f2u(ts->pm[tid]));
+        }
+        if (tid == 0) st_agent(&pub[0], (int32_t)ts->len);
+        publish_fence();
+        __syncthreads();
+        if (tid == 0) st_agent(&sy.path_flag[b], sy.epoch);
+    } else {
+        if (tid == 0) {
+            ts->ok = wait_reached(&sy.path_flag[b], sy.epoch, sy.wait_ticks) ? 1 : 0;
+            ts->len = ts->ok ? ld_agent(&pub[0]) : 0;
+        }
+        __syncthreads();
+        if (tid < ts->len) {
+            ts->path[tid] = ld_agent(&pub[1 + tid]);
+            ts->pm[tid] = u2f((uint32_t)ld_agent(&pub[1 + (kMaxDepth + 2) + tid]));
+        }
+        __syncthreads();
     }
-    __syncthreads();
     consume_fence();
     const int len = ts->len;
 
-    // ---- exact partial sums: item (path row j, segment) number i goes to wave i mod (G * waves)
+    // ---- exact partial sums.  An item is (path row j, segment).  The first G * waves - 1 items of a trajectory
+    // belong to its own waves, one each (a row has at most that many segments; the first wave of the first
+    // workgroup has other work, see below); further items (paths of several rows) are handed out by a counter
+    // to whichever wave asks next: the trajectory's own waves, then those of other trajectories' helper
+    // workgroups that have run out of work.  A partial sum is stored with its top bit set ("there").
     const int nseg = a.nseg;
-    for (int item = g * kStepWPR + wave; item < len * nseg; item += A.G * kStepWPR) {
+    auto sum_item = [&](int t, int item, int node, float m) {
         const int j = item / nseg, seg = item % nseg;
-        const int row = b * N + ts->path[j];
+        const int row = t * N + node;
         const char *rowp = (const char *)a.logits + (size_t)row * (size_t)a.V * ES;
-        const float m = ld_agent(&a.src_m[row]);
         const RowGeom geo = row_geom<DT>(rowp, a.V);
         const int per = (geo.nvec + nseg - 1) / nseg;
         const int v0 = seg * per < geo.nvec ? seg * per : geo.nvec;
@@ -161,15 +199,63 @@ __device__ __forceinline__ void tail_role(const StepArgs &A, int b, int g, char 
 #else
         unsigned long long S = thread_exact_partial<DT, kTailInflight>(rowp, geo, v0, v1, seg == 0, m, a.c, lane, 64);
 #endif
-        S = wave_sum_u64(S);
-        if (lane == 0) st_agent(&a.seg_part[((size_t)b * a.R + j) * kSegMax + seg], S);
+        S = wave_sum_u64(S);  // below 2^62 (a whole row's sum is)
+        if (lane == 0) st_agent(&a.seg_part[((size_t)t * a.R + j) * kSegMax + seg], S | kPartThere);
+    };
+    // asks for the next item of trajectory t; the answer (lane 0's register) is looked at after the current
+    // item has been summed, so the round trip of the request is not waited for
+    auto request = [&](int t) {
+        unsigned v = 0u;
+        if (lane == 0) v = atomicAdd(&sy.item_next[t], 1u);
+        return v;
+    };
+    auto answer = [&](unsigned v) { return (unsigned)__builtin_amdgcn_readfirstlane((int)v) - tag; };
+    const bool control = g == 0 && wave == 0;  // this wave writes the outputs and claims the table slots meanwhile
+    if (!control) {
+        const unsigned n_items = (unsigned)(len * nseg), own = (unsigned)(A.G * kStepWPR - 1);
+        unsigned it = (unsigned)(g * kStepWPR + wave - 1);
+        while (it < n_items) {
+            const bool more = n_items > own;  // uniform: only paths of several rows have items beyond the first round
+            const unsigned req = more ? request(b) : 0u;
+            sum_item(b, (int)it, ts->path[it / nseg], ts->pm[it / nseg]);
+            it = more ? answer(req) : n_items;
+        }
     }
-    publish_fence();
-    __syncthreads();
-    if (tid == 0) atomicAdd(&sy.sum_done[b], 1u);
-    if (g != 0) return;  // the trajectory's other workgroups only help with the sums
+    if (g != 0) {
+        // help the trajectories that still have items (one look at all of them, starting behind this one)
+        for (int k0 = 0; k0 < a.B; k0 += 64) {
+            const int t = (b + 1 + k0 + lane) % a.B;
+            int tl = 0;
+            bool has = false;
+            if (k0 + lane < a.B - 1 && ld_agent(&sy.path_flag[t]) == sy.epoch) {
+                tl = ld_agent(&sy.path_pub[(size_t)t * kPathPub]);
+                has = ld_agent(&sy.item_next[t]) - tag < (unsigned)(tl * nseg);
+            }
+            unsigned long long todo = __ballot(has);
+            while (todo) {
+                const int src = __ffsll((long long)todo) - 1;
+                todo &= todo - 1;
+                const int tt = __builtin_amdgcn_readlane(t, src);
+                const unsigned n_items = (unsigned)(__builtin_amdgcn_readlane(tl, src) * nseg);
+                const int32_t *tp = sy.path_pub + (size_t)tt * kPathPub;
+                unsigned it = answer(request(tt));
+                while (it < n_items) {
+                    const int j = (int)it / nseg;
+                    const int node = ld_agent(&tp[1 + j]);
+                    const float m = u2f((uint32_t)ld_agent(&tp[1 + (kMaxDepth + 2) + j]));
+                    const unsigned req = request(tt);
+                    if ((uint32_t)node < (uint32_t)N) sum_item(tt, (int)it, node, m);  // (always true for a published path)
+                    it = answer(req);
+                }
+            }
+        }
+        return;  // the trajectory's other workgroups only help with the sums
+    }
 
-    // ---- outputs of the verification; the stop node's proposal is requested now and used after the sums
+    // (the code from here on runs in the trajectory's first workgroup only)
+    // ---- its first wave, while the others sum: the outputs of the verification, the stop node's proposal
+    // (requested now, used after the sums) and the table slots of the trajectory's merge records, which
+    // depend on the path's tokens only
     const int stop_node = len > 0 ? ts->path[len - 1] : 0;
     const int stop_row = b * N + stop_node;
     const char *stop_rowp = (const char *)a.logits + (size_t)stop_row * (size_t)a.V * ES;
@@ -179,61 +265,72 @@ __device__ __forceinline__ void tail_role(const StepArgs &A, int b, int g, char 
     if (len > 0) {
         fc = a.tree.first_child[stop_node];
         nch = a.draft_has[stop_row];
-        stop_m = ld_agent(&a.src_m[stop_row]);
-        if (wave == 0) {
+        stop_m = ts->pm[len - 1];
+    }
+    if (control) {
+        if (len > 0) {
             if (lane < K) { my_id = a.draft_qid[(size_t)stop_row * K + lane]; my_mu = a.draft_qmu[(size_t)stop_row * K + lane]; }
             if (lane < nch && lane < kMaxK && fc >= 0 && fc + lane < N) ch = a.draft_tok[(size_t)b * N + fc + lane];
             if ((uint32_t)my_id >= (uint32_t)a.V) { my_id = -1; my_mu = 0.0f; }  // never index outside the row
             else my_l = load_scalar<DT>(stop_rowp, my_id);
         }
-    }
-    if (tid < W) {
-        a.out_node[(size_t)b * W + tid] = tid < len ? ts->path[tid] : -1;
-        // accepted tokens are the tokens of the path nodes after the root; the last emitted token
-        // (position len - 1) is written by finish_row
-        if (tid + 1 < len) a.out_tok[(size_t)b * W + tid] = a.draft_tok[(size_t)b * N + ts->path[tid + 1]];
-        else if (tid >= len - 1) a.out_tok[(size_t)b * W + tid] = -1;
-    }
-    if (tid < len) atomicAdd(&a.node_count[ts->path[tid]], 1ull);  // paper Sec. 4.3: acceptance statistics per node
-    if (tid == 0) {
-        a.out_len[b] = len;
-        if (len > 0) {
-            unsigned long long tests = (unsigned long long)nch;
-            for (int q = 0; q + 1 < len; ++q) tests += (unsigned long long)(ts->acc[q] + 1);
-            atomicAdd(&a.stats[kStatTokens], (unsigned long long)len);
-            atomicAdd(&a.stats[kStatTests], tests);
-        } else {
-            atomicAdd(&a.stats[kStatWaitExpired], 1ull);
+        if (lane < W) {  // W <= 32
+            a.out_node[(size_t)b * W + lane] = lane < len ? ts->path[lane] : -1;
+            // accepted tokens are the tokens of the path nodes after the root; the last emitted token
+            // (position len - 1) is written by finish_row
+            if (lane + 1 < len) a.out_tok[(size_t)b * W + lane] = a.draft_tok[(size_t)b * N + ts->path[lane + 1]];
+            else if (lane >= len - 1) a.out_tok[(size_t)b * W + lane] = -1;
         }
-    }
-    __syncthreads();  // out_len and the accepted tokens are what the claims read
-    // ---- slots of this trajectory's merge records (they depend on the path's tokens only)
-    {
+        if (lane < len) atomicAdd(&a.node_count[ts->path[lane]], 1ull);  // paper Sec. 4.3: acceptance statistics per node
+        if (lane == 0) {
+            a.out_len[b] = len;
+            if (len > 0) {
+                unsigned long long tests = (unsigned long long)nch;
+                for (int q = 0; q + 1 < len; ++q) tests += (unsigned long long)(ts->acc[q] + 1);
+                atomicAdd(&a.stats[kStatTokens], (unsigned long long)len);
+                atomicAdd(&a.stats[kStatTests], tests);
+            } else {
+                atomicAdd(&a.stats[kStatWaitExpired], 1ull);
+            }
+        }
+        publish_fence();  // out_len and the accepted tokens, written by this wave, are what its claims read
         const int per_traj = A.mg.R * (A.mg.omax - A.mg.omin + 1);
-        for (int i = tid; i < per_traj; i += kStepThreads) merge_claim_record(A.mg, b * per_traj + i);
+        for (int i = lane; i < per_traj; i += 64) merge_claim_record(A.mg, b * per_traj + i);
     }
-    // ---- the sums of all of the trajectory's workgroups, then the rows' observations and the resampled token
-    if (tid == 0) {
-        stamp(sy, b, 3);
-        if (!wait_reached(&sy.sum_done[b], (unsigned)A.G * sy.epoch, sy.wait_ticks)) ts->ok = 0;
-        stamp(sy, b, 2);
-    }
-    __syncthreads();
-    consume_fence();
-    if (len > 0 && ts->ok) {
+    // ---- the partial sums (of whichever waves summed them), then the rows' observations and the resampled token
+    if (tid == 0) stamp(sy, b, 3);
+    auto wait_parts = [&](int j) {  // one wave: lanes < nseg each wait for their segment of path row j
+        const unsigned long long *p = &a.seg_part[((size_t)b * a.R + j) * kSegMax];
+        unsigned long long v = lane < nseg ? ld_agent(p + lane) : kPartThere;
+        if (!__all((v & kPartThere) != 0ull)) {
+            const unsigned long long t0 = wall_clock64();
+            for (unsigned polls = 0; polls < kWaitMaxPolls; ++polls) {
+                __builtin_amdgcn_s_sleep(STAND_POLL_SLEEP);
+                if (!(v & kPartThere)) v = ld_agent(p + lane);
+                if (__all((v & kPartThere) != 0ull)) break;
+                if (wall_clock64() - t0 > sy.wait_ticks) break;
+            }
+        }
+        if (!__all((v & kPartThere) != 0ull) && lane == 0) ts->ok = 0;
+        consume_fence();
+        return v & ~kPartThere;
+    };
+    if (len > 0) {
+        const unsigned long long part_stop = wave == 0 ? wait_parts(len - 1) : 0ull;
+        if (tid == 0) stamp(sy, b, 2);
         for (int j = wave; j + 1 < len; j += kStepWPR) {  // rows above the stop row: one wave each
             const int node = ts->path[j];
-            const unsigned long long part = lane < nseg ? ld_agent(&a.seg_part[((size_t)b * a.R + j) * kSegMax + lane]) : 0ull;
-            finish_row<DT, kStepThreads>(a, ts->fin, b, j, node, false, ld_agent(&a.src_m[b * N + node]), 0, -1, len, -1, 0.0f, 0.0f, -1,
-                                         part, lane, 0);
+            const unsigned long long part = wait_parts(j);
+            finish_row<DT, kStepThreads>(a, ts->fin, b, j, node, false, ts->pm[j], 0, -1, len, -1, 0.0f, 0.0f, -1, part, lane, 0);
         }
-        const unsigned long long part =
-            (wave == 0 && lane < nseg) ? ld_agent(&a.seg_part[((size_t)b * a.R + (len - 1)) * kSegMax + lane]) : 0ull;
-        finish_row<DT, kStepThreads>(a, ts->fin, b, len - 1, stop_node, true, stop_m, nch, fc, len, my_id, my_mu, my_l, ch, part,
-                                     tid, wave);
-    } else if (len > 0 && tid == 0) {
-        a.out_tok[(size_t)b * W + (len - 1)] = -1;
-        atomicAdd(&a.stats[kStatWaitExpired], 1ull);
+        __syncthreads();
+        if (ts->ok) {
+            finish_row<DT, kStepThreads>(a, ts->fin, b, len - 1, stop_node, true, stop_m, nch, fc, len, my_id, my_mu, my_l, ch, part_stop,
+                                         tid, wave);
+        } else if (tid == 0) {
+            a.out_tok[(size_t)b * W + (len - 1)] = -1;
+            atomicAdd(&a.stats[kStatWaitExpired], 1ull);
+        }
     }
 
     // ---- every trajectory's claims and observations, then this trajectory's records

@@ -18,10 +18,15 @@ CONFIGS = {
                  T=0.6, steps=2048, capacity=1 << 20, rho=0.5, seed=BASE_SEED + 1),
     "cfg3": dict(B=32, V=152064, dtype="bf16", N=64, D=8, caps=[8, 4, 2, 1], order_min=1, order_max=4, K=16,
                  T=0.6, steps=4096, capacity=1 << 22, rho=0.5, seed=BASE_SEED + 2),
+    # best-of-N: all trajectories start from one 512-token prompt, then diverge; 60 % of the repeated spans are
+    # copies from ANOTHER trajectory's history
     "cfg4": dict(B=64, V=128256, dtype="bf16", N=48, D=7, caps=[6, 3, 2, 1], order_min=1, order_max=4, K=10,
-                 T=1.0, steps=8192, capacity=1 << 23, rho=0.6, seed=BASE_SEED + 3),
+                 T=1.0, steps=8192, capacity=1 << 23, rho=0.6, cross=0.6, shared_prefix=512, prompt_len=512,
+                 seed=BASE_SEED + 3),
+    # tree search: every 64 steps half of the beams are pruned and the survivors are expanded (each beam
+    # continues from the context of a surviving parent; the table is shared and kept)
     "cfg5": dict(B=128, V=152064, dtype="bf16", N=128, D=10, caps=[8, 4, 2, 1], order_min=1, order_max=5, K=32,
-                 T=0.8, steps=16384, capacity=1 << 24, rho=0.5, seed=BASE_SEED + 4),
+                 T=0.8, steps=16384, capacity=1 << 24, rho=0.5, reorder_every=64, seed=BASE_SEED + 4),
 }
 
 
@@ -224,6 +229,51 @@ def peaked_tokens(seed, step, b, parent, depth, first_child, nchild, draft_tok, 
     return out
 
 
+def peaked_tokens_batch(seed, step, parent, depth, first_child, nchild, draft_tok, stream_next, V, max_peaks=4):
+    """peaked_tokens for all B trajectories at once (same results, array operations instead of loops over the
+    nodes of every trajectory): draft_tok [B, N]; stream_next [B, L] with L >= D + 1, padded with -1 where a
+    stream ends.  Returns int64 [B, N, 4] padded with -1, or None if the fixed number of fillers it draws did
+    not give enough distinct tokens."""
+    draft_tok = np.asarray(draft_tok, np.int64)
+    stream_next = np.asarray(stream_next, np.int64)
+    B, N = draft_tok.shape
+    L = stream_next.shape[1]
+    on_stream = np.zeros((B, N), bool)
+    on_stream[:, 0] = True
+    for u in range(1, N):            # parents come first in the numbering
+        d = int(depth[u])
+        nxt = stream_next[:, d - 1] if d - 1 < L else np.full(B, -1, np.int64)
+        on_stream[:, u] = on_stream[:, parent[u]] & (draft_tok[:, u] >= 0) & (nxt >= 0) & (draft_tok[:, u] == nxt)
+    bb = np.arange(B, dtype=np.uint64)[:, None]
+    uu = np.arange(N, dtype=np.uint64)[None, :]
+    r = 1 + (_h(seed, step, bb, uu, 77) % np.uint64(max_peaks)).astype(np.int64)          # [B, N]
+    maxc = int(nchild.max()) if N > 1 else 0
+    nfill = max_peaks + 6                                                               # spare fillers for duplicates
+    cand = np.full((B, N, 1 + maxc + nfill), -1, np.int64)
+    dn = np.minimum(depth, L - 1)
+    sn = stream_next[:, dn]                                                             # [B, N]: stream token after node u's path
+    cand[:, :, 0] = np.where(on_stream & (depth[None, :] < L) & (sn >= 0), sn, -1)
+    for j in range(maxc):
+        has = nchild > j
+        idx = np.where(has, first_child + j, 0)
+        cand[:, :, 1 + j] = np.where(has[None, :], draft_tok[:, idx], -1)
+    for j in range(nfill):
+        cand[:, :, 1 + maxc + j] = (_h(seed, step, bb, uu, 1000 + j) % np.uint64(V)).astype(np.int64)
+    # drop negative entries and later duplicates, keep the order, take the first r
+    C = cand.shape[2]
+    keep = cand >= 0
+    for i in range(1, C):
+        keep[:, :, i] &= ~((cand[:, :, :i] == cand[:, :, i:i + 1]) & (cand[:, :, :i] >= 0)).any(axis=2)
+    rank = np.cumsum(keep, axis=2) - 1                                                  # position among the kept
+    out = np.full((B, N, 4), -1, np.int64)
+    sel = keep & (rank < r[:, :, None])
+    bi, ui, ci = np.nonzero(sel)
+    out[bi, ui, rank[bi, ui, ci]] = cand[bi, ui, ci]
+    if not (np.sum(out >= 0, axis=2) == r).all():
+        return None                  # too many duplicate fillers (tiny vocabularies): the caller takes the loops
+    return out
+
+
 def logits_step(seed, step, B, N, V, dtype, peaks, sigma2=3.0, peak=8.0):
     """Verify-pass logits [B, N, V] of one step: i.i.d. N(0, sigma2) noise plus `peak` on the
     tokens listed in peaks[B, N, 4] (-1 = none).  dtype "f32" -> float32, "bf16" -> uint16
@@ -270,7 +320,29 @@ class Workload:
     def prompt(self, b):
         return self.streams[b, : self.prompt_len]
 
+    def reorder_map(self, step):
+        """Beam re-parenting due BEFORE the verification of `step` (tree-search workloads), or None: a seeded
+        half of the beams survives, beam b continues from the context of survivor b mod (B / 2) -- a map with
+        duplicates.  Each beam keeps its own exogenous stream, so copies of one parent diverge afterwards."""
+        every = self.cfg.get("reorder_every", 0)
+        if not every or step == 0 or step % every or self.B < 2:
+            return None
+        rng = np.random.Generator(np.random.Philox(key=[int(self.seed) & (2 ** 64 - 1), 0x7265 + int(step)]))
+        survivors = rng.permutation(self.B)[: self.B // 2]
+        return survivors[np.arange(self.B) % len(survivors)].astype(np.int32)
+
     def peaks(self, step, draft_tok):
+        L = self.D + 2
+        nxt = np.full((self.B, L), -1, np.int64)
+        for b in range(self.B):
+            t = self.streams[b, self.pos[b] + 1: self.pos[b] + 1 + L]
+            nxt[b, : len(t)] = t
+        out = peaked_tokens_batch(self.seed, step, self.parent, self.depth, self.first_child, self.nchild,
+                                  draft_tok, nxt, self.V, self.cfg.get("max_peaks", 4))
+        return out if out is not None else self.peaks_by_loops(step, draft_tok)
+
+    def peaks_by_loops(self, step, draft_tok):
+        """The same by the per-trajectory function (kept as the definition; tests compare the two)."""
         out = np.full((self.B, self.N, 4), -1, np.int64)
         for b in range(self.B):
             nxt = self.streams[b, self.pos[b] + 1: self.pos[b] + self.D + 3]

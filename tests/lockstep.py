@@ -18,6 +18,55 @@ def _logits_to_device(lg, dtype):
     return t.view(torch.bfloat16) if dtype == "bf16" else t
 
 
+def gpu_logits(w, step, draft_tok, gen, peak=8.0):
+    """Full-size steps: the workload's logits recipe (N(0, 3) noise, +8 on each row's peaked tokens) with the
+    noise drawn on the GPU, in slices of trajectories; returns (host uint16 bit patterns, device bf16 tensor).
+    Both implementations are fed the same bytes."""
+    assert w.dtype == "bf16"
+    peaks = torch.from_numpy(w.peaks(step, draft_tok)).cuda()
+    out = torch.empty((w.B, w.N, w.V), device="cuda", dtype=torch.bfloat16)
+    sl = max(1, (1 << 28) // (w.N * w.V))
+    for b0 in range(0, w.B, sl):
+        b1 = min(w.B, b0 + sl)
+        x = torch.randn((b1 - b0, w.N, w.V), generator=gen, device="cuda", dtype=torch.float32) * (3.0 ** 0.5)
+        pk = peaks[b0:b1]
+        x.scatter_add_(2, pk.clamp(min=0), torch.where(pk >= 0, peak, 0.0).to(torch.float32))
+        out[b0:b1] = x.to(torch.bfloat16)
+        del x
+    host = out.view(torch.int16).cpu().numpy().view(np.uint16)
+    return host, out
+
+
+def preload_tables(o, g, w, n_entries, seed=1):
+    """The same n_entries random entries (orders and contexts drawn at random, plausible top-K vectors) in both
+    tables before the run, so that the run works on a loaded table: displaced keys, probes past the home slot."""
+    r = np.random.default_rng(seed)
+    K, es = w.K, 16 + 8 * w.K
+    omin, omax = w.cfg["order_min"], w.cfg["order_max"]
+    buf = np.zeros(n_entries * es, np.uint8)
+    seen = set()
+    i = 0
+    while i < n_entries:
+        n = int(r.integers(omin, omax + 1))
+        toks = r.integers(w.V, size=n).astype(np.int32)
+        fp = oracle.fingerprint(toks)
+        if fp in seen:
+            continue
+        seen.add(fp)
+        ids = r.choice(w.V, size=K, replace=False).astype(np.int32)
+        mu = np.sort(r.dirichlet(np.full(K, 0.5)).astype(np.float32) * np.float32(0.9))[::-1].copy()
+        cnt = int(r.integers(1, 9))
+        assert o.table_put(toks, cnt, ids, mu) == 0
+        rec = buf[i * es:(i + 1) * es]
+        rec[0:8] = np.frombuffer(np.uint64(fp).tobytes(), np.uint8)
+        rec[8:12] = np.frombuffer(np.uint32(cnt).tobytes(), np.uint8)
+        rec[12:16] = np.frombuffer(np.uint32(n).tobytes(), np.uint8)
+        rec[16:16 + 4 * K] = np.frombuffer(ids.tobytes(), np.uint8)
+        rec[16 + 4 * K:] = np.frombuffer(mu.tobytes(), np.uint8)
+        i += 1
+    g.table_import(buf)
+
+
 def make_pair(w, capacity, max_probe=64, seed=None, order_min=None, order_max=None):
     cfg = w.cfg
     seed = cfg["seed"] ^ 0xABCDEF if seed is None else seed
@@ -67,10 +116,16 @@ def compare_rows(o_logits, w, g, rows=None, rtol=1e-5):
 
 
 def run_lockstep(w, steps, mode="separate", capacity=1 << 12, check_rows=True, table_every=1, forced=True,
-                 max_probe=64, verbose=False):
+                 max_probe=64, verbose=False, on_gpu=False, preload=0, sample_rows=None):
     """mode "separate": stand_verify / stand_update / stand_draft; mode "step": stand_step.
-    forced=True commits the workload's stream tokens (open-loop replay); False commits what was emitted."""
+    forced=True commits the workload's stream tokens (open-loop replay); False commits what was emitted.
+    on_gpu: the logits' noise is drawn on the GPU (full-size shapes); preload: random entries put into both
+    tables first; sample_rows: row-pass results are compared on these flat row indices only.
+    Workloads with beam re-parenting (reorder_map) copy the contexts on both sides when it is due."""
     o, g = make_pair(w, capacity, max_probe)
+    if preload:
+        preload_tables(o, g, w, preload)
+    gen = torch.Generator(device="cuda").manual_seed(int(w.seed) & 0x7FFFFFFF) if on_gpu else None
     if w.cfg.get("step_plan") is not None:
         g.set_step_plan(*w.cfg["step_plan"])          # GPU only: (mode, upper_depth, tail_groups, shuffle) of stand_step
     if w.cfg.get("filter_margin") is not None:
@@ -85,8 +140,21 @@ def run_lockstep(w, steps, mode="separate", capacity=1 << 12, check_rows=True, t
     assert np.array_equal(d_draft.cpu().numpy(), od), "draft 0 differs"
     info = dict(emitted=0, len_hist=np.zeros(w.W + 1, int), worst_rel=0.0, entries=0)
     for step in range(steps):
-        lg = w.logits(step, od)
-        dl = _logits_to_device(lg, w.dtype)
+        src = w.reorder_map(step)
+        if src is not None:
+            # beam copy: contexts move, the pending drafts are void; both sides draft again for this step
+            o.reorder(src)
+            g.reorder(src)
+            od = o.draft(step)
+            g.draft(step, d_draft)
+            torch.cuda.synchronize()
+            assert np.array_equal(d_draft.cpu().numpy(), od), "step %d: draft after the beam copy differs" % step
+            info["reorders"] = info.get("reorders", 0) + 1
+        if on_gpu:
+            lg, dl = gpu_logits(w, step, od, gen)
+        else:
+            lg = w.logits(step, od)
+            dl = _logits_to_device(lg, w.dtype)
         otok, onode, olen = o.verify(step, lg)
         W = w.W if hasattr(w, "W") else w.D + 1
         if forced:
@@ -124,7 +192,7 @@ def run_lockstep(w, steps, mode="separate", capacity=1 << 12, check_rows=True, t
         assert np.array_equal(gn, onode), "step %d: accepted nodes differ" % step
         assert np.array_equal(gt, otok), "step %d: emitted tokens differ\n%s\n%s" % (step, gt, otok)
         if check_rows:
-            info["worst_rel"] = max(info["worst_rel"], compare_rows(lg, w, g))
+            info["worst_rel"] = max(info["worst_rel"], compare_rows(lg, w, g, rows=sample_rows))
         assert np.array_equal(d_draft.cpu().numpy(), od), "step %d: next draft differs" % step
         if step % 4 == 0:
             gm, gp = g.tree_packing()

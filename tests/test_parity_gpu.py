@@ -357,6 +357,33 @@ def test_other_configs_at_their_row_shapes(gpu, name, over, steps):
     assert info["emitted"] >= steps * w.B
 
 
+@pytest.mark.parametrize("name,over,steps,kw", [
+    # configs[3] as stated: 64 trajectories from one 512-token prompt, 60 % cross-trajectory span reuse,
+    # V=128256, 48 nodes, K=10, T=1.0 (3072 rows, 788 MB of logits per step)
+    ("cfg4", dict(), 4, dict(capacity=1 << 16)),
+    # configs[4] as stated, with the beam re-parenting inside the run (every 2 steps instead of 64):
+    # 128 beams, 128 nodes, K=32, orders 1-5, T=0.8 (16384 rows, 4.98 GB of logits per step)
+    ("cfg5", dict(reorder_every=2), 4, dict(capacity=1 << 18)),
+    # configs[2] shape on a table that is 30 % full before the run (probes past the home slot, displaced keys)
+    ("cfg3", dict(), 4, dict(capacity=1 << 15, preload=9830)),
+])
+def test_configs_at_full_batch(gpu, name, over, steps, kw):
+    """The BASELINE configurations at their real batch sizes, whole stand_step calls in lock step with the oracle
+    (which evaluates only the rows its walk visits): tokens, nodes, lengths, next drafts, table export, counters;
+    row-pass results on a sample of rows."""
+    binding, lockstep = gpu
+    w = synth.Workload(name, run_steps=steps, **over)
+    rows = [0, 1, w.N - 1, w.N, w.B * w.N - 1] + [int(x) for x in np.random.default_rng(5).integers(0, w.B * w.N, 5)]
+    _say("%s at full batch: B=%d, %d rows of %d logits, %d steps %s" % (name, w.B, w.B * w.N, w.V, steps, kw))
+    info = lockstep.run_lockstep(w, steps, mode="step", forced=True, on_gpu=True, sample_rows=rows, **kw)
+    _say("  -> %s" % {k: v for k, v in info.items() if k != "node_counts"})
+    assert info["emitted"] >= steps * w.B and info["worst_rel"] < 1e-5
+    if name == "cfg5":
+        assert info["reorders"] >= 1
+    if name == "cfg4":
+        assert info["len_hist"][2:].sum() > 0      # shared contexts: drafts exist and some are accepted from step 1 on
+
+
 def test_tree_optimisation_on_the_initial_tree(gpu):
     """Paper Sec. 4.3 end to end at a small vocabulary: speculate on the 625-node initial tree
     (depth 20), count accepted nodes on both sides, keep the best 80 and speculate on that tree."""
