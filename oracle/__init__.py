@@ -123,6 +123,7 @@ def lib():
         L.so_verify.argtypes = [C.c_void_p, C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         L.so_update.argtypes = [C.c_void_p, C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         L.so_step.argtypes = [C.c_void_p, C.c_uint64, C.c_void_p] + [C.c_void_p] * 4
+        L.so_update_drops.argtypes = [C.c_void_p, C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         L.so_table_size.restype = C.c_int64
         L.so_table_size.argtypes = [C.c_void_p]
         L.so_table_export.restype = C.c_int64
@@ -378,11 +379,17 @@ class Oracle:
         lib().so_verify(self.h, step, _p(logits), _p(tok), _p(node), _p(ln))
         return tok, node, ln
 
-    def update(self, step, logits, commit_tok, commit_row, commit_len):
+    def update(self, step, logits, commit_tok, commit_row, commit_len, drops=None):
+        """drops: optional uint8 flags, one per record (b, position or node, order): these records are dropped and
+        all others applied (the capacity model is then off), see so_update_drops."""
         self._check_logits(logits)
         ct, cr, cl = _i32(commit_tok), _i32(commit_row), _i32(commit_len)
         assert ct.shape == (self.B, self.W) and cr.shape == (self.B, self.W) and cl.shape == (self.B,)
-        lib().so_update(self.h, step, _p(logits), _p(ct), _p(cr), _p(cl))
+        if drops is None:
+            lib().so_update(self.h, step, _p(logits), _p(ct), _p(cr), _p(cl))
+        else:
+            d = np.ascontiguousarray(drops, dtype=np.uint8).reshape(-1)
+            lib().so_update_drops(self.h, step, _p(logits), _p(ct), _p(cr), _p(cl), _p(d))
 
     def step(self, step, logits):
         self._check_logits(logits)

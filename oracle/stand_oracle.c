@@ -626,6 +626,7 @@ typedef struct so_handle {
     int32_t *draft_qid;   /* [B][N][K] */
     float *draft_qmu;     /* [B][N][K] */
     uint64_t *node_count; /* [N] how often each tree node lay on an accepted path (Sec. 4.3) */
+    const uint8_t *ext_drop; /* during so_update_drops: which records of this update are dropped (see there) */
     so_stats st;
 } so_handle;
 
@@ -757,12 +758,14 @@ static int slot_claim(so_handle *h, uint64_t fp)
     return 0;
 }
 
-static void table_merge(so_handle *h, int n, const int32_t *tok, const int32_t *obs_ids, const float *obs_p)
+static void table_merge(so_handle *h, int64_t rec, int n, const int32_t *tok, const int32_t *obs_ids, const float *obs_p)
 {
+    if (h->ext_drop && h->ext_drop[rec]) { h->st.drops++; return; } /* dropped by decree, see so_update_drops */
     int64_t e = table_find(h, n, tok);
     uint64_t fp = so_fingerprint(n, tok);
     if (e < 0) {
-        int sc = slot_claim(h, fp);
+        /* with the drops given from outside the capacity model is off: every other record is applied */
+        int sc = h->ext_drop ? 1 : slot_claim(h, fp);
         if (sc == 0) { h->st.drops++; return; }
         if (sc == 2) h->st.fp_collisions++; /* a different tuple with the same fingerprint */
         if (h->n_ent == h->cap_ent) {
@@ -1000,6 +1003,7 @@ void so_update(so_handle *h, uint64_t step, const void *logits, const int32_t *c
 {
     (void)step;
     int K = h->K, V = h->V, W = h->D + 1;
+    int NO = h->cfg.order_max - h->cfg.order_min + 1; /* records are numbered (b, position or node, order) */
     int32_t obs_id[SO_MAX_K];
     float obs_p[SO_MAX_K];
     if (h->cfg.update_mode == SO_UPDATE_ALL_NODES) {
@@ -1023,7 +1027,7 @@ void so_update(so_handle *h, uint64_t step, const void *logits, const int32_t *c
                         int64_t pos = base_len + d - n + i; /* position in context ++ path */
                         key[i] = pos < base_len ? h->ctx[b][pos] : path_tok[pos - base_len];
                     }
-                    table_merge(h, n, key, obs_id, obs_p);
+                    table_merge(h, ((int64_t)b * N + u) * NO + (n - h->cfg.order_min), n, key, obs_id, obs_p);
                 }
             }
         }
@@ -1041,12 +1045,27 @@ void so_update(so_handle *h, uint64_t step, const void *logits, const int32_t *c
                     int64_t pos = base_len + j - n + i; /* position in context ++ commit */
                     key[i] = pos < base_len ? h->ctx[b][pos] : commit_tok[(int64_t)b * W + (pos - base_len)];
                 }
-                table_merge(h, n, key, obs_id, obs_p);
+                table_merge(h, ((int64_t)b * W + j) * NO + (n - h->cfg.order_min), n, key, obs_id, obs_p);
             }
         }
     }
     for (int b = 0; b < h->B; ++b)
         for (int j = 0; j < commit_len[b]; ++j) ctx_push(h, b, commit_tok[(int64_t)b * W + j]);
+}
+
+/* Update with the dropped records named from outside.  Which updates a full table drops depends on the order
+ * in which the keys of one step claim the last free slots (a reading of this build: the paper's table is an
+ * unbounded dictionary, Sec. 4.1), so a second implementation that claims in another order drops other
+ * records, validly.  Here drop[r] != 0 says that record r -- numbered (b * R + position) * orders + (n -
+ * order_min), R = depth + 1, or the number of tree nodes when every node's row is merged -- is dropped and
+ * counted; every other record is applied whatever the capacity model says.  What is stored afterwards is
+ * the recount of the applied updates, which a second implementation must reproduce. */
+void so_update_drops(so_handle *h, uint64_t step, const void *logits, const int32_t *commit_tok,
+                     const int32_t *commit_row, const int32_t *commit_len, const uint8_t *drop)
+{
+    h->ext_drop = drop;
+    so_update(h, step, logits, commit_tok, commit_row, commit_len);
+    h->ext_drop = NULL;
 }
 
 /* One speculation step: verify the pending tree, merge the accepted path, draft the next tree. */

@@ -956,3 +956,37 @@ def test_near_threshold_counts_tests_within_1e6_of_the_acceptance_ratio():
         assert abs(float(got) / w_t - (om + delta)) < 2e-7            # the row really gives that ratio
         o.verify(0, lg)
         assert o.stats().accept_tests == 1 and o.stats().near_threshold == near
+
+
+def test_update_with_named_drops_stores_the_recount_of_the_applied_records():
+    """so_update_drops: the records flagged from outside are dropped and counted, all others are applied even where
+    the capacity model would have refused them; the table is the dictionary recount of the applied records."""
+    V, K, T = 8, 8, 0.6
+    o = oracle.Oracle(V, 1, 1, 2, K, np.array([-1, 0, 0, 1], np.int32), T, 16, 2, 9, oracle.DT_F32)   # tiny table
+    r = np.random.default_rng(3)
+    ctx = [int(x) for x in r.integers(V, size=2)]
+    o.set_context(0, ctx)
+    applied, n_drop, n_rec = {}, 0, 0
+    for step in range(50):
+        lg = r.standard_normal((1, o.N, V)).astype(np.float32)
+        n = int(r.integers(1, o.W + 1))
+        toks, rows = r.integers(V, size=n), r.integers(o.N, size=n)
+        ct = np.full((1, o.W), -1, np.int32)
+        cr = np.full((1, o.W), -1, np.int32)
+        ct[0, :n], cr[0, :n] = toks, rows
+        drops = (r.random((1, o.W, 2)) < 0.3).astype(np.uint8)
+        for j in range(n):
+            for oi, order in enumerate((1, 2)):
+                n_rec += 1
+                if drops[0, j, oi]:
+                    n_drop += 1
+                    continue
+                acc = applied.setdefault(tuple(ctx[-order:]), [0, np.zeros(V)])
+                acc[0] += 1
+                acc[1] += _softmax64(lg[0, rows[j]], T)
+            ctx.append(int(toks[j]))
+        o.update(step, lg, ct, cr, np.array([n], np.int32), drops=drops)
+    st = o.stats()
+    assert len(applied) > 16                      # more keys than the table has slots: the capacity model is off
+    assert st.drops == n_drop and st.inserts == len(applied) and st.inserts + st.merges + st.drops == n_rec
+    _check_stored(o, applied)
