@@ -255,6 +255,14 @@ int stand_table_import(stand_handle *h, const void *host_buf, uint64_t bytes);
  * and returns the context length through *len_out.  Synchronises `stream`. */
 int stand_get_context(stand_handle *h, int32_t b, int32_t *host_tail, int32_t n, int64_t *len_out, void *stream);
 
+/* Table slot of every merge record of the last stand_update / stand_step, for inspection: host_slots
+ * [max_batch * R * orders] with R = depth + 1 (or tree_nodes with STAND_UPDATE_ALL_NODES), record
+ * (b, position or node, order) at index (b * R + position) * orders + (order - order_min); -1 for a record
+ * that did not exist in that update (position beyond the committed tokens, context shorter than the order,
+ * undrafted node) AND for a record that was dropped because no slot was in reach (paper Sec. 4.1 has an
+ * unbounded table; see max_probe).  Synchronises the device. */
+int stand_get_record_slots(stand_handle *h, int64_t *host_slots);
+
 /* Counters since creation.  Synchronises the device. */
 int stand_get_stats(stand_handle *h, stand_stats *out);
 
@@ -263,11 +271,15 @@ int stand_get_stats(stand_handle *h, stand_stats *out);
  * stand_verify / stand_step is bracketed by a pair of HIP events on the caller's stream.
  * stand_profile_end synchronises the device, returns the summed event time in milliseconds
  * and the number of launches measured, and switches the timing off. */
-/* Accept tests are first decided with a fast normaliser of the row whose relative error is below
- * 5e-5; a test whose margin is smaller than the assumed error is decided again with the exact
- * normaliser (counted in stand_stats.near_threshold), so results never depend on this value.
- * `margin` in [5e-5, 1] replaces the assumed error for later calls: a larger value only sends
- * more tests to the exact path (1 sends practically all of them).  STAND_EINVAL outside the range. */
+/* Accept tests are first decided with a fast normaliser of the row.  Its relative error is bounded from
+ * the shape of the launch (2^-23 per addition a lane performs: vocab / (8 or 4 elements * 64 lanes *
+ * waves per row), plus the combination of lanes and waves) and never assumed below 5e-5.  A test whose margin
+ * is smaller than the assumed error is decided again with the exact normaliser (counted in
+ * stand_stats.near_threshold), and every node on an accepted path is replayed with exact
+ * probabilities afterwards (stand_stats.filter_mismatch counts disagreements; it must stay 0), so
+ * results never depend on this value.  `margin` in [5e-5, 1] replaces the 5e-5 floor for later calls:
+ * a larger value only sends more tests to the exact path (1 sends practically all of them).
+ * STAND_EINVAL outside the range. */
 int stand_set_filter_margin(stand_handle *h, float margin);
 
 int stand_profile_begin(stand_handle *h, int32_t max_launches);

@@ -27,6 +27,7 @@ EXPORTED = [
     "stand_tree_initial", "stand_tree_select", "stand_get_node_counts", "stand_reset_node_counts",
     "stand_tree_packing", "stand_verify_static", "stand_static_scratch_need",
     "stand_set_step_plan", "stand_set_wait_limit", "stand_step_timeline", "stand_step_is_one_launch",
+    "stand_get_record_slots",
 ]
 
 
@@ -84,6 +85,7 @@ def load_library():
     lib.stand_tree_initial.argtypes = [C.c_int32, i32p, C.c_int32, C.POINTER(C.c_int32)]
     lib.stand_tree_select.argtypes = [i32p, vp, C.c_int32, C.c_int32, i32p, i32p]
     lib.stand_get_node_counts.argtypes = [vp, vp]
+    lib.stand_get_record_slots.argtypes = [vp, vp]
     lib.stand_tree_packing.argtypes = [vp, vp, vp, vp]
     lib.stand_reset_node_counts.argtypes = [vp]
     lib.stand_strerror.restype = C.c_char_p
@@ -312,6 +314,12 @@ class Stand:
         pos = torch.empty((self.B, self.N), dtype=torch.int64, device=self.device)
         _check(lib().stand_tree_packing(self.h, _dptr(mask), _dptr(pos), _stream_ptr()), self.h)
         return mask, pos
+
+    def record_slots(self, rows_per_trajectory, orders):
+        """Slot of every merge record of the last update, [B, R, orders] (-1: no such record, or dropped)."""
+        out = np.zeros(self.B * rows_per_trajectory * orders, np.int64)
+        _check(lib().stand_get_record_slots(self.h, out.ctypes.data), self.h)
+        return out.reshape(self.B, rows_per_trajectory, orders)
 
     def node_counts(self):
         out = np.zeros(self.N, np.uint64)

@@ -347,6 +347,21 @@ __device__ __forceinline__ void finish_row(const PathArgs &a, FinishShared &sh, 
                 st_agent(&a.obs_idx[((size_t)b * a.R + j) * a.K + lane], o_idx);
                 st_agent(&a.obs_p[((size_t)b * a.R + j) * a.K + lane], exact_exp2(scaled_offset(o_l, m, a.c)) / s);
             }
+            if (a.mode == 0 && a.draft_has[row] > 0) {
+                // self-check of the row pass's decision at this node (taken with the fast normaliser and its
+                // error bound): the accept tests again with exact probabilities must name the same child
+                const int c_n = a.draft_has[row], c_fc = a.tree.first_child[node];
+                int32_t c_id = -1, c_ch = -1;
+                float c_mu = 0.0f, c_l = 0.0f;
+                if (lane < a.K) { c_id = a.draft_qid[(size_t)row * a.K + lane]; c_mu = a.draft_qmu[(size_t)row * a.K + lane]; }
+                if (lane < c_n && lane < kMaxK && c_fc >= 0 && c_fc + lane < a.N) c_ch = a.draft_tok[(size_t)b * a.N + c_fc + lane];
+                if ((uint32_t)c_id >= (uint32_t)a.V) { c_id = -1; c_mu = 0.0f; }  // never index outside the row
+                else c_l = load_scalar<DT>(rowp, c_id);
+                const float c_e = c_id >= 0 ? exact_exp2(scaled_offset(c_l, m, a.c)) : 0.0f;
+                const NodeResult nr = wave_node_outcome(lane, a.K, c_id, c_mu, c_e / s, c_n, c_ch, a.seed, (uint32_t)b, a.step, c_fc,
+                                                        false, 0.0f, a.onehot);
+                if (lane == 0 && nr.accepted != ld_agent(&a.outcome[row])) atomicAdd(&a.stats[kStatMismatch], 1ull);
+            }
             return;
         }
 

@@ -249,13 +249,22 @@ __device__ __forceinline__ WavePartial wave_row_stream(const void *rowp, int V, 
     st.cnt = 0;
     set_theta(st, 0ull);
     float m_ref = -3.402823466e38f, nb = 0.0f, s_t = 0.0f;  // m_ref, nb wave-uniform
+    // The exponent of a term is formed as fma(l, c, nb) with nb = -m_ref * c rounded to binary32.  That rounding
+    // shifts EVERY exponent by the same dlt = (-m_ref * c) - nb (exact; a fused multiply-add recovers it), i.e.
+    // the whole sum is off by the factor 2^dlt -- negligible for ordinary logits, 1e-4 for |m_ref| c in the
+    // thousands (large logits at a low temperature).  The sum is kept in those shifted units and corrected where
+    // the reference changes and at the end, in the rare path only.
+    float dlt = 0.0f;
 
     auto raise_reference = [&](float cm) {
         // some lane saw a value above the reference: move the reference to the wave's maximum
         const float nm = uniform_f32(fmaxf(wave_max_f32(cm), m_ref));
-        s_t *= fast_exp2((m_ref - nm) * c);
+        const float nb_new = -nm * c;
+        const float dlt_new = __builtin_fmaf(-nm, c, -nb_new);
+        s_t *= fast_exp2((m_ref - nm) * c + (dlt - dlt_new));
         m_ref = nm;
-        nb = -nm * c;
+        nb = nb_new;
+        dlt = dlt_new;
     };
     // Loads are issued unconditionally (indices clamped to the last vector) so that the number of
     // loads in flight is the same on every path and only the oldest batch is waited for.
@@ -355,7 +364,7 @@ __device__ __forceinline__ WavePartial wave_row_stream(const void *rowp, int V, 
     for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off);
     WavePartial out;
     out.m_ref = m_ref;
-    out.s = s;
+    out.s = s * fast_exp2(dlt);
     out.cnt = st.cnt;
     return out;
 }
@@ -500,7 +509,7 @@ struct RowPassArgs {
     int32_t *outcome;           // [B*N] accepted child rank or -1
     unsigned long long *stats;
     bool onehot;                // deterministic drafting: one-hot proposals in the accept tests
-    float eps;                  // relative error assumed for the fast normaliser (>= kFastEps)
+    float eps;                  // relative error assumed for the fast normaliser from its additions (>= kFastEps)
 };
 
 // Shared memory of one row's workgroup of WPR waves.
@@ -553,8 +562,13 @@ __device__ __forceinline__ void row_role(const RowPassArgs &a, int row, RowShare
             return;
         }
         const float e = (lane < a.K && my_id >= 0) ? exact_exp2(scaled_offset(my_l, m, a.c)) : 0.0f;
+        // Relative error assumed for s: the part that grows with the terms a lane adds (a.eps, from the host);
+        // the offset every exponent shares is corrected in the streaming loop, what is left of it (the
+        // rounding of each term's own argument, relative to that argument, and of the waves' combination)
+        // is covered by a term in |m| c that stays far below a.eps for ordinary inputs.
+        const float eps_row = a.eps + 1e-9f * fabsf(m) * a.c;
         NodeResult nr = wave_node_outcome(lane, a.K, my_id, my_mu, e / s, nch, ch, a.seed, (uint32_t)b, a.step, fc,
-                                          true, a.eps, a.onehot);
+                                          true, eps_row, a.onehot);
         if (nr.near) {
             // a test fell inside the error bound of the fast normaliser: decide with the exact one
             const unsigned long long S = wave_row_exact_sum<DT>(rowp, a.V, m, a.c, lane);

@@ -355,7 +355,19 @@ extern "C" int stand_reorder(stand_handle *h, const int32_t *host_src_of, void *
 }
 
 // ---- launches ----------------------------------------------------------------------------------
-static RowPassArgs make_row_args(const stand_handle *h, const VerifyScratch &vs, uint64_t step, const void *d_logits)
+// Relative error assumed for the row pass's fast normaliser when `wpr` waves share a row: every lane adds
+// ceil(vectors / (64 wpr)) vector sums of EPV terms in binary32, then lanes and waves are combined; each
+// addition may lose 2^-24 of the running sum (the worst case, all roundings one way), doubled for the hardware
+// exponential and the rescaling of partial sums.  Never below the caller's margin (default 5e-5).
+static float fast_eps(const stand_handle *h, int wpr)
+{
+    const int epv = h->cfg.logits_dtype == STAND_BF16 ? 8 : 4;
+    const double per_lane = std::ceil((double)h->V / epv / (64.0 * wpr)) + epv + 6 + wpr + 16;
+    const double bound = 2.0 * per_lane * 5.9604644775390625e-08;
+    return (float)std::max((double)h->filter_margin, bound);
+}
+
+static RowPassArgs make_row_args(const stand_handle *h, const VerifyScratch &vs, uint64_t step, const void *d_logits, int wpr)
 {
     RowPassArgs a;
     a.logits = d_logits; a.B = h->B; a.N = h->N; a.V = h->V; a.K = h->K; a.c = h->c;
@@ -364,13 +376,14 @@ static RowPassArgs make_row_args(const stand_handle *h, const VerifyScratch &vs,
     a.row_m = vs.row_m; a.row_s = vs.row_s; a.top_idx = vs.top_idx; a.top_l = vs.top_l; a.top_p = vs.top_p;
     a.outcome = vs.outcome; a.stats = h->stats;
     a.onehot = h->cfg.draft_mode == STAND_DRAFT_DETERMINISTIC;
-    a.eps = h->filter_margin;
+    a.eps = fast_eps(h, wpr);
     return a;
 }
 
 static int launch_row_pass(stand_handle *h, const VerifyScratch &vs, uint64_t step, const void *d_logits, hipStream_t s)
 {
-    RowPassArgs a = make_row_args(h, vs, step, d_logits);
+    const int rows_all = h->B * h->N;
+    RowPassArgs a = make_row_args(h, vs, step, d_logits, rows_all <= kRowsFew ? kRowWPRFewRows : kRowWPR);
     const int rows = h->B * h->N;
     const bool few = rows <= kRowsFew;  // one workgroup per row; more waves per row when rows are few
     const bool bf16 = h->cfg.logits_dtype == STAND_BF16;
@@ -618,7 +631,7 @@ static int launch_step_fused(stand_handle *h, uint64_t step, const void *d_logit
 {
     const bool bf16 = h->cfg.logits_dtype == STAND_BF16;
     StepArgs A;
-    A.row = make_row_args(h, h->vs, step, d_logits);
+    A.row = make_row_args(h, h->vs, step, d_logits, kStepWPR);
     A.G = step_tail_groups(h);
     // one wave sums one segment: a few rounds of loads per lane; a row has at most as many segments as the
     // trajectory has summing waves (all waves of its tail workgroups but one)
@@ -914,6 +927,15 @@ extern "C" int stand_profile_end(stand_handle *h, double *row_pass_ms_total, int
     *launches = (int32_t)h->ev_used;
     h->profiling = false;
     h->ev_used = 0;
+    return STAND_OK;
+}
+
+extern "C" int stand_get_record_slots(stand_handle *h, int64_t *host_slots)
+{
+    if (!h || !host_slots) return STAND_EINVAL;
+    HIP_TRY(h, hipSetDevice(h->cfg.device));
+    HIP_TRY(h, hipDeviceSynchronize());
+    HIP_TRY(h, hipMemcpy(host_slots, h->rec_slot, sizeof(int64_t) * (size_t)h->B * h->R * h->NO, hipMemcpyDeviceToHost));
     return STAND_OK;
 }
 

@@ -274,10 +274,11 @@ def peaked_tokens_batch(seed, step, parent, depth, first_child, nchild, draft_to
     return out
 
 
-def logits_step(seed, step, B, N, V, dtype, peaks, sigma2=3.0, peak=8.0):
+def logits_step(seed, step, B, N, V, dtype, peaks, sigma2=3.0, peak=8.0, scale=1.0):
     """Verify-pass logits [B, N, V] of one step: i.i.d. N(0, sigma2) noise plus `peak` on the
-    tokens listed in peaks[B, N, 4] (-1 = none).  dtype "f32" -> float32, "bf16" -> uint16
-    bit patterns (rounded to nearest even)."""
+    tokens listed in peaks[B, N, 4] (-1 = none), all multiplied by `scale` (1: the recipe; larger values
+    give the large logits of stress cases).  dtype "f32" -> float32, "bf16" -> uint16 bit patterns
+    (rounded to nearest even)."""
     rng = np.random.Generator(np.random.Philox(key=[int(seed) & (2 ** 64 - 1), int(step)]))
     x = rng.standard_normal((B, N, V), dtype=np.float32)
     x *= np.float32(np.sqrt(sigma2))
@@ -286,6 +287,8 @@ def logits_step(seed, step, B, N, V, dtype, peaks, sigma2=3.0, peak=8.0):
             for t in peaks[b][u]:
                 if t >= 0:
                     x[b, u, int(t)] += np.float32(peak)
+    if scale != 1.0:
+        x *= np.float32(scale)
     if dtype == "f32":
         return x
     return f32_to_bf16_bits(x)
@@ -351,7 +354,8 @@ class Workload:
         return out
 
     def logits(self, step, draft_tok):
-        return logits_step(self.seed, step, self.B, self.N, self.V, self.dtype, self.peaks(step, draft_tok))
+        return logits_step(self.seed, step, self.B, self.N, self.V, self.dtype, self.peaks(step, draft_tok),
+                           scale=self.cfg.get("logit_scale", 1.0))
 
     def commit(self, out_len):
         """Tokens to commit after a verify that emitted out_len[b] tokens: the stream's next ones."""

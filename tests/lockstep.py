@@ -31,6 +31,7 @@ def gpu_logits(w, step, draft_tok, gen, peak=8.0):
         x = torch.randn((b1 - b0, w.N, w.V), generator=gen, device="cuda", dtype=torch.float32) * (3.0 ** 0.5)
         pk = peaks[b0:b1]
         x.scatter_add_(2, pk.clamp(min=0), torch.where(pk >= 0, peak, 0.0).to(torch.float32))
+        x.mul_(float(w.cfg.get("logit_scale", 1.0)))
         out[b0:b1] = x.to(torch.bfloat16)
         del x
     host = out.view(torch.int16).cpu().numpy().view(np.uint16)
