@@ -439,44 +439,43 @@ def parse_table_export(buf, K):
 
 # ---- data-driven draft tree (Sec. 4.3, App. "Initial tree for optimization") -----------------------
 def tree_initial(levels=20):
-    """The large initial tree of the tree optimisation (Alg. 1 of the appendix), as parent[].
+    """The large initial tree of the tree optimisation (appendix "Initial tree for optimization", Alg. 1), as parent[].
 
-    Built level by level from the root.  A node's fan-out depends on its depth and on its rank
-    among its siblings: the root gets 8 children; a depth-1 node of rank r gets max(8 - 2r, 1);
-    a deeper node gets ceil((s - 1) / (0.7 r + 1)) where s is the number of its siblings
-    (itself included), but at least 2 at depths 2 and 3; the first node of every level gets at
-    least 3.  Nodes are numbered in creation order, which is breadth first with the children of
-    a node contiguous in rank order.  levels = 20 gives the paper's 625 nodes of depth 20.
+    Level by level, on whole levels at once.  A level is described by two arrays: each node's rank r among its
+    siblings and its number of siblings s (itself included).  Its fan-outs follow from them -- depth 0: 8;
+    depth 1: max(8 - 2r, 1); deeper: ceil((s - 1) / (0.7 r + 1)), at least 2 at depths 2 and 3; the first node of
+    a level at least 3 -- and the next level is their expansion: fan-out f contributes ranks 0..f-1 with s = f,
+    and the parents' ids repeat f times.  Ids are handed out level after level, so the numbering is breadth first
+    with the children of a node contiguous in rank order.  levels = 20 gives the paper's 625 nodes of depth 20.
     """
-    parent, depth, rank, fanout = [-1], [0], [0], [0]
-    level = [0]
-    for _ in range(levels):
-        nxt = []
-        for pos, u in enumerate(level):
-            if depth[u] == 0:
-                n = 8
-            elif depth[u] == 1:
-                n = max(8 - 2 * rank[u], 1)
-            else:
-                siblings = fanout[parent[u]]
-                n = int(np.ceil((siblings - 1) / (rank[u] * 0.7 + 1)))
-                n = max(n, 2 if depth[u] <= 3 else 0)
-            if pos == 0:
-                n = max(n, 3)
-            fanout[u] = n
-            for r in range(n):
-                parent.append(u)
-                depth.append(depth[u] + 1)
-                rank.append(r)
-                fanout.append(0)
-                nxt.append(len(parent) - 1)
-        level = nxt
-    return np.asarray(parent, np.int32)
+    parent = [np.array([-1], np.int64)]
+    rank, sibs = np.zeros(1, np.int64), np.ones(1, np.int64)
+    first_id = 0
+    for depth in range(levels):
+        if depth == 0:
+            fan = np.full(1, 8, np.int64)
+        elif depth == 1:
+            fan = np.maximum(8 - 2 * rank, 1)
+        else:
+            fan = np.ceil((sibs - 1) / (0.7 * rank + 1.0)).astype(np.int64)
+            if depth <= 3:
+                fan = np.maximum(fan, 2)
+        fan[0] = max(int(fan[0]), 3)
+        total = int(fan.sum())
+        if total == 0:
+            break
+        ids = first_id + np.arange(len(fan), dtype=np.int64)
+        parent.append(np.repeat(ids, fan))
+        starts = np.repeat(np.cumsum(fan) - fan, fan)
+        rank = np.arange(total, dtype=np.int64) - starts
+        sibs = np.repeat(fan, fan)
+        first_id += len(fan)
+    return np.concatenate(parent).astype(np.int32)
 
 
 def tree_select(parent, counts, n_keep):
-    """Keeps the n_keep most often accepted nodes of a tree and re-packs them (Sec. 4.3: "select
-    the top-80 most effective nodes and reorganize them into a compact tree structure").
+    """Keeps the n_keep most often accepted nodes of a tree and re-packs them into a tree of that size
+    (paper Sec. 4.3; there n_keep = 80).
 
     A node can only be used if all its ancestors are, so a node counts as often as the least
     counted node on its way to the root; nodes are ranked by (that count descending, depth

@@ -962,36 +962,41 @@ extern "C" int stand_tree_initial(int32_t levels, int32_t *host_parent_out, int3
 {
     if (levels < 1 || levels > STAND_MAX_DEPTH || !n_out || capacity < 0 || (capacity > 0 && !host_parent_out))
         return STAND_EINVAL;
-    // Nodes of the current level are expanded left to right; `first`/`count` describe a level as
-    // a range of ids because ids are handed out in creation order.
-    struct Node { int32_t parent, depth, rank, fanout; };
-    std::vector<Node> nodes;
-    nodes.push_back(Node{-1, 0, 0, 0});
-    size_t first = 0, count = 1;
-    for (int32_t lv = 0; lv < levels; ++lv) {
-        const size_t next_first = nodes.size();
-        for (size_t pos = 0; pos < count; ++pos) {
-            const size_t u = first + pos;
-            const Node nd = nodes[u];
-            int32_t n;
-            if (nd.depth == 0) n = 8;
-            else if (nd.depth == 1) n = std::max(8 - 2 * nd.rank, 1);
-            else {
-                const double q = (double)(nodes[(size_t)nd.parent].fanout - 1) / ((double)nd.rank * 0.7 + 1.0);
-                n = std::max((int32_t)std::ceil(q), nd.depth <= 3 ? 2 : 0);
-            }
-            if (pos == 0) n = std::max(n, 3);
-            nodes[u].fanout = n;
-            for (int32_t r = 0; r < n; ++r) nodes.push_back(Node{(int32_t)u, nd.depth + 1, r, 0});
+    // One level at a time, as arrays: rank[i] of node i among its siblings and sibs[i], the size of its
+    // sibling group.  The level's fan-outs are a function of (depth, rank, sibs); the next level is their
+    // expansion, and the parents of its nodes are this level's ids repeated fan-out times.
+    std::vector<int32_t> parents(1, -1), rank(1, 0), sibs(1, 1), fan;
+    int32_t level_first = 0;  // id of the level's first node
+    for (int32_t depth = 0; depth < levels; ++depth) {
+        const size_t n = rank.size();
+        fan.assign(n, 0);
+        for (size_t i = 0; i < n; ++i) {
+            int32_t f;
+            if (depth == 0) f = 8;
+            else if (depth == 1) f = std::max(8 - 2 * rank[i], 1);
+            else f = std::max((int32_t)std::ceil((double)(sibs[i] - 1) / (0.7 * (double)rank[i] + 1.0)), depth <= 3 ? 2 : 0);
+            fan[i] = f;
         }
-        first = next_first;
-        count = nodes.size() - next_first;
-        if (count == 0) break;
+        fan[0] = std::max(fan[0], 3);
+        size_t total = 0;
+        for (size_t i = 0; i < n; ++i) total += (size_t)fan[i];
+        if (total == 0) break;
+        std::vector<int32_t> next_rank, next_sibs;
+        next_rank.reserve(total);
+        next_sibs.reserve(total);
+        for (size_t i = 0; i < n; ++i) {
+            parents.insert(parents.end(), (size_t)fan[i], level_first + (int32_t)i);
+            for (int32_t r = 0; r < fan[i]; ++r) next_rank.push_back(r);
+            next_sibs.insert(next_sibs.end(), (size_t)fan[i], fan[i]);
+        }
+        level_first += (int32_t)n;
+        rank.swap(next_rank);
+        sibs.swap(next_sibs);
     }
-    *n_out = (int32_t)nodes.size();
+    *n_out = (int32_t)parents.size();
     if (capacity > 0) {
-        if ((size_t)capacity < nodes.size()) return STAND_EINVAL;
-        for (size_t u = 0; u < nodes.size(); ++u) host_parent_out[u] = nodes[u].parent;
+        if ((size_t)capacity < parents.size()) return STAND_EINVAL;
+        std::copy(parents.begin(), parents.end(), host_parent_out);
     }
     return STAND_OK;
 }
