@@ -68,7 +68,8 @@ extern "C" {
                                     /* of each child is one-hot, so it is accepted with probability r(x) */
 
 /* How stand_step issues its work (results are the same; see stand_set_step_plan). */
-#define STAND_STEP_AUTO 0   /* one launch where it pays (more than 768 rows, accepted-path updates), else serial */
+#define STAND_STEP_AUTO 0   /* one launch where it pays (more than 768 rows, accepted-path updates, accepted paths */
+                            /* that seldom reach below upper_depth: watched while running), else serial         */
 #define STAND_STEP_SERIAL 1 /* five dependent launches: rows, exact sums, finish + claims, apply, draft           */
 #define STAND_STEP_FUSED 2  /* one launch: the dependent tail runs beside the rows that are still streaming      */
 
@@ -114,6 +115,8 @@ typedef struct {
                                         /* (must stay 0; a self-check of the error bound)              */
     uint64_t wait_expired;              /* one-launch step: bounded waits that ran out (must stay 0;   */
                                         /* the outputs of that step are void, see stand_set_wait_limit) */
+    uint64_t late_paths;                /* accepted paths that reached below tree depth upper_depth    */
+                                        /* (stand_set_step_plan): what STAND_STEP_AUTO watches          */
 } stand_stats;
 
 /* Creates a handle: validates the configuration, copies the tree, allocates and clears the
@@ -202,7 +205,11 @@ int stand_step(stand_handle *h, uint64_t step, const void *d_logits, int32_t *d_
 /* How stand_step is issued (paper: the step is verify -> update -> draft, Sec. 3.2, 4.1, 4.2; this only
  * chooses the launch structure, every output is the same bit for bit).
  *   mode         STAND_STEP_AUTO / SERIAL / FUSED.  FUSED is refused (STAND_EINVAL) with
- *                STAND_UPDATE_ALL_NODES, whose records need every drafted row.
+ *                STAND_UPDATE_ALL_NODES, whose records need every drafted row.  AUTO copies one counter
+ *                (stand_stats.late_paths) to pinned host memory every 32 steps, without waiting for it,
+ *                and takes the serial launches while more than 0.4 paths per step reach below
+ *                upper_depth (they would wait for rows that stream late), the one launch again below
+ *                0.25; no such copy is made while the stream is being captured, or in the other modes.
  *   upper_depth  FUSED: the rows of tree nodes up to this depth take the first places in the launch
  *                (default 2: paths that end above depth 3 never wait for a late row; deeper paths are
  *                still correct, the tail then waits for the rows it needs).  0 .. STAND_MAX_DEPTH.

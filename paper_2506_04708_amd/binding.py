@@ -46,7 +46,7 @@ class Stats(C.Structure):
         ("hits", C.c_uint64 * (MAX_ORDER + 1)), ("misses", C.c_uint64),
         ("inserts", C.c_uint64), ("merges", C.c_uint64), ("drops", C.c_uint64),
         ("near_threshold", C.c_uint64), ("tokens_emitted", C.c_uint64), ("accept_tests", C.c_uint64),
-        ("filter_mismatch", C.c_uint64), ("wait_expired", C.c_uint64),
+        ("filter_mismatch", C.c_uint64), ("wait_expired", C.c_uint64), ("late_paths", C.c_uint64),
     ]
 
 

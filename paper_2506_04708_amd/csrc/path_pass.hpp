@@ -53,6 +53,7 @@ struct PathArgs {
     unsigned long long *stats;
     unsigned long long *node_count;  // [N] verifications in which a node lay on the accepted path (mode 0)
     bool onehot;                     // deterministic drafting: one-hot proposals in the accept tests
+    int late_len;                    // paths longer than this count as late (kStatLatePaths)
 };
 
 // Walks the accepted path of trajectory b and leaves it in path[0..len) (shared memory).  Must be
@@ -179,6 +180,7 @@ __global__ __launch_bounds__(kPathThreads) void path_exact_kernel(PathArgs a)
             for (int q = 0; q + 1 < len; ++q) tests += (unsigned long long)(stage.oc[path[q]] + 1);
             atomicAdd(&a.stats[kStatTokens], (unsigned long long)len);
             atomicAdd(&a.stats[kStatTests], tests);
+            if (len > a.late_len) atomicAdd(&a.stats[kStatLatePaths], 1ull);
         }
         return;
     }

@@ -56,6 +56,12 @@ struct stand_handle {
     uint32_t shuffle;    // non-zero: row slots are permuted (a test of independence from the work mapping)
     uint64_t wait_limit_us;
     int wall_khz;        // rate of the device's constant clock (wall_clock64)
+    // STAND_STEP_AUTO watches how often accepted paths reach below the rows that are scheduled first and
+    // takes the separate launches while that is common (plan_observe)
+    unsigned long long *probe_host;  // pinned: kStatLatePaths as last copied
+    hipEvent_t probe_ev;
+    bool probe_pending, plan_serial;
+    uint64_t probe_steps, probe_issue_steps, probe_base_steps, probe_base_late;
     unsigned long long *stamps;  // [2 + 8 * B] clock readings of the last one-launch step, or NULL (stand_step_timeline)
     VerifyScratch vs;  // row results, partial sums, stop records, observations (hipMalloc'ed at create)
     long long *rec_slot;
@@ -135,6 +141,8 @@ static void free_all(stand_handle *h)
     for (void *p : ptrs) (void)hipFree(p);
     for (hipEvent_t e : h->ev_begin) (void)hipEventDestroy(e);
     for (hipEvent_t e : h->ev_end) (void)hipEventDestroy(e);
+    if (h->probe_ev) (void)hipEventDestroy(h->probe_ev);
+    if (h->probe_host) (void)hipHostFree(h->probe_host);
     delete h;
 }
 
@@ -185,6 +193,9 @@ extern "C" int stand_create(const stand_config *cfg, stand_handle **out)
     h->shuffle = 0;
     h->wait_limit_us = 200000;
     h->stamps = nullptr;
+    h->probe_host = nullptr; h->probe_ev = nullptr;
+    h->probe_pending = false; h->plan_serial = false;
+    h->probe_steps = h->probe_issue_steps = h->probe_base_steps = h->probe_base_late = 0;
     {
         int khz = 0;
         if (hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, cfg->device) != hipSuccess || khz <= 0) khz = 100000;
@@ -294,6 +305,9 @@ extern "C" int stand_create(const stand_config *cfg, stand_handle **out)
     acc(hipMemset(h->vs.top_l, 0, rows * K * sizeof(float))); acc(hipMemset(h->vs.top_p, 0, rows * K * sizeof(float)));
     acc(hipMemset(h->vs.top_idx, 0, rows * K * sizeof(int32_t)));
     acc(hipMemset(h->stats, 0, kStatCount * sizeof(unsigned long long)));
+    acc(hipHostMalloc((void **)&h->probe_host, sizeof(unsigned long long), hipHostMallocDefault));
+    if (h->probe_host) *h->probe_host = 0;
+    acc(hipEventCreateWithFlags(&h->probe_ev, hipEventDisableTiming));
     acc(hipDeviceSynchronize());
     if (e != hipSuccess) { free_all(h); return STAND_EHIP; }
     *out = h;
@@ -441,6 +455,7 @@ static PathArgs make_path_args(const stand_handle *h, const VerifyScratch &vs, u
     a.stop_i = vs.stop_i; a.stop_m = vs.stop_m; a.stop_qid = vs.stop_qid; a.stop_qmu = vs.stop_qmu; a.stop_ql = vs.stop_ql;
     a.stop_child = vs.stop_child;
     a.obs_idx = vs.obs_idx; a.obs_p = vs.obs_p; a.stats = h->stats;
+    a.late_len = (h->upper_depth < h->D ? h->upper_depth : h->D) + 1;
     // segments of seg_vectors 16-byte vectors where kSegMax allows it
     const int row_vectors = (int)(((size_t)h->V * (bf16 ? 2 : 4) + 15) / 16);
     a.nseg = clampi((row_vectors + seg_vectors - 1) / seg_vectors, 1, kSegMax);
@@ -617,7 +632,47 @@ static bool step_fused_wanted(const stand_handle *h)
     // never hold more than a fraction of the device (256 compute units, three such workgroups each)
     if (h->B * (h->tail_groups > 0 ? h->tail_groups : 1) > 256) return false;
     if (h->step_mode == STAND_STEP_FUSED) return true;
+    if (h->plan_serial) return false;  // (deep accepted paths are common at present, see plan_observe)
     return h->B * h->N > kRowsFew;  // with few rows the pass is latency-bound and sixteen waves per row serve it better
+}
+
+// STAND_STEP_AUTO only.  In the one-launch step a trajectory whose accepted path reaches below the tree
+// levels scheduled first waits for a row that streams late, and everything after the first barrier waits
+// with it; the separate launches do not care.  Both kinds of step count such paths (kStatLatePaths).
+// Every kPlanWindow steps the counter is copied to pinned memory without waiting; when a copy has arrived,
+// the late paths per step over the window it closed decide the plan: above kPlanSerialAbove the separate
+// launches, below kPlanFusedBelow the one launch again.  Results do not depend on the plan.  Nothing is
+// observed while the stream is being captured.
+constexpr uint64_t kPlanWindow = 32;
+constexpr double kPlanSerialAbove = 0.40, kPlanFusedBelow = 0.25;
+static void plan_observe(stand_handle *h, hipStream_t s)
+{
+    if (h->step_mode != STAND_STEP_AUTO || !h->probe_host || !h->probe_ev) return;
+    hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(s, &cap) != hipSuccess || cap != hipStreamCaptureStatusNone) { (void)hipGetLastError(); return; }
+    ++h->probe_steps;
+    if (h->probe_pending) {
+        if (hipEventQuery(h->probe_ev) != hipSuccess) { (void)hipGetLastError(); return; }  // (not there yet)
+        h->probe_pending = false;
+        const uint64_t late = *(volatile unsigned long long *)h->probe_host;
+        const uint64_t steps = h->probe_issue_steps - h->probe_base_steps;
+        if (steps > 0 && late >= h->probe_base_late) {
+            const double per_step = (double)(late - h->probe_base_late) / (double)steps;
+            if (per_step > kPlanSerialAbove) h->plan_serial = true;
+            else if (per_step < kPlanFusedBelow) h->plan_serial = false;
+        }
+        h->probe_base_steps = h->probe_issue_steps; h->probe_base_late = late;
+    }
+    if (h->probe_steps - h->probe_issue_steps >= kPlanWindow) {
+        // (the copy is ordered after the steps enqueued so far: it sees the count up to the step before this one)
+        if (hipMemcpyAsync(h->probe_host, h->stats + kStatLatePaths, sizeof(unsigned long long), hipMemcpyDeviceToHost, s) == hipSuccess &&
+            hipEventRecord(h->probe_ev, s) == hipSuccess) {
+            h->probe_pending = true;
+            h->probe_issue_steps = h->probe_steps - 1;
+        } else {
+            (void)hipGetLastError();
+        }
+    }
 }
 static int step_tail_groups(const stand_handle *h)
 {
@@ -709,6 +764,7 @@ extern "C" int stand_set_step_plan(stand_handle *h, int32_t mode, int32_t upper_
     if (mode == STAND_STEP_FUSED && h->cfg.update_mode != STAND_UPDATE_ACCEPTED_PATH) return STAND_EINVAL;
     h->step_mode = mode; h->upper_depth = upper_depth; h->tail_groups = tail_groups; h->rows_first = rows_first;
     h->shuffle = shuffle;
+    h->plan_serial = false;  // (a new plan starts from the one launch; the window in progress is kept)
     return STAND_OK;
 }
 
@@ -752,6 +808,7 @@ extern "C" int stand_step(stand_handle *h, uint64_t step, const void *d_logits, 
     hipStream_t s = (hipStream_t)stream;
     HIP_TRY(h, hipSetDevice(h->cfg.device));
     const int32_t *commit = d_force_tok ? d_force_tok : d_out_tok;
+    plan_observe(h, s);
     if (step_fused_wanted(h))
         return launch_step_fused(h, step, d_logits, d_out_tok, d_out_node, d_out_len, d_next_draft_tok, commit, s);
     int rc = launch_row_pass(h, h->vs, step, d_logits, s);
@@ -885,7 +942,7 @@ extern "C" int stand_get_stats(stand_handle *h, stand_stats *out)
     out->misses = st[kStatMisses]; out->inserts = st[kStatInserts]; out->merges = st[kStatMerges];
     out->drops = st[kStatDrops]; out->near_threshold = st[kStatNear]; out->tokens_emitted = st[kStatTokens];
     out->accept_tests = st[kStatTests]; out->filter_mismatch = st[kStatMismatch];
-    out->wait_expired = st[kStatWaitExpired];
+    out->wait_expired = st[kStatWaitExpired]; out->late_paths = st[kStatLatePaths];
     return STAND_OK;
 }
 

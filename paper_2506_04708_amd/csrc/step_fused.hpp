@@ -289,6 +289,7 @@ __device__ __forceinline__ void tail_role(const StepArgs &A, int b, int g, char 
                 for (int q = 0; q + 1 < len; ++q) tests += (unsigned long long)(ts->acc[q] + 1);
                 atomicAdd(&a.stats[kStatTokens], (unsigned long long)len);
                 atomicAdd(&a.stats[kStatTests], tests);
+                if (len > a.late_len) atomicAdd(&a.stats[kStatLatePaths], 1ull);
             } else {
                 atomicAdd(&a.stats[kStatWaitExpired], 1ull);
             }

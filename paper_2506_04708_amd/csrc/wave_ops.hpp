@@ -24,6 +24,7 @@ enum StatSlot {
     kStatHits = 0,  // kStatHits + n, n = 1..8
     kStatMisses = 9, kStatInserts, kStatMerges, kStatDrops, kStatNear, kStatTokens, kStatTests, kStatMismatch,
     kStatWaitExpired,
+    kStatLatePaths,  // accepted paths that reach below the tree levels whose rows the one-launch step schedules first
     kStatCount
 };
 

@@ -139,8 +139,14 @@ def run_lockstep(w, steps, mode="separate", capacity=1 << 12, check_rows=True, t
     g.draft(0, d_draft)
     torch.cuda.synchronize()
     assert np.array_equal(d_draft.cpu().numpy(), od), "draft 0 differs"
-    info = dict(emitted=0, len_hist=np.zeros(w.W + 1, int), worst_rel=0.0, entries=0)
+    info = dict(emitted=0, len_hist=np.zeros(w.W + 1, int), worst_rel=0.0, entries=0, one_launch=[])
+    plans, plan_every = w.cfg.get("step_plans"), w.cfg.get("plan_every", 3)
+    upper_depth = w.cfg["step_plan"][1] if w.cfg.get("step_plan") is not None else 2
+    late = 0
     for step in range(steps):
+        if plans and step % plan_every == 0:
+            g.set_step_plan(*plans[(step // plan_every) % len(plans)])   # the launch structure changes while running
+            upper_depth = plans[(step // plan_every) % len(plans)][1]
         src = w.reorder_map(step)
         if src is not None:
             # beam copy: contexts move, the pending drafts are void; both sides draft again for this step
@@ -173,6 +179,7 @@ def run_lockstep(w, steps, mode="separate", capacity=1 << 12, check_rows=True, t
         if mode == "step":
             d_force = torch.from_numpy(force).cuda() if forced else None
             g.step(step, dl, out_tok, out_node, out_len, d_draft, d_force)
+            info["one_launch"].append(bool(g.step_is_one_launch()))   # (the plan this step ran under)
         else:
             g.verify(step, dl, out_tok, out_node, out_len)
             torch.cuda.synchronize()
@@ -205,11 +212,14 @@ def run_lockstep(w, steps, mode="separate", capacity=1 << 12, check_rows=True, t
             tail, ln = g.get_context(b, 1)
             assert ln == o.context_len(b) and tail[0] == o.context_tail(b, 1)[0]
         info["emitted"] += int(olen.sum())
+        late += int((olen > min(upper_depth, w.D) + 1).sum())
         for l in olen:
             info["len_hist"][l] += 1
         if verbose:
             print("step", step, "len", olen.tolist(), flush=True)
     so, sg = o.stats(), g.stats()
+    info["late_paths"] = int(sg.late_paths)
+    assert sg.late_paths == late, "paths below the first-scheduled levels: %d counted, %d expected" % (sg.late_paths, late)
     assert list(so.hits) == list(sg.hits) and so.misses == sg.misses, "lookup statistics differ"
     assert (so.inserts, so.merges, so.drops) == (sg.inserts, sg.merges, sg.drops), "update statistics differ"
     assert so.tokens_emitted == sg.tokens_emitted and so.accept_tests == sg.accept_tests

@@ -94,6 +94,38 @@ def test_lockstep_one_launch_step(gpu, name, over, steps, forced):
     assert info["emitted"] >= steps * w.B and info["worst_rel"] < 1e-5
 
 
+def test_step_plan_changes_while_running(gpu):
+    """The launch structure of stand_step is changed every three steps (one launch with different splits, the five
+    launches, the automatic choice): the draft state, the contexts and the table carry over, every output stays
+    equal to the oracle's."""
+    binding, lockstep = gpu
+    _say("step plan rotation")
+    plans = [(FUSED, 2, 0, 0), (1, 2, 0, 0), (FUSED, 0, 8, 3), (0, 2, 0, 0), (FUSED, 3, 2, 0)]
+    w = synth.Workload("cfg3", run_steps=40, V=48, B=4, rho=0.5, step_plans=plans, plan_every=3)
+    info = lockstep.run_lockstep(w, 40, mode="step", capacity=1 << 14, forced=False)
+    _say("  -> %s" % info)
+    assert True in info["one_launch"] and False in info["one_launch"]
+
+
+def test_automatic_plan_follows_the_acceptance_depth(gpu):
+    """STAND_STEP_AUTO starts with the one launch; where most steps have an accepted path that reaches below the
+    rows scheduled first (tiny vocabulary, closed loop) it goes over to the five launches after its first window of
+    32 steps, and it stays with the one launch where paths are short (random rows).  Outputs equal the oracle's
+    under either plan."""
+    binding, lockstep = gpu
+    _say("automatic plan, deep acceptance")
+    w = synth.Workload("cfg3", run_steps=48, V=48, B=13, rho=0.5)   # 832 rows: the one launch is the automatic start
+    info = lockstep.run_lockstep(w, 48, mode="step", capacity=1 << 14, forced=False)
+    _say("  -> %s" % info)
+    assert info["late_paths"] > 0.4 * 48, "the case is meant to accept deep paths"
+    assert info["one_launch"][0] and all(info["one_launch"][:32]) and not any(info["one_launch"][34:])
+    _say("automatic plan, short paths")
+    w = synth.Workload("cfg3", run_steps=40, V=3000, B=13, rho=0.5, logit_scale=0.25)  # nearly flat rows
+    info = lockstep.run_lockstep(w, 40, mode="step", capacity=1 << 14, forced=False, check_rows=False)
+    _say("  -> %s" % info)
+    assert info["late_paths"] < 0.25 * 40 and all(info["one_launch"])
+
+
 def test_one_launch_step_waits_are_bounded(gpu):
     """With the wait limit at zero every wait of the one-launch step that is not satisfied at once runs out:
     the launches still end, the expiry is reported in the statistics and the outputs are marked void."""
