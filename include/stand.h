@@ -68,8 +68,8 @@ extern "C" {
                                     /* of each child is one-hot, so it is accepted with probability r(x) */
 
 /* How stand_step issues its work (results are the same; see stand_set_step_plan). */
-#define STAND_STEP_AUTO 0   /* one launch where it pays (more than 768 rows, accepted-path updates, accepted paths */
-                            /* that seldom reach below upper_depth: watched while running), else serial         */
+#define STAND_STEP_AUTO 0   /* one launch where it pays (769 .. 8192 rows, accepted-path updates, accepted paths */
+                            /* that seldom reach below upper_depth: watched while running), else serial        */
 #define STAND_STEP_SERIAL 1 /* five dependent launches: rows, exact sums, finish + claims, apply, draft           */
 #define STAND_STEP_FUSED 2  /* one launch: the dependent tail runs beside the rows that are still streaming      */
 

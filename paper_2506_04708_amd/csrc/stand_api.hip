@@ -633,7 +633,10 @@ static bool step_fused_wanted(const stand_handle *h)
     if (h->B * (h->tail_groups > 0 ? h->tail_groups : 1) > 256) return false;
     if (h->step_mode == STAND_STEP_FUSED) return true;
     if (h->plan_serial) return false;  // (deep accepted paths are common at present, see plan_observe)
-    return h->B * h->N > kRowsFew;  // with few rows the pass is latency-bound and sixteen waves per row serve it better
+    // With few rows the pass is latency-bound and sixteen waves per row serve it better.  With very many the
+    // dependent launches are a few per cent of the step, which is all one launch could save, and it varied more
+    // from run to run than that (B=128 x 128 nodes: 0.84-0.96 ms against 0.85-0.88 ms).
+    return h->B * h->N > kRowsFew && h->B * h->N <= kRowsMany;
 }
 
 // STAND_STEP_AUTO only.  In the one-launch step a trajectory whose accepted path reaches below the tree

@@ -15,6 +15,7 @@ constexpr int kDtBf16 = 0, kDtF32 = 1;
 #endif
 constexpr int kRowWPR = STAND_ROW_WPR, kRowWPRFewRows = 16;
 constexpr int kRowsFew = 768;               // at most this many rows: kRowWPRFewRows waves per row
+constexpr int kRowsMany = 8192;             // more rows than this: the step's automatic plan keeps the separate launches
 constexpr int kMaxNodes = 1024;
 constexpr int kMaxDepth = 31;
 constexpr int kPathThreads = 256;

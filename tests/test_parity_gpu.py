@@ -126,6 +126,19 @@ def test_automatic_plan_follows_the_acceptance_depth(gpu):
     assert info["late_paths"] < 0.25 * 40 and all(info["one_launch"])
 
 
+def test_automatic_plan_by_row_count(gpu):
+    """The automatic plan takes the one launch between 769 and 8192 rows only; both forms in lock step with the
+    oracle at the batch size of the largest configuration (128 beams, 128 nodes: 16384 rows) on a small vocabulary."""
+    binding, lockstep = gpu
+    for name, over, want in (("cfg5", dict(V=96, rho=0.5), False), ("cfg3", dict(V=96, rho=0.5), True),
+                             ("cfg3", dict(V=96, B=12, rho=0.5), False)):
+        _say("automatic plan %s %s" % (name, over))
+        w = synth.Workload(name, run_steps=5, **over)
+        info = lockstep.run_lockstep(w, 5, mode="step", capacity=1 << 16, forced=False, check_rows=False)
+        _say("  -> rows %d one launch %s emitted %d" % (w.B * w.N, info["one_launch"], info["emitted"]))
+        assert all(x == want for x in info["one_launch"])
+
+
 def test_one_launch_step_waits_are_bounded(gpu):
     """With the wait limit at zero every wait of the one-launch step that is not satisfied at once runs out:
     the launches still end, the expiry is reported in the statistics and the outputs are marked void."""
@@ -395,7 +408,8 @@ def test_other_configs_at_their_row_shapes(gpu, name, over, steps):
     ("cfg4", dict(), 4, dict(capacity=1 << 16)),
     # configs[4] as stated, with the beam re-parenting inside the run (every 2 steps instead of 64):
     # 128 beams, 128 nodes, K=32, orders 1-5, T=0.8 (16384 rows, 4.98 GB of logits per step)
-    ("cfg5", dict(reorder_every=2), 4, dict(capacity=1 << 18)),
+    # (the one launch is asked for: with this many rows the automatic plan keeps the separate launches)
+    ("cfg5", dict(reorder_every=2, step_plan=(FUSED, 2, 0, 0)), 4, dict(capacity=1 << 18)),
     # configs[2] shape on a table that is 30 % full before the run (probes past the home slot, displaced keys)
     ("cfg3", dict(), 4, dict(capacity=1 << 15, preload=9830)),
 ])
