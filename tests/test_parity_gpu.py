@@ -548,6 +548,47 @@ def test_determinism_and_import_export(gpu):
     assert np.array_equal(exports[0], exports[1])
 
 
+def test_results_do_not_depend_on_the_work_mapping(gpu):
+    """Race detection by permutation: the same 14 closed-loop steps under different workgroup -> work mappings of
+    the one-launch step (order in which workgroups take rows, rows placed before the tail, tail workgroups per
+    trajectory, tree levels scheduled first) and as five launches.  Every output, the next draft and the exported
+    table are equal bit for bit in all runs; among the one-launch runs (same waves per row) so are the row results
+    with their fast normalisers."""
+    binding, lockstep = gpu
+    plans = [(FUSED, 2, 4, 0, 0), (FUSED, 2, 4, 12345, 0), (FUSED, 1, 2, 777, 600), (FUSED, 0, 8, 31, 0), (FUSED, 8, 1, 5, 0),
+             (1, 2, 0, 0, 0)]
+    runs = []
+    for plan in plans:
+        _say("work mapping %s" % (plan,))
+        w = synth.Workload("cfg3", run_steps=14, V=600, B=13, rho=0.6)
+        o, g = lockstep.make_pair(w, 1 << 14)
+        o.close()
+        g.set_step_plan(*plan)
+        for b in range(w.B):
+            g.set_context(b, w.prompt(b))
+        out_tok, out_node, out_len, d = g.new_outputs()
+        g.draft(0, d)
+        rec = []
+        for step in range(14):
+            lg = w.logits(step, d.cpu().numpy())
+            g.step(step, lockstep._logits_to_device(lg, w.dtype), out_tok, out_node, out_len, d)
+            torch.cuda.synchronize()
+            m, sfast, idx, p = g.row_results()
+            rec.append([x.cpu().numpy().copy() for x in (out_tok, out_node, out_len, d, m, idx, sfast, p)])
+        st = g.stats()
+        assert st.wait_expired == 0 and st.filter_mismatch == 0
+        runs.append((rec, g.table_export().copy(), (st.inserts, st.merges, st.drops, st.tokens_emitted, st.accept_tests)))
+        g.close()
+    assert sum(int(r[2].sum()) for r in runs[0][0]) > 14 * 13, "some drafts must be accepted for the test to mean anything"
+    for k in range(1, len(runs)):
+        one_launch = plans[k][0] == FUSED
+        for step in range(14):
+            n_same = 8 if one_launch else 6      # (maximum and ids of every row always; fast sums among equal wave counts)
+            for a, b in zip(runs[0][0][step][:n_same], runs[k][0][step][:n_same]):
+                assert np.array_equal(a, b), "plan %s differs from plan %s at step %d" % (plans[k], plans[0], step)
+        assert np.array_equal(runs[0][1], runs[k][1]) and runs[0][2] == runs[k][2]
+
+
 def test_reorder_matches_oracle(gpu):
     binding, lockstep = gpu
     w = synth.Workload("cfg1", run_steps=10, V=2000, B=4, rho=0.7)
