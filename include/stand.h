@@ -82,7 +82,8 @@ extern "C" {
 typedef struct stand_handle stand_handle;
 
 typedef struct {
-    int32_t vocab;              /* V, topk <= V < 2^22                                              */
+    int32_t vocab;              /* V >= max(2, topk); a row of logits must stay 128 KiB below 4 GiB    */
+                                /* (V <= 2 147 418 112 for bf16, 1 073 709 056 for fp32)               */
     int32_t max_batch;          /* B >= 1 trajectories sharing the table                            */
     int32_t order_min;          /* shortest context length used as a key, >= 1                      */
     int32_t order_max;          /* longest, <= STAND_MAX_ORDER (paper Sec. 4.1: unigram .. 4-gram)   */

@@ -99,12 +99,13 @@ __device__ __forceinline__ float scaled_offset(float l, float m, float c)
     return d * c;
 }
 
-// The row normaliser is the integer S = sum_v floor(E(y_v) * 2^40) (V < 2^22, so S < 2^63);
-// s = (float)((double)S * 2^-40).
-__device__ __forceinline__ float normaliser_from_fixed(uint64_t S)
+// The row normaliser is the integer S = sum_v floor(E(y_v) * 2^fx) with fx = min(40, 62 - ceil(log2 V)), so
+// that S < 2^63 for every vocabulary; s = (float)((double)S * 2^-fx).  `shift` below is 40 - fx (0 up to
+// V = 2^22).
+__device__ __forceinline__ float normaliser_from_fixed(uint64_t S, int shift)
 {
     double d = (double)S;
-    d = __builtin_ldexp(d, -40);
+    d = __builtin_ldexp(d, shift - 40);
     return (float)d;
 }
 

@@ -54,6 +54,7 @@ struct PathArgs {
     unsigned long long *node_count;  // [N] verifications in which a node lay on the accepted path (mode 0)
     bool onehot;                     // deterministic drafting: one-hot proposals in the accept tests
     int late_len;                    // paths longer than this count as late (kStatLatePaths)
+    int fx_shift;                    // the exact normaliser counts in units of 2^-(40 - fx_shift)
 };
 
 // Walks the accepted path of trajectory b and leaves it in path[0..len) (shared memory).  Must be
@@ -122,11 +123,11 @@ __device__ __forceinline__ unsigned long long wave_sum_u64(unsigned long long x)
 {
     return readlane_u64(wave_inclusive_scan_u64(x), 63);
 }
-__device__ __forceinline__ unsigned long long fixed_mass(float e)
+__device__ __forceinline__ unsigned long long fixed_mass(float e, int shift)
 {
     uint32_t hi, lo;
     fixed_split(e, hi, lo);
-    return ((unsigned long long)hi << 20) + lo;
+    return ((unsigned long long)hi << (20 - shift)) + (lo >> shift);
 }
 
 template <int DT>
@@ -214,7 +215,7 @@ __global__ __launch_bounds__(kPathThreads) void path_exact_kernel(PathArgs a)
         const int per = (g.nvec + nseg - 1) / nseg;
         const int v0 = seg * per < g.nvec ? seg * per : g.nvec;
         const int v1 = (v0 + per < g.nvec) ? v0 + per : g.nvec;
-        unsigned long long S = thread_exact_partial<DT>(rowp, g, v0, v1, seg == 0, m, a.c, tid, kPathThreads);
+        unsigned long long S = thread_exact_partial<DT>(rowp, g, v0, v1, seg == 0, m, a.c, tid, kPathThreads, a.fx_shift);
         S = wave_sum_u64(S);
         __syncthreads();  // s_part of the previous row has been read
         if (lane == 0) s_part[wave] = S;
@@ -237,7 +238,7 @@ struct FinishShared {
 
 // masked integer masses of the EPV elements of vector idx (elements e0 .. e0 + EPV - 1 of the row)
 template <int DT>
-__device__ __forceinline__ void vector_masses(const uint4 &w, int e0, float m, float c, const FinishShared &sh,
+__device__ __forceinline__ void vector_masses(const uint4 &w, int e0, float m, float c, int shift, const FinishShared &sh,
                                               unsigned long long *f)
 {
     constexpr int EPV = VecTraits<DT>::EPV;
@@ -249,7 +250,7 @@ __device__ __forceinline__ void vector_masses(const uint4 &w, int e0, float m, f
         if (d < (uint32_t)EPV) bits |= 1u << d;
     }
 #pragma unroll
-    for (int q = 0; q < EPV; ++q) f[q] = ((bits >> q) & 1u) ? 0ull : fixed_mass(exact_exp2(scaled_offset(x[q], m, c)));
+    for (int q = 0; q < EPV; ++q) f[q] = ((bits >> q) & 1u) ? 0ull : fixed_mass(exact_exp2(scaled_offset(x[q], m, c)), shift);
 }
 // Update mode: maximum and top-K of the given commit rows (one workgroup of 4 waves per row).
 struct CommitScanArgs {
@@ -339,10 +340,10 @@ __device__ __forceinline__ void finish_row(const PathArgs &a, FinishShared &sh, 
             else if (lane < g.head + g.ntail) edge_id = g.tail0 + (lane - g.head);
         }
         const unsigned long long edge_f =
-            edge_id >= 0 ? fixed_mass(exact_exp2(scaled_offset(load_scalar<DT>(rowp, edge_id), m, a.c))) : 0ull;
+            edge_id >= 0 ? fixed_mass(exact_exp2(scaled_offset(load_scalar<DT>(rowp, edge_id), m, a.c)), a.fx_shift) : 0ull;
 
         const unsigned long long S = wave_sum_u64(part);
-        const float s = normaliser_from_fixed(S);
+        const float s = normaliser_from_fixed(S, a.fx_shift);
         if (!stop) {
             // observation of this row (paper Sec. 4.1: top-k ids and probabilities)
             if (lane < a.K) {
@@ -386,7 +387,7 @@ __device__ __forceinline__ void finish_row(const PathArgs &a, FinishShared &sh, 
             st_agent(&a.obs_idx[((size_t)b * a.R + j) * a.K + lane], o_idx);
             st_agent(&a.obs_p[((size_t)b * a.R + j) * a.K + lane], exact_exp2(scaled_offset(o_l, m, a.c)) / s);
         }
-        // ---- integer masses (unit 2^-40 / s * rho): support token i weighs floor(r_i * (S / rho)),
+        // ---- integer masses (unit 2^-(40 - fx_shift) / s * rho): support token i weighs floor(r_i * (S / rho)),
         // a token outside the support the term it contributes to S
         const bool has_edge = g.head + g.ntail > 0;  // rows that start on a 16-byte boundary have none
         const unsigned long long edge_all = has_edge ? wave_sum_u64(edge_f) : 0ull;
@@ -398,7 +399,7 @@ __device__ __forceinline__ void finish_row(const PathArgs &a, FinishShared &sh, 
             if (support && lane < a.K && my_id >= 0) {
                 const double ratio = (double)S / (double)rho;  // skipped by the whole wave without a support
                 my_g = (unsigned long long)((double)my_r * ratio);
-                my_f = fixed_mass(my_e);
+                my_f = fixed_mass(my_e, a.fx_shift);
                 my_ps = my_id < g.head ? 0 : (my_id >= g.tail0 ? nseg + 1 : 1 + ((my_id - g.head) / EPV) / per);
             }
             unsigned long long head_m = 0ull, tail_m = 0ull;
@@ -475,7 +476,7 @@ __device__ __forceinline__ void finish_row(const PathArgs &a, FinishShared &sh, 
     auto vec_sum = [&](const uint4 &w, int idx) {
         if (idx < r1) {
             unsigned long long f[EPV];
-            vector_masses<DT>(w, g.head + idx * EPV, m, a.c, sh, f);
+            vector_masses<DT>(w, g.head + idx * EPV, m, a.c, a.fx_shift, sh, f);
 #pragma unroll
             for (int q = 0; q < EPV; ++q) mine += f[q];
         }
@@ -486,7 +487,7 @@ __device__ __forceinline__ void finish_row(const PathArgs &a, FinishShared &sh, 
     for (int q = 0; q < EPV; ++q) f1[q] = 0ull;
     if (cpt == 1) {
         if (r0 < r1) {
-            vector_masses<DT>(g.vp[r0], g.head + r0 * EPV, m, a.c, sh, f1);
+            vector_masses<DT>(g.vp[r0], g.head + r0 * EPV, m, a.c, a.fx_shift, sh, f1);
 #pragma unroll
             for (int q = 0; q < EPV; ++q) mine += f1[q];
         }
@@ -510,7 +511,7 @@ __device__ __forceinline__ void finish_row(const PathArgs &a, FinishShared &sh, 
         auto vec_find = [&](const uint4 &w, int idx) {
             if (idx < r1 && token < 0) {
                 unsigned long long f[EPV];
-                vector_masses<DT>(w, g.head + idx * EPV, m, a.c, sh, f);
+                vector_masses<DT>(w, g.head + idx * EPV, m, a.c, a.fx_shift, sh, f);
 #pragma unroll
                 for (int q = 0; q < EPV; ++q) {
                     if (token < 0) {

@@ -429,10 +429,13 @@ __device__ __forceinline__ void fixed_split(float e, uint32_t &hi, uint32_t &lo)
 }
 
 // Exact fixed-point sum over the vectors [v0, v1) of a row (plus the edge elements if with_edge),
-// strided over `nthreads` threads; returns this thread's partial sum_v floor(E((l_v - m) c) * 2^40).
+// strided over `nthreads` threads; returns this thread's partial sum_v floor(E((l_v - m) c) * 2^(40 - shift)).
+// floor(e 2^40) = hi 2^20 + lo, and hi 2^20 is a multiple of 2^shift (shift <= 20), so
+// floor(e 2^(40 - shift)) = hi 2^(20 - shift) + (lo >> shift): the parts are shifted, then summed.
 template <int DT, int INFLIGHT = 4>
 __device__ __forceinline__ unsigned long long thread_exact_partial(const void *rowp, const RowGeom &g, int v0, int v1,
-                                                                   bool with_edge, float m, float c, int t, int nthreads)
+                                                                   bool with_edge, float m, float c, int t, int nthreads,
+                                                                   int shift)
 {
     constexpr int EPV = VecTraits<DT>::EPV;
     unsigned long long S = 0ull;
@@ -444,7 +447,7 @@ __device__ __forceinline__ unsigned long long thread_exact_partial(const void *r
         if (edge_id >= 0) {
             uint32_t hi, lo;
             fixed_split(exact_exp2(scaled_offset(load_scalar<DT>(rowp, edge_id), m, c)), hi, lo);
-            ahi += hi; alo += lo;
+            ahi += hi; alo += lo >> shift;
         }
     }
     // INFLIGHT independent loads are issued before any of them is used (indices clamped, so the
@@ -458,7 +461,7 @@ __device__ __forceinline__ unsigned long long thread_exact_partial(const void *r
             for (int j = 0; j < EPV; ++j) {
                 uint32_t hi, lo;
                 fixed_split(exact_exp2(scaled_offset(x[j], m, c)), hi, lo);
-                ahi += hi; alo += lo;
+                ahi += hi; alo += lo >> shift;
             }
         }
     };
@@ -474,20 +477,20 @@ __device__ __forceinline__ unsigned long long thread_exact_partial(const void *r
             add_vec(w[q], base + q * nthreads);
             if ((q & 3) == 3 || q == INFLIGHT - 1) {
                 // at most 32 elements since the last flush: the 32-bit accumulators stay below 2^26
-                S += ((unsigned long long)ahi << 20) + alo;
+                S += ((unsigned long long)ahi << (20 - shift)) + alo;
                 ahi = 0; alo = 0;
             }
         }
     }
-    return S + ((unsigned long long)ahi << 20) + alo;
+    return S + ((unsigned long long)ahi << (20 - shift)) + alo;
 }
 
 // Exact normaliser of a row by one wave (rare path).
 template <int DT>
-__device__ unsigned long long wave_row_exact_sum(const void *rowp, int V, float m, float c, int lane)
+__device__ unsigned long long wave_row_exact_sum(const void *rowp, int V, float m, float c, int lane, int shift)
 {
     const RowGeom g = row_geom<DT>(rowp, V);
-    unsigned long long S = thread_exact_partial<DT>(rowp, g, 0, g.nvec, true, m, c, lane, 64);
+    unsigned long long S = thread_exact_partial<DT>(rowp, g, 0, g.nvec, true, m, c, lane, 64, shift);
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) S += __shfl_xor(S, off);
     return S;
@@ -510,6 +513,7 @@ struct RowPassArgs {
     unsigned long long *stats;
     bool onehot;                // deterministic drafting: one-hot proposals in the accept tests
     float eps;                  // relative error assumed for the fast normaliser from its additions (>= kFastEps)
+    int fx_shift;               // the exact normaliser counts in units of 2^-(40 - fx_shift) (0 up to V = 2^22)
 };
 
 // Shared memory of one row's workgroup of WPR waves.
@@ -571,8 +575,8 @@ __device__ __forceinline__ void row_role(const RowPassArgs &a, int row, RowShare
                                           true, eps_row, a.onehot);
         if (nr.near) {
             // a test fell inside the error bound of the fast normaliser: decide with the exact one
-            const unsigned long long S = wave_row_exact_sum<DT>(rowp, a.V, m, a.c, lane);
-            const float sx = normaliser_from_fixed(S);
+            const unsigned long long S = wave_row_exact_sum<DT>(rowp, a.V, m, a.c, lane, a.fx_shift);
+            const float sx = normaliser_from_fixed(S, a.fx_shift);
             nr = wave_node_outcome(lane, a.K, my_id, my_mu, e / sx, nch, ch, a.seed, (uint32_t)b, a.step, fc, false,
                                    0.0f, a.onehot);
             if (lane == 0) atomicAdd(&a.stats[kStatNear], 1ull);

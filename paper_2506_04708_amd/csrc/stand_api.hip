@@ -56,6 +56,7 @@ struct stand_handle {
     uint32_t shuffle;    // non-zero: row slots are permuted (a test of independence from the work mapping)
     uint64_t wait_limit_us;
     int wall_khz;        // rate of the device's constant clock (wall_clock64)
+    int fx_shift;        // 40 - (fraction bits of the exact normaliser's terms): 0 up to V = 2^22
     // STAND_STEP_AUTO watches how often accepted paths reach below the rows that are scheduled first and
     // takes the separate launches while that is common (plan_observe)
     unsigned long long *probe_host;  // pinned: kStatLatePaths as last copied
@@ -152,7 +153,10 @@ extern "C" int stand_create(const stand_config *cfg, stand_handle **out)
     *out = nullptr;
     const int N = cfg->tree_nodes, K = cfg->topk;
     if (K < 1 || K > STAND_MAX_TOPK) return STAND_EINVAL;
-    if (cfg->vocab < K || cfg->vocab < 2 || cfg->vocab >= (1 << 22)) return STAND_EINVAL;
+    // a row is addressed with 32-bit byte offsets (buffer loads, prefetch a few batches past its end):
+    // it must stay 128 KiB below 4 GiB
+    if (cfg->vocab < K || cfg->vocab < 2) return STAND_EINVAL;
+    if ((uint64_t)cfg->vocab * (cfg->logits_dtype == STAND_F32 ? 4u : 2u) > (1ull << 32) - (1ull << 17)) return STAND_EINVAL;
     if (cfg->max_batch < 1 || cfg->max_batch >= (1 << 20)) return STAND_EINVAL;
     if (cfg->order_min < 1 || cfg->order_max < cfg->order_min || cfg->order_max > STAND_MAX_ORDER) return STAND_EINVAL;
     if (N < 1 || N > STAND_MAX_NODES) return STAND_EINVAL;
@@ -178,6 +182,13 @@ extern "C" int stand_create(const stand_config *cfg, stand_handle **out)
     h->NO = cfg->order_max - cfg->order_min + 1;
     h->slot_bytes = 16 + 8 * K;
     h->c = (float)(1.4426950408889634 / (double)cfg->temperature);
+    {
+        // the exact normaliser sums floor(E * 2^fx) over the row; fx = min(40, 62 - ceil(log2 V)) keeps it below 2^63
+        int lg = 0;
+        while (((int64_t)1 << lg) < (int64_t)cfg->vocab) ++lg;
+        const int fx = 62 - lg < 40 ? 62 - lg : 40;
+        h->fx_shift = 40 - fx;
+    }
     h->last_hip = 0;
     h->table_used = false;
     h->profiling = false;
@@ -391,6 +402,7 @@ static RowPassArgs make_row_args(const stand_handle *h, const VerifyScratch &vs,
     a.outcome = vs.outcome; a.stats = h->stats;
     a.onehot = h->cfg.draft_mode == STAND_DRAFT_DETERMINISTIC;
     a.eps = fast_eps(h, wpr);
+    a.fx_shift = h->fx_shift;
     return a;
 }
 
@@ -456,6 +468,7 @@ static PathArgs make_path_args(const stand_handle *h, const VerifyScratch &vs, u
     a.stop_child = vs.stop_child;
     a.obs_idx = vs.obs_idx; a.obs_p = vs.obs_p; a.stats = h->stats;
     a.late_len = (h->upper_depth < h->D ? h->upper_depth : h->D) + 1;
+    a.fx_shift = h->fx_shift;
     // segments of seg_vectors 16-byte vectors where kSegMax allows it
     const int row_vectors = (int)(((size_t)h->V * (bf16 ? 2 : 4) + 15) / 16);
     a.nseg = clampi((row_vectors + seg_vectors - 1) / seg_vectors, 1, kSegMax);

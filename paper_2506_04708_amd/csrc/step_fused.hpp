@@ -197,7 +197,7 @@ __device__ __forceinline__ void tail_role(const StepArgs &A, int b, int g, char 
 #ifdef STAND_DEBUG_SKIP_SUMS
         unsigned long long S = (unsigned long long)(v1 - v0);
 #else
-        unsigned long long S = thread_exact_partial<DT, kTailInflight>(rowp, geo, v0, v1, seg == 0, m, a.c, lane, 64);
+        unsigned long long S = thread_exact_partial<DT, kTailInflight>(rowp, geo, v0, v1, seg == 0, m, a.c, lane, 64, a.fx_shift);
 #endif
         S = wave_sum_u64(S);  // below 2^62 (a whole row's sum is)
         if (lane == 0) st_agent(&a.seg_part[((size_t)t * a.R + j) * kSegMax + seg], S | kPartThere);

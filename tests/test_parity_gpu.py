@@ -548,6 +548,24 @@ def test_determinism_and_import_export(gpu):
     assert np.array_equal(exports[0], exports[1])
 
 
+@pytest.mark.parametrize("over,steps,rows", [
+    # 2^22 < V <= 2^23: the exact normaliser counts in units of 2^-39; misaligned bf16 rows
+    (dict(V=6300017, B=1, dtype="bf16", rho=0.7), 3, [0, 5, 15]),
+    # fp32 rows just above 2^22
+    (dict(V=(1 << 22) + 5, B=2, dtype="f32", rho=0.7), 2, [0, 17, 31]),
+])
+def test_vocabularies_above_2_22(gpu, over, steps, rows):
+    """Vocabularies above 2^22: the integer normaliser's terms keep fewer fraction bits (62 - ceil(log2 V)) so that
+    the sum stays below 2^63; tokens, tables and the sampled rows' results equal the oracle's, whose scaling follows
+    the same rule."""
+    binding, lockstep = gpu
+    _say("large vocabulary %s" % over)
+    w = synth.Workload("cfg1", run_steps=steps, **over)
+    info = lockstep.run_lockstep(w, steps, mode="step", capacity=1 << 12, forced=True, sample_rows=rows)
+    _say("  -> %s" % {k: v for k, v in info.items() if k != "node_counts"})
+    assert info["emitted"] >= steps * w.B and info["worst_rel"] < 1e-5
+
+
 def test_results_do_not_depend_on_the_work_mapping(gpu):
     """Race detection by permutation: the same 14 closed-loop steps under different workgroup -> work mappings of
     the one-launch step (order in which workgroups take rows, rows placed before the tail, tail workgroups per
@@ -760,7 +778,7 @@ def test_bad_arguments_are_rejected(gpu):
     for bad in [dict(temperature=0.0), dict(topk=1), dict(topk=33), dict(table_capacity=100), dict(order_max=9),
                 dict(tree_parent=np.array([-1, 1, 0], np.int32)), dict(tree_parent=np.array([-1, 0, 1, 0], np.int32)),
                 dict(vocab=3), dict(max_probe=0), dict(logits_dtype=7), dict(draft_mode=3), dict(update_mode=2),
-                dict(merge_policy=2), dict(vocab=1 << 22)]:
+                dict(merge_policy=2), dict(vocab=1 << 30), dict(vocab=(1 << 31) - 1, logits_dtype=binding.STAND_BF16)]:
         with pytest.raises(binding.StandError):
             binding.Stand(**{**ok, **bad})
     g = binding.Stand(**ok)
