@@ -664,6 +664,14 @@ constexpr double kPlanSerialAbove = 0.40, kPlanFusedBelow = 0.25;
 static void plan_observe(stand_handle *h, hipStream_t s)
 {
     if (h->step_mode != STAND_STEP_AUTO || !h->probe_host || !h->probe_ev) return;
+    {
+        // nothing to decide where the one launch is not among the choices
+        const bool was = h->plan_serial;
+        h->plan_serial = false;
+        const bool could = step_fused_wanted(h);
+        h->plan_serial = was;
+        if (!could) return;
+    }
     hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
     if (hipStreamIsCapturing(s, &cap) != hipSuccess || cap != hipStreamCaptureStatusNone) { (void)hipGetLastError(); return; }
     ++h->probe_steps;
