@@ -211,6 +211,8 @@ int stand_step(stand_handle *h, uint64_t step, const void *d_logits, int32_t *d_
  *                and takes the serial launches while more than 0.4 paths per step reach below
  *                upper_depth (they would wait for rows that stream late), the one launch again below
  *                0.25; no such copy is made while the stream is being captured, or in the other modes.
+ *                While the stream is being captured (HIP graphs) stand_step always issues the five
+ *                launches: the one launch carries its own number as an argument and cannot be replayed.
  *   upper_depth  FUSED: the rows of tree nodes up to this depth take the first places in the launch
  *                (default 2: paths that end above depth 3 never wait for a late row; deeper paths are
  *                still correct, the tail then waits for the rows it needs).  0 .. STAND_MAX_DEPTH.

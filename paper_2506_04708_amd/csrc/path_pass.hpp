@@ -55,6 +55,8 @@ struct PathArgs {
     bool onehot;                     // deterministic drafting: one-hot proposals in the accept tests
     int late_len;                    // paths longer than this count as late (kStatLatePaths)
     int fx_shift;                    // the exact normaliser counts in units of 2^-(40 - fx_shift)
+    // one-launch step: the rows' top-K as self-validating words of the same launch (RowPub), else NULL
+    const unsigned long long *top_pub;
 };
 
 // Walks the accepted path of trajectory b and leaves it in path[0..len) (shared memory).  Must be
@@ -234,6 +236,7 @@ struct FinishShared {
     unsigned long long rem;             // position inside the chosen segment
     int32_t sup_id[kMaxK];              // stored ids that lie inside the chosen segment
     int nsup, seg, found;
+    int32_t top0;                       // the row's best token
 };
 
 // masked integer masses of the EPV elements of vector idx (elements e0 .. e0 + EPV - 1 of the row)
@@ -313,11 +316,13 @@ __global__ __launch_bounds__(256) void commit_scan_kernel(CommitScanArgs a)
 // not a stop row is finished by ONE wave (wave = 0, tid = lane); the stop row by all NT threads of the
 // workgroup, which all call this with their wave and thread numbers.  m: the row's maximum.  Wave 0's
 // lanes hold the stop node's proposal (my_id, my_mu), the row's logits at those ids (my_l) and the
-// tokens of the drafted children (ch); nch / fc / len as in the stop record.
+// tokens of the drafted children (ch); nch / fc / len as in the stop record.  `walked`: the node's outcome as
+// the caller followed it (a path node that is not the stop node is replayed against it), or -2: read it from
+// the row pass's results.
 template <int DT, int NT>
 __device__ __forceinline__ void finish_row(const PathArgs &a, FinishShared &sh, int b, int j, int node, bool stop, float m,
                                            int nch, int fc, int len, int32_t my_id, float my_mu, float my_l, int32_t ch,
-                                           unsigned long long part, int tid, int wave)
+                                           unsigned long long part, int tid, int wave, int walked = -2)
 {
     constexpr int ES = VecTraits<DT>::ES, EPV = VecTraits<DT>::EPV;
     const int lane = tid & 63;
@@ -331,7 +336,16 @@ __device__ __forceinline__ void finish_row(const PathArgs &a, FinishShared &sh, 
     if (wave == 0) {
         int32_t o_idx = 0;
         float o_l = 0.0f;
-        if (lane < a.K) { o_idx = ld_agent(&a.src_top_idx[(size_t)src * a.K + lane]); o_l = ld_agent(&a.src_top_l[(size_t)src * a.K + lane]); }
+        if (lane < a.K) {
+            if (a.top_pub) {
+                // (the caller has seen these words carry this launch's mark)
+                const unsigned long long tw = ld_agent(&a.top_pub[(size_t)src * a.K + lane]);
+                o_idx = top_pub_id(tw); o_l = top_pub_logit(tw);
+            } else {
+                o_idx = a.src_top_idx[(size_t)src * a.K + lane]; o_l = a.src_top_l[(size_t)src * a.K + lane];
+            }
+        }
+        if (stop && lane == 0) sh.top0 = o_idx;
         if (!stop || nch <= 0 || lane >= a.K) { my_id = -1; my_mu = 0.0f; }
         const float my_e = my_id >= 0 ? exact_exp2(scaled_offset(my_l, m, a.c)) : 0.0f;
         int edge_id = -1;
@@ -363,7 +377,7 @@ __device__ __forceinline__ void finish_row(const PathArgs &a, FinishShared &sh, 
                 const float c_e = c_id >= 0 ? exact_exp2(scaled_offset(c_l, m, a.c)) : 0.0f;
                 const NodeResult nr = wave_node_outcome(lane, a.K, c_id, c_mu, c_e / s, c_n, c_ch, a.seed, (uint32_t)b, a.step, c_fc,
                                                         false, 0.0f, a.onehot);
-                if (lane == 0 && nr.accepted != ld_agent(&a.outcome[row])) atomicAdd(&a.stats[kStatMismatch], 1ull);
+                if (lane == 0 && nr.accepted != (walked != -2 ? walked : a.outcome[row])) atomicAdd(&a.stats[kStatMismatch], 1ull);
             }
             return;
         }
@@ -546,7 +560,7 @@ __device__ __forceinline__ void finish_row(const PathArgs &a, FinishShared &sh, 
     __syncthreads();
     if (tid == 0 && !sh.found) {
         // not reachable while the partial sums describe this row; keep the output a valid token
-        a.out_tok[(size_t)b * a.W + (len - 1)] = a.src_top_idx[(size_t)src * a.K];
+        a.out_tok[(size_t)b * a.W + (len - 1)] = sh.top0;
         atomicAdd(&a.stats[kStatMismatch], 1ull);
     }
 }

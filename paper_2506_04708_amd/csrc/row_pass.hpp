@@ -526,10 +526,10 @@ struct RowShared {
 };
 
 // One logits row by the WPR waves of the calling workgroup (all of its 64 * WPR threads call this).
-// `done`, if given, counts the two waves that write the row's results: each adds 1 once its stores
-// have completed at device scope, so a reader that sees the counter advance by 2 may read them.
+// With pub.row set, the testing wave and the ranking wave also publish what the tail of the same launch
+// reads (maximum and outcome; top-K ids and logits) as self-validating words (RowPub).
 template <int DT, int WPR>
-__device__ __forceinline__ void row_role(const RowPassArgs &a, int row, RowShared<WPR> *sm, unsigned *done)
+__device__ __forceinline__ void row_role(const RowPassArgs &a, int row, RowShared<WPR> *sm, const RowPub &pub)
 {
     constexpr int ES = VecTraits<DT>::ES;
     // the wave's number is the same in all its lanes: say so, so that everything derived from it
@@ -560,10 +560,10 @@ __device__ __forceinline__ void row_role(const RowPassArgs &a, int row, RowShare
         if (lane < nch && lane < kMaxK && fc >= 0 && fc + lane < a.N) ch = a.draft_tok[(size_t)b * a.N + fc + lane];
     };
     // ---- accept / reject outcome of this node's children (paper Sec. 3.2, applied recursively)
-    auto node_tests = [&](float m, float s) {
+    auto node_tests = [&](float m, float s) -> int {
         if (nch == 0) {  // uniform over the wave
-            if (lane == 0) st_agent(&a.outcome[row], (int32_t)-1);
-            return;
+            if (lane == 0) a.outcome[row] = -1;
+            return -1;
         }
         const float e = (lane < a.K && my_id >= 0) ? exact_exp2(scaled_offset(my_l, m, a.c)) : 0.0f;
         // Relative error assumed for s: the part that grows with the terms a lane adds (a.eps, from the host);
@@ -581,12 +581,8 @@ __device__ __forceinline__ void row_role(const RowPassArgs &a, int row, RowShare
                                    0.0f, a.onehot);
             if (lane == 0) atomicAdd(&a.stats[kStatNear], 1ull);
         }
-        if (lane == 0) st_agent(&a.outcome[row], (int32_t)nr.accepted);
-    };
-    auto signal_done = [&]() {
-        if (!done) return;
-        publish_fence();  // the wave's result stores (device scope) are complete before the counter moves
-        if (lane == 0) atomicAdd(done, 1u);
+        if (lane == 0) a.outcome[row] = (int32_t)nr.accepted;
+        return nr.accepted;
     };
     // Wave 0 ranks the row at its end, wave 1 runs the accept tests meanwhile.
     static_assert(WPR >= 2, "a row is shared by at least two waves");
@@ -607,8 +603,8 @@ __device__ __forceinline__ void row_role(const RowPassArgs &a, int row, RowShare
     if (wave == kTestWave) {
         // the accept tests need the row's maximum and normaliser, not its ranking
         request_proposal_logits();
-        node_tests(m, s);
-        signal_done();
+        const int oc = node_tests(m, s);
+        if (pub.row && lane == 0) st_agent(&pub.row[row], pack_row_pub(m, oc, pub.tag));
         return;
     }
     if (wave != 0) return;
@@ -634,12 +630,12 @@ __device__ __forceinline__ void row_role(const RowPassArgs &a, int row, RowShare
     if (lane < a.K) {
         const unsigned long long key = ws->top[lane];
         const float l = rank_key_value(key);
-        st_agent(&a.top_idx[(size_t)row * a.K + lane], (int32_t)rank_key_id(key));
-        st_agent(&a.top_l[(size_t)row * a.K + lane], l);
-        st_agent(&a.top_p[(size_t)row * a.K + lane], exact_exp2(scaled_offset(l, m, a.c)) / s);
+        a.top_idx[(size_t)row * a.K + lane] = (int32_t)rank_key_id(key);
+        a.top_l[(size_t)row * a.K + lane] = l;
+        a.top_p[(size_t)row * a.K + lane] = exact_exp2(scaled_offset(l, m, a.c)) / s;
+        if (pub.top) st_agent(&pub.top[(size_t)row * a.K + lane], pack_top_pub((int32_t)rank_key_id(key), l, pub.tag));
     }
-    if (lane == 0) { st_agent(&a.row_m[row], m); st_agent(&a.row_s[row], s); }
-    signal_done();
+    if (lane == 0) { a.row_m[row] = m; a.row_s[row] = s; }
 }
 
 template <int DT, int WPR>
@@ -652,7 +648,7 @@ __global__ __launch_bounds__(64 * WPR) void row_pass_kernel(RowPassArgs a)
     // rows that finish the kernel are leaves.
     const int slot = blockIdx.x;
     if (slot >= a.B * a.N) return;
-    row_role<DT, WPR>(a, (slot % a.B) * a.N + slot / a.B, &sm, nullptr);
+    row_role<DT, WPR>(a, (slot % a.B) * a.N + slot / a.B, &sm, RowPub{nullptr, nullptr, 0u});
 }
 
 }  // namespace stand

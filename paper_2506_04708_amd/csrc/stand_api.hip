@@ -44,7 +44,8 @@ struct stand_handle {
     int32_t *draft_tok2, *draft_has2, *draft_qid2;  // second copy: the one-launch step writes the next draft here
     float *draft_qmu2;                              // while rows that are still streaming read the pending one
     // one-launch step (stand_step_kernel)
-    unsigned *row_done, *bar;  // counters that only grow, see step_fused.hpp
+    unsigned long long *row_pub, *top_pub;  // what a row hands to the tail of the same launch (RowPub)
+    unsigned *bar;             // counters that only grow, see step_fused.hpp
     unsigned *item_next, *path_flag;
     int32_t *path_pub;
     unsigned step_epoch;
@@ -138,7 +139,7 @@ static void free_all(stand_handle *h)
     if (!h) return;
     void *ptrs[] = {h->d_tree, h->table, h->ctx_tail, h->ctx_len, h->ctx_tail2, h->ctx_len2, h->reorder_map, h->export_buf, h->draft_tok, h->draft_has, h->draft_qid, h->draft_qmu,
                     h->vs.row_m, h->vs.row_s, h->vs.top_l, h->vs.top_p, h->vs.top_idx, h->vs.outcome, h->vs.obs_idx, h->vs.obs_p, h->rec_slot,
-                    h->recent, h->draft_tok2, h->draft_has2, h->draft_qid2, h->draft_qmu2, h->row_done, h->bar, h->item_next, h->path_flag, h->path_pub, h->stamps, h->vs.seg_part, h->node_count, h->anc, h->vs.stop_i, h->vs.stop_qid, h->vs.stop_child, h->vs.stop_m, h->vs.stop_qmu, h->vs.stop_ql, h->pr_m, h->pr_top_l, h->pr_top_idx, h->stats, h->counter};
+                    h->recent, h->draft_tok2, h->draft_has2, h->draft_qid2, h->draft_qmu2, h->row_pub, h->top_pub, h->bar, h->item_next, h->path_flag, h->path_pub, h->stamps, h->vs.seg_part, h->node_count, h->anc, h->vs.stop_i, h->vs.stop_qid, h->vs.stop_child, h->vs.stop_m, h->vs.stop_qmu, h->vs.stop_ql, h->pr_m, h->pr_top_l, h->pr_top_idx, h->stats, h->counter};
     for (void *p : ptrs) (void)hipFree(p);
     for (hipEvent_t e : h->ev_begin) (void)hipEventDestroy(e);
     for (hipEvent_t e : h->ev_end) (void)hipEventDestroy(e);
@@ -258,7 +259,7 @@ extern "C" int stand_create(const stand_config *cfg, stand_handle **out)
     acc(dmalloc(&h->draft_qid, rows * K)); acc(dmalloc(&h->draft_qmu, rows * K));
     acc(dmalloc(&h->draft_tok2, rows)); acc(dmalloc(&h->draft_has2, rows));
     acc(dmalloc(&h->draft_qid2, rows * K)); acc(dmalloc(&h->draft_qmu2, rows * K));
-    acc(dmalloc(&h->row_done, rows)); acc(dmalloc(&h->bar, 2));
+    acc(dmalloc(&h->row_pub, rows)); acc(dmalloc(&h->top_pub, rows * (size_t)K)); acc(dmalloc(&h->bar, 2));
     acc(dmalloc(&h->item_next, B)); acc(dmalloc(&h->path_flag, B));
     acc(dmalloc(&h->path_pub, B * kPathPub));
     acc(dmalloc(&h->vs.row_m, rows)); acc(dmalloc(&h->vs.row_s, rows));
@@ -296,7 +297,8 @@ extern "C" int stand_create(const stand_config *cfg, stand_handle **out)
     acc(hipMemset(h->draft_has2, 0, rows * sizeof(int32_t)));
     acc(hipMemset(h->draft_qid2, 0, rows * K * sizeof(int32_t)));
     acc(hipMemset(h->draft_qmu2, 0, rows * K * sizeof(float)));
-    acc(hipMemset(h->row_done, 0, rows * sizeof(unsigned)));
+    acc(hipMemset(h->row_pub, 0, rows * sizeof(unsigned long long)));
+    acc(hipMemset(h->top_pub, 0, rows * (size_t)K * sizeof(unsigned long long)));
     acc(hipMemset(h->bar, 0, 2 * sizeof(unsigned)));
     acc(hipMemset(h->item_next, 0, B * sizeof(unsigned)));
     acc(hipMemset(h->path_flag, 0, B * sizeof(unsigned))); acc(hipMemset(h->path_pub, 0, B * kPathPub * sizeof(int32_t)));
@@ -469,6 +471,7 @@ static PathArgs make_path_args(const stand_handle *h, const VerifyScratch &vs, u
     a.obs_idx = vs.obs_idx; a.obs_p = vs.obs_p; a.stats = h->stats;
     a.late_len = (h->upper_depth < h->D ? h->upper_depth : h->D) + 1;
     a.fx_shift = h->fx_shift;
+    a.top_pub = nullptr;
     // segments of seg_vectors 16-byte vectors where kSegMax allows it
     const int row_vectors = (int)(((size_t)h->V * (bf16 ? 2 : 4) + 15) / 16);
     a.nseg = clampi((row_vectors + seg_vectors - 1) / seg_vectors, 1, kSegMax);
@@ -721,10 +724,12 @@ static int launch_step_fused(stand_handle *h, uint64_t step, const void *d_logit
     // the next draft goes to the second copy of the draft state; the copies change roles after the launch
     A.draft.draft_tok = h->draft_tok2; A.draft.draft_has = h->draft_has2;
     A.draft.draft_qid = h->draft_qid2; A.draft.draft_qmu = h->draft_qmu2;
-    A.sync.row_done = h->row_done; A.sync.bar = h->bar;
+    A.sync.bar = h->bar;
     A.sync.item_next = h->item_next; A.sync.path_flag = h->path_flag;
     A.sync.path_pub = h->path_pub;
     A.sync.epoch = ++h->step_epoch;
+    A.sync.pub = RowPub{h->row_pub, h->top_pub, A.sync.epoch};
+    A.path.top_pub = h->top_pub;
     A.sync.wait_ticks = h->wait_limit_us * (uint64_t)h->wall_khz / 1000ull;
     A.sync.stamps = h->stamps;
     if (h->stamps) {
@@ -833,7 +838,12 @@ extern "C" int stand_step(stand_handle *h, uint64_t step, const void *d_logits, 
     HIP_TRY(h, hipSetDevice(h->cfg.device));
     const int32_t *commit = d_force_tok ? d_force_tok : d_out_tok;
     plan_observe(h, s);
-    if (step_fused_wanted(h))
+    // The one launch numbers itself (its waits and the words its rows publish carry the launch's number, given as
+    // a kernel argument): recorded into a graph it would be replayed with a number that has passed.  While the
+    // stream is being captured the separate launches are taken, whatever the plan says; they replay correctly.
+    hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(s, &cap) != hipSuccess) { (void)hipGetLastError(); cap = hipStreamCaptureStatusNone; }
+    if (cap == hipStreamCaptureStatusNone && step_fused_wanted(h))
         return launch_step_fused(h, step, d_logits, d_out_tok, d_out_node, d_out_len, d_next_draft_tok, commit, s);
     int rc = launch_row_pass(h, h->vs, step, d_logits, s);
     if (rc) return rc;

@@ -12,8 +12,8 @@
 //
 // Workgroups start in index order, so the first P rows fill the device and finish together; the tail's
 // workgroups take the first places that become free and work while the remaining rows stream.  A tail workgroup never
-// assumes anything about timing: it WAITS for what it needs -- the two result counts of each row on
-// its path (any row, also one that is dispatched after it), the partial sums of its trajectory's
+// assumes anything about timing: it WAITS for what it needs -- the published results of each row on
+// its path (any row, also one that is dispatched after it; self-validating words, see RowPub), the partial sums of its trajectory's
 // other workgroups, and twice for all trajectories (every claim before the first apply, every apply
 // before the first lookup of the draft).  Every wait polls a device-scope counter, sleeps between the
 // polls and gives up after a bounded time (counted in the statistics; the trajectory's outputs are
@@ -46,7 +46,7 @@ constexpr unsigned long long kPartThere = 1ull << 63;  // set in a stored partia
 constexpr unsigned kWaitMaxPolls = 1u << 24;  // a wait ends after this many polls whatever the clock says
 
 struct StepSync {
-    unsigned *row_done;             // [B*N]  +2 per launch: the ranking wave and the testing wave of the row
+    RowPub pub;                     // what a row hands to the tail: self-validating words, tag = epoch
     unsigned *item_next;            // [B]    next (path row, segment) item to hand out: (launch number & 0xFFFF) << 16 | item
     unsigned *path_flag;            // [B]    launch number once the trajectory's path is published
     int32_t *path_pub;              // [B][kPathPub] the path: length, nodes, then the bit patterns of the rows' maxima
@@ -86,6 +86,24 @@ __device__ __forceinline__ bool wait_reached(const unsigned *p, unsigned target,
         }
     }
     if (seen) consume_fence();
+    return seen;
+}
+
+// Polls a row's published word until it carries this launch's tag (bounded like every wait).
+__device__ __forceinline__ bool wait_row_pub(const unsigned long long *p, unsigned tag, unsigned long long ticks,
+                                             unsigned long long &w)
+{
+    w = ld_agent(p);
+    bool seen = row_pub_there(w, tag);
+    if (!seen) {
+        const unsigned long long t0 = wall_clock64();
+        for (unsigned polls = 0; polls < kWaitMaxPolls && !seen; ++polls) {
+            __builtin_amdgcn_s_sleep(STAND_POLL_SLEEP);
+            w = ld_agent(p);
+            seen = row_pub_there(w, tag);
+            if (!seen && wall_clock64() - t0 > ticks) break;
+        }
+    }
     return seen;
 }
 
@@ -136,9 +154,10 @@ __device__ __forceinline__ void tail_role(const StepArgs &A, int b, int g, char 
             stamp(sy, b, 0);
             int cur = 0, len = 0, ok = 1;
             for (;;) {
-                if (!wait_reached(&sy.row_done[(size_t)b * N + cur], 2u * sy.epoch, sy.wait_ticks)) { ok = 0; break; }
-                const int acc = ld_agent(&a.outcome[(size_t)b * N + cur]);
-                ts->pm[len] = ld_agent(&a.src_m[(size_t)b * N + cur]);
+                unsigned long long rw;
+                if (!wait_row_pub(&sy.pub.row[(size_t)b * N + cur], sy.epoch, sy.wait_ticks, rw)) { ok = 0; break; }
+                const int acc = row_pub_outcome(rw);
+                ts->pm[len] = row_pub_max(rw);
                 ts->path[len] = cur;
                 ts->acc[len] = acc;
                 ++len;
@@ -300,19 +319,23 @@ __device__ __forceinline__ void tail_role(const StepArgs &A, int b, int g, char 
     }
     // ---- the partial sums (of whichever waves summed them), then the rows' observations and the resampled token
     if (tid == 0) stamp(sy, b, 3);
-    auto wait_parts = [&](int j) {  // one wave: lanes < nseg each wait for their segment of path row j
+    auto wait_parts = [&](int j) {  // one wave: lanes < nseg each wait for their segment of path row j,
+                                    // lanes < K for their word of the row's top-K (its ranking wave may still be at work)
         const unsigned long long *p = &a.seg_part[((size_t)b * a.R + j) * kSegMax];
+        const unsigned long long *tp = &sy.pub.top[((size_t)b * N + ts->path[j]) * K];
         unsigned long long v = lane < nseg ? ld_agent(p + lane) : kPartThere;
-        if (!__all((v & kPartThere) != 0ull)) {
+        bool top_ok = lane < K ? top_pub_there(ld_agent(tp + lane), sy.epoch) : true;
+        if (!__all((v & kPartThere) != 0ull && top_ok)) {
             const unsigned long long t0 = wall_clock64();
             for (unsigned polls = 0; polls < kWaitMaxPolls; ++polls) {
                 __builtin_amdgcn_s_sleep(STAND_POLL_SLEEP);
                 if (!(v & kPartThere)) v = ld_agent(p + lane);
-                if (__all((v & kPartThere) != 0ull)) break;
+                if (!top_ok) top_ok = top_pub_there(ld_agent(tp + lane), sy.epoch);
+                if (__all((v & kPartThere) != 0ull && top_ok)) break;
                 if (wall_clock64() - t0 > sy.wait_ticks) break;
             }
         }
-        if (!__all((v & kPartThere) != 0ull) && lane == 0) ts->ok = 0;
+        if (!__all((v & kPartThere) != 0ull && top_ok) && lane == 0) ts->ok = 0;
         consume_fence();
         return v & ~kPartThere;
     };
@@ -322,7 +345,7 @@ __device__ __forceinline__ void tail_role(const StepArgs &A, int b, int g, char 
         for (int j = wave; j + 1 < len; j += kStepWPR) {  // rows above the stop row: one wave each
             const int node = ts->path[j];
             const unsigned long long part = wait_parts(j);
-            finish_row<DT, kStepThreads>(a, ts->fin, b, j, node, false, ts->pm[j], 0, -1, len, -1, 0.0f, 0.0f, -1, part, lane, 0);
+            finish_row<DT, kStepThreads>(a, ts->fin, b, j, node, false, ts->pm[j], 0, -1, len, -1, 0.0f, 0.0f, -1, part, lane, 0, ts->acc[j]);
         }
         __syncthreads();
         if (ts->ok) {
@@ -377,7 +400,7 @@ __global__ __launch_bounds__(kStepThreads) __attribute__((amdgpu_waves_per_eu(ST
     }
     const int row = (slot % B) * A.row.N + slot / B;
     if (A.sync.stamps && threadIdx.x == 0) atomicMin(&A.sync.stamps[0], (unsigned long long)wall_clock64());
-    row_role<DT, kStepWPR>(A.row, row, (RowShared<kStepWPR> *)step_smem, &A.sync.row_done[row]);
+    row_role<DT, kStepWPR>(A.row, row, (RowShared<kStepWPR> *)step_smem, A.sync.pub);
     if (A.sync.stamps && (threadIdx.x == 0 || threadIdx.x == 64)) atomicMax(&A.sync.stamps[1], (unsigned long long)wall_clock64());
 }
 

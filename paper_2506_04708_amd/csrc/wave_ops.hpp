@@ -118,6 +118,33 @@ __device__ __forceinline__ void publish_fence()
 }
 __device__ __forceinline__ void consume_fence() { __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup"); }
 
+// Row results handed from a row's workgroup to the tail of the SAME launch (one-launch step) as
+// self-validating 64-bit words: a single aligned store is seen whole or not at all, so the producer
+// neither waits for its stores nor moves a counter (a wave that waits for a store to be acknowledged
+// keeps its workgroup's place on the device occupied for microseconds), and the consumer polls the
+// word it needs.  `row`: {maximum's bits, (tag & 0xFFFFFF) << 8 | outcome + 1}, tag = number of the
+// one-launch step on the handle.  `top`: {logit's bits, id | (tag & 1) << 31}: every such launch
+// rewrites every word, so a stale word always carries the other parity.
+struct RowPub {
+    unsigned long long *row;   // [B*N], or NULL: nothing is published (separate launches)
+    unsigned long long *top;   // [B*N][K]
+    unsigned tag;
+};
+__device__ __forceinline__ unsigned long long pack_row_pub(float m, int outcome, unsigned tag)
+{
+    return ((unsigned long long)(((tag & 0xFFFFFFu) << 8) | (unsigned)(outcome + 1)) << 32) | f2u(m);
+}
+__device__ __forceinline__ bool row_pub_there(unsigned long long w, unsigned tag) { return (unsigned)(w >> 40) == (tag & 0xFFFFFFu); }
+__device__ __forceinline__ int row_pub_outcome(unsigned long long w) { return (int)((w >> 32) & 0xFFu) - 1; }
+__device__ __forceinline__ float row_pub_max(unsigned long long w) { return u2f((uint32_t)w); }
+__device__ __forceinline__ unsigned long long pack_top_pub(int32_t id, float l, unsigned tag)
+{
+    return ((unsigned long long)((uint32_t)id | ((tag & 1u) << 31)) << 32) | f2u(l);
+}
+__device__ __forceinline__ bool top_pub_there(unsigned long long w, unsigned tag) { return (unsigned)(w >> 63) == (tag & 1u); }
+__device__ __forceinline__ int32_t top_pub_id(unsigned long long w) { return (int32_t)((w >> 32) & 0x7FFFFFFFu); }
+__device__ __forceinline__ float top_pub_logit(unsigned long long w) { return u2f((uint32_t)w); }
+
 // ---------------------------------------------------------------------------------------------
 // Accept/reject sequence at one tree node, executed by one wave (lane i = stored id i).
 // Returns the rank of the accepted child or -1.  With track_err the values r are taken to

@@ -566,6 +566,48 @@ def test_vocabularies_above_2_22(gpu, over, steps, rows):
     assert info["emitted"] >= steps * w.B and info["worst_rel"] < 1e-5
 
 
+def test_step_recorded_into_a_graph_replays_correctly(gpu):
+    """stand_step recorded into a HIP graph (the five launches are taken while a stream is being captured, whatever the
+    plan) and replayed three times, with eager work and synchronisations between the replays: every replay gives what
+    the same call gives eagerly on a twin handle (which runs it as one launch)."""
+    binding, lockstep = gpu
+    w = synth.Workload("cfg3", run_steps=12, V=3000, B=13, rho=0.7)
+    hs = []
+    for _ in range(2):
+        o, g = lockstep.make_pair(w, 1 << 14)
+        o.close()
+        for b in range(w.B):
+            g.set_context(b, w.prompt(b))
+        hs.append((g,) + tuple(g.new_outputs()))
+    (ga, ta, na, la, da), (gb, tb, nb, lb, db) = hs
+    ga.draft(0, da)
+    gb.draft(0, db)
+    for step in range(6):                       # the same eager steps on both, closed loop
+        lg = lockstep._logits_to_device(w.logits(step, da.cpu().numpy()), w.dtype)
+        ga.step(step, lg, ta, na, la, da)
+        gb.step(step, lg, tb, nb, lb, db)
+    torch.cuda.synchronize()
+    assert ga.step_is_one_launch() and torch.equal(da, db)
+    lg = lockstep._logits_to_device(w.logits(6, da.cpu().numpy()), w.dtype)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        gb.step(6, lg, tb, nb, lb, db)
+    scratch = torch.zeros(1 << 20, device="cuda")
+    for rep in range(3):
+        ga.step(6, lg, ta, na, la, da)          # the call itself, eagerly (contexts and table move on each time)
+        graph.replay()
+        torch.cuda.synchronize()
+        for x, y in ((ta, tb), (na, nb), (la, lb), (da, db)):
+            assert torch.equal(x, y), "replay %d differs from the eager call" % rep
+        scratch.add_(1.0)                       # eager work of the program between the replays
+        assert float(scratch.sum().item()) == float((rep + 1) << 20)
+    assert np.array_equal(ga.table_export(), gb.table_export())
+    sa, sb = ga.stats(), gb.stats()
+    assert (sa.inserts, sa.merges, sa.tokens_emitted) == (sb.inserts, sb.merges, sb.tokens_emitted) and sb.wait_expired == 0
+    ga.close()
+    gb.close()
+
+
 def test_results_do_not_depend_on_the_work_mapping(gpu):
     """Race detection by permutation: the same 14 closed-loop steps under different workgroup -> work mappings of
     the one-launch step (order in which workgroups take rows, rows placed before the tail, tail workgroups per
