@@ -219,8 +219,9 @@ int stand_step(stand_handle *h, uint64_t step, const void *d_logits, int32_t *d_
  *   tail_groups  FUSED: workgroups per trajectory that share the exact sums of the path rows, 1 .. 8;
  *                0 = chosen from the batch size.
  *   rows_first   FUSED: number of row workgroups placed before the tail's workgroups (at least the
- *                upper levels' rows); 0 = as many as the device holds at once, so that the tail starts
- *                when the first round of rows ends.
+ *                upper levels' rows); 0 = as many as the device holds at once less two tail workgroups
+ *                per trajectory, which are then resident from the start and follow the path as soon as
+ *                the root rows are done; the other tail workgroups start when the first rows end.
  *   shuffle      non-zero: the order in which row workgroups take rows is permuted (seeded by the value);
  *                a test that results do not depend on the workgroup -> work mapping. */
 int stand_set_step_plan(stand_handle *h, int32_t mode, int32_t upper_depth, int32_t tail_groups, int32_t rows_first,
