@@ -443,10 +443,10 @@ def main():
                     help="0 running mean over all observations of a context (the method), 1 keep only the newest "
                          "observation (the replace policy the paper compares against)")
     ap.add_argument("--peak", type=float, default=8.0,
-                    help="logit height of the peaked tokens (BASELINE: +8, p about 0.23 each); higher peaks give "
+                    help="logit height of the peaked tokens (workload recipe: +8, p about 0.23 each); higher peaks give "
                          "sharper targets, longer acceptance and deeper drafts")
     ap.add_argument("--max-peaks", type=int, default=4,
-                    help="each row peaks on 1..max-peaks tokens (BASELINE: 1-4); 1 with a high --peak models a confident "
+                    help="each row peaks on 1..max-peaks tokens (workload recipe: 1-4); 1 with a high --peak models a confident "
                          "target, where acceptance follows the quality of the drafts")
     ap.add_argument("--step-mode", type=int, default=0,
                     help="how stand_step is issued: 0 the library's choice, 1 five dependent launches, 2 one launch")

@@ -1,7 +1,7 @@
 """Lock-step parity runner: drives libstand (GPU, through the C ABI binding) and the CPU oracle
 with the same seeded inputs and compares every output of every step.
 
-Bars (BASELINE the benchmark spec): token ids, tree nodes, lengths, table fingerprints, counts and ids
+Bars (as stated for this build): token ids, tree nodes, lengths, table fingerprints, counts and ids
 bit-exact; stored probabilities bit-exact as well (both sides follow one numeric contract);
 the row pass's fast per-row probabilities within 1e-5 relative of the oracle's.
 """

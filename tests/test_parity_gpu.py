@@ -1,7 +1,7 @@
 """GPU parity: libstand (HIP, through the C ABI) against the CPU oracle, element by element.
 
 Ids, nodes, lengths, table keys/counts/ids and stored probabilities must be bit-exact; the row
-pass's fast probabilities within 1e-5 relative (north star of the benchmark spec).
+pass's fast probabilities within 1e-5 relative (the tolerance stated for this build).
 """
 import numpy as np
 import pytest
@@ -236,7 +236,7 @@ def test_lockstep_random_configs(gpu, seed):
 
 
 def test_lockstep_cfg1_full(gpu):
-    """BASELINE configs[0] at its real shape: B=1, V=32000, fp32, 16-node tree, 64 steps."""
+    """The smallest benchmark configuration (cfg1) at its real shape: B=1, V=32000, fp32, 16-node tree, 64 steps."""
     binding, lockstep = gpu
     w = synth.Workload("cfg1", run_steps=64)
     info = lockstep.run_lockstep(w, 64, mode="step", capacity=4096, forced=True)
@@ -301,7 +301,7 @@ def test_rows_sizes(gpu, V, K):
 
 
 def test_full_shape_rows_sampled(gpu):
-    """BASELINE configs[2] shape (B=32, N=64, V=152064, bf16, K=16) in the launch configuration the
+    """The headline benchmark configuration's (cfg3) shape (B=32, N=64, V=152064, bf16, K=16) in the launch configuration the
     benchmark times: one verify over all 2048 rows; the oracle checks a sample of them and the
     emitted tokens of every trajectory whose root row is in the sample."""
     binding, lockstep = gpu
@@ -336,7 +336,7 @@ def test_full_shape_rows_sampled(gpu):
 
 
 def test_largest_config_rows_sampled(gpu):
-    """BASELINE configs[4] at its full size (B=128, N=128, V=152064, bf16, K=32, T=0.8: 16384 rows, 4.98 GB of
+    """The largest benchmark configuration (cfg5) at its full size (B=128, N=128, V=152064, bf16, K=32, T=0.8: 16384 rows, 4.98 GB of
     logits) in one verify; the oracle checks sampled rows one by one, torch checks every row's maximum."""
     binding, lockstep = gpu
     w = synth.Workload("cfg5", run_steps=1)
@@ -392,7 +392,7 @@ def test_full_shape_step(gpu):
     ("cfg5", dict(B=8), 4),                                           # configs[4] rows (128 nodes, K=32, orders 1-5, T=0.8), 8 of its 128 beams
 ])
 def test_other_configs_at_their_row_shapes(gpu, name, over, steps):
-    """The remaining BASELINE configs with their real vocabulary, tree, K, orders and temperature
+    """The remaining benchmark configurations with their real vocabulary, tree, K, orders and temperature
     (fewer trajectories where the full batch would not fit a test's time), whole steps in lock step."""
     binding, lockstep = gpu
     w = synth.Workload(name, run_steps=steps, **over)
@@ -414,7 +414,7 @@ def test_other_configs_at_their_row_shapes(gpu, name, over, steps):
     ("cfg3", dict(), 4, dict(capacity=1 << 15, preload=9830)),
 ])
 def test_configs_at_full_batch(gpu, name, over, steps, kw):
-    """The BASELINE configurations at their real batch sizes, whole stand_step calls in lock step with the oracle
+    """The benchmark configurations at their real batch sizes, whole stand_step calls in lock step with the oracle
     (which evaluates only the rows its walk visits): tokens, nodes, lengths, next drafts, table export, counters;
     row-pass results on a sample of rows."""
     binding, lockstep = gpu
