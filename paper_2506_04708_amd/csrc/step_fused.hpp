@@ -6,20 +6,22 @@
 // step, because it is a chain of dependent round trips to memory.  Here it runs BESIDE the row pass:
 //
 //   workgroups [0, P)          rows: first those of the tree's upper levels (node-major), one row per
-//                              workgroup, then as many others as the device holds at once
-//   workgroups [P, P + B*G)    the tail: G workgroups per trajectory
+//                              workgroup, then others up to what the device holds at once less two tail
+//                              workgroups per trajectory
+//   workgroups [P, P + B*G)    the tail: G workgroups per trajectory (all first ones, then all second ones, ...)
 //   the rest                   all other rows
 //
-// Workgroups start in index order, so the first P rows fill the device and finish together; the tail's
-// workgroups take the first places that become free and work while the remaining rows stream.  A tail workgroup never
-// assumes anything about timing: it WAITS for what it needs -- the published results of each row on
-// its path (any row, also one that is dispatched after it; self-validating words, see RowPub), the partial sums of its trajectory's
-// other workgroups, and twice for all trajectories (every claim before the first apply, every apply
-// before the first lookup of the draft).  Every wait polls a device-scope counter, sleeps between the
-// polls and gives up after a bounded time (counted in the statistics; the trajectory's outputs are
-// then void); counters only ever grow (launch number times arrivals per launch), so nothing needs
-// clearing between launches.  What a workgroup waits for is always produced by workgroups that need
-// nothing from it.
+// Workgroups start in index order, so the first P rows and the first two tail workgroups of every trajectory
+// fill the device: the rows finish together, those tail workgroups wait in place and follow the path the moment
+// its rows are there; the other tail workgroups take the first places that become free.  All of the tail works
+// while the remaining rows stream.  A tail workgroup never assumes anything about timing: it WAITS for what it
+// needs -- the published results of each row on its path (any row, also one that is dispatched after it;
+// self-validating words, see RowPub), the partial sums of its trajectory's other workgroups, and twice for all
+// trajectories (every claim before the first apply, every apply before the first lookup of the draft).  Every
+// wait polls a word at device scope, sleeps between the polls and gives up after a bounded time (counted in the
+// statistics; the trajectory's outputs are then void); counters only ever grow (launch number times arrivals
+// per launch) and published words carry the launch number, so nothing needs clearing between launches.  What a
+// workgroup waits for is always produced by workgroups that need nothing from it.
 #pragma once
 #include "draft.hpp"
 #include "path_pass.hpp"
