@@ -74,6 +74,21 @@ __device__ __forceinline__ float exact_exp2(float y)
     return __builtin_ldexpf(p, (int)k);
 }
 
+// The same for -64 <= y <= 0 without the test (callers that clamp y themselves).
+__device__ __forceinline__ float exact_exp2_noguard(float y)
+{
+    float k = __builtin_rintf(y);
+    float f = y - k;
+    float q = 0x1.44138ap-13f;
+    q = __builtin_fmaf(q, f, 0x1.5f0890p-10f);
+    q = __builtin_fmaf(q, f, 0x1.3b2a54p-7f);
+    q = __builtin_fmaf(q, f, 0x1.c6af6cp-5f);
+    q = __builtin_fmaf(q, f, 0x1.ebfbe0p-3f);
+    q = __builtin_fmaf(q, f, 0x1.62e430p-1f);
+    float p = __builtin_fmaf(q, f, 1.0f);
+    return __builtin_ldexpf(p, (int)k);
+}
+
 // ---- ln x for positive normal x ---------------------------------------------------------------
 __device__ __forceinline__ float exact_log(float x)
 {

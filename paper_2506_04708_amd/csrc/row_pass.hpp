@@ -432,7 +432,7 @@ __device__ __forceinline__ void fixed_split(float e, uint32_t &hi, uint32_t &lo)
 // strided over `nthreads` threads; returns this thread's partial sum_v floor(E((l_v - m) c) * 2^(40 - shift)).
 // floor(e 2^40) = hi 2^20 + lo, and hi 2^20 is a multiple of 2^shift (shift <= 20), so
 // floor(e 2^(40 - shift)) = hi 2^(20 - shift) + (lo >> shift): the parts are shifted, then summed.
-template <int DT, int INFLIGHT = 4>
+template <int DT, int INFLIGHT = 4, bool SHORT_FORM = true>
 __device__ __forceinline__ unsigned long long thread_exact_partial(const void *rowp, const RowGeom &g, int v0, int v1,
                                                                    bool with_edge, float m, float c, int t, int nthreads,
                                                                    int shift)
@@ -453,15 +453,30 @@ __device__ __forceinline__ unsigned long long thread_exact_partial(const void *r
     // INFLIGHT independent loads are issued before any of them is used (indices clamped, so the
     // number of loads in flight does not depend on the position in the row)
     const int vlast = v1 > v0 ? v1 - 1 : v0;
+    // A term below 2^-14 (nearly all of a row) needs no split: e * 2^40 < 2^26 is an integer-valued binary32 once
+    // truncated, so floor(e * 2^40) is one multiplication and one conversion.  The wave takes the split form
+    // for a vector in which any lane holds a larger term.  (y is clamped at -64 instead of tested: E(-64) = 2^-64
+    // contributes 0 like the E = 0 of smaller y, and a NaN is clamped as well.)
     auto add_vec = [&](const uint4 &w, int idx) {
         if (idx < v1) {
-            float x[EPV];
+            float x[EPV], e[EPV];
             unpack<DT>(w, x);
+            float emax = 0.0f;
 #pragma unroll
             for (int j = 0; j < EPV; ++j) {
-                uint32_t hi, lo;
-                fixed_split(exact_exp2(scaled_offset(x[j], m, c)), hi, lo);
-                ahi += hi; alo += lo >> shift;
+                e[j] = exact_exp2_noguard(fmaxf(scaled_offset(x[j], m, c), -64.0f));
+                emax = fmaxf(emax, e[j]);
+            }
+            if (SHORT_FORM && !__any(emax >= 0x1p-14f)) {
+#pragma unroll
+                for (int j = 0; j < EPV; ++j) alo += (uint32_t)(e[j] * 0x1p40f) >> shift;
+            } else {
+#pragma unroll
+                for (int j = 0; j < EPV; ++j) {
+                    uint32_t hi, lo;
+                    fixed_split(e[j], hi, lo);
+                    ahi += hi; alo += lo >> shift;
+                }
             }
         }
     };
@@ -476,7 +491,8 @@ __device__ __forceinline__ unsigned long long thread_exact_partial(const void *r
         for (int q = 0; q < INFLIGHT; ++q) {
             add_vec(w[q], base + q * nthreads);
             if ((q & 3) == 3 || q == INFLIGHT - 1) {
-                // at most 32 elements since the last flush: the 32-bit accumulators stay below 2^26
+                // at most 32 elements since the last flush: the 32-bit accumulators stay below 2^31 (terms
+                // below 2^26 in the short form, below 2^20 and 2^21 in the split form)
                 S += ((unsigned long long)ahi << (20 - shift)) + alo;
                 ahi = 0; alo = 0;
             }
@@ -490,7 +506,8 @@ template <int DT>
 __device__ unsigned long long wave_row_exact_sum(const void *rowp, int V, float m, float c, int lane, int shift)
 {
     const RowGeom g = row_geom<DT>(rowp, V);
-    unsigned long long S = thread_exact_partial<DT>(rowp, g, 0, g.nvec, true, m, c, lane, 64, shift);
+    // (the split form only: this rare path shares its registers with the streaming loop of the same kernel)
+    unsigned long long S = thread_exact_partial<DT, 4, false>(rowp, g, 0, g.nvec, true, m, c, lane, 64, shift);
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) S += __shfl_xor(S, off);
     return S;
