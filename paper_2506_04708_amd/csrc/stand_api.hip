@@ -728,7 +728,8 @@ static int launch_step_fused(stand_handle *h, uint64_t step, const void *d_logit
     A.sync.bar = h->bar;
     A.sync.item_next = h->item_next; A.sync.path_flag = h->path_flag;
     A.sync.path_pub = h->path_pub;
-    A.sync.epoch = ++h->step_epoch;
+    A.sync.epoch = h->step_epoch + 1;  // (taken only once the launch has been accepted: the rows' published words rely on
+                                        // consecutive numbers, see RowPub)
     A.sync.pub = RowPub{h->row_pub, h->top_pub, A.sync.epoch};
     A.path.top_pub = h->top_pub;
     A.sync.wait_ticks = h->wait_limit_us * (uint64_t)h->wall_khz / 1000ull;
@@ -786,6 +787,7 @@ static int launch_step_fused(stand_handle *h, uint64_t step, const void *d_logit
         HIP_TRY(h, hipLaunchKernel(fn, grid, block, args, smem, s));
     }
     HIP_TRY(h, hipGetLastError());
+    h->step_epoch = A.sync.epoch;
     std::swap(h->draft_tok, h->draft_tok2); std::swap(h->draft_has, h->draft_has2);
     std::swap(h->draft_qid, h->draft_qid2); std::swap(h->draft_qmu, h->draft_qmu2);
     h->table_used = true;
