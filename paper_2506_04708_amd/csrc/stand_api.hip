@@ -640,7 +640,8 @@ extern "C" uint64_t stand_static_scratch_need(const stand_handle *h)
 }
 
 // The whole step in one launch (step_fused.hpp).
-static bool step_fused_wanted(const stand_handle *h)
+// Whether the one launch is among the choices at all (whatever the acceptance depth at present).
+static bool step_fused_possible(const stand_handle *h)
 {
     if (h->cfg.update_mode != STAND_UPDATE_ACCEPTED_PATH) return false;
     if (h->step_mode == STAND_STEP_SERIAL) return false;
@@ -648,11 +649,16 @@ static bool step_fused_wanted(const stand_handle *h)
     // never hold more than a fraction of the device (256 compute units, three such workgroups each)
     if (h->B * (h->tail_groups > 0 ? h->tail_groups : 1) > 256) return false;
     if (h->step_mode == STAND_STEP_FUSED) return true;
-    if (h->plan_serial) return false;  // (deep accepted paths are common at present, see plan_observe)
     // With few rows the pass is latency-bound and sixteen waves per row serve it better.  With very many the
     // dependent launches are a few per cent of the step, which is all one launch could save, and it varied more
     // from run to run than that (B=128 x 128 nodes: 0.84-0.96 ms against 0.85-0.88 ms).
     return h->B * h->N > kRowsFew && h->B * h->N <= kRowsMany;
+}
+static bool step_fused_wanted(const stand_handle *h)
+{
+    if (!step_fused_possible(h)) return false;
+    // (automatic plan: not while deep accepted paths are common, see plan_observe)
+    return h->step_mode == STAND_STEP_FUSED || !h->plan_serial;
 }
 
 // STAND_STEP_AUTO only.  In the one-launch step a trajectory whose accepted path reaches below the tree
@@ -664,19 +670,10 @@ static bool step_fused_wanted(const stand_handle *h)
 // observed while the stream is being captured.
 constexpr uint64_t kPlanWindow = 32;
 constexpr double kPlanSerialAbove = 0.40, kPlanFusedBelow = 0.25;
-static void plan_observe(stand_handle *h, hipStream_t s)
+static void plan_observe(stand_handle *h, hipStream_t s, bool capturing)
 {
-    if (h->step_mode != STAND_STEP_AUTO || !h->probe_host || !h->probe_ev) return;
-    {
-        // nothing to decide where the one launch is not among the choices
-        const bool was = h->plan_serial;
-        h->plan_serial = false;
-        const bool could = step_fused_wanted(h);
-        h->plan_serial = was;
-        if (!could) return;
-    }
-    hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
-    if (hipStreamIsCapturing(s, &cap) != hipSuccess || cap != hipStreamCaptureStatusNone) { (void)hipGetLastError(); return; }
+    if (h->step_mode != STAND_STEP_AUTO || !h->probe_host || !h->probe_ev || capturing) return;
+    if (!step_fused_possible(h)) return;  // nothing to decide where the one launch is not among the choices
     ++h->probe_steps;
     if (h->probe_pending) {
         if (hipEventQuery(h->probe_ev) != hipSuccess) { (void)hipGetLastError(); return; }  // (not there yet)
@@ -741,7 +738,6 @@ static int launch_step_fused(stand_handle *h, uint64_t step, const void *d_logit
     }
     const int ud = h->upper_depth < h->D ? h->upper_depth : h->D;
     A.upper_nodes = h->level_start[ud + 1];
-    A.G = step_tail_groups(h);
     const void *fn = bf16 ? (const void *)stand_step_kernel<kDtBf16> : (const void *)stand_step_kernel<kDtF32>;
     const size_t smem = step_shared_bytes(h->N, h->D);
     if (h->step_slots == 0) {
@@ -847,13 +843,14 @@ extern "C" int stand_step(stand_handle *h, uint64_t step, const void *d_logits, 
     hipStream_t s = (hipStream_t)stream;
     HIP_TRY(h, hipSetDevice(h->cfg.device));
     const int32_t *commit = d_force_tok ? d_force_tok : d_out_tok;
-    plan_observe(h, s);
     // The one launch numbers itself (its waits and the words its rows publish carry the launch's number, given as
     // a kernel argument): recorded into a graph it would be replayed with a number that has passed.  While the
     // stream is being captured the separate launches are taken, whatever the plan says; they replay correctly.
     hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
     if (hipStreamIsCapturing(s, &cap) != hipSuccess) { (void)hipGetLastError(); cap = hipStreamCaptureStatusNone; }
-    if (cap == hipStreamCaptureStatusNone && step_fused_wanted(h))
+    const bool capturing = cap != hipStreamCaptureStatusNone;
+    plan_observe(h, s, capturing);
+    if (!capturing && step_fused_wanted(h))
         return launch_step_fused(h, step, d_logits, d_out_tok, d_out_node, d_out_len, d_next_draft_tok, commit, s);
     int rc = launch_row_pass(h, h->vs, step, d_logits, s);
     if (rc) return rc;
