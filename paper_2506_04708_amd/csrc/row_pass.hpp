@@ -485,7 +485,7 @@ __device__ __forceinline__ unsigned long long thread_exact_partial(const void *r
 #pragma unroll
         for (int q = 0; q < INFLIGHT; ++q) {
             const int i = base + q * nthreads;
-            w[q] = g.vp[i < vlast ? i : vlast];
+            w[q] = load_streamed(&g.vp[i < vlast ? i : vlast]);  // (read once more, then never: 0.5 % of a step against plain loads)
         }
 #pragma unroll
         for (int q = 0; q < INFLIGHT; ++q) {
